@@ -1,0 +1,378 @@
+"""fp64 numpy oracle of the Q-GaLore per-matrix optimizer step.
+
+TEST INFRASTRUCTURE ONLY: nothing in the product path may import this module.
+It is independent of the HIP library (no shared code, tables or constants
+generators) and is pinned by tests/test_oracle_*.py against closed forms,
+invariants, library routines and brute force.
+
+Notation follows the paper: W is the m x n weight (INT8 codes Wq plus one fp32
+scale per block of 256 elements of a row), G the m x n bf16 gradient, P the
+m x r projection matrix (INT4 codes plus one fp32 scale per block of 256
+elements of the flattened row-major array), R = P^T G the projected gradient,
+M and V the Adam moments (r x n), N the Adam direction, U = alpha * P * N the
+back-projected update, t the 1-based step count.
+
+Every function states the passage of the paper it follows.  Where the paper
+is silent the reading taken is stated in the function's docstring; all such
+readings are "parity unpinned" (no value printed in the paper can confirm
+them): the symmetric absmax scale with z = 0, the reciprocal-multiply form of
+W/s, the flat/row block rules, the nibble packing, the hash constants of the
+stochastic-rounding generator, the textbook Adam form and the column-mean
+cosine.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+GROUP = 256          # block size of the quantizer (Sec. 3.1, "block size of 256")
+QMAX = {4: 7, 8: 127}  # 2^(n-1) - 1
+
+
+# --------------------------------------------------------------------------
+# bf16 helpers (Sec. 3.1: activations and gradients are BFloat16)
+# --------------------------------------------------------------------------
+def bf16_rne(x) -> np.ndarray:
+    """Round fp64 values to the nearest bf16 value (ties to even), ONE rounding.
+
+    Result is returned as fp64 (every bf16 value is exactly representable).
+    bf16 keeps 8 significant bits and fp32's exponent range; values below the
+    smallest normal (2^-126) are rounded on the subnormal grid 2^-133.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    out = np.empty_like(x)
+    bits = x.view(np.uint64) if x.flags["C_CONTIGUOUS"] else np.ascontiguousarray(x).view(np.uint64)
+    bits = bits.reshape(x.shape).copy()
+    drop = np.uint64(52 - 7)                       # fp64 has 52 fraction bits, bf16 has 7
+    lsb = (bits >> drop) & np.uint64(1)
+    bits = bits + ((np.uint64(1) << (drop - np.uint64(1))) - np.uint64(1)) + lsb
+    bits &= ~((np.uint64(1) << drop) - np.uint64(1))
+    out[...] = bits.view(np.float64).reshape(x.shape)
+    tiny = np.abs(x) < 2.0 ** -126
+    if np.any(tiny):
+        q = 2.0 ** -133
+        out[tiny] = np.rint(x[tiny] / q) * q
+    nonfinite = ~np.isfinite(x)
+    if np.any(nonfinite):
+        out[nonfinite] = x[nonfinite]
+    return out
+
+
+def bf16_bits_to_f64(bits) -> np.ndarray:
+    """Decode bf16 bit patterns (uint16) to their exact values."""
+    b = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return b.view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16_bits(x) -> np.ndarray:
+    """Round to bf16 (one rounding) and return the uint16 bit patterns."""
+    r = bf16_rne(x).astype(np.float32)             # exact: bf16 values are fp32 values
+    return (r.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+# --------------------------------------------------------------------------
+# Block-wise uniform quantization (Sec. 3.1, the Quant_n equation)
+# --------------------------------------------------------------------------
+def _scale_pair(absmax32: np.ndarray, bits: int):
+    """fp32 scale s = a/qmax and fp32 reciprocal scale qmax/a of each block.
+
+    A block whose absmax is 0 gets s = 0 and reciprocal 0 (all codes 0).
+    Both quotients are correctly rounded fp32 quotients: an fp64 quotient of two
+    fp32 numbers rounded to fp32 equals the fp32 quotient (53 >= 2*24 + 2).
+    """
+    a = absmax32.astype(np.float64)
+    qmax = float(QMAX[bits])
+    with np.errstate(divide="ignore", invalid="ignore"):
+        s = np.where(a > 0, a / qmax, 0.0).astype(np.float32)
+        inv = np.where(a > 0, qmax / a, 0.0).astype(np.float32)
+    return s, inv
+
+
+def _codes_rne(x32: np.ndarray, inv32: np.ndarray, bits: int) -> np.ndarray:
+    """clamp(round_half_even(fl32(x * (1/s))), -2^(n-1), 2^(n-1)-1) with z = 0."""
+    t = (x32.astype(np.float32) * inv32.astype(np.float32)).astype(np.float32)  # one fp32 product
+    q = np.rint(t.astype(np.float64))
+    return np.clip(q, -(QMAX[bits] + 1), QMAX[bits]).astype(np.int8)
+
+
+def quant_int8(x) -> tuple[np.ndarray, np.ndarray]:
+    """Quant_8 of an fp32 matrix; a block = 256 consecutive elements of a row.
+
+    The last block of a row is short when cols % 256 != 0.  Returns int8 codes
+    [rows][cols] and fp32 scales [rows][ceil(cols/256)].  (Sec. 3.1; symmetric
+    absmax scale, zero point 0.)
+    """
+    x = np.asarray(x, dtype=np.float32)
+    rows, cols = x.shape
+    ng = (cols + GROUP - 1) // GROUP
+    q = np.zeros((rows, cols), dtype=np.int8)
+    scales = np.zeros((rows, ng), dtype=np.float32)
+    for g in range(ng):
+        blk = x[:, g * GROUP:(g + 1) * GROUP]
+        a = np.max(np.abs(blk), axis=1).astype(np.float32)
+        s, inv = _scale_pair(a, 8)
+        scales[:, g] = s
+        q[:, g * GROUP:(g + 1) * GROUP] = _codes_rne(blk, inv[:, None], 8)
+    return q, scales
+
+
+def dequant_int8(q, scales) -> np.ndarray:
+    """W = W_q * s per block (Appendix A dequantization with zeros = 0), exact in fp64."""
+    q = np.asarray(q)
+    rows, cols = q.shape
+    s = np.repeat(np.asarray(scales, dtype=np.float64), GROUP, axis=1)[:, :cols]
+    return q.astype(np.float64) * s
+
+
+def quant_int4_codes(x) -> tuple[np.ndarray, np.ndarray]:
+    """Quant_4 of an fp32 matrix; a block = 256 consecutive elements of the
+    flattened row-major array (Sec. 3.3: block size 256 across all layers).
+
+    Returns int8 codes in [-7, 7], shape of x, and fp32 scales [ceil(size/256)].
+    """
+    x = np.asarray(x, dtype=np.float32)
+    flat = x.reshape(-1)
+    ng = (flat.size + GROUP - 1) // GROUP
+    codes = np.zeros(flat.size, dtype=np.int8)
+    scales = np.zeros(ng, dtype=np.float32)
+    full = (flat.size // GROUP) * GROUP
+    if full:
+        blk = flat[:full].reshape(-1, GROUP)
+        a = np.max(np.abs(blk), axis=1).astype(np.float32)
+        s, inv = _scale_pair(a, 4)
+        scales[: full // GROUP] = s
+        codes[:full] = _codes_rne(blk, inv[:, None], 4).reshape(-1)
+    if full < flat.size:
+        blk = flat[full:]
+        a = np.max(np.abs(blk)).astype(np.float32).reshape(1)
+        s, inv = _scale_pair(a, 4)
+        scales[-1] = s[0]
+        codes[full:] = _codes_rne(blk, inv, 4)
+    return codes.reshape(x.shape), scales
+
+
+def pack_int4(codes) -> np.ndarray:
+    """Two codes per byte: flat element 2b in the low nibble of byte b, 2b+1 in
+    the high nibble; stored nibble = code + 8 (offset binary).  An odd count
+    leaves the last high nibble at 8 (code 0)."""
+    c = np.asarray(codes, dtype=np.int16).reshape(-1) + 8
+    if np.any((c < 0) | (c > 15)):
+        raise ValueError("INT4 code out of range")
+    if c.size % 2:
+        c = np.concatenate([c, np.array([8], dtype=np.int16)])
+    return (c[0::2] | (c[1::2] << 4)).astype(np.uint8)
+
+
+def unpack_int4(packed, count: int) -> np.ndarray:
+    """Inverse of pack_int4: the first `count` codes as int8."""
+    p = np.asarray(packed, dtype=np.uint8).astype(np.int16)
+    c = np.empty(p.size * 2, dtype=np.int16)
+    c[0::2] = p & 0xF
+    c[1::2] = p >> 4
+    return (c[:count] - 8).astype(np.int8)
+
+
+def quant_int4(x) -> tuple[np.ndarray, np.ndarray]:
+    """Quant_4 followed by nibble packing: (packed uint8 [ceil(size/2)], scales)."""
+    codes, scales = quant_int4_codes(x)
+    return pack_int4(codes), scales
+
+
+def dequant_int4(packed, scales, rows: int, cols: int) -> np.ndarray:
+    """P = P_q * s per flat block of 256, exact in fp64, shape [rows][cols]."""
+    codes = unpack_int4(packed, rows * cols).astype(np.float64)
+    s = np.repeat(np.asarray(scales, dtype=np.float64), GROUP)[: rows * cols]
+    return (codes * s).reshape(rows, cols)
+
+
+# --------------------------------------------------------------------------
+# Stochastic rounding (Sec. 3.4, the F_SR equation) and its generator
+# --------------------------------------------------------------------------
+_M32 = 0xFFFFFFFF
+_GOLDEN = 0x9E3779B9
+
+
+def _mix32(x):
+    """32-bit avalanche mixer: xorshift 16, multiply 0x7FEB352D, xorshift 15,
+    multiply 0x846CA68B, xorshift 16 (a published public-domain integer hash)."""
+    x = np.asarray(x, dtype=np.uint64) & np.uint64(_M32)
+    x ^= x >> np.uint64(16)
+    x = (x * np.uint64(0x7FEB352D)) & np.uint64(_M32)
+    x ^= x >> np.uint64(15)
+    x = (x * np.uint64(0x846CA68B)) & np.uint64(_M32)
+    x ^= x >> np.uint64(16)
+    return x
+
+
+def sr_key(seed: int, step: int, idx_hi: int = 0) -> int:
+    """Fold (seed_lo, seed_hi, step_lo, step_hi, idx_hi) into one 32-bit key:
+    key <- mix32((key xor word) + 0x9E3779B9), starting from 0x9E3779B9."""
+    seed &= (1 << 64) - 1
+    step &= (1 << 64) - 1
+    key = _GOLDEN
+    for w in (seed & _M32, seed >> 32, step & _M32, step >> 32, idx_hi & _M32):
+        key = int(_mix32(((key ^ w) + _GOLDEN) & _M32))
+    return key
+
+
+def sr_hash(seed: int, step: int, idx) -> np.ndarray:
+    """32-bit hash of (seed, step, element index): mix32(key xor idx_lo)."""
+    idx = np.asarray(idx, dtype=np.uint64)
+    hi = idx >> np.uint64(32)
+    lo = idx & np.uint64(_M32)
+    if hi.size and np.any(hi != hi.reshape(-1)[0]):
+        keys = np.array([sr_key(seed, step, int(h)) for h in hi.reshape(-1)], dtype=np.uint64).reshape(hi.shape)
+    else:
+        keys = np.uint64(sr_key(seed, step, int(hi.reshape(-1)[0]) if hi.size else 0))
+    return _mix32(keys ^ lo)
+
+
+def sr_uniform(seed: int, step: int, idx) -> np.ndarray:
+    """u in [0, 1): the top 24 bits of the hash times 2^-24 (exact in fp32)."""
+    return (sr_hash(seed, step, idx) >> np.uint64(8)).astype(np.float64) * 2.0 ** -24
+
+
+def sr_round(v, u) -> np.ndarray:
+    """F_SR(v) = floor(v + u), u uniform in [0,1): floor(v) with probability
+    ceil(v) - v and ceil(v) with probability v - floor(v).  The sum is taken in
+    fp32, the precision in which the library takes this decision."""
+    s = (np.asarray(v, dtype=np.float32) + np.asarray(u, dtype=np.float32)).astype(np.float32)
+    return np.floor(s.astype(np.float64))
+
+
+# --------------------------------------------------------------------------
+# The optimizer step (Sec. 3.5)
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class HParams:
+    """Adam and GaLore hyper-parameters, held as the fp32 values the library
+    receives (Sec. 4.1: scale factor alpha = 0.25)."""
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    lr: float = 1e-3
+    alpha: float = 0.25
+
+    def f32(self):
+        f = lambda v: float(np.float32(v))
+        return HParams(f(self.beta1), f(self.beta2), f(self.eps), f(self.lr), f(self.alpha))
+
+
+def dequant_p_bf16(Pq, Ps, m: int, r: int) -> np.ndarray:
+    """P as the GEMMs see it: code * scale (exact), rounded once to bf16."""
+    return bf16_rne(dequant_int4(Pq, Ps, m, r))
+
+
+def project(Pq, Ps, G_bits, m: int, n: int, r: int) -> np.ndarray:
+    """R = P^T G (Sec. 3.5: the full-rank gradient is projected into a low-rank
+    format), P dequantized and rounded to bf16, G's bf16 values taken exactly."""
+    Pd = dequant_p_bf16(Pq, Ps, m, r)
+    G = bf16_bits_to_f64(np.asarray(G_bits).reshape(m, n))
+    return Pd.T @ G
+
+
+def lowrank_adam(R, M, V, t: int, hp: HParams):
+    """Adam on the low-rank gradient (Sec. 3.5; Adam as cited in Sec. 4.1):
+    M' = b1 M + (1-b1) R;  V' = b2 V + (1-b2) R^2;
+    N = (M'/(1-b1^t)) / (sqrt(V'/(1-b2^t)) + eps).  Returns (M', V', N)."""
+    hp = hp.f32()
+    R = np.asarray(R, dtype=np.float64)
+    M1 = hp.beta1 * np.asarray(M, dtype=np.float64) + (1.0 - hp.beta1) * R
+    V1 = hp.beta2 * np.asarray(V, dtype=np.float64) + (1.0 - hp.beta2) * R * R
+    mhat = M1 / (1.0 - hp.beta1 ** t)
+    vhat = V1 / (1.0 - hp.beta2 ** t)
+    N = mhat / (np.sqrt(vhat) + hp.eps)
+    return M1, V1, N
+
+
+def backproject(Pq, Ps, Nb, m: int, r: int, alpha: float) -> np.ndarray:
+    """U = alpha * P * N (Sec. 3.5: the low-rank update is projected back to full
+    rank; Sec. 4.1: scale factor alpha), Nb being N already rounded to bf16."""
+    Pd = dequant_p_bf16(Pq, Ps, m, r)
+    return float(np.float32(alpha)) * (Pd @ np.asarray(Nb, dtype=np.float64))
+
+
+def update_sr(Wq, Ws, U, lr: float, seed: int, t: int, n_total: int | None = None, col0: int = 0):
+    """INT8 weight update with stochastic rounding (Sec. 3.4, Sec. 3.5).
+
+    x = W_q * s - lr * U; per block of 256 of each row a = max|x|, new scale
+    s' = a/127, code = clamp(F_SR(x * (127/a)), -128, 127) with the uniform draw
+    u(seed, t, i*n_total + col0 + j).  The decision steps (absmax, the two
+    quotients, the product, the sum with u) are taken in fp32.
+    Returns (new codes, new scales).
+    """
+    Wq = np.asarray(Wq)
+    m, n = Wq.shape
+    n_total = n if n_total is None else n_total
+    x = dequant_int8(Wq, Ws) - float(np.float32(lr)) * np.asarray(U, dtype=np.float64)
+    x32 = x.astype(np.float32)
+    ng = (n + GROUP - 1) // GROUP
+    newq = np.zeros((m, n), dtype=np.int8)
+    news = np.zeros((m, ng), dtype=np.float32)
+    ii = np.arange(m, dtype=np.uint64)[:, None]
+    for g in range(ng):
+        c0, c1 = g * GROUP, min((g + 1) * GROUP, n)
+        blk = x32[:, c0:c1]
+        a = np.max(np.abs(blk), axis=1).astype(np.float32)
+        s, inv = _scale_pair(a, 8)
+        news[:, g] = s
+        tq = (blk * inv[:, None]).astype(np.float32)
+        idx = ii * np.uint64(n_total) + np.arange(col0 + c0, col0 + c1, dtype=np.uint64)[None, :]
+        u = sr_uniform(seed, t, idx)
+        newq[:, c0:c1] = np.clip(sr_round(tq, u), -128, 127).astype(np.int8)
+    return newq, news
+
+
+def step(Wq, Ws, G_bits, Pq, Ps, M, V, t: int, hp: HParams, seed: int,
+         r: int, n_total: int | None = None, col0: int = 0) -> dict:
+    """One Q-GaLore step on one matrix (Sec. 3.5): project, Adam, back-project,
+    INT8 stochastic-rounding update.  All operations are column-separable, so a
+    slice of columns [col0, col0+n) of a wider matrix (n_total columns, col0 a
+    multiple of 256) can be stepped alone and gives that slice of the result.
+    """
+    Wq = np.asarray(Wq)
+    m, n = Wq.shape
+    R = project(Pq, Ps, G_bits, m, n, r)
+    M1, V1, N = lowrank_adam(R, M, V, t, hp)
+    Nb = bf16_rne(N)
+    U = backproject(Pq, Ps, Nb, m, r, hp.alpha)
+    newq, news = update_sr(Wq, Ws, U, hp.lr, seed, t, n_total, col0)
+    return dict(R=R, M=M1, V=V1, N=N, Nb=Nb, U=U, Wq=newq, Ws=news)
+
+
+# --------------------------------------------------------------------------
+# Layer-adaptive subspace check (Sec. 3.2)
+# --------------------------------------------------------------------------
+def subspace_cossim(PqA, PsA, PqB, PsB, m: int, r: int) -> float:
+    """Cosine similarity between two adjacent projection matrices (Fig. 2): the
+    mean over the r columns of cos(a_k, b_k) on the dequantized INT4 values."""
+    A = dequant_int4(PqA, PsA, m, r)
+    B = dequant_int4(PqB, PsB, m, r)
+    dots = np.sum(A * B, axis=0)
+    den = np.maximum(np.sqrt(np.sum(A * A, axis=0)) * np.sqrt(np.sum(B * B, axis=0)), 1e-8)
+    return float(np.mean(dots / den))
+
+
+@dataclass
+class Policy:
+    """Adaptive lazy update of the SVD interval (Sec. 3.2): when the similarity
+    stayed at or above the threshold over the previous k checks, the interval
+    doubles."""
+    interval: int = 200
+    k: int = 1
+    threshold: float = 0.4
+    streak: int = 0
+    next_refresh: int = 200
+    last_cos: float = 0.0
+
+    def update(self, cos: float) -> bool:
+        self.last_cos = float(cos)
+        self.streak = self.streak + 1 if cos >= self.threshold else 0
+        doubled = False
+        if self.streak >= self.k:
+            self.interval *= 2
+            self.streak = 0
+            doubled = True
+        self.next_refresh += self.interval
+        return doubled
