@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the Q-GaLore optimizer step on one MI355X.
+
+A "step" is one pass of the whole hot path (project -> Adam -> back-project + INT8 stochastic-rounding
+update) over every linear weight of the workload, by the three grouped launches of qg_step_many.  The
+default workload is the one the headline metric is quoted on: LLaMA-7B shapes (224 matrices, r = 1024).
+Inputs are synthetic, generated on the device before the timed region, and stay resident in HBM.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
+
+WORKLOADS = {
+    0: "config0: one 512x512 matrix, r=128",
+    1: "LLaMA-130M shapes: 84 matrices, r=256",
+    2: "LLaMA-350M shapes: 168 matrices, r=256",
+    3: "LLaMA-1B shapes: 168 matrices, r=512",
+    4: "LLaMA-7B shapes: 224 matrices (32 layers x [4x 4096x4096, 2x 11008x4096, 1x 4096x11008]), r=1024, "
+       "INT8 W / bf16 G / INT4 P, group 256",
+}
+
+
+def algorithmic_work(shapes):
+    """Flops and HBM bytes each kernel must move for these (m, n, r) matrices (no re-reads counted)."""
+    flops = sum(2 * m * n * r for m, n, r in shapes)
+    p_bytes = lambda m, r: m * r // 2 + 4 * ((m * r + 255) // 256)
+    proj = sum(2 * m * n + p_bytes(m, r) + 4 * r * n for m, n, r in shapes)
+    adam = sum(22 * r * n for m, n, r in shapes)
+    bp = sum(2 * m * n + 8 * m * ((n + 255) // 256) + p_bytes(m, r) + 2 * r * n for m, n, r in shapes)
+    return flops, proj, adam, bp
+
+
+def build_state(config: int, device):
+    """Device-resident synthetic state of every matrix of the workload.
+
+    W ~ N(0, 0.02) quantized by qg_quant_int8; G = A B^T + E (rank 16 plus noise) in bf16; one orthonormal P per
+    distinct (m, r) (host QR, quantized by qg_quant_int4) shared by the matrices of that shape - values do not
+    affect timing.  Generated with torch's device RNG (the host generators of the parity tests would take minutes
+    for 6.5e9 elements); distributions and shapes are the same.
+    """
+    import torch
+
+    from paper_2407_08296_amd import inputs as I
+    from paper_2407_08296_amd import qgalore as qg
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(0)
+    pcache = {}
+    mats = []
+    for (layer, kind, m, n, r) in I.config_matrices(config):
+        if (m, r) not in pcache:
+            P = torch.from_numpy(I.projection_f32(m, r)).to(device)
+            pcache[(m, r)] = qg.quant_int4(P)
+        Pq, Ps = pcache[(m, r)]
+        W = torch.randn((m, n), generator=gen, device=device, dtype=torch.float32) * 0.02
+        Wq, Ws = qg.quant_int8(W)
+        del W
+        A = torch.randn((m, 16), generator=gen, device=device) * 0.01
+        B = torch.randn((n, 16), generator=gen, device=device) * 0.01
+        G = torch.randn((m, n), generator=gen, device=device) * 1e-4
+        G.addmm_(A, B.t())
+        Gb = G.to(torch.bfloat16)
+        del G
+        mats.append(qg.MatrixState(m, n, r, Pq, Ps, Gb, Wq, Ws,
+                                   torch.zeros((r, n), dtype=torch.float32, device=device),
+                                   torch.zeros((r, n), dtype=torch.float32, device=device),
+                                   torch.empty((r, n), dtype=torch.float32, device=device),
+                                   torch.empty((r, n), dtype=torch.bfloat16, device=device)))
+    torch.cuda.synchronize()
+    return mats
+
+
+def cpu_baseline(config: int, shapes):
+    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the workload."""
+    import numpy as np
+
+    from oracle import qgalore as Q
+    from paper_2407_08296_amd import inputs as I
+
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    if config >= 3:
+        sample = [shapes[0]]                       # one attention matrix; the rest is extrapolated by m*n*r
+        note = f"one {shapes[0][0]}x{shapes[0][1]} r={shapes[0][2]} matrix, scaled by sum(m*n*r) to the whole step"
+    elif config == 2:
+        sample = shapes[:7]
+        note = "one layer (7 matrices), scaled by sum(m*n*r) to the whole step"
+    else:
+        sample = shapes
+        note = "the whole step"
+    total = 0.0
+    for i, (m, n, r) in enumerate(sample):
+        Wq, Ws = Q.quant_int8(I.weight_f32(m, n, kind=i))
+        Pq, Ps = Q.quant_int4(I.projection_f32(m, r, kind=i))
+        Gb = I.gradient_bf16(m, n, 1, kind=i)
+        M = np.zeros((r, n)); V = np.zeros((r, n))
+        t0 = time.perf_counter()
+        Q.step(Wq, Ws, Gb, Pq, Ps, M, V, 1, Q.HParams(), seed=0, r=r)
+        total += time.perf_counter() - t0
+    scale = sum(m * n * r for m, n, r in shapes) / sum(m * n * r for m, n, r in sample)
+    return {"value": total * scale * 1e3, "unit": "ms", "cores": int(threads), "kind": "oracle",
+            "sample": note, "sample_seconds": total, "host_cpus": len(os.sched_getaffinity(0))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (the step has no cross-GPU part); use --gpus 1")
+
+    import torch
+
+    from paper_2407_08296_amd import inputs as I
+    from paper_2407_08296_amd import qgalore as qg
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    qg.lib()                                   # fail loudly if the HIP library is not built
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(device)
+
+    shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(args.config)]
+    mats = build_state(args.config, device)
+    plan = qg.StepPlan(mats)
+    hp = qg.hparams()
+    K, W = args.steps, args.warmup
+
+    t = 0
+    for _ in range(W):
+        t += 1
+        qg.step_many(plan, hp, 0, t)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        t += 1
+        ev[k][0].record()
+        qg.project_many(plan)
+        ev[k][1].record()
+        qg.lowrank_adam_many(plan, hp, t)
+        ev[k][2].record()
+        qg.backproject_update_sr_many(plan, hp, 0, t)
+        ev[k][3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / K
+
+    dur = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)) / K for i in range(3)]   # ms per launch
+    flops, b_proj, b_adam, b_bp = algorithmic_work(shapes)
+    kernels = {
+        "project": {"ms": dur[0], "TFLOP/s": flops / dur[0] / 1e9, "frac_mfma": flops / dur[0] / 1e9 / PEAK_BF16_TFLOPS,
+                    "GB/s": b_proj / dur[0] / 1e6},
+        "lowrank_adam": {"ms": dur[1], "GB/s": b_adam / dur[1] / 1e6, "frac_hbm": b_adam / dur[1] / 1e6 / PEAK_HBM_GBS},
+        "backproject_update_sr": {"ms": dur[2], "TFLOP/s": flops / dur[2] / 1e9,
+                                  "frac_mfma": flops / dur[2] / 1e9 / PEAK_BF16_TFLOPS, "GB/s": b_bp / dur[2] / 1e6},
+    }
+    dom = max(range(3), key=lambda i: dur[i])
+    if dom == 1:
+        roofline = {"kernel": "k_lowrank_adam_many", "bound": "hbm", "achieved": kernels["lowrank_adam"]["GB/s"],
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": kernels["lowrank_adam"]["frac_hbm"], "traffic": None}
+    else:
+        name = "project" if dom == 0 else "backproject_update_sr"
+        roofline = {"kernel": "k_project_many" if dom == 0 else "k_backproject_many", "bound": "mfma",
+                    "achieved": kernels[name]["TFLOP/s"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": kernels[name]["frac_mfma"], "traffic": None}
+
+    out = {
+        "metric": "qgalore_step_ms_all_linear_weights", "value": ms_per_step, "unit": "ms", "n_gpus": 1,
+        "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "launches_per_step": 3},
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        del plan, mats
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(args.config, shapes)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

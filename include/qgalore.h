@@ -1,0 +1,182 @@
+/*
+ * libqgalore - the per-weight-matrix Q-GaLore optimizer step for AMD MI355X (gfx950).
+ *
+ * C ABI.  Conventions that hold for every entry point unless stated otherwise:
+ *
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *    never allocates, frees or retains device memory; scratch space is passed
+ *    in as `workspace` (size from the matching *_workspace_bytes query).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue work and return WITHOUT synchronising.
+ *  - All matrices are dense row-major with leading dimension = row length.
+ *    Base pointers must be 16-byte aligned (QG_ERR_ALIGN otherwise).
+ *  - Notation (the paper's): W is the m x n weight, G the m x n gradient,
+ *    P the m x r projection matrix, R = P^T G (r x n), M and V the Adam moments
+ *    (r x n), N the Adam direction (r x n), U = alpha P N (m x n), t the 1-based
+ *    step count.
+ *  - `group` is the quantization block size; only 256 (the paper's value,
+ *    Sec. 3.1) is accepted, anything else returns QG_ERR_GROUP.
+ *  - INT8 weight format: codes int8 [m][n]; one fp32 scale per block of 256
+ *    consecutive elements OF A ROW, scales [m][ceil(n/256)] (a row's last block
+ *    is short when n % 256 != 0).  Symmetric: zero point 0, scale = absmax/127.
+ *  - INT4 projection format: block = 256 consecutive elements of the FLATTENED
+ *    row-major m x r array, scales [ceil(m*r/256)], scale = absmax/7.  Two
+ *    codes per byte, flat element 2b in the low nibble of byte b, stored
+ *    nibble = code + 8.
+ *  - bf16 tensors are passed as uint16_t bit patterns.
+ *  - Return value: QG_OK or a QG_ERR_* code.  Arguments are validated before
+ *    any HIP call, so argument errors are reported even with no GPU present.
+ *    After QG_ERR_HIP, qg_last_hip_error() returns the hipError_t value.
+ */
+#ifndef QGALORE_H
+#define QGALORE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    QG_OK = 0,
+    QG_ERR_NULL = 1,       /* a required pointer is NULL */
+    QG_ERR_SHAPE = 2,      /* m, n, r, count, step out of range (see each call) */
+    QG_ERR_GROUP = 3,      /* group != 256 */
+    QG_ERR_ALIGN = 4,      /* a base pointer is not 16-byte aligned */
+    QG_ERR_WORKSPACE = 5,  /* workspace missing or too small */
+    QG_ERR_HIP = 6         /* a HIP call or kernel launch failed */
+};
+
+/* Adam and GaLore hyper-parameters (Sec. 4.1: Adam as the inner optimizer,
+ * scale factor alpha = 0.25). */
+typedef struct {
+    float beta1, beta2, eps, lr, alpha;
+} qg_hparams;
+
+/* Per-layer state of the adaptive lazy subspace update (Sec. 3.2). */
+typedef struct {
+    int interval;      /* current refresh interval t (steps) */
+    int streak;        /* consecutive checks with cos >= threshold */
+    int k;             /* checks in a row required before the interval doubles */
+    int next_refresh;  /* step at which the next refresh is due */
+    float threshold;   /* 0.4 in the paper */
+    float last_cos;
+} qg_policy;
+
+/* One matrix of a grouped step (qg_step_many).  All pointers are device
+ * pointers with the layouts of the single-matrix calls. */
+typedef struct {
+    int64_t m, n, r;
+    const uint8_t*  Pq;   /* INT4 P, packed            */
+    const float*    Ps;   /* INT4 P block scales        */
+    const uint16_t* G;    /* bf16 gradient m x n        */
+    int8_t*         Wq;   /* INT8 weight codes, in/out  */
+    float*          Ws;   /* INT8 weight scales, in/out */
+    float*          M;    /* first moment r x n, in/out */
+    float*          V;    /* second moment r x n, in/out*/
+    float*          R;    /* projected gradient r x n, out (scratch the caller may inspect) */
+    uint16_t*       N;    /* bf16 Adam direction r x n, out */
+} qg_matrix_desc;
+
+const char* qg_status_string(int status);
+int qg_last_hip_error(void);
+
+/* ---- Block-wise uniform quantization, Quant_n of Sec. 3.1 (z = 0, s = absmax/qmax,
+ * code = clamp(round_half_even(fl32(x * fl32(qmax/absmax))), -2^(n-1), 2^(n-1)-1)).
+ * A block whose absmax is 0 gets scale 0 and codes 0.
+ * qg_quant_int8: x fp32 [rows][cols] -> q int8 [rows][cols], scales [rows][ceil(cols/256)].
+ * qg_quant_int4: x fp32 [rows][cols] -> q_packed uint8 [ceil(rows*cols/2)], scales [ceil(rows*cols/256)].
+ * Errors: NULL pointer, rows/cols <= 0 (or rows*cols >= 2^40), group, alignment. */
+int qg_quant_int8(const float* x, int64_t rows, int64_t cols, int group,
+                  int8_t* q, float* scales, void* stream);
+int qg_quant_int4(const float* x, int64_t rows, int64_t cols, int group,
+                  uint8_t* q_packed, float* scales, void* stream);
+
+/* ---- Dequantization, W = W_q * s (Appendix A with zeros = 0); fp32 out [rows][cols]. */
+int qg_dequant_int8(const int8_t* q, const float* scales, int64_t rows, int64_t cols, int group,
+                    float* x, void* stream);
+int qg_dequant_int4(const uint8_t* q_packed, const float* scales, int64_t rows, int64_t cols, int group,
+                    float* x, void* stream);
+
+/* ---- Gradient projection (Sec. 3.5): R = dequant(P)^T G.
+ * P is dequantized inside the GEMM: code*scale in fp32, rounded once to bf16;
+ * bf16 MFMA with fp32 accumulation; R fp32 [r][n] is overwritten.
+ * Requires 1 <= r <= m, r % 8 == 0, m*n < 2^32.  workspace may be NULL (unused
+ * by the current kernels; qg_workspace_bytes reports 0 for this call). */
+int qg_project(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
+               int64_t m, int64_t n, int64_t r, int group,
+               float* R, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- Adam on the low-rank gradient (Sec. 3.5; Adam of Sec. 4.1), element-wise over
+ * count = r*n elements:  M <- b1 M + (1-b1) R;  V <- b2 V + (1-b2) R^2;
+ * N = bf16( (M/(1-b1^t)) / (sqrt(V/(1-b2^t)) + eps) ).  M, V updated in place (fp32).
+ * step = t >= 1.  R may not alias M, V or N. */
+int qg_lowrank_adam(const float* R, float* M, float* V, uint16_t* N_bf16,
+                    int64_t count, int64_t step, const qg_hparams* hp, void* stream);
+
+/* ---- Back-projection and INT8 weight update with stochastic rounding
+ * (Sec. 3.4, Sec. 3.5):  U = alpha * dequant(P) * N;  x = W_q*s - lr*U;  per block
+ * of 256 of each row a = max|x|, s' = a/127, code' = clamp(floor(x*(127/a) + u), -128, 127)
+ * with u = 2^-24 * (hash32(seed, step, i*n+j) >> 8).  Wq and Ws are updated in
+ * place.  U_debug (nullable) receives U as fp32 [m][n] for parity checks.
+ * Requires r % 8 == 0, r <= m, m*n < 2^32. */
+int qg_backproject_update_sr(const uint8_t* Pq, const float* Ps, const uint16_t* N_bf16,
+                             int8_t* Wq, float* Ws, int64_t m, int64_t n, int64_t r, int group,
+                             float alpha, float lr, uint64_t seed, int64_t step,
+                             float* U_debug, void* stream);
+
+/* ---- Subspace convergence check (Sec. 3.2, Fig. 2): mean over the r columns of
+ * the cosine between column k of dequant(PA) and of dequant(PB).  cos_out is one
+ * device float.  workspace: at least qg_cossim_workspace_bytes(m, r) bytes. */
+size_t qg_cossim_workspace_bytes(int64_t m, int64_t r);
+int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB, const float* PsB,
+                       int64_t m, int64_t r, int group, float* cos_out,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- Adaptive lazy update policy (Sec. 3.2), HOST ONLY (p is a host pointer):
+ * streak counts consecutive checks with cos >= threshold; at k in a row the
+ * interval doubles and the streak restarts; next_refresh advances by the
+ * (possibly doubled) interval.  Returns 1 if the interval doubled, 0 if not,
+ * -1 if p is NULL. */
+int qg_policy_update(qg_policy* p, float cos);
+
+/* ---- One full step on one matrix (Sec. 3.5): project -> Adam -> back-project +
+ * SR update, three kernels on `stream`.  R and N are caller-provided outputs
+ * (r x n fp32 / bf16).  No subspace refresh happens inside. */
+size_t qg_workspace_bytes(int64_t m, int64_t n, int64_t r);
+int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
+            int8_t* Wq, float* Ws, float* M, float* V, float* R, uint16_t* N_bf16,
+            int64_t m, int64_t n, int64_t r, int group,
+            const qg_hparams* hp, uint64_t seed, int64_t step,
+            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- Grouped step over many matrices (the whole model's linear weights) in
+ * three grouped launches.  `descs` is a HOST array of `count` descriptors.
+ * The library needs a device-resident launch plan: the caller provides
+ * `plan_host` (host scratch) and `plan_dev` (device memory), each of
+ * qg_plan_bytes(count, descs) bytes; qg_plan_build fills plan_host, the
+ * caller copies it to plan_dev (any memcpy), and qg_step_many uses both.
+ * Matrix i draws its SR numbers with seed + i * 0x9E3779B97F4A7C15 (mod 2^64). */
+size_t qg_plan_bytes(int count, const qg_matrix_desc* descs);
+int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_host, size_t plan_bytes);
+int qg_step_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
+                 const qg_hparams* hp, uint64_t seed, int64_t step, void* stream);
+
+/* The three grouped launches of qg_step_many, one by one (same plan arguments):
+ * projection of every matrix, Adam over every matrix, back-projection + SR update
+ * of every matrix.  qg_step_many(...) == these three in this order. */
+int qg_project_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes, void* stream);
+int qg_lowrank_adam_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
+                         const qg_hparams* hp, int64_t step, void* stream);
+int qg_backproject_update_sr_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
+                                  const qg_hparams* hp, uint64_t seed, int64_t step, void* stream);
+
+/* ---- Test helper: out[i] = u(seed, step, idx0 + i) for i < count, the uniform
+ * draws of the stochastic-rounding generator, as fp32. */
+int qg_sr_uniform(uint64_t seed, int64_t step, uint64_t idx0, int64_t count, float* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QGALORE_H */

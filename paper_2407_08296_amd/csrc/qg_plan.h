@@ -1,0 +1,52 @@
+// Launch plan of the grouped step: a flat blob (header + one record per matrix)
+// built on the host, copied to the device by the caller, read by the grouped kernels.
+#pragma once
+
+#include <stdint.h>
+
+#include "qgalore.h"
+
+namespace qg {
+
+constexpr uint32_t kPlanMagic = 0x51474C50u;  // "QGLP"
+
+// Tile shapes of the grouped GEMM launches (must match the kernel instantiations).
+constexpr int kManyProjBM = 256;  // rows of R (r) per tile
+constexpr int kManyProjBN = 256;  // columns of R (n) per tile
+constexpr int kManyBpBM = 256;    // rows of W (m) per tile
+constexpr int kManyBpBN = 256;    // columns of W (n) per tile = one quantization block per row
+
+struct PlanMatrix {
+    int64_t m, n, r;
+    const uint8_t* Pq;
+    const float* Ps;
+    const uint16_t* G;
+    int8_t* Wq;
+    float* Ws;
+    float* M;
+    float* V;
+    float* R;
+    uint16_t* N;
+    uint32_t adam_chunk0;   // first Adam chunk (workgroup) of this matrix
+    uint32_t proj_tile0;    // first projection tile
+    uint32_t bp_tile0;      // first back-projection tile
+    uint32_t proj_tiles_r;  // tiles along r of the projection
+    uint32_t bp_tiles_m;    // tiles along m of the back-projection
+    uint32_t pad_;
+};
+
+struct PlanHeader {
+    uint32_t magic;
+    int32_t count;
+    uint32_t adam_chunks;
+    uint32_t proj_tiles;
+    uint32_t bp_tiles;
+    uint32_t ragged;        // 1 if any matrix needs the bounds-checked kernels
+    uint32_t pad_[2];
+};
+
+__host__ __device__ inline const PlanMatrix* plan_matrices(const PlanHeader* h) {
+    return reinterpret_cast<const PlanMatrix*>(h + 1);
+}
+
+}  // namespace qg

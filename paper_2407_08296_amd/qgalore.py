@@ -1,0 +1,258 @@
+"""ctypes binding of libqgalore.so: argument marshalling only.
+
+Every function has the name and argument order of the C entry point it wraps
+(see include/qgalore.h) minus the `qg_` prefix.  Tensors are torch CUDA(HIP)
+tensors used purely as device-memory handles; all arithmetic happens in the
+library's kernels.  There is no CPU fallback: if the shared library has not
+been built, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqgalore.so")
+GROUP = 256
+
+EXPORTS = [
+    "qg_status_string", "qg_last_hip_error", "qg_quant_int8", "qg_quant_int4", "qg_dequant_int8", "qg_dequant_int4",
+    "qg_project", "qg_lowrank_adam", "qg_backproject_update_sr", "qg_cossim_workspace_bytes", "qg_subspace_cossim",
+    "qg_policy_update", "qg_workspace_bytes", "qg_step", "qg_plan_bytes", "qg_plan_build", "qg_step_many",
+    "qg_sr_uniform", "qg_project_many", "qg_lowrank_adam_many", "qg_backproject_update_sr_many",
+]
+
+
+class QGError(RuntimeError):
+    pass
+
+
+class HParams(C.Structure):
+    _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("lr", C.c_float),
+                ("alpha", C.c_float)]
+
+
+class Policy(C.Structure):
+    _fields_ = [("interval", C.c_int), ("streak", C.c_int), ("k", C.c_int), ("next_refresh", C.c_int),
+                ("threshold", C.c_float), ("last_cos", C.c_float)]
+
+
+class MatrixDesc(C.Structure):
+    _fields_ = [("m", C.c_int64), ("n", C.c_int64), ("r", C.c_int64),
+                ("Pq", C.c_void_p), ("Ps", C.c_void_p), ("G", C.c_void_p), ("Wq", C.c_void_p), ("Ws", C.c_void_p),
+                ("M", C.c_void_p), ("V", C.c_void_p), ("R", C.c_void_p), ("N", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libqgalore.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise QGError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_08296_amd.build` "
+                          "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        i64, vp, i32, u64, f32, sz = C.c_int64, C.c_void_p, C.c_int, C.c_uint64, C.c_float, C.c_size_t
+        L.qg_status_string.restype = C.c_char_p
+        L.qg_status_string.argtypes = [i32]
+        L.qg_last_hip_error.restype = i32
+        L.qg_quant_int8.argtypes = [vp, i64, i64, i32, vp, vp, vp]
+        L.qg_quant_int4.argtypes = [vp, i64, i64, i32, vp, vp, vp]
+        L.qg_dequant_int8.argtypes = [vp, vp, i64, i64, i32, vp, vp]
+        L.qg_dequant_int4.argtypes = [vp, vp, i64, i64, i32, vp, vp]
+        L.qg_project.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, sz, vp]
+        L.qg_lowrank_adam.argtypes = [vp, vp, vp, vp, i64, i64, C.POINTER(HParams), vp]
+        L.qg_backproject_update_sr.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, f32, f32, u64, i64, vp, vp]
+        L.qg_cossim_workspace_bytes.restype = sz
+        L.qg_cossim_workspace_bytes.argtypes = [i64, i64]
+        L.qg_subspace_cossim.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, sz, vp]
+        L.qg_policy_update.argtypes = [C.POINTER(Policy), f32]
+        L.qg_workspace_bytes.restype = sz
+        L.qg_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qg_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, C.POINTER(HParams), u64, i64,
+                              vp, sz, vp]
+        L.qg_plan_bytes.restype = sz
+        L.qg_plan_bytes.argtypes = [i32, C.POINTER(MatrixDesc)]
+        L.qg_plan_build.argtypes = [i32, C.POINTER(MatrixDesc), vp, sz]
+        L.qg_step_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), u64, i64, vp]
+        L.qg_sr_uniform.argtypes = [u64, i64, u64, i64, vp, vp]
+        L.qg_project_many.argtypes = [i32, vp, vp, sz, vp]
+        L.qg_lowrank_adam_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), i64, vp]
+        L.qg_backproject_update_sr_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), u64, i64, vp]
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        L = lib()
+        msg = L.qg_status_string(status).decode()
+        if status == 6:
+            msg += f" (hipError {L.qg_last_hip_error()})"
+        raise QGError(f"libqgalore: {msg}")
+
+
+def _ptr(t: torch.Tensor | None, dtypes=None) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise QGError("device tensor expected")
+    if not t.is_contiguous():
+        raise QGError("contiguous tensor expected")
+    if dtypes is not None and t.dtype not in dtypes:
+        raise QGError(f"dtype {t.dtype} not in {dtypes}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+_BF16 = (torch.bfloat16, torch.int16, torch.uint16)
+
+
+def hparams(beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=0.25) -> HParams:
+    return HParams(beta1, beta2, eps, lr, alpha)
+
+
+# ---------------------------------------------------------------- quantizers
+def quant_int8(x: torch.Tensor):
+    rows, cols = x.shape
+    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device)
+    s = torch.empty((rows, (cols + GROUP - 1) // GROUP), dtype=torch.float32, device=x.device)
+    _check(lib().qg_quant_int8(_ptr(x, (torch.float32,)), rows, cols, GROUP, _ptr(q), _ptr(s), _stream()))
+    return q, s
+
+
+def quant_int4(x: torch.Tensor):
+    rows, cols = x.shape
+    total = rows * cols
+    q = torch.empty(((total + 1) // 2,), dtype=torch.uint8, device=x.device)
+    s = torch.empty(((total + GROUP - 1) // GROUP,), dtype=torch.float32, device=x.device)
+    _check(lib().qg_quant_int4(_ptr(x, (torch.float32,)), rows, cols, GROUP, _ptr(q), _ptr(s), _stream()))
+    return q, s
+
+
+def dequant_int8(q: torch.Tensor, s: torch.Tensor) -> torch.Tensor:
+    rows, cols = q.shape
+    x = torch.empty((rows, cols), dtype=torch.float32, device=q.device)
+    _check(lib().qg_dequant_int8(_ptr(q, (torch.int8,)), _ptr(s, (torch.float32,)), rows, cols, GROUP, _ptr(x),
+                                 _stream()))
+    return x
+
+
+def dequant_int4(q: torch.Tensor, s: torch.Tensor, rows: int, cols: int) -> torch.Tensor:
+    x = torch.empty((rows, cols), dtype=torch.float32, device=q.device)
+    _check(lib().qg_dequant_int4(_ptr(q, (torch.uint8,)), _ptr(s, (torch.float32,)), rows, cols, GROUP, _ptr(x),
+                                 _stream()))
+    return x
+
+
+# ---------------------------------------------------------------- step pieces
+def project(Pq, Ps, G, m: int, n: int, r: int, R: torch.Tensor | None = None) -> torch.Tensor:
+    if R is None:
+        R = torch.empty((r, n), dtype=torch.float32, device=G.device)
+    _check(lib().qg_project(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(G, _BF16), m, n, r, GROUP,
+                            _ptr(R, (torch.float32,)), None, 0, _stream()))
+    return R
+
+
+def lowrank_adam(R, M, V, N, step: int, hp: HParams) -> None:
+    _check(lib().qg_lowrank_adam(_ptr(R, (torch.float32,)), _ptr(M, (torch.float32,)), _ptr(V, (torch.float32,)),
+                                 _ptr(N, _BF16), R.numel(), step, C.byref(hp), _stream()))
+
+
+def backproject_update_sr(Pq, Ps, N, Wq, Ws, m: int, n: int, r: int, alpha: float, lr: float, seed: int, step: int,
+                          U_debug: torch.Tensor | None = None) -> None:
+    _check(lib().qg_backproject_update_sr(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(N, _BF16),
+                                          _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)), m, n, r, GROUP,
+                                          alpha, lr, seed, step, _ptr(U_debug, (torch.float32,)), _stream()))
+
+
+def subspace_cossim(PqA, PsA, PqB, PsB, m: int, r: int) -> torch.Tensor:
+    nbytes = lib().qg_cossim_workspace_bytes(m, r)
+    ws = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=PqA.device)
+    out = torch.empty((1,), dtype=torch.float32, device=PqA.device)
+    _check(lib().qg_subspace_cossim(_ptr(PqA, (torch.uint8,)), _ptr(PsA, (torch.float32,)), _ptr(PqB, (torch.uint8,)),
+                                    _ptr(PsB, (torch.float32,)), m, r, GROUP, _ptr(out), _ptr(ws), nbytes, _stream()))
+    return out
+
+
+def policy_update(p: Policy, cos: float) -> bool:
+    rc = lib().qg_policy_update(C.byref(p), cos)
+    if rc < 0:
+        raise QGError("libqgalore: null policy")
+    return bool(rc)
+
+
+def step(Pq, Ps, G, Wq, Ws, M, V, R, N, m: int, n: int, r: int, hp: HParams, seed: int, step: int) -> None:
+    _check(lib().qg_step(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(G, _BF16),
+                         _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)), _ptr(M, (torch.float32,)),
+                         _ptr(V, (torch.float32,)), _ptr(R, (torch.float32,)), _ptr(N, _BF16), m, n, r, GROUP,
+                         C.byref(hp), seed, step, None, 0, _stream()))
+
+
+@dataclass
+class MatrixState:
+    """Device tensors of one weight matrix, as passed to qg_step / qg_step_many."""
+    m: int
+    n: int
+    r: int
+    Pq: torch.Tensor
+    Ps: torch.Tensor
+    G: torch.Tensor
+    Wq: torch.Tensor
+    Ws: torch.Tensor
+    M: torch.Tensor
+    V: torch.Tensor
+    R: torch.Tensor
+    N: torch.Tensor
+
+
+class StepPlan:
+    """Host + device copies of the grouped-launch plan of qg_step_many."""
+
+    def __init__(self, mats: list[MatrixState]):
+        self.count = len(mats)
+        self.mats = mats
+        descs = (MatrixDesc * self.count)()
+        for d, s in zip(descs, mats):
+            d.m, d.n, d.r = s.m, s.n, s.r
+            d.Pq, d.Ps, d.G = _ptr(s.Pq, (torch.uint8,)), _ptr(s.Ps, (torch.float32,)), _ptr(s.G, _BF16)
+            d.Wq, d.Ws = _ptr(s.Wq, (torch.int8,)), _ptr(s.Ws, (torch.float32,))
+            d.M, d.V, d.R = _ptr(s.M, (torch.float32,)), _ptr(s.V, (torch.float32,)), _ptr(s.R, (torch.float32,))
+            d.N = _ptr(s.N, _BF16)
+        self.nbytes = lib().qg_plan_bytes(self.count, descs)
+        self.host = torch.empty((self.nbytes,), dtype=torch.uint8).pin_memory()
+        _check(lib().qg_plan_build(self.count, descs, self.host.data_ptr(), self.nbytes))
+        self.dev = self.host.to(mats[0].Wq.device)
+
+
+def step_many(plan: StepPlan, hp: HParams, seed: int, step: int) -> None:
+    _check(lib().qg_step_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes, C.byref(hp), seed,
+                              step, _stream()))
+
+
+def project_many(plan: StepPlan) -> None:
+    _check(lib().qg_project_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes, _stream()))
+
+
+def lowrank_adam_many(plan: StepPlan, hp: HParams, step: int) -> None:
+    _check(lib().qg_lowrank_adam_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
+                                      C.byref(hp), step, _stream()))
+
+
+def backproject_update_sr_many(plan: StepPlan, hp: HParams, seed: int, step: int) -> None:
+    _check(lib().qg_backproject_update_sr_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
+                                               C.byref(hp), seed, step, _stream()))
+
+
+def sr_uniform(seed: int, step: int, idx0: int, count: int, device="cuda") -> torch.Tensor:
+    out = torch.empty((count,), dtype=torch.float32, device=device)
+    _check(lib().qg_sr_uniform(seed, step, idx0, count, _ptr(out), _stream()))
+    return out

@@ -1,0 +1,110 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, rejects bad arguments before any HIP call, and the host-only policy matches Sec. 3.2."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2407_08296_amd import qgalore as qg
+from oracle import qgalore as Q
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(__file__)), "include", "qgalore.h")
+FAKE = 0x10000          # non-null, 16-byte aligned, never dereferenced on the error paths
+
+
+@pytest.fixture(scope="module")
+def L():
+    return qg.lib()
+
+
+def test_header_symbols_are_exported(L):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(qg_[a-z0-9_]+)\s*\(", text))
+    assert names == set(qg.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings(L):
+    assert L.qg_status_string(0) == b"ok"
+    for code in range(1, 7):
+        assert len(L.qg_status_string(code)) > 0
+
+
+def test_quant_argument_errors(L):
+    assert L.qg_quant_int8(None, 4, 256, 256, FAKE, FAKE, None) == 1
+    assert L.qg_quant_int8(FAKE, 0, 256, 256, FAKE, FAKE, None) == 2
+    assert L.qg_quant_int8(FAKE, 4, -1, 256, FAKE, FAKE, None) == 2
+    assert L.qg_quant_int8(FAKE, 4, 256, 128, FAKE, FAKE, None) == 3
+    assert L.qg_quant_int8(FAKE + 4, 4, 256, 256, FAKE, FAKE, None) == 4
+    assert L.qg_quant_int4(FAKE, 4, 256, 256, None, FAKE, None) == 1
+    assert L.qg_quant_int4(FAKE, 4, 256, 64, FAKE, FAKE, None) == 3
+    assert L.qg_dequant_int4(FAKE, FAKE, 4, 256, 256, FAKE + 8, None) == 4
+    assert L.qg_dequant_int8(FAKE, None, 4, 256, 256, FAKE, None) == 1
+
+
+def test_step_piece_argument_errors(L):
+    hp = qg.hparams()
+    assert L.qg_project(None, FAKE, FAKE, 512, 512, 128, 256, FAKE, None, 0, None) == 1
+    assert L.qg_project(FAKE, FAKE, FAKE, 512, 512, 0, 256, FAKE, None, 0, None) == 2
+    assert L.qg_project(FAKE, FAKE, FAKE, 512, 512, 127, 256, FAKE, None, 0, None) == 2      # r % 8 != 0
+    assert L.qg_project(FAKE, FAKE, FAKE, 64, 512, 128, 256, FAKE, None, 0, None) == 2       # r > m
+    assert L.qg_project(FAKE, FAKE, FAKE, 1 << 17, 1 << 17, 128, 256, FAKE, None, 0, None) == 2   # m*n >= 2^32
+    assert L.qg_project(FAKE, FAKE, FAKE, 512, 512, 128, 512, FAKE, None, 0, None) == 3
+    assert L.qg_project(FAKE, FAKE, FAKE + 2, 512, 512, 128, 256, FAKE, None, 0, None) == 4
+    assert L.qg_lowrank_adam(FAKE, FAKE, FAKE, FAKE, 100, 0, C.byref(hp), None) == 2        # t >= 1
+    assert L.qg_lowrank_adam(FAKE, FAKE, FAKE, FAKE, 100, 1, None, None) == 1
+    assert L.qg_lowrank_adam(FAKE, FAKE, FAKE, FAKE, 0, 1, C.byref(hp), None) == 2
+    assert L.qg_backproject_update_sr(FAKE, FAKE, FAKE, FAKE, None, 512, 512, 128, 256, 0.25, 1e-3, 0, 1, None, None) == 1
+    assert L.qg_backproject_update_sr(FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 128, 256, 0.25, 1e-3, 0, 0, None, None) == 2
+    assert L.qg_backproject_update_sr(FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 128, 256, 0.25, 1e-3, 0, 1, FAKE + 4, None) == 4
+    assert L.qg_subspace_cossim(FAKE, FAKE, FAKE, FAKE, 512, 128, 256, FAKE, None, 0, None) == 5
+    assert L.qg_subspace_cossim(FAKE, FAKE, FAKE, FAKE, 512, 128, 256, FAKE, FAKE, 16, None) == 5
+    assert L.qg_subspace_cossim(FAKE, FAKE, FAKE, FAKE, 512, 130, 256, FAKE, FAKE, 1 << 20, None) == 2
+    assert L.qg_cossim_workspace_bytes(512, 128) == 8 * 3 * 128 * 4
+    assert L.qg_step(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 128, 256, None, 0, 1, None, 0, None) == 1
+    assert L.qg_step(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 128, 256, C.byref(hp), 0, 0, None, 0, None) == 2
+    assert L.qg_sr_uniform(0, 1, 0, 0, FAKE, None) == 2
+    assert L.qg_sr_uniform(0, 1, 0, 16, None, None) == 1
+
+
+def test_plan_build_on_host(L):
+    descs = (qg.MatrixDesc * 2)()
+    for d, (m, n, r) in zip(descs, [(4096, 4096, 1024), (11008, 4096, 1024)]):
+        d.m, d.n, d.r = m, n, r
+        for f in ("Pq", "Ps", "G", "Wq", "Ws", "M", "V", "R", "N"):
+            setattr(d, f, FAKE)
+    nbytes = L.qg_plan_bytes(2, descs)
+    assert nbytes > 0
+    buf = C.create_string_buffer(nbytes)
+    assert L.qg_plan_build(2, descs, buf, nbytes - 1) == 5
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 0
+    hdr = (C.c_uint32 * 8).from_buffer(buf)
+    assert hdr[1] == 2                                       # count
+    assert hdr[2] == 2 * (1024 * 4096) // 4096               # Adam chunks of 4096 elements
+    assert hdr[3] == 2 * 4 * 16                              # projection tiles 256 x 256 over r x n
+    assert hdr[4] == 16 * 16 + 43 * 16                       # back-projection tiles over m x n
+    assert hdr[5] == 0                                       # nothing ragged
+    descs[1].n = 5461
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 0
+    assert (C.c_uint32 * 8).from_buffer(buf)[5] == 1
+    descs[1].r = 12
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 2
+    descs[1].r = 1024
+    descs[0].G = None
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 1
+    hp = qg.hparams()
+    assert L.qg_step_many(2, None, FAKE, nbytes, C.byref(hp), 0, 1, None) == 1
+    assert L.qg_step_many(3, buf, FAKE, nbytes, C.byref(hp), 0, 1, None) == 5
+
+
+def test_policy_matches_oracle_tables(L):
+    for k, seq in [(1, [0.9, 0.1, 0.4, 0.39]), (2, [0.9, 0.9, 0.9, 0.1, 0.9, 0.9]), (3, [0.5, 0.5, 0.3, 0.5, 0.5, 0.5, 0.5])]:
+        p = qg.Policy(200, 0, k, 200, 0.4, 0.0)
+        o = Q.Policy(interval=200, k=k, threshold=0.4, next_refresh=200)
+        for c in seq:
+            assert qg.policy_update(p, c) == o.update(float(C.c_float(c).value))
+            assert (p.interval, p.streak, p.next_refresh) == (o.interval, o.streak, o.next_refresh)
+    assert L.qg_policy_update(None, 0.5) == -1
