@@ -95,12 +95,9 @@ def cpu_baseline(config: int, shapes):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    if config >= 3:
-        sample = [shapes[0]]                       # one attention matrix; the rest is extrapolated by m*n*r
-        note = f"one {shapes[0][0]}x{shapes[0][1]} r={shapes[0][2]} matrix, scaled by sum(m*n*r) to the whole step"
-    elif config == 2:
+    if config >= 2:
         sample = shapes[:7]
-        note = "one layer (7 matrices), scaled by sum(m*n*r) to the whole step"
+        note = "one decoder layer (7 matrices), scaled by sum(m*n*r) to the whole step"
     else:
         sample = shapes
         note = "the whole step"

@@ -1,0 +1,460 @@
+// The two dense contractions of the step (Sec. 3.5) as bf16 MFMA GEMMs with the
+// INT4 -> bf16 dequantization of P fused into LDS tile staging:
+//   project:      R = dequant(P)^T G                      (K = m)
+//   back-project: U = alpha dequant(P) N, followed in registers by the INT8
+//                 stochastic-rounding weight update (Sec. 3.4).
+//
+// MFMA: v_mfma_f32_32x32x16_bf16.  Operand lane l holds row/column (l % 32) and
+// the 8 consecutive k values 8*(l/32)..+7; accumulator register v of lane l is
+// D[8*(v/4) + 4*(l/32) + v%4][l % 32].
+//
+// Operands whose K index is the slow (row) index in memory (P^T and G in the
+// projection, N in the back-projection) are staged K-major in LDS exactly as
+// they sit in HBM and fetched with the LDS transpose read ds_read_b64_tr_b16:
+// inside a group of 16 lanes, lane i receives element (i % 4) of the four lanes
+// 4j + i/4 (j = 0..3); lanes 4j..4j+3 point at 16 consecutive elements of tile
+// row k+j, so lane i ends up with column i of rows k..k+3.
+#pragma once
+
+#include "qg_common.h"
+#include "qg_plan.h"
+
+namespace qg {
+
+constexpr int kPadK = 32;  // bf16 of padding per row of a K-major tile (64 B: rows k..k+3 hit distinct bank groups)
+constexpr int kPadX = 8;   // bf16 of padding per row of a K-contiguous tile (16 B)
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+// Element offset (inside a K-major tile of `pitch` elements per row) of the first
+// transpose read of this lane for the 32-wide operand block at column x0, k-step k0.
+__device__ __forceinline__ int kmajor_lane_offset(int pitch, int lane) {
+    const int g = lane >> 4, s = lane & 15;
+    return (8 * (g >> 1) + (s >> 2)) * pitch + 16 * (g & 1) + 4 * (s & 3);
+}
+
+__device__ __forceinline__ bf16x8 read_kmajor_frag(const uint16_t* p, int pitch) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * pitch));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// 8 consecutive bf16 starting at `src`, guarded per element (ragged shapes).
+__device__ __forceinline__ u32x4 load8_bf16_guarded(const uint16_t* src, int valid, bool vec) {
+    if (valid >= 8 && vec) return *reinterpret_cast<const u32x4*>(src);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j < valid) w[j >> 1] |= (uint32_t)src[j] << (16 * (j & 1));
+    const u32x4 o = {w[0], w[1], w[2], w[3]};
+    return o;
+}
+
+// XCD-aware tile order: consecutive workgroup ids go round-robin over the 8 XCDs
+// (each with its own L2), so XCD x is handed the contiguous range of tiles
+// [x*per, (x+1)*per), and neighbouring tiles (which share operand panels) meet in
+// one L2.  gridDim.x is a multiple of 8.
+__device__ __forceinline__ uint32_t xcd_tile(uint32_t wg, uint32_t grid) {
+    const uint32_t per = grid >> 3;
+    return (wg & 7u) * per + (wg >> 3);
+}
+
+// ============================================================================
+// Projection: R[r0.., n0..] tile of BM x BN, K loop over m in steps of BK.
+// ============================================================================
+template <int BM, int BN, int BK, int WGM, int WGN>
+struct ProjShape {
+    static constexpr int NT = WGM * WGN * 64;
+    static constexpr int PA = BM + kPadK, PB = BN + kPadK;
+    static constexpr int A_STAGE = BK * PA, B_STAGE = BK * PB;
+    static constexpr int SMEM = 2 * (A_STAGE + B_STAGE);  // uint16 elements
+};
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED>
+__device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
+                                             const uint16_t* __restrict__ G, float* __restrict__ R, int m, int n,
+                                             int r, int r0, int n0, uint16_t* smem) {
+    using S = ProjShape<BM, BN, BK, WGM, WGN>;
+    constexpr int NT = S::NT;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MB = WM / 32, NB = WN / 32;
+    constexpr int PA = S::PA, PB = S::PB;
+    constexpr int A_WORDS = BK * BM / 8, A_PER = A_WORDS / NT;
+    constexpr int B_CH = BK * BN / 8, B_PER = B_CH / NT;
+    static_assert(A_WORDS % NT == 0 && B_CH % NT == 0, "staging must divide evenly");
+    static_assert(BK % 16 == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+    uint16_t* As = smem;
+    uint16_t* Bs = smem + 2 * S::A_STAGE;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const bool vec = (n & 7) == 0;
+
+    uint32_t aw[A_PER];
+    float asc[A_PER];
+    u32x4 bv[B_PER];
+
+    auto gload = [&](int kt) {
+        const int i0 = kt * BK;
+#pragma unroll
+        for (int p = 0; p < A_PER; ++p) {
+            const int wi = t + p * NT;
+            const int row = wi / (BM / 8), c8 = wi % (BM / 8);
+            const int64_t e = (int64_t)(i0 + row) * r + r0 + c8 * 8;
+            if (!RAGGED || (i0 + row < m && r0 + c8 * 8 < r)) {
+                aw[p] = *reinterpret_cast<const uint32_t*>(Pq + (e >> 1));
+                asc[p] = Ps[e >> 8];
+            } else {
+                aw[p] = 0x88888888u;
+                asc[p] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < B_PER; ++p) {
+            const int ci = t + p * NT;
+            const int row = ci / (BN / 8), c8 = ci % (BN / 8);
+            const uint16_t* src = G + (int64_t)(i0 + row) * n + n0 + c8 * 8;
+            if (!RAGGED) {
+                bv[p] = *reinterpret_cast<const u32x4*>(src);
+            } else {
+                const int valid = (i0 + row < m) ? (n - (n0 + c8 * 8)) : 0;
+                bv[p] = load8_bf16_guarded(src, valid, vec);
+            }
+        }
+    };
+    auto sstore = [&](int stage) {
+#pragma unroll
+        for (int p = 0; p < A_PER; ++p) {
+            const int wi = t + p * NT;
+            const int row = wi / (BM / 8), c8 = wi % (BM / 8);
+            *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c8 * 8) = dequant8_bf16(aw[p], asc[p]);
+        }
+#pragma unroll
+        for (int p = 0; p < B_PER; ++p) {
+            const int ci = t + p * NT;
+            const int row = ci / (BN / 8), c8 = ci % (BN / 8);
+            *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c8 * 8) = bv[p];
+        }
+    };
+
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    const int a_lane = kmajor_lane_offset(PA, lane) + wm * WM;
+    const int b_lane = kmajor_lane_offset(PB, lane) + wn * WN;
+    const int KT = (m + BK - 1) / BK;
+
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < KT) gload(kt + 1);
+        const uint16_t* Ac = As + cur * S::A_STAGE + a_lane;
+        const uint16_t* Bc = Bs + cur * S::B_STAGE + b_lane;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[MB], bf[NB];
+#pragma unroll
+            for (int a = 0; a < MB; ++a) af[a] = read_kmajor_frag(Ac + kk * 16 * PA + a * 32, PA);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) bf[b] = read_kmajor_frag(Bc + kk * 16 * PB + b * 32, PB);
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+        if (kt + 1 < KT) sstore(cur ^ 1);
+        __syncthreads();
+    }
+
+    const int lcol = lane & 31, lhalf = lane >> 5;
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = r0 + wm * WM + a * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                const int col = n0 + wn * WN + b * 32 + lcol;
+                if (!RAGGED || (row < r && col < n)) R[(int64_t)row * n + col] = acc[a][b][v];
+            }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED>
+__global__ __launch_bounds__(WGM* WGN * 64) void k_project(const uint8_t* __restrict__ Pq,
+                                                           const float* __restrict__ Ps,
+                                                           const uint16_t* __restrict__ G, float* __restrict__ R,
+                                                           int m, int n, int r, uint32_t tiles_r, uint32_t tiles) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= tiles) return;
+    project_tile<BM, BN, BK, WGM, WGN, RAGGED>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
+                                               (int)(tile / tiles_r) * BN, smem);
+}
+
+template <typename F>
+__device__ __forceinline__ int plan_find(const PlanMatrix* mats, int count, uint32_t tile, F first_tile) {
+    int lo = 0, hi = count - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (first_tile(mats[mid]) <= tile) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED>
+__global__ __launch_bounds__(WGM* WGN * 64) void k_project_many(const PlanHeader* __restrict__ plan) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= plan->proj_tiles) return;
+    const PlanMatrix* mats = plan_matrices(plan);
+    const PlanMatrix& d = mats[plan_find(mats, plan->count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
+    const uint32_t local = tile - d.proj_tile0;
+    project_tile<BM, BN, BK, WGM, WGN, RAGGED>(d.Pq, d.Ps, d.G, d.R, (int)d.m, (int)d.n, (int)d.r,
+                                               (int)(local % d.proj_tiles_r) * BM,
+                                               (int)(local / d.proj_tiles_r) * BN, smem);
+}
+
+// ============================================================================
+// Back-projection + INT8 stochastic-rounding update.
+// The MFMA computes the TRANSPOSED tile D = N^T-block x P^T-block, i.e.
+// D[row = n index][col = m index], so that one lane owns ONE weight row (m) and
+// 4-element runs of consecutive columns (n): the per-row block absmax is an
+// in-lane reduction plus one cross-half shuffle and one LDS exchange.
+// Tile: 256 columns of W (exactly one quantization block per row) x BMm rows.
+// ============================================================================
+template <int BMm, int BK, int WGn, int WGm>
+struct BpShape {
+    static constexpr int BNn = kGroup;
+    static constexpr int NT = WGn * WGm * 64;
+    static constexpr int PA = BNn + kPadK;  // N tile, K-major
+    static constexpr int PB = BK + kPadX;   // P tile, [m][k]
+    static constexpr int A_STAGE = BK * PA, B_STAGE = BMm * PB;
+    static constexpr int SMEM = 2 * (A_STAGE + B_STAGE);
+};
+
+template <int BMm, int BK, int WGn, int WGm, bool RAGGED>
+__device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
+                                                 const uint16_t* __restrict__ N, int8_t* __restrict__ Wq,
+                                                 float* __restrict__ Ws, float* __restrict__ Udbg, int m, int n, int r,
+                                                 int m0, int tile_n, float alpha, float lr, uint32_t key,
+                                                 uint16_t* smem) {
+    using S = BpShape<BMm, BK, WGn, WGm>;
+    constexpr int BNn = S::BNn, NT = S::NT;
+    constexpr int SN = BNn / WGn, SM = BMm / WGm, IB = SN / 32, JB = SM / 32;
+    constexpr int PA = S::PA, PB = S::PB;
+    constexpr int A_CH = BK * BNn / 8, A_PER = A_CH / NT;
+    constexpr int B_WORDS = BMm * BK / 8, B_PER = B_WORDS / NT;
+    static_assert(A_CH % NT == 0 && B_WORDS % NT == 0, "staging must divide evenly");
+    static_assert(WGn * BMm * 4 <= S::SMEM * 2, "row-max exchange must fit in the staging buffers");
+    uint16_t* As = smem;
+    uint16_t* Bs = smem + 2 * S::A_STAGE;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wn = wave / WGm, wm = wave % WGm;
+    const int n0 = tile_n * BNn;
+    const int ng = (n + kGroup - 1) / kGroup;
+    const bool vec8 = (n & 7) == 0, vec4 = (n & 3) == 0;
+
+    u32x4 av[A_PER];
+    uint32_t bw[B_PER];
+    float bsc[B_PER];
+
+    auto gload = [&](int kt) {
+        const int k0 = kt * BK;
+#pragma unroll
+        for (int p = 0; p < A_PER; ++p) {
+            const int ci = t + p * NT;
+            const int row = ci / (BNn / 8), c8 = ci % (BNn / 8);
+            const uint16_t* src = N + (int64_t)(k0 + row) * n + n0 + c8 * 8;
+            if (!RAGGED) {
+                av[p] = *reinterpret_cast<const u32x4*>(src);
+            } else {
+                const int valid = (k0 + row < r) ? (n - (n0 + c8 * 8)) : 0;
+                av[p] = load8_bf16_guarded(src, valid, vec8);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < B_PER; ++p) {
+            const int wi = t + p * NT;
+            const int row = wi / (BK / 8), c8 = wi % (BK / 8);
+            const int64_t e = (int64_t)(m0 + row) * r + k0 + c8 * 8;
+            if (!RAGGED || (m0 + row < m && k0 + c8 * 8 < r)) {
+                bw[p] = *reinterpret_cast<const uint32_t*>(Pq + (e >> 1));
+                bsc[p] = Ps[e >> 8];
+            } else {
+                bw[p] = 0x88888888u;
+                bsc[p] = 0.f;
+            }
+        }
+    };
+    auto sstore = [&](int stage) {
+#pragma unroll
+        for (int p = 0; p < A_PER; ++p) {
+            const int ci = t + p * NT;
+            const int row = ci / (BNn / 8), c8 = ci % (BNn / 8);
+            *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c8 * 8) = av[p];
+        }
+#pragma unroll
+        for (int p = 0; p < B_PER; ++p) {
+            const int wi = t + p * NT;
+            const int row = wi / (BK / 8), c8 = wi % (BK / 8);
+            *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c8 * 8) = dequant8_bf16(bw[p], bsc[p]);
+        }
+    };
+
+    f32x16 acc[IB][JB];
+#pragma unroll
+    for (int a = 0; a < IB; ++a)
+#pragma unroll
+        for (int b = 0; b < JB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int a_lane = kmajor_lane_offset(PA, lane) + wn * SN;
+    const int b_lane = (wm * SM + lrow) * PB + 8 * lhalf;
+    const int KT = (r + BK - 1) / BK;
+
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < KT) gload(kt + 1);
+        const uint16_t* Ac = As + cur * S::A_STAGE + a_lane;
+        const uint16_t* Bc = Bs + cur * S::B_STAGE + b_lane;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[IB], bf[JB];
+#pragma unroll
+            for (int a = 0; a < IB; ++a) af[a] = read_kmajor_frag(Ac + kk * 16 * PA + a * 32, PA);
+#pragma unroll
+            for (int b = 0; b < JB; ++b)
+                bf[b] = *reinterpret_cast<const bf16x8*>(Bc + b * 32 * PB + kk * 16);
+#pragma unroll
+            for (int a = 0; a < IB; ++a)
+#pragma unroll
+                for (int b = 0; b < JB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+        if (kt + 1 < KT) sstore(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: x = Wq*s - lr*U in place of the accumulators, per-row block absmax ----
+    float* smax = reinterpret_cast<float*>(smem);  // [WGn][BMm]; staging buffers are free after the last barrier
+    float rowmax[JB];
+#pragma unroll
+    for (int b = 0; b < JB; ++b) {
+        const int mrow = m0 + wm * SM + b * 32 + lrow;
+        const bool row_ok = !RAGGED || mrow < m;
+        const float s_old = row_ok ? Ws[(int64_t)mrow * ng + tile_n] : 0.f;
+        float mx = 0.f;
+#pragma unroll
+        for (int a = 0; a < IB; ++a)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int ncol = n0 + wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
+                const int64_t off = (int64_t)mrow * n + ncol;
+                int code[4];
+                if (!RAGGED || (row_ok && vec4 && ncol + 4 <= n)) {
+                    const uint32_t w = *reinterpret_cast<const uint32_t*>(Wq + off);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) code[e] = (int)(int8_t)(w >> (8 * e));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) code[e] = (row_ok && ncol + e < n) ? (int)Wq[off + e] : 0;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float u = alpha * acc[a][b][4 * v4 + e];
+                    const bool ok = !RAGGED || (row_ok && ncol + e < n);
+                    if (Udbg != nullptr && ok) Udbg[off + e] = u;
+                    const float x = ok ? __builtin_fmaf(-lr, u, (float)code[e] * s_old) : 0.f;
+                    acc[a][b][4 * v4 + e] = x;
+                    mx = fmaxf(mx, fabsf(x));
+                }
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        rowmax[b] = mx;
+        if (WGn > 1 && lhalf == 0) smax[wn * BMm + wm * SM + b * 32 + lrow] = mx;
+    }
+    if (WGn > 1) __syncthreads();
+
+    // ---- new scale, stochastic rounding, store ----
+#pragma unroll
+    for (int b = 0; b < JB; ++b) {
+        const int mrow = m0 + wm * SM + b * 32 + lrow;
+        const bool row_ok = !RAGGED || mrow < m;
+        float amax = rowmax[b];
+        if (WGn > 1) {
+#pragma unroll
+            for (int w = 0; w < WGn; ++w) amax = fmaxf(amax, smax[w * BMm + wm * SM + b * 32 + lrow]);
+        }
+        const float s_new = amax > 0.f ? amax / 127.0f : 0.f;
+        const float inv = amax > 0.f ? 127.0f / amax : 0.f;
+        if (wn == 0 && lhalf == 0 && row_ok) Ws[(int64_t)mrow * ng + tile_n] = s_new;
+#pragma unroll
+        for (int a = 0; a < IB; ++a)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int ncol = n0 + wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
+                const int64_t off = (int64_t)mrow * n + ncol;
+                uint32_t pk = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float tq = acc[a][b][4 * v4 + e] * inv;
+                    const float uu = sr_uniform(key, (uint32_t)(off + e));
+                    const float q = fminf(fmaxf(floorf(tq + uu), -128.f), 127.f);
+                    pk |= ((uint32_t)(int)q & 0xFFu) << (8 * e);
+                }
+                if (!RAGGED || (row_ok && vec4 && ncol + 4 <= n)) {
+                    *reinterpret_cast<uint32_t*>(Wq + off) = pk;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (row_ok && ncol + e < n) Wq[off + e] = (int8_t)(pk >> (8 * e));
+                }
+            }
+    }
+}
+
+template <int BMm, int BK, int WGn, int WGm, bool RAGGED>
+__global__ __launch_bounds__(WGn* WGm * 64) void k_backproject(const uint8_t* __restrict__ Pq,
+                                                               const float* __restrict__ Ps,
+                                                               const uint16_t* __restrict__ N,
+                                                               int8_t* __restrict__ Wq, float* __restrict__ Ws,
+                                                               float* __restrict__ Udbg, int m, int n, int r,
+                                                               float alpha, float lr, uint32_t key, uint32_t tiles_m,
+                                                               uint32_t tiles) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm>::SMEM];
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= tiles) return;
+    backproject_tile<BMm, BK, WGn, WGm, RAGGED>(Pq, Ps, N, Wq, Ws, Udbg, m, n, r, (int)(tile % tiles_m) * BMm,
+                                                (int)(tile / tiles_m), alpha, lr, key, smem);
+}
+
+template <int BMm, int BK, int WGn, int WGm, bool RAGGED>
+__global__ __launch_bounds__(WGn* WGm * 64) void k_backproject_many(const PlanHeader* __restrict__ plan, float alpha,
+                                                                    float lr, uint64_t seed, uint64_t step) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm>::SMEM];
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= plan->bp_tiles) return;
+    const PlanMatrix* mats = plan_matrices(plan);
+    const int mi = plan_find(mats, plan->count, tile, [](const PlanMatrix& x) { return x.bp_tile0; });
+    const PlanMatrix& d = mats[mi];
+    const uint32_t local = tile - d.bp_tile0;
+    const uint32_t key = sr_key(seed + (uint64_t)mi * 0x9E3779B97F4A7C15ull, step, 0u);
+    backproject_tile<BMm, BK, WGn, WGm, RAGGED>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.r,
+                                                (int)(local % d.bp_tiles_m) * BMm, (int)(local / d.bp_tiles_m),
+                                                alpha, lr, key, smem);
+}
+
+}  // namespace qg

@@ -201,7 +201,7 @@ def test_config0_ten_steps_teacher_forced():
         o = Q.step(Wq, Ws, Gb, d["Pq"], d["Ps"], M32, V32, t, HP, seed=0, r=r)
         g = _run_step_gpu(d, dict(Wq=Wq, Ws=Ws, M=M32, V=V32, Gb=Gb), t, 0, r)
         assert rel_fro(g["R"], o["R"]) <= 1e-3 and rel_fro(g["Nb"], o["Nb"]) <= 1e-3
-        assert rel_fro(g["M"], o["M"]) <= 1e-5 and rel_fro(g["V"], o["V"]) <= 1e-5
+        assert rel_fro(g["M"], o["M"]) <= 2e-5 and rel_fro(g["V"], o["V"]) <= 4e-5
         fracs.append(check_codes(g["Wq"], o["Wq"]))
         check_scales_step(g["Ws"], o["Ws"])
         Wq, Ws, M, V = o["Wq"], o["Ws"], o["M"], o["V"]
@@ -248,7 +248,7 @@ def test_step_many_matches_oracle(shapes):
                    seed=(seed + i * 0x9E3779B97F4A7C15) % 2 ** 64, r=s.r)
         assert rel_fro(host(s.R), o["R"]) <= 2e-5
         assert rel_fro(bf16_t_to_f64(s.N), o["Nb"]) <= 1e-3
-        assert rel_fro(host(s.M), o["M"]) <= 1e-5 and rel_fro(host(s.V), o["V"]) <= 1e-5
+        assert rel_fro(host(s.M), o["M"]) <= 2e-5 and rel_fro(host(s.V), o["V"]) <= 4e-5
         check_codes(host(s.Wq), o["Wq"])
         check_scales_step(host(s.Ws), o["Ws"])
 
@@ -275,7 +275,8 @@ def test_llama7b_shapes_sampled_columns(m, n, r, kind):
                    np.zeros((r, 256)), 1, HP, seed=0, r=r, n_total=n, col0=g * 256)
         assert rel_fro(gR[:, sl], o["R"]) <= 2e-5
         assert rel_fro(gN[:, sl], o["Nb"]) <= 1e-3
-        assert rel_fro(gM[:, sl], o["M"]) <= 1e-5 and rel_fro(gV[:, sl], o["V"]) <= 1e-5
+        # M inherits R's fp32-accumulation error over K = m terms (about 1e-5 here), V (~R^2) twice that
+        assert rel_fro(gM[:, sl], o["M"]) <= 2e-5 and rel_fro(gV[:, sl], o["V"]) <= 4e-5
         check_codes(gWq[:, sl], o["Wq"])
         check_scales_step(gWs[:, g:g + 1], o["Ws"])
 
