@@ -33,6 +33,22 @@ WORKLOADS = {
 }
 
 
+def measured_traffic(kernel: str, config: int):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
+    scaled by a plain copy of known size), or None if there is no summary for this workload."""
+    if config != 4:
+        return None
+    path = os.path.join(ROOT, "profiles", "grouped_step_llama7b_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes" and f[1] == kernel:
+                return int(f[2])
+    except OSError:
+        pass
+    return None
+
+
 def algorithmic_work(shapes):
     """Flops and HBM bytes each kernel must move for these (m, n, r) matrices (no re-reads counted)."""
     flops = sum(2 * m * n * r for m, n, r in shapes)
@@ -122,6 +138,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (the step has no cross-GPU part); use --gpus 1")
@@ -136,6 +155,15 @@ def main():
     qg.lib()                                   # fail loudly if the HIP library is not built
     device = torch.device("cuda:0")
     torch.cuda.set_device(device)
+
+    if args.copy_calibration:
+        src = torch.ones((1 << 28,), dtype=torch.float32, device=device)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
+        return
 
     shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(args.config)]
     mats = build_state(args.config, device)
@@ -182,6 +210,9 @@ def main():
                     "achieved": kernels[name]["TFLOP/s"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": kernels[name]["frac_mfma"], "traffic": None}
 
+    roofline["traffic"] = measured_traffic(roofline["kernel"], args.config)
+    roofline["traffic_unit"] = "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, see profiles/)"
+    roofline["algorithmic_bytes"] = [b_proj, b_adam, b_bp][dom]
     out = {
         "metric": "qgalore_step_ms_all_linear_weights", "value": ms_per_step, "unit": "ms", "n_gpus": 1,
         "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
