@@ -8,42 +8,48 @@ namespace qg {
 // ---------------------------------------------------------------------------
 static inline unsigned grid8(uint32_t tiles) { return ((tiles + 7u) / 8u) * 8u; }
 
-template <int BM, int BN, int BK, int WGM, int WGN>
+template <int BM, int BN, int BK, int WGM, int WGN, int MINWG>
 static int launch_project_cfg(const uint8_t* Pq, const float* Ps, const uint16_t* G, float* R, int m, int n, int r,
                               hipStream_t stream) {
     const uint32_t tiles_r = (uint32_t)((r + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
     const uint32_t tiles = tiles_r * tiles_n;
     const bool ragged = (r % BM) || (n % BN) || (m % BK);
     if (ragged)
-        hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, true>), dim3(grid8(tiles)), dim3(WGM * WGN * 64), 0,
+        hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, true, MINWG>), dim3(grid8(tiles)), dim3(WGM * WGN * 64), 0,
                            stream, Pq, Ps, G, R, m, n, r, tiles_r, tiles);
     else
-        hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, false>), dim3(grid8(tiles)), dim3(WGM * WGN * 64), 0,
+        hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, false, MINWG>), dim3(grid8(tiles)), dim3(WGM * WGN * 64), 0,
                            stream, Pq, Ps, G, R, m, n, r, tiles_r, tiles);
     return check_launch();
 }
 
+// Tile choice: 128 x 256 tiles of R with two workgroups resident per CU (one's staging and epilogue overlap the
+// other's MFMA work) when that still yields enough workgroups to fill 256 CUs twice; 128 x 128 tiles otherwise.
 int launch_project(const uint8_t* Pq, const float* Ps, const uint16_t* G, float* R, int64_t m, int64_t n, int64_t r,
                    hipStream_t stream) {
-    const int64_t big_tiles = ((r + 255) / 256) * ((n + 255) / 256);
-    if (r % 256 == 0 && big_tiles >= 192)
-        return launch_project_cfg<256, 256, 32, 2, 2>(Pq, Ps, G, R, (int)m, (int)n, (int)r, stream);
-    return launch_project_cfg<128, 128, 32, 2, 2>(Pq, Ps, G, R, (int)m, (int)n, (int)r, stream);
+    const int64_t big_tiles = ((r + 127) / 128) * ((n + 255) / 256);
+    if (big_tiles >= 384)
+        return launch_project_cfg<128, 256, 32, 2, 2, 2>(Pq, Ps, G, R, (int)m, (int)n, (int)r, stream);
+    return launch_project_cfg<128, 128, 32, 2, 2, 2>(Pq, Ps, G, R, (int)m, (int)n, (int)r, stream);
 }
 
-template <int BMm, int BK, int WGn, int WGm>
+template <int BMm, int BK, int WGn, int WGm, bool PREF, int MINWG>
 static int launch_backproject_cfg(const uint8_t* Pq, const float* Ps, const uint16_t* N, int8_t* Wq, float* Ws,
                                   float* Udbg, int m, int n, int r, float alpha, float lr, uint32_t key,
                                   hipStream_t stream) {
     const uint32_t tiles_m = (uint32_t)((m + BMm - 1) / BMm), tiles_n = (uint32_t)((n + kGroup - 1) / kGroup);
     const uint32_t tiles = tiles_m * tiles_n;
     const bool ragged = (m % BMm) || (n % kGroup) || (r % BK);
-    if (ragged)
-        hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, true>), dim3(grid8(tiles)), dim3(WGn * WGm * 64), 0,
-                           stream, Pq, Ps, N, Wq, Ws, Udbg, m, n, r, alpha, lr, key, tiles_m, tiles);
-    else
-        hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, false>), dim3(grid8(tiles)), dim3(WGn * WGm * 64), 0,
-                           stream, Pq, Ps, N, Wq, Ws, Udbg, m, n, r, alpha, lr, key, tiles_m, tiles);
+    const dim3 grid(grid8(tiles)), block(WGn * WGm * 64);
+#define QG_LAUNCH_BP(RAG, DUMP)                                                                                     \
+    hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, RAG, DUMP, PREF, MINWG>), grid, block, 0, stream, Pq, Ps, N, Wq, Ws, Udbg, \
+                       m, n, r, alpha, lr, key, tiles_m, tiles)
+    if (ragged) {
+        if (Udbg) QG_LAUNCH_BP(true, true); else QG_LAUNCH_BP(true, false);
+    } else {
+        if (Udbg) QG_LAUNCH_BP(false, true); else QG_LAUNCH_BP(false, false);
+    }
+#undef QG_LAUNCH_BP
     return check_launch();
 }
 
@@ -51,21 +57,19 @@ int launch_backproject(const uint8_t* Pq, const float* Ps, const uint16_t* N, in
                        int64_t m, int64_t n, int64_t r, float alpha, float lr, uint64_t seed, int64_t step,
                        hipStream_t stream) {
     const uint32_t key = sr_key(seed, (uint64_t)step, 0u);
-    const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-    if (big_tiles >= 192)
-        return launch_backproject_cfg<256, 32, 2, 2>(Pq, Ps, N, Wq, Ws, Udbg, (int)m, (int)n, (int)r, alpha, lr, key,
-                                                     stream);
-    return launch_backproject_cfg<128, 32, 2, 2>(Pq, Ps, N, Wq, Ws, Udbg, (int)m, (int)n, (int)r, alpha, lr, key,
-                                                 stream);
+    // 128-row tiles, weight tile sharing the staging LDS, two workgroups per CU: the VALU-heavy update epilogue of
+    // one workgroup overlaps the MFMA main loop of the other.
+    return launch_backproject_cfg<128, 32, 2, 2, false, 2>(Pq, Ps, N, Wq, Ws, Udbg, (int)m, (int)n, (int)r, alpha, lr,
+                                                           key, stream);
 }
 
 int launch_project_many(const PlanHeader* plan_host, const PlanHeader* plan_dev, hipStream_t stream) {
     const unsigned grid = grid8(plan_host->proj_tiles);
     if (plan_host->ragged)
-        hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, true>), dim3(grid), dim3(256), 0, stream,
+        hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, true, 2>), dim3(grid), dim3(256), 0, stream,
                            plan_dev);
     else
-        hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, false>), dim3(grid), dim3(256), 0,
+        hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, false, 2>), dim3(grid), dim3(256), 0,
                            stream, plan_dev);
     return check_launch();
 }
@@ -74,10 +78,10 @@ int launch_backproject_many(const PlanHeader* plan_host, const PlanHeader* plan_
                             uint64_t seed, int64_t step, hipStream_t stream) {
     const unsigned grid = grid8(plan_host->bp_tiles);
     if (plan_host->ragged)
-        hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, true>), dim3(grid), dim3(256), 0, stream, plan_dev,
+        hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, true, false, 2>), dim3(grid), dim3(256), 0, stream, plan_dev,
                            alpha, lr, seed, (uint64_t)step);
     else
-        hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, false>), dim3(grid), dim3(256), 0, stream,
+        hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, false, false, 2>), dim3(grid), dim3(256), 0, stream,
                            plan_dev, alpha, lr, seed, (uint64_t)step);
     return check_launch();
 }

@@ -187,8 +187,8 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
             }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED>
-__global__ __launch_bounds__(WGM* WGN * 64) void k_project(const uint8_t* __restrict__ Pq,
+template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
+__global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project(const uint8_t* __restrict__ Pq,
                                                            const float* __restrict__ Ps,
                                                            const uint16_t* __restrict__ G, float* __restrict__ R,
                                                            int m, int n, int r, uint32_t tiles_r, uint32_t tiles) {
@@ -209,8 +209,8 @@ __device__ __forceinline__ int plan_find(const PlanMatrix* mats, int count, uint
     return lo;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED>
-__global__ __launch_bounds__(WGM* WGN * 64) void k_project_many(const PlanHeader* __restrict__ plan) {
+template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
+__global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(const PlanHeader* __restrict__ plan) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= plan->proj_tiles) return;
@@ -230,37 +230,75 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_project_many(const PlanHeader
 // in-lane reduction plus one cross-half shuffle and one LDS exchange.
 // Tile: 256 columns of W (exactly one quantization block per row) x BMm rows.
 // ============================================================================
-template <int BMm, int BK, int WGn, int WGm>
+// W_PREFETCH: the weight tile has LDS of its own and is fetched before the main loop (one workgroup per CU);
+// otherwise it reuses the staging buffers after the main loop (smaller footprint, two workgroups per CU, whose
+// epilogue and main loop then overlap).
+template <int BMm, int BK, int WGn, int WGm, bool W_PREFETCH = true>
 struct BpShape {
     static constexpr int BNn = kGroup;
     static constexpr int NT = WGn * WGm * 64;
     static constexpr int PA = BNn + kPadK;  // N tile, K-major
     static constexpr int PB = BK + kPadX;   // P tile, [m][k]
     static constexpr int A_STAGE = BK * PA, B_STAGE = BMm * PB;
-    static constexpr int SMEM = 2 * (A_STAGE + B_STAGE);
+    static constexpr int STAGING = 2 * (A_STAGE + B_STAGE);   // uint16 elements
+    static constexpr int WTILE = BMm * BNn / 2;                // INT8 weight tile, in uint16 elements
+    static constexpr int WOFF = W_PREFETCH ? STAGING : WGn * BMm * 2;   // after the row-max exchange area if aliased
+    static constexpr int SMEM = W_PREFETCH ? STAGING + WTILE : (STAGING > WOFF + WTILE ? STAGING : WOFF + WTILE);
 };
 
-template <int BMm, int BK, int WGn, int WGm, bool RAGGED>
+// Byte offset of weight-tile element (row, col) in LDS.  Rows are 256 bytes (one quantization block); the 16
+// 16-byte chunks of a row are stored at chunk ^ (row & 15), so the 32 lanes of an MFMA accumulator column (32
+// consecutive rows, same column) spread over 16 bank groups, while every row still fills 256 contiguous bytes
+// (direct global->LDS loads deposit whole rows).
+__device__ __forceinline__ int wtile_offset(int row, int col) {
+    return row * kGroup + ((((col >> 4) ^ row) & 15) << 4) + (col & 15);
+}
+
+template <int BMm, int BK, int WGn, int WGm, bool RAGGED, bool DUMP_U, bool W_PREFETCH = true>
 __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
                                                  const uint16_t* __restrict__ N, int8_t* __restrict__ Wq,
                                                  float* __restrict__ Ws, float* __restrict__ Udbg, int m, int n, int r,
                                                  int m0, int tile_n, float alpha, float lr, uint32_t key,
                                                  uint16_t* smem) {
-    using S = BpShape<BMm, BK, WGn, WGm>;
-    constexpr int BNn = S::BNn, NT = S::NT;
+    using S = BpShape<BMm, BK, WGn, WGm, W_PREFETCH>;
+    constexpr int BNn = S::BNn, NT = S::NT, NW = WGn * WGm;
     constexpr int SN = BNn / WGn, SM = BMm / WGm, IB = SN / 32, JB = SM / 32;
     constexpr int PA = S::PA, PB = S::PB;
     constexpr int A_CH = BK * BNn / 8, A_PER = A_CH / NT;
     constexpr int B_WORDS = BMm * BK / 8, B_PER = B_WORDS / NT;
+    constexpr int W_ROUNDS = BMm / 4 / NW;   // each wave-wide 16-byte access covers 4 tile rows
     static_assert(A_CH % NT == 0 && B_WORDS % NT == 0, "staging must divide evenly");
-    static_assert(WGn * BMm * 4 <= S::SMEM * 2, "row-max exchange must fit in the staging buffers");
+    static_assert(WGn * BMm * 4 <= S::STAGING * 2, "row-max exchange must fit in the staging buffers");
+    static_assert((BMm / 4) % NW == 0, "weight tile rows must divide evenly over the waves");
     uint16_t* As = smem;
     uint16_t* Bs = smem + 2 * S::A_STAGE;
+    uint8_t* wt = reinterpret_cast<uint8_t*>(smem + S::WOFF);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wn = wave / WGm, wm = wave % WGm;
     const int n0 = tile_n * BNn;
     const int ng = (n + kGroup - 1) / kGroup;
-    const bool vec8 = (n & 7) == 0, vec4 = (n & 3) == 0;
+    const bool vec8 = (n & 7) == 0;
+
+    // ---- weight tile -> LDS (asynchronous direct loads where shapes allow) ----
+    auto load_wtile = [&]() {
+    if (!RAGGED) {
+#pragma unroll
+        for (int i = 0; i < W_ROUNDS; ++i) {
+            const int rb = (wave * W_ROUNDS + i) * 4;             // first of the 4 rows this wave access covers
+            const int row = rb + (lane >> 4), chunk = (lane ^ row) & 15;
+            const int8_t* src = Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(wt + rb * kGroup), 16, 0, 0);
+        }
+    } else {
+        for (int idx = t; idx < BMm * BNn; idx += NT) {
+            const int row = idx / BNn, col = idx % BNn;
+            const bool ok = m0 + row < m && n0 + col < n;
+            wt[wtile_offset(row, col)] = ok ? (uint8_t)Wq[(int64_t)(m0 + row) * n + n0 + col] : (uint8_t)0;
+        }
+    }
+    };
+    if (W_PREFETCH) load_wtile();   // lands while the GEMM main loop runs
 
     u32x4 av[A_PER];
     uint32_t bw[B_PER];
@@ -348,12 +386,19 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         __syncthreads();
     }
 
+    if (!W_PREFETCH) load_wtile();    // the staging buffers are free now (the main loop ends with a barrier)
+    // The weight tile's direct loads are counted by vmcnt like any other load.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
     // ---- epilogue: x = Wq*s - lr*U in place of the accumulators, per-row block absmax ----
     float* smax = reinterpret_cast<float*>(smem);  // [WGn][BMm]; staging buffers are free after the last barrier
+    const float nlra = -(lr * alpha);
     float rowmax[JB];
 #pragma unroll
     for (int b = 0; b < JB; ++b) {
-        const int mrow = m0 + wm * SM + b * 32 + lrow;
+        const int rl = wm * SM + b * 32 + lrow;       // row inside the tile
+        const int mrow = m0 + rl;
         const bool row_ok = !RAGGED || mrow < m;
         const float s_old = row_ok ? Ws[(int64_t)mrow * ng + tile_n] : 0.f;
         float mx = 0.f;
@@ -361,90 +406,96 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         for (int a = 0; a < IB; ++a)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
-                const int ncol = n0 + wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
-                const int64_t off = (int64_t)mrow * n + ncol;
-                int code[4];
-                if (!RAGGED || (row_ok && vec4 && ncol + 4 <= n)) {
-                    const uint32_t w = *reinterpret_cast<const uint32_t*>(Wq + off);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) code[e] = (int)(int8_t)(w >> (8 * e));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) code[e] = (row_ok && ncol + e < n) ? (int)Wq[off + e] : 0;
-                }
+                const int col = wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
+                const uint32_t w = *reinterpret_cast<const uint32_t*>(wt + wtile_offset(rl, col));
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float u = alpha * acc[a][b][4 * v4 + e];
-                    const bool ok = !RAGGED || (row_ok && ncol + e < n);
-                    if (Udbg != nullptr && ok) Udbg[off + e] = u;
-                    const float x = ok ? __builtin_fmaf(-lr, u, (float)code[e] * s_old) : 0.f;
+                    const float cw = (float)(int)(int8_t)(w >> (8 * e)) * s_old;
+                    const bool ok = !RAGGED || (row_ok && n0 + col + e < n);
+                    if (DUMP_U) {
+                        if (ok) Udbg[(int64_t)mrow * n + n0 + col + e] = alpha * acc[a][b][4 * v4 + e];
+                    }
+                    const float x = ok ? __builtin_fmaf(nlra, acc[a][b][4 * v4 + e], cw) : 0.f;
                     acc[a][b][4 * v4 + e] = x;
                     mx = fmaxf(mx, fabsf(x));
                 }
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         rowmax[b] = mx;
-        if (WGn > 1 && lhalf == 0) smax[wn * BMm + wm * SM + b * 32 + lrow] = mx;
+        if (WGn > 1 && lhalf == 0) smax[wn * BMm + rl] = mx;
     }
     if (WGn > 1) __syncthreads();
 
-    // ---- new scale, stochastic rounding, store ----
+    // ---- new scale, stochastic rounding; the new codes replace the old ones in the LDS tile ----
 #pragma unroll
     for (int b = 0; b < JB; ++b) {
-        const int mrow = m0 + wm * SM + b * 32 + lrow;
+        const int rl = wm * SM + b * 32 + lrow;
+        const int mrow = m0 + rl;
         const bool row_ok = !RAGGED || mrow < m;
         float amax = rowmax[b];
         if (WGn > 1) {
 #pragma unroll
-            for (int w = 0; w < WGn; ++w) amax = fmaxf(amax, smax[w * BMm + wm * SM + b * 32 + lrow]);
+            for (int w = 0; w < WGn; ++w) amax = fmaxf(amax, smax[w * BMm + rl]);
         }
         const float s_new = amax > 0.f ? amax / 127.0f : 0.f;
         const float inv = amax > 0.f ? 127.0f / amax : 0.f;
         if (wn == 0 && lhalf == 0 && row_ok) Ws[(int64_t)mrow * ng + tile_n] = s_new;
+        const uint32_t idx_row = (uint32_t)mrow * (uint32_t)n + (uint32_t)n0;   // m*n < 2^32
 #pragma unroll
         for (int a = 0; a < IB; ++a)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
-                const int ncol = n0 + wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
-                const int64_t off = (int64_t)mrow * n + ncol;
+                const int col = wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
                 uint32_t pk = 0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float tq = acc[a][b][4 * v4 + e] * inv;
-                    const float uu = sr_uniform(key, (uint32_t)(off + e));
-                    const float q = fminf(fmaxf(floorf(tq + uu), -128.f), 127.f);
+                    const uint32_t h = mix32(key ^ (idx_row + (uint32_t)(col + e)));
+                    // fl32(tq + u) with u = (h >> 8) * 2^-24: the product is exact, so one fma rounds the same sum
+                    const float v = __builtin_fmaf((float)(h >> 8), 0x1p-24f, tq);
+                    const float q = fminf(fmaxf(floorf(v), -128.f), 127.f);
                     pk |= ((uint32_t)(int)q & 0xFFu) << (8 * e);
                 }
-                if (!RAGGED || (row_ok && vec4 && ncol + 4 <= n)) {
-                    *reinterpret_cast<uint32_t*>(Wq + off) = pk;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (row_ok && ncol + e < n) Wq[off + e] = (int8_t)(pk >> (8 * e));
-                }
+                *reinterpret_cast<uint32_t*>(wt + wtile_offset(rl, col)) = pk;
             }
+    }
+    __syncthreads();
+
+    // ---- updated tile -> global, whole 256-byte rows per 16 lanes ----
+    if (!RAGGED) {
+#pragma unroll
+        for (int i = 0; i < W_ROUNDS; ++i) {
+            const int row = (wave * W_ROUNDS + i) * 4 + (lane >> 4), chunk = (lane ^ row) & 15;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(wt + row * kGroup + (lane & 15) * 16);
+            *reinterpret_cast<u32x4*>(Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16) = v;
+        }
+    } else {
+        for (int idx = t; idx < BMm * BNn; idx += NT) {
+            const int row = idx / BNn, col = idx % BNn;
+            if (m0 + row < m && n0 + col < n) Wq[(int64_t)(m0 + row) * n + n0 + col] = (int8_t)wt[wtile_offset(row, col)];
+        }
     }
 }
 
-template <int BMm, int BK, int WGn, int WGm, bool RAGGED>
-__global__ __launch_bounds__(WGn* WGm * 64) void k_backproject(const uint8_t* __restrict__ Pq,
+template <int BMm, int BK, int WGn, int WGm, bool RAGGED, bool DUMP_U, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
+__global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject(const uint8_t* __restrict__ Pq,
                                                                const float* __restrict__ Ps,
                                                                const uint16_t* __restrict__ N,
                                                                int8_t* __restrict__ Wq, float* __restrict__ Ws,
                                                                float* __restrict__ Udbg, int m, int n, int r,
                                                                float alpha, float lr, uint32_t key, uint32_t tiles_m,
                                                                uint32_t tiles) {
-    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm>::SMEM];
+    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    backproject_tile<BMm, BK, WGn, WGm, RAGGED>(Pq, Ps, N, Wq, Ws, Udbg, m, n, r, (int)(tile % tiles_m) * BMm,
+    backproject_tile<BMm, BK, WGn, WGm, RAGGED, DUMP_U, W_PREFETCH>(Pq, Ps, N, Wq, Ws, Udbg, m, n, r, (int)(tile % tiles_m) * BMm,
                                                 (int)(tile / tiles_m), alpha, lr, key, smem);
 }
 
-template <int BMm, int BK, int WGn, int WGm, bool RAGGED>
-__global__ __launch_bounds__(WGn* WGm * 64) void k_backproject_many(const PlanHeader* __restrict__ plan, float alpha,
+template <int BMm, int BK, int WGn, int WGm, bool RAGGED, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
+__global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_many(const PlanHeader* __restrict__ plan, float alpha,
                                                                     float lr, uint64_t seed, uint64_t step) {
-    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm>::SMEM];
+    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= plan->bp_tiles) return;
     const PlanMatrix* mats = plan_matrices(plan);
@@ -452,7 +503,7 @@ __global__ __launch_bounds__(WGn* WGm * 64) void k_backproject_many(const PlanHe
     const PlanMatrix& d = mats[mi];
     const uint32_t local = tile - d.bp_tile0;
     const uint32_t key = sr_key(seed + (uint64_t)mi * 0x9E3779B97F4A7C15ull, step, 0u);
-    backproject_tile<BMm, BK, WGn, WGm, RAGGED>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.r,
+    backproject_tile<BMm, BK, WGn, WGm, RAGGED, false, W_PREFETCH>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.r,
                                                 (int)(local % d.bp_tiles_m) * BMm, (int)(local / d.bp_tiles_m),
                                                 alpha, lr, key, smem);
 }

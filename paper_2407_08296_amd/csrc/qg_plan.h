@@ -11,9 +11,9 @@ namespace qg {
 constexpr uint32_t kPlanMagic = 0x51474C50u;  // "QGLP"
 
 // Tile shapes of the grouped GEMM launches (must match the kernel instantiations).
-constexpr int kManyProjBM = 256;  // rows of R (r) per tile
+constexpr int kManyProjBM = 128;  // rows of R (r) per tile
 constexpr int kManyProjBN = 256;  // columns of R (n) per tile
-constexpr int kManyBpBM = 256;    // rows of W (m) per tile
+constexpr int kManyBpBM = 128;    // rows of W (m) per tile
 constexpr int kManyBpBN = 256;    // columns of W (n) per tile = one quantization block per row
 
 struct PlanMatrix {

@@ -84,8 +84,8 @@ def test_plan_build_on_host(L):
     hdr = (C.c_uint32 * 8).from_buffer(buf)
     assert hdr[1] == 2                                       # count
     assert hdr[2] == 2 * (1024 * 4096) // 4096               # Adam chunks of 4096 elements
-    assert hdr[3] == 2 * 4 * 16                              # projection tiles 256 x 256 over r x n
-    assert hdr[4] == 16 * 16 + 43 * 16                       # back-projection tiles over m x n
+    assert hdr[3] == 2 * 8 * 16                              # projection tiles 128 x 256 over r x n
+    assert hdr[4] == 32 * 16 + 86 * 16                       # back-projection tiles 128 x 256 over m x n
     assert hdr[5] == 0                                       # nothing ragged
     descs[1].n = 5461
     assert L.qg_plan_build(2, descs, buf, nbytes) == 0
