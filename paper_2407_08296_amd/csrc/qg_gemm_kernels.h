@@ -52,6 +52,30 @@ __device__ __forceinline__ u32x4 load8_bf16_guarded(const uint16_t* src, int val
     return o;
 }
 
+// WPT consecutive 32-bit words (WPT = 1, 2 or 4) from a pointer aligned to 4*WPT bytes.
+template <int WPT>
+__device__ __forceinline__ void load_words(const uint8_t* p, uint32_t (&w)[WPT]) {
+    if constexpr (WPT == 4) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+        w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+    } else if constexpr (WPT == 2) {
+        typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+        const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+        w[0] = v[0]; w[1] = v[1];
+    } else {
+        w[0] = *reinterpret_cast<const uint32_t*>(p);
+    }
+}
+
+// Words of INT4 codes a thread fetches with one load when staging a P tile: as wide as the tile allows
+// (the unguarded kernels only; 8*WPT codes never straddle a block of 256 because tiles start at multiples of 32).
+template <int WORDS, int NT, bool RAGGED>
+struct P_Task {
+    static constexpr int WPT = RAGGED ? 1 : (WORDS / NT >= 4 ? 4 : (WORDS / NT >= 2 ? 2 : 1));
+    static constexpr int PER = WORDS / (NT * WPT);
+    static_assert(WORDS % (NT * WPT) == 0 && PER >= 1, "staging must divide evenly");
+};
+
 // XCD-aware tile order: consecutive workgroup ids go round-robin over the 8 XCDs
 // (each with its own L2), so XCD x is handed the contiguous range of tiles
 // [x*per, (x+1)*per), and neighbouring tiles (which share operand panels) meet in
@@ -80,9 +104,11 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     constexpr int NT = S::NT;
     constexpr int WM = BM / WGM, WN = BN / WGN, MB = WM / 32, NB = WN / 32;
     constexpr int PA = S::PA, PB = S::PB;
-    constexpr int A_WORDS = BK * BM / 8, A_PER = A_WORDS / NT;
+    constexpr int A_WORDS = BK * BM / 8;
+    using AT = P_Task<A_WORDS, NT, RAGGED>;
+    constexpr int A_PER = AT::PER, WPT = AT::WPT, A_TPR = BM / (8 * WPT);   // tasks per tile row
     constexpr int B_CH = BK * BN / 8, B_PER = B_CH / NT;
-    static_assert(A_WORDS % NT == 0 && B_CH % NT == 0, "staging must divide evenly");
+    static_assert(B_CH % NT == 0, "staging must divide evenly");
     static_assert(BK % 16 == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     uint16_t* As = smem;
     uint16_t* Bs = smem + 2 * S::A_STAGE;
@@ -90,7 +116,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     const int wm = wave / WGN, wn = wave % WGN;
     const bool vec = (n & 7) == 0;
 
-    uint32_t aw[A_PER];
+    uint32_t aw[A_PER][WPT];
     float asc[A_PER];
     u32x4 bv[B_PER];
 
@@ -98,14 +124,14 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
         const int i0 = kt * BK;
 #pragma unroll
         for (int p = 0; p < A_PER; ++p) {
-            const int wi = t + p * NT;
-            const int row = wi / (BM / 8), c8 = wi % (BM / 8);
-            const int64_t e = (int64_t)(i0 + row) * r + r0 + c8 * 8;
-            if (!RAGGED || (i0 + row < m && r0 + c8 * 8 < r)) {
-                aw[p] = *reinterpret_cast<const uint32_t*>(Pq + (e >> 1));
+            const int ti = t + p * NT;
+            const int row = ti / A_TPR, c = (ti % A_TPR) * (8 * WPT);
+            const int64_t e = (int64_t)(i0 + row) * r + r0 + c;
+            if (!RAGGED || (i0 + row < m && r0 + c < r)) {
+                load_words<WPT>(Pq + (e >> 1), aw[p]);
                 asc[p] = Ps[e >> 8];
             } else {
-                aw[p] = 0x88888888u;
+                aw[p][0] = 0x88888888u;
                 asc[p] = 0.f;
             }
         }
@@ -125,9 +151,11 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     auto sstore = [&](int stage) {
 #pragma unroll
         for (int p = 0; p < A_PER; ++p) {
-            const int wi = t + p * NT;
-            const int row = wi / (BM / 8), c8 = wi % (BM / 8);
-            *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c8 * 8) = dequant8_bf16(aw[p], asc[p]);
+            const int ti = t + p * NT;
+            const int row = ti / A_TPR, c = (ti % A_TPR) * (8 * WPT);
+#pragma unroll
+            for (int j = 0; j < WPT; ++j)
+                *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c + 8 * j) = dequant8_bf16(aw[p][j], asc[p]);
         }
 #pragma unroll
         for (int p = 0; p < B_PER; ++p) {
@@ -265,9 +293,12 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     constexpr int SN = BNn / WGn, SM = BMm / WGm, IB = SN / 32, JB = SM / 32;
     constexpr int PA = S::PA, PB = S::PB;
     constexpr int A_CH = BK * BNn / 8, A_PER = A_CH / NT;
-    constexpr int B_WORDS = BMm * BK / 8, B_PER = B_WORDS / NT;
+    constexpr int B_WORDS = BMm * BK / 8;
+    using BT = P_Task<B_WORDS, NT, RAGGED>;
+    constexpr int B_PER = BT::PER, WPT = BT::WPT, B_TPR = BK / (8 * WPT);   // tasks per tile row
+    static_assert(BK % (8 * WPT) == 0, "tile shape");
     constexpr int W_ROUNDS = BMm / 4 / NW;   // each wave-wide 16-byte access covers 4 tile rows
-    static_assert(A_CH % NT == 0 && B_WORDS % NT == 0, "staging must divide evenly");
+    static_assert(A_CH % NT == 0, "staging must divide evenly");
     static_assert(WGn * BMm * 4 <= S::STAGING * 2, "row-max exchange must fit in the staging buffers");
     static_assert((BMm / 4) % NW == 0, "weight tile rows must divide evenly over the waves");
     uint16_t* As = smem;
@@ -301,7 +332,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     if (W_PREFETCH) load_wtile();   // lands while the GEMM main loop runs
 
     u32x4 av[A_PER];
-    uint32_t bw[B_PER];
+    uint32_t bw[B_PER][WPT];
     float bsc[B_PER];
 
     auto gload = [&](int kt) {
@@ -320,14 +351,14 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         }
 #pragma unroll
         for (int p = 0; p < B_PER; ++p) {
-            const int wi = t + p * NT;
-            const int row = wi / (BK / 8), c8 = wi % (BK / 8);
-            const int64_t e = (int64_t)(m0 + row) * r + k0 + c8 * 8;
-            if (!RAGGED || (m0 + row < m && k0 + c8 * 8 < r)) {
-                bw[p] = *reinterpret_cast<const uint32_t*>(Pq + (e >> 1));
+            const int ti = t + p * NT;
+            const int row = ti / B_TPR, c = (ti % B_TPR) * (8 * WPT);
+            const int64_t e = (int64_t)(m0 + row) * r + k0 + c;
+            if (!RAGGED || (m0 + row < m && k0 + c < r)) {
+                load_words<WPT>(Pq + (e >> 1), bw[p]);
                 bsc[p] = Ps[e >> 8];
             } else {
-                bw[p] = 0x88888888u;
+                bw[p][0] = 0x88888888u;
                 bsc[p] = 0.f;
             }
         }
@@ -341,9 +372,11 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         }
 #pragma unroll
         for (int p = 0; p < B_PER; ++p) {
-            const int wi = t + p * NT;
-            const int row = wi / (BK / 8), c8 = wi % (BK / 8);
-            *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c8 * 8) = dequant8_bf16(bw[p], bsc[p]);
+            const int ti = t + p * NT;
+            const int row = ti / B_TPR, c = (ti % B_TPR) * (8 * WPT);
+#pragma unroll
+            for (int j = 0; j < WPT; ++j)
+                *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c + 8 * j) = dequant8_bf16(bw[p][j], bsc[p]);
         }
     };
 
