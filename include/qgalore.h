@@ -75,7 +75,7 @@ typedef struct {
     float*          Ws;   /* INT8 weight scales, in/out */
     float*          M;    /* first moment r x n, in/out */
     float*          V;    /* second moment r x n, in/out*/
-    float*          R;    /* projected gradient r x n, out (scratch the caller may inspect) */
+    float*          R;    /* projected gradient r x n, out; may be NULL (not written then) */
     uint16_t*       N;    /* bf16 Adam direction r x n, out */
 } qg_matrix_desc;
 
@@ -115,6 +115,16 @@ int qg_project(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
 int qg_lowrank_adam(const float* R, float* M, float* V, uint16_t* N_bf16,
                     int64_t count, int64_t step, const qg_hparams* hp, void* stream);
 
+/* ---- Projection and Adam fused (Sec. 3.5): the same arithmetic as qg_project followed by qg_lowrank_adam, with
+ * Adam applied in the GEMM epilogue while R is still in registers.  M, V in/out, N out; R (nullable) receives the
+ * projected gradient only if the caller wants to inspect it - leaving it NULL saves writing and re-reading
+ * 8 bytes per low-rank element.  Results are bit-identical to the two separate calls.  At LLaMA-7B shapes the
+ * separate calls are faster (the per-lane M/V accesses of the epilogue are latency-bound, the stand-alone Adam
+ * pass streams at ~70 % of HBM peak); the fused form pays off where launches, not bytes, bound the step. */
+int qg_project_adam(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
+                    float* R /* nullable */, float* M, float* V, uint16_t* N_bf16,
+                    int64_t m, int64_t n, int64_t r, int group, int64_t step, const qg_hparams* hp, void* stream);
+
 /* ---- Back-projection and INT8 weight update with stochastic rounding
  * (Sec. 3.4, Sec. 3.5):  U = alpha * dequant(P) * N;  x = W_q*s - lr*U;  per block
  * of 256 of each row a = max|x|, s' = a/127, code' = clamp(floor(x*(127/a) + u), -128, 127)
@@ -152,7 +162,8 @@ int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
             void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- Grouped step over many matrices (the whole model's linear weights) in
- * three grouped launches.  `descs` is a HOST array of `count` descriptors.
+ * three grouped launches (projection, Adam, back-projection + update).
+ * A descriptor's R may be NULL only for plans used with qg_project_adam_many alone.  `descs` is a HOST array of `count` descriptors.
  * The library needs a device-resident launch plan: the caller provides
  * `plan_host` (host scratch) and `plan_dev` (device memory), each of
  * qg_plan_bytes(count, descs) bytes; qg_plan_build fills plan_host, the
@@ -163,12 +174,14 @@ int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_host, size_
 int qg_step_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
                  const qg_hparams* hp, uint64_t seed, int64_t step, void* stream);
 
-/* The three grouped launches of qg_step_many, one by one (same plan arguments):
- * projection of every matrix, Adam over every matrix, back-projection + SR update
- * of every matrix.  qg_step_many(...) == these three in this order. */
+/* The grouped launches one by one (same plan arguments): projection of every matrix, Adam over every matrix
+ * (these two need every descriptor's R), their fusion (write_R != 0 also stores R), and back-projection + SR update
+ * of every matrix.  qg_step_many(...) == qg_project_many, qg_lowrank_adam_many, qg_backproject_update_sr_many. */
 int qg_project_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes, void* stream);
 int qg_lowrank_adam_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
                          const qg_hparams* hp, int64_t step, void* stream);
+int qg_project_adam_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
+                         const qg_hparams* hp, int64_t step, int write_R, void* stream);
 int qg_backproject_update_sr_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
                                   const qg_hparams* hp, uint64_t seed, int64_t step, void* stream);
 

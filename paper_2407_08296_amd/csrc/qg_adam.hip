@@ -7,18 +7,6 @@
 
 namespace qg {
 
-struct AdamCoef {
-    float b1, b2, omb1, omb2, rc1, rc2, eps;  // rc = 1/(1 - beta^t)
-};
-
-__device__ inline float adam_one(float r, float& m, float& v, const AdamCoef& c) {
-    m = __builtin_fmaf(c.b1, m, c.omb1 * r);
-    v = __builtin_fmaf(c.b2, v, c.omb2 * (r * r));
-    const float mhat = m * c.rc1;
-    const float vhat = v * c.rc2;
-    return mhat / (sqrtf(vhat) + c.eps);
-}
-
 constexpr int kAdamVec = 4;                              // float4 per thread per array
 constexpr int kAdamChunk = 256 * 4 * kAdamVec;           // elements per workgroup chunk
 

@@ -29,6 +29,9 @@ int launch_adam(const float*, float*, float*, uint16_t*, int64_t, int64_t, const
 int launch_project_many(const PlanHeader*, const PlanHeader*, hipStream_t);
 int launch_backproject_many(const PlanHeader*, const PlanHeader*, float, float, uint64_t, int64_t, hipStream_t);
 int launch_adam_many(const PlanHeader*, const PlanHeader*, int64_t, const qg_hparams*, hipStream_t);
+int launch_project_adam(const uint8_t*, const float*, const uint16_t*, float*, float*, float*, uint16_t*, int64_t, int64_t,
+                        int64_t, int64_t, const qg_hparams*, hipStream_t);
+int launch_project_adam_many(const PlanHeader*, const PlanHeader*, int, int64_t, const qg_hparams*, hipStream_t);
 constexpr int kAdamChunkElems = 256 * 4 * 4;  // must equal kAdamChunk of qg_adam.hip
 
 static int check_mnr(int64_t m, int64_t n, int64_t r, int group) {
@@ -131,10 +134,11 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
     uint64_t adam = 0, proj = 0, bp = 0;
     for (int i = 0; i < count; ++i) {
         const qg_matrix_desc& d = descs[i];
-        if (!d.Pq || !d.Ps || !d.G || !d.Wq || !d.Ws || !d.M || !d.V || !d.R || !d.N) return QG_ERR_NULL;
+        if (!d.Pq || !d.Ps || !d.G || !d.Wq || !d.Ws || !d.M || !d.V || !d.N) return QG_ERR_NULL;
+        if (!d.R) h.pad_[0] = 1;   // some matrix has no R buffer: the unfused phases cannot run on this plan
         if (int e = check_mnr(d.m, d.n, d.r, kGroup)) return e;
         if (!aligned16(d.Pq) || !aligned16(d.Ps) || !aligned16(d.G) || !aligned16(d.Wq) || !aligned16(d.Ws) ||
-            !aligned16(d.M) || !aligned16(d.V) || !aligned16(d.R) || !aligned16(d.N))
+            !aligned16(d.M) || !aligned16(d.V) || (d.R && !aligned16(d.R)) || !aligned16(d.N))
             return QG_ERR_ALIGN;
         PlanMatrix pm;
         std::memset(&pm, 0, sizeof pm);
@@ -173,6 +177,7 @@ static int check_plan(int count, const void* plan_host, const void* plan_dev, si
 extern "C" int qg_project_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
                                void* stream) {
     if (int e = check_plan(count, plan_host, plan_dev, plan_bytes)) return e;
+    if (reinterpret_cast<const PlanHeader*>(plan_host)->pad_[0]) return QG_ERR_NULL;   // needs every R buffer
     return launch_project_many(reinterpret_cast<const PlanHeader*>(plan_host),
                                reinterpret_cast<const PlanHeader*>(plan_dev), (hipStream_t)stream);
 }
@@ -182,6 +187,7 @@ extern "C" int qg_lowrank_adam_many(int count, const void* plan_host, const void
     if (int e = check_plan(count, plan_host, plan_dev, plan_bytes)) return e;
     if (!hp) return QG_ERR_NULL;
     if (step < 1) return QG_ERR_SHAPE;
+    if (reinterpret_cast<const PlanHeader*>(plan_host)->pad_[0]) return QG_ERR_NULL;   // needs every R buffer
     return launch_adam_many(reinterpret_cast<const PlanHeader*>(plan_host),
                             reinterpret_cast<const PlanHeader*>(plan_dev), step, hp, (hipStream_t)stream);
 }
@@ -195,6 +201,29 @@ extern "C" int qg_backproject_update_sr_many(int count, const void* plan_host, c
     return launch_backproject_many(reinterpret_cast<const PlanHeader*>(plan_host),
                                    reinterpret_cast<const PlanHeader*>(plan_dev), hp->alpha, hp->lr, seed, step,
                                    (hipStream_t)stream);
+}
+
+extern "C" int qg_project_adam(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, float* R, float* M,
+                              float* V, uint16_t* N_bf16, int64_t m, int64_t n, int64_t r, int group, int64_t step,
+                              const qg_hparams* hp, void* stream) {
+    if (!Pq || !Ps || !G_bf16 || !M || !V || !N_bf16 || !hp) return QG_ERR_NULL;
+    if (int e = check_mnr(m, n, r, group)) return e;
+    if (step < 1) return QG_ERR_SHAPE;
+    if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(G_bf16) || (R && !aligned16(R)) || !aligned16(M) ||
+        !aligned16(V) || !aligned16(N_bf16))
+        return QG_ERR_ALIGN;
+    return launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, r, step, hp, (hipStream_t)stream);
+}
+
+extern "C" int qg_project_adam_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
+                                    const qg_hparams* hp, int64_t step, int write_R, void* stream) {
+    if (int e = check_plan(count, plan_host, plan_dev, plan_bytes)) return e;
+    if (!hp) return QG_ERR_NULL;
+    if (step < 1) return QG_ERR_SHAPE;
+    const PlanHeader* h = reinterpret_cast<const PlanHeader*>(plan_host);
+    if (write_R && h->pad_[0]) return QG_ERR_NULL;
+    return launch_project_adam_many(h, reinterpret_cast<const PlanHeader*>(plan_dev), write_R ? 1 : 0, step, hp,
+                                    (hipStream_t)stream);
 }
 
 extern "C" int qg_step_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,

@@ -80,6 +80,21 @@ __device__ inline float wave_sum(float v) {
     return v;
 }
 
+// ---- Adam on one element (Sec. 3.5; Adam as cited in Sec. 4.1) ----
+struct AdamCoef {
+    float b1, b2, omb1, omb2, rc1, rc2, eps;  // rc = 1/(1 - beta^t)
+};
+
+__device__ inline float adam_one(float r, float& m, float& v, const AdamCoef& c) {
+    m = __builtin_fmaf(c.b1, m, c.omb1 * r);
+    v = __builtin_fmaf(c.b2, v, c.omb2 * (r * r));
+    const float mhat = m * c.rc1;
+    const float vhat = v * c.rc2;
+    return mhat / (sqrtf(vhat) + c.eps);
+}
+
+AdamCoef make_adam_coef(const qg_hparams* hp, int64_t step);   // host, qg_adam.hip
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace qg

@@ -23,6 +23,44 @@ static int launch_project_cfg(const uint8_t* Pq, const float* Ps, const uint16_t
     return check_launch();
 }
 
+template <int BM, int BN, int BK, int WGM, int WGN, int MINWG>
+static int launch_project_adam_cfg(const uint8_t* Pq, const float* Ps, const uint16_t* G, float* R, float* M, float* V,
+                                   uint16_t* N, int m, int n, int r, const AdamCoef& coef, hipStream_t stream) {
+    const uint32_t tiles_r = (uint32_t)((r + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
+    const uint32_t tiles = tiles_r * tiles_n;
+    const bool ragged = (r % BM) || (n % BN) || (m % BK);
+    if (ragged)
+        hipLaunchKernelGGL((k_project_adam<BM, BN, BK, WGM, WGN, true, MINWG>), dim3(grid8(tiles)),
+                           dim3(WGM * WGN * 64), 0, stream, Pq, Ps, G, R, M, V, N, m, n, r, tiles_r, tiles, coef);
+    else
+        hipLaunchKernelGGL((k_project_adam<BM, BN, BK, WGM, WGN, false, MINWG>), dim3(grid8(tiles)),
+                           dim3(WGM * WGN * 64), 0, stream, Pq, Ps, G, R, M, V, N, m, n, r, tiles_r, tiles, coef);
+    return check_launch();
+}
+
+int launch_project_adam(const uint8_t* Pq, const float* Ps, const uint16_t* G, float* R, float* M, float* V,
+                        uint16_t* N, int64_t m, int64_t n, int64_t r, int64_t step, const qg_hparams* hp,
+                        hipStream_t stream) {
+    const AdamCoef coef = make_adam_coef(hp, step);
+    const int64_t big_tiles = ((r + 127) / 128) * ((n + 255) / 256);
+    if (big_tiles >= 384)
+        return launch_project_adam_cfg<128, 256, 32, 2, 2, 2>(Pq, Ps, G, R, M, V, N, (int)m, (int)n, (int)r, coef, stream);
+    return launch_project_adam_cfg<128, 128, 32, 2, 2, 2>(Pq, Ps, G, R, M, V, N, (int)m, (int)n, (int)r, coef, stream);
+}
+
+int launch_project_adam_many(const PlanHeader* plan_host, const PlanHeader* plan_dev, int write_R, int64_t step,
+                             const qg_hparams* hp, hipStream_t stream) {
+    const unsigned grid = grid8(plan_host->proj_tiles);
+    const AdamCoef coef = make_adam_coef(hp, step);
+    if (plan_host->ragged)
+        hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, true, 2>), dim3(grid), dim3(256), 0,
+                           stream, plan_dev, write_R, coef);
+    else
+        hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, false, 2>), dim3(grid), dim3(256),
+                           0, stream, plan_dev, write_R, coef);
+    return check_launch();
+}
+
 // Tile choice: 128 x 256 tiles of R with two workgroups resident per CU (one's staging and epilogue overlap the
 // other's MFMA work) when that still yields enough workgroups to fill 256 CUs twice; 128 x 128 tiles otherwise.
 int launch_project(const uint8_t* Pq, const float* Ps, const uint16_t* G, float* R, int64_t m, int64_t n, int64_t r,

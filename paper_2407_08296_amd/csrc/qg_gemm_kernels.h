@@ -96,10 +96,15 @@ struct ProjShape {
     static constexpr int SMEM = 2 * (A_STAGE + B_STAGE);  // uint16 elements
 };
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED>
+// With FUSE_ADAM the epilogue runs Adam on the tile while R is still in the accumulators: M and V are read and
+// written in place, N is stored as bf16 and R goes to memory only if the caller asked for it (R != nullptr), which
+// saves the 8 bytes per element of writing R and reading it back in a separate pass.
+template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, bool FUSE_ADAM = false>
 __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
                                              const uint16_t* __restrict__ G, float* __restrict__ R, int m, int n,
-                                             int r, int r0, int n0, uint16_t* smem) {
+                                             int r, int r0, int n0, uint16_t* smem, float* __restrict__ Mo = nullptr,
+                                             float* __restrict__ Vo = nullptr, uint16_t* __restrict__ No = nullptr,
+                                             const AdamCoef* coef = nullptr) {
     using S = ProjShape<BM, BN, BK, WGM, WGN>;
     constexpr int NT = S::NT;
     constexpr int WM = BM / WGM, WN = BN / WGN, MB = WM / 32, NB = WN / 32;
@@ -203,16 +208,59 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     }
 
     const int lcol = lane & 31, lhalf = lane >> 5;
+    if (!FUSE_ADAM) {
 #pragma unroll
-    for (int a = 0; a < MB; ++a)
+        for (int a = 0; a < MB; ++a)
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = r0 + wm * WM + a * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                for (int v = 0; v < 16; ++v) {
+                    const int row = r0 + wm * WM + a * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                    const int col = n0 + wn * WN + b * 32 + lcol;
+                    if (!RAGGED || (row < r && col < n)) R[(int64_t)row * n + col] = acc[a][b][v];
+                }
+    } else {
+        const AdamCoef c = *coef;
+        const bool odd = (lane & 1) != 0;
+#pragma unroll
+        for (int a = 0; a < MB; ++a)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
                 const int col = n0 + wn * WN + b * 32 + lcol;
-                if (!RAGGED || (row < r && col < n)) R[(int64_t)row * n + col] = acc[a][b][v];
+#pragma unroll
+                for (int v = 0; v < 16; v += 2) {
+                    // registers v, v+1 of a lane are rows i, i+1 of one column
+                    const int row = r0 + wm * WM + a * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                    const int64_t off = (int64_t)row * n + col;
+                    float nn[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const bool ok = !RAGGED || (row + e < r && col < n);
+                        const float rr = acc[a][b][v + e];
+                        float mm = ok ? Mo[off + (int64_t)e * n] : 0.f;
+                        float vv = ok ? Vo[off + (int64_t)e * n] : 0.f;
+                        nn[e] = adam_one(rr, mm, vv, c);
+                        if (ok) {
+                            if (R != nullptr) R[off + (int64_t)e * n] = rr;
+                            Mo[off + (int64_t)e * n] = mm;
+                            Vo[off + (int64_t)e * n] = vv;
+                        }
+                    }
+                    if (!RAGGED) {
+                        // pair neighbouring columns into one 4-byte bf16x2 store: even lanes write row i, odd
+                        // lanes row i+1, each taking the value it lacks from its neighbour lane
+                        const float recv = __shfl_xor(odd ? nn[0] : nn[1], 1, 64);
+                        const uint32_t pk = odd ? pack_bf16x2(recv, nn[1]) : pack_bf16x2(nn[0], recv);
+                        const int64_t o2 = odd ? off + n - 1 : off;
+                        *reinterpret_cast<uint32_t*>(No + o2) = pk;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 2; ++e)
+                            if (row + e < r && col < n) No[off + (int64_t)e * n] = to_bf16(nn[e]);
+                    }
+                }
             }
+    }
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
@@ -225,6 +273,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project(const 
     if (tile >= tiles) return;
     project_tile<BM, BN, BK, WGM, WGN, RAGGED>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
                                                (int)(tile / tiles_r) * BN, smem);
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
+__global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam(
+    const uint8_t* __restrict__ Pq, const float* __restrict__ Ps, const uint16_t* __restrict__ G,
+    float* __restrict__ R, float* __restrict__ M, float* __restrict__ V, uint16_t* __restrict__ N, int m, int n, int r,
+    uint32_t tiles_r, uint32_t tiles, AdamCoef coef) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= tiles) return;
+    project_tile<BM, BN, BK, WGM, WGN, RAGGED, true>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
+                                                     (int)(tile / tiles_r) * BN, smem, M, V, N, &coef);
 }
 
 template <typename F>
@@ -248,6 +308,20 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(c
     project_tile<BM, BN, BK, WGM, WGN, RAGGED>(d.Pq, d.Ps, d.G, d.R, (int)d.m, (int)d.n, (int)d.r,
                                                (int)(local % d.proj_tiles_r) * BM,
                                                (int)(local / d.proj_tiles_r) * BN, smem);
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
+__global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam_many(const PlanHeader* __restrict__ plan,
+                                                                                     int write_R, AdamCoef coef) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= plan->proj_tiles) return;
+    const PlanMatrix* mats = plan_matrices(plan);
+    const PlanMatrix& d = mats[plan_find(mats, plan->count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
+    const uint32_t local = tile - d.proj_tile0;
+    project_tile<BM, BN, BK, WGM, WGN, RAGGED, true>(d.Pq, d.Ps, d.G, write_R ? d.R : nullptr, (int)d.m, (int)d.n,
+                                                     (int)d.r, (int)(local % d.proj_tiles_r) * BM,
+                                                     (int)(local / d.proj_tiles_r) * BN, smem, d.M, d.V, d.N, &coef);
 }
 
 // ============================================================================

@@ -42,7 +42,7 @@ struct PlanHeader {
     uint32_t proj_tiles;
     uint32_t bp_tiles;
     uint32_t ragged;        // 1 if any matrix needs the bounds-checked kernels
-    uint32_t pad_[2];
+    uint32_t pad_[2];       // pad_[0] = 1 if some matrix has no R buffer
 };
 
 __host__ __device__ inline const PlanMatrix* plan_matrices(const PlanHeader* h) {

@@ -23,6 +23,7 @@ EXPORTS = [
     "qg_project", "qg_lowrank_adam", "qg_backproject_update_sr", "qg_cossim_workspace_bytes", "qg_subspace_cossim",
     "qg_policy_update", "qg_workspace_bytes", "qg_step", "qg_plan_bytes", "qg_plan_build", "qg_step_many",
     "qg_sr_uniform", "qg_project_many", "qg_lowrank_adam_many", "qg_backproject_update_sr_many",
+    "qg_project_adam", "qg_project_adam_many",
 ]
 
 
@@ -84,6 +85,8 @@ def lib() -> C.CDLL:
         L.qg_project_many.argtypes = [i32, vp, vp, sz, vp]
         L.qg_lowrank_adam_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), i64, vp]
         L.qg_backproject_update_sr_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), u64, i64, vp]
+        L.qg_project_adam.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i64, C.POINTER(HParams), vp]
+        L.qg_project_adam_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), i64, i32, vp]
         _lib = L
     return _lib
 
@@ -167,6 +170,12 @@ def lowrank_adam(R, M, V, N, step: int, hp: HParams) -> None:
                                  _ptr(N, _BF16), R.numel(), step, C.byref(hp), _stream()))
 
 
+def project_adam(Pq, Ps, G, R, M, V, N, m: int, n: int, r: int, step: int, hp: HParams) -> None:
+    _check(lib().qg_project_adam(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(G, _BF16),
+                                 _ptr(R, (torch.float32,)), _ptr(M, (torch.float32,)), _ptr(V, (torch.float32,)),
+                                 _ptr(N, _BF16), m, n, r, GROUP, step, C.byref(hp), _stream()))
+
+
 def backproject_update_sr(Pq, Ps, N, Wq, Ws, m: int, n: int, r: int, alpha: float, lr: float, seed: int, step: int,
                           U_debug: torch.Tensor | None = None) -> None:
     _check(lib().qg_backproject_update_sr(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(N, _BF16),
@@ -210,7 +219,7 @@ class MatrixState:
     Ws: torch.Tensor
     M: torch.Tensor
     V: torch.Tensor
-    R: torch.Tensor
+    R: torch.Tensor | None
     N: torch.Tensor
 
 
@@ -245,6 +254,11 @@ def project_many(plan: StepPlan) -> None:
 def lowrank_adam_many(plan: StepPlan, hp: HParams, step: int) -> None:
     _check(lib().qg_lowrank_adam_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
                                       C.byref(hp), step, _stream()))
+
+
+def project_adam_many(plan: StepPlan, hp: HParams, step: int, write_R: bool = False) -> None:
+    _check(lib().qg_project_adam_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
+                                      C.byref(hp), step, int(write_R), _stream()))
 
 
 def backproject_update_sr_many(plan: StepPlan, hp: HParams, seed: int, step: int) -> None:

@@ -168,6 +168,31 @@ def test_lowrank_adam(count_shape, t):
         assert np.all(bf16_t_to_f64(dN)[0, :8] == 0.0)          # zero gradient, zero moments: 0/eps = 0
 
 
+@pytest.mark.parametrize("m,n,r", [(512, 512, 128), (2048, 768, 256), (300, 700, 40), (4096, 4096, 256)])
+def test_project_adam_fused_equals_separate_calls(m, n, r):
+    d = make_inputs(m, n, r)
+    rs = np.random.default_rng(13)
+    M0 = (rs.standard_normal((r, n)) * 1e-4).astype(np.float32)
+    V0 = (rs.random((r, n)) * 1e-8).astype(np.float32)
+    Pq, Ps, G = dev(d["Pq"]), dev(d["Ps"]), dev(d["Gb"])
+    R1 = qg.project(Pq, Ps, G, m, n, r)
+    M1, V1 = dev(M0), dev(V0)
+    N1 = torch.empty((r, n), dtype=torch.bfloat16, device=DEV)
+    qg.lowrank_adam(R1, M1, V1, N1, 5, qg.hparams())
+    for with_R in (True, False):
+        M2, V2 = dev(M0), dev(V0)
+        N2 = torch.empty((r, n), dtype=torch.bfloat16, device=DEV)
+        R2 = torch.empty((r, n), dtype=torch.float32, device=DEV) if with_R else None
+        qg.project_adam(Pq, Ps, G, R2, M2, V2, N2, m, n, r, 5, qg.hparams())
+        assert torch.equal(M1, M2) and torch.equal(V1, V2)
+        assert torch.equal(N1.view(torch.int16), N2.view(torch.int16))
+        if with_R:
+            assert torch.equal(R1, R2)
+    oM, oV, oN = Q.lowrank_adam(Q.project(d["Pq"], d["Ps"], d["Gb"], m, n, r), M0, V0, 5, HP)
+    assert rel_fro(host(M1), oM) <= 2e-5 and rel_fro(host(V1), oV) <= 4e-5
+    assert rel_fro(bf16_t_to_f64(N1), Q.bf16_rne(oN)) <= 1e-3
+
+
 # ------------------------------------------------------------------ back-projection + SR update
 @pytest.mark.parametrize("m,n,r", [(512, 512, 128), (768, 768, 256), (2048, 768, 256), (768, 2048, 256),
                                    (300, 700, 40), (1000, 264, 8), (4096, 4096, 64)])
