@@ -131,35 +131,51 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
     h.magic = kPlanMagic;
     h.count = count;
     PlanMatrix* mats = reinterpret_cast<PlanMatrix*>(reinterpret_cast<char*>(plan_host) + sizeof(PlanHeader));
-    uint64_t adam = 0, proj = 0, bp = 0;
     for (int i = 0; i < count; ++i) {
         const qg_matrix_desc& d = descs[i];
         if (!d.Pq || !d.Ps || !d.G || !d.Wq || !d.Ws || !d.M || !d.V || !d.N) return QG_ERR_NULL;
-        if (!d.R) h.pad_[0] = 1;   // some matrix has no R buffer: the unfused phases cannot run on this plan
+        if (!d.R) h.no_R = 1;   // the unfused phases cannot run on this plan
         if (int e = check_mnr(d.m, d.n, d.r, kGroup)) return e;
         if (!aligned16(d.Pq) || !aligned16(d.Ps) || !aligned16(d.G) || !aligned16(d.Wq) || !aligned16(d.Ws) ||
             !aligned16(d.M) || !aligned16(d.V) || (d.R && !aligned16(d.R)) || !aligned16(d.N))
             return QG_ERR_ALIGN;
-        PlanMatrix pm;
-        std::memset(&pm, 0, sizeof pm);
-        pm.m = d.m; pm.n = d.n; pm.r = d.r;
-        pm.Pq = d.Pq; pm.Ps = d.Ps; pm.G = d.G; pm.Wq = d.Wq; pm.Ws = d.Ws;
-        pm.M = d.M; pm.V = d.V; pm.R = d.R; pm.N = d.N;
-        pm.adam_chunk0 = (uint32_t)adam;
-        pm.proj_tile0 = (uint32_t)proj;
-        pm.bp_tile0 = (uint32_t)bp;
-        pm.proj_tiles_r = (uint32_t)((d.r + kManyProjBM - 1) / kManyProjBM);
-        pm.bp_tiles_m = (uint32_t)((d.m + kManyBpBM - 1) / kManyBpBM);
-        adam += (uint64_t)((d.r * d.n + kAdamChunkElems - 1) / kAdamChunkElems);
-        proj += (uint64_t)pm.proj_tiles_r * (uint64_t)((d.n + kManyProjBN - 1) / kManyProjBN);
-        bp += (uint64_t)pm.bp_tiles_m * (uint64_t)((d.n + kManyBpBN - 1) / kManyBpBN);
-        if ((d.r % kManyProjBM) || (d.n % 256) || (d.m % 256)) h.ragged = 1;
-        mats[i] = pm;
     }
-    if (adam > 0x7FFFFFF0ull || proj > 0x7FFFFFF0ull || bp > 0x7FFFFFF0ull) return QG_ERR_SHAPE;
+    // shapes that fit the unguarded kernels: whole tiles everywhere and an even number of K steps
+    auto is_fast = [](const qg_matrix_desc& d) {
+        return (d.r % kManyProjBM) == 0 && (d.n % 256) == 0 && (d.m % 256) == 0;
+    };
+    uint64_t adam = 0, proj[2] = {0, 0}, bp[2] = {0, 0};
+    int out = 0;
+    for (int cls = 0; cls < 2; ++cls) {
+        for (int i = 0; i < count; ++i) {
+            const qg_matrix_desc& d = descs[i];
+            if ((is_fast(d) ? 0 : 1) != cls) continue;
+            PlanMatrix pm;
+            std::memset(&pm, 0, sizeof pm);
+            pm.m = d.m; pm.n = d.n; pm.r = d.r;
+            pm.Pq = d.Pq; pm.Ps = d.Ps; pm.G = d.G; pm.Wq = d.Wq; pm.Ws = d.Ws;
+            pm.M = d.M; pm.V = d.V; pm.R = d.R; pm.N = d.N;
+            pm.index = (uint32_t)i;
+            pm.adam_chunk0 = (uint32_t)adam;
+            pm.proj_tile0 = (uint32_t)proj[cls];
+            pm.bp_tile0 = (uint32_t)bp[cls];
+            pm.proj_tiles_r = (uint32_t)((d.r + kManyProjBM - 1) / kManyProjBM);
+            pm.bp_tiles_m = (uint32_t)((d.m + kManyBpBM - 1) / kManyBpBM);
+            adam += (uint64_t)((d.r * d.n + kAdamChunkElems - 1) / kAdamChunkElems);
+            proj[cls] += (uint64_t)pm.proj_tiles_r * (uint64_t)((d.n + kManyProjBN - 1) / kManyProjBN);
+            bp[cls] += (uint64_t)pm.bp_tiles_m * (uint64_t)((d.n + kManyBpBN - 1) / kManyBpBN);
+            mats[out++] = pm;
+        }
+        if (cls == 0) h.n_fast = out;
+    }
+    if (adam > 0x7FFFFFF0ull || proj[0] > 0x7FFFFFF0ull || proj[1] > 0x7FFFFFF0ull || bp[0] > 0x7FFFFFF0ull ||
+        bp[1] > 0x7FFFFFF0ull)
+        return QG_ERR_SHAPE;
     h.adam_chunks = (uint32_t)adam;
-    h.proj_tiles = (uint32_t)proj;
-    h.bp_tiles = (uint32_t)bp;
+    for (int cls = 0; cls < 2; ++cls) {
+        h.proj_tiles[cls] = (uint32_t)proj[cls];
+        h.bp_tiles[cls] = (uint32_t)bp[cls];
+    }
     std::memcpy(plan_host, &h, sizeof h);
     return QG_OK;
 }
@@ -177,7 +193,7 @@ static int check_plan(int count, const void* plan_host, const void* plan_dev, si
 extern "C" int qg_project_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
                                void* stream) {
     if (int e = check_plan(count, plan_host, plan_dev, plan_bytes)) return e;
-    if (reinterpret_cast<const PlanHeader*>(plan_host)->pad_[0]) return QG_ERR_NULL;   // needs every R buffer
+    if (reinterpret_cast<const PlanHeader*>(plan_host)->no_R) return QG_ERR_NULL;   // needs every R buffer
     return launch_project_many(reinterpret_cast<const PlanHeader*>(plan_host),
                                reinterpret_cast<const PlanHeader*>(plan_dev), (hipStream_t)stream);
 }
@@ -187,7 +203,7 @@ extern "C" int qg_lowrank_adam_many(int count, const void* plan_host, const void
     if (int e = check_plan(count, plan_host, plan_dev, plan_bytes)) return e;
     if (!hp) return QG_ERR_NULL;
     if (step < 1) return QG_ERR_SHAPE;
-    if (reinterpret_cast<const PlanHeader*>(plan_host)->pad_[0]) return QG_ERR_NULL;   // needs every R buffer
+    if (reinterpret_cast<const PlanHeader*>(plan_host)->no_R) return QG_ERR_NULL;   // needs every R buffer
     return launch_adam_many(reinterpret_cast<const PlanHeader*>(plan_host),
                             reinterpret_cast<const PlanHeader*>(plan_dev), step, hp, (hipStream_t)stream);
 }
@@ -221,7 +237,7 @@ extern "C" int qg_project_adam_many(int count, const void* plan_host, const void
     if (!hp) return QG_ERR_NULL;
     if (step < 1) return QG_ERR_SHAPE;
     const PlanHeader* h = reinterpret_cast<const PlanHeader*>(plan_host);
-    if (write_R && h->pad_[0]) return QG_ERR_NULL;
+    if (write_R && h->no_R) return QG_ERR_NULL;
     return launch_project_adam_many(h, reinterpret_cast<const PlanHeader*>(plan_dev), write_R ? 1 : 0, step, hp,
                                     (hipStream_t)stream);
 }

@@ -48,17 +48,26 @@ int launch_project_adam(const uint8_t* Pq, const float* Ps, const uint16_t* G, f
     return launch_project_adam_cfg<128, 128, 32, 2, 2, 2>(Pq, Ps, G, R, M, V, N, (int)m, (int)n, (int)r, coef, stream);
 }
 
+// Grouped launches: class 0 = matrices [0, n_fast) with the unguarded kernels, class 1 = the rest, guarded.
+static inline int class_first(const PlanHeader* h, int cls) { return cls == 0 ? 0 : h->n_fast; }
+static inline int class_count(const PlanHeader* h, int cls) { return cls == 0 ? h->n_fast : h->count - h->n_fast; }
+
 int launch_project_adam_many(const PlanHeader* plan_host, const PlanHeader* plan_dev, int write_R, int64_t step,
                              const qg_hparams* hp, hipStream_t stream) {
-    const unsigned grid = grid8(plan_host->proj_tiles);
     const AdamCoef coef = make_adam_coef(hp, step);
-    if (plan_host->ragged)
-        hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, true, 2>), dim3(grid), dim3(256), 0,
-                           stream, plan_dev, write_R, coef);
-    else
-        hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, false, 2>), dim3(grid), dim3(256),
-                           0, stream, plan_dev, write_R, coef);
-    return check_launch();
+    for (int cls = 0; cls < 2; ++cls) {
+        const int cnt = class_count(plan_host, cls);
+        const uint32_t tiles = plan_host->proj_tiles[cls];
+        if (cnt == 0 || tiles == 0) continue;
+        if (cls == 0)
+            hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, false, 2>), dim3(grid8(tiles)),
+                               dim3(256), 0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, write_R, coef);
+        else
+            hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, true, 2>), dim3(grid8(tiles)),
+                               dim3(256), 0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, write_R, coef);
+        if (int e = check_launch()) return e;
+    }
+    return QG_OK;
 }
 
 // Tile choice: 128 x 256 tiles of R with two workgroups resident per CU (one's staging and epilogue overlap the
@@ -102,26 +111,38 @@ int launch_backproject(const uint8_t* Pq, const float* Ps, const uint16_t* N, in
 }
 
 int launch_project_many(const PlanHeader* plan_host, const PlanHeader* plan_dev, hipStream_t stream) {
-    const unsigned grid = grid8(plan_host->proj_tiles);
-    if (plan_host->ragged)
-        hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, true, 2>), dim3(grid), dim3(256), 0, stream,
-                           plan_dev);
-    else
-        hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, false, 2>), dim3(grid), dim3(256), 0,
-                           stream, plan_dev);
-    return check_launch();
+    for (int cls = 0; cls < 2; ++cls) {
+        const int cnt = class_count(plan_host, cls);
+        const uint32_t tiles = plan_host->proj_tiles[cls];
+        if (cnt == 0 || tiles == 0) continue;
+        if (cls == 0)
+            hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, false, 2>), dim3(grid8(tiles)),
+                               dim3(256), 0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles);
+        else
+            hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, true, 2>), dim3(grid8(tiles)),
+                               dim3(256), 0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles);
+        if (int e = check_launch()) return e;
+    }
+    return QG_OK;
 }
 
 int launch_backproject_many(const PlanHeader* plan_host, const PlanHeader* plan_dev, float alpha, float lr,
                             uint64_t seed, int64_t step, hipStream_t stream) {
-    const unsigned grid = grid8(plan_host->bp_tiles);
-    if (plan_host->ragged)
-        hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, true, false, 2>), dim3(grid), dim3(256), 0, stream, plan_dev,
-                           alpha, lr, seed, (uint64_t)step);
-    else
-        hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, false, false, 2>), dim3(grid), dim3(256), 0, stream,
-                           plan_dev, alpha, lr, seed, (uint64_t)step);
-    return check_launch();
+    for (int cls = 0; cls < 2; ++cls) {
+        const int cnt = class_count(plan_host, cls);
+        const uint32_t tiles = plan_host->bp_tiles[cls];
+        if (cnt == 0 || tiles == 0) continue;
+        if (cls == 0)
+            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, false, false, 2>), dim3(grid8(tiles)), dim3(256),
+                               0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, alpha, lr, seed,
+                               (uint64_t)step);
+        else
+            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, true, false, 2>), dim3(grid8(tiles)), dim3(256),
+                               0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, alpha, lr, seed,
+                               (uint64_t)step);
+        if (int e = check_launch()) return e;
+    }
+    return QG_OK;
 }
 
 }  // namespace qg

@@ -298,12 +298,13 @@ __device__ __forceinline__ int plan_find(const PlanMatrix* mats, int count, uint
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
-__global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(const PlanHeader* __restrict__ plan) {
+__global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(const PlanHeader* __restrict__ plan, int first,
+                                                                               int count, uint32_t tiles) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
-    if (tile >= plan->proj_tiles) return;
-    const PlanMatrix* mats = plan_matrices(plan);
-    const PlanMatrix& d = mats[plan_find(mats, plan->count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
+    if (tile >= tiles) return;
+    const PlanMatrix* mats = plan_matrices(plan) + first;
+    const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
     const uint32_t local = tile - d.proj_tile0;
     project_tile<BM, BN, BK, WGM, WGN, RAGGED>(d.Pq, d.Ps, d.G, d.R, (int)d.m, (int)d.n, (int)d.r,
                                                (int)(local % d.proj_tiles_r) * BM,
@@ -312,12 +313,14 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(c
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam_many(const PlanHeader* __restrict__ plan,
-                                                                                     int write_R, AdamCoef coef) {
+                                                                                     int first, int count,
+                                                                                     uint32_t tiles, int write_R,
+                                                                                     AdamCoef coef) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
-    if (tile >= plan->proj_tiles) return;
-    const PlanMatrix* mats = plan_matrices(plan);
-    const PlanMatrix& d = mats[plan_find(mats, plan->count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
+    if (tile >= tiles) return;
+    const PlanMatrix* mats = plan_matrices(plan) + first;
+    const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
     const uint32_t local = tile - d.proj_tile0;
     project_tile<BM, BN, BK, WGM, WGN, RAGGED, true>(d.Pq, d.Ps, d.G, write_R ? d.R : nullptr, (int)d.m, (int)d.n,
                                                      (int)d.r, (int)(local % d.proj_tiles_r) * BM,
@@ -385,8 +388,10 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     const bool vec8 = (n & 7) == 0;
 
     // ---- weight tile -> LDS (asynchronous direct loads where shapes allow) ----
+    // whole tile inside the matrix and rows 16-byte aligned: the wide path works even in the guarded kernel
+    const bool w_fast = !RAGGED || (m0 + BMm <= m && n0 + BNn <= n && (n & 15) == 0);
     auto load_wtile = [&]() {
-    if (!RAGGED) {
+    if (w_fast) {
 #pragma unroll
         for (int i = 0; i < W_ROUNDS; ++i) {
             const int rb = (wave * W_ROUNDS + i) * 4;             // first of the 4 rows this wave access covers
@@ -569,7 +574,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     __syncthreads();
 
     // ---- updated tile -> global, whole 256-byte rows per 16 lanes ----
-    if (!RAGGED) {
+    if (w_fast) {
 #pragma unroll
         for (int i = 0; i < W_ROUNDS; ++i) {
             const int row = (wave * W_ROUNDS + i) * 4 + (lane >> 4), chunk = (lane ^ row) & 15;
@@ -600,16 +605,17 @@ __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject(co
 }
 
 template <int BMm, int BK, int WGn, int WGm, bool RAGGED, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
-__global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_many(const PlanHeader* __restrict__ plan, float alpha,
-                                                                    float lr, uint64_t seed, uint64_t step) {
+__global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_many(const PlanHeader* __restrict__ plan, int first,
+                                                                                   int count, uint32_t tiles,
+                                                                                   float alpha, float lr,
+                                                                                   uint64_t seed, uint64_t step) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
-    if (tile >= plan->bp_tiles) return;
-    const PlanMatrix* mats = plan_matrices(plan);
-    const int mi = plan_find(mats, plan->count, tile, [](const PlanMatrix& x) { return x.bp_tile0; });
-    const PlanMatrix& d = mats[mi];
+    if (tile >= tiles) return;
+    const PlanMatrix* mats = plan_matrices(plan) + first;
+    const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.bp_tile0; })];
     const uint32_t local = tile - d.bp_tile0;
-    const uint32_t key = sr_key(seed + (uint64_t)mi * 0x9E3779B97F4A7C15ull, step, 0u);
+    const uint32_t key = sr_key(seed + (uint64_t)d.index * 0x9E3779B97F4A7C15ull, step, 0u);
     backproject_tile<BMm, BK, WGn, WGm, RAGGED, false, W_PREFETCH>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.r,
                                                 (int)(local % d.bp_tiles_m) * BMm, (int)(local / d.bp_tiles_m),
                                                 alpha, lr, key, smem);

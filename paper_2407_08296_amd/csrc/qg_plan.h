@@ -32,18 +32,23 @@ struct PlanMatrix {
     uint32_t bp_tile0;      // first back-projection tile
     uint32_t proj_tiles_r;  // tiles along r of the projection
     uint32_t bp_tiles_m;    // tiles along m of the back-projection
-    uint32_t pad_;
+    uint32_t index;         // position in the caller's descriptor array (selects the SR seed of the matrix)
 };
 
+// The records are stored in two classes, each served by its own launch: first the `n_fast` matrices whose
+// shapes fit the unguarded kernels, then the rest (bounds-checked kernels).  Tile indices (proj_tile0, bp_tile0)
+// count within a class; Adam chunks run over all matrices.
 struct PlanHeader {
     uint32_t magic;
     int32_t count;
     uint32_t adam_chunks;
-    uint32_t proj_tiles;
-    uint32_t bp_tiles;
-    uint32_t ragged;        // 1 if any matrix needs the bounds-checked kernels
-    uint32_t pad_[2];       // pad_[0] = 1 if some matrix has no R buffer
+    int32_t n_fast;            // matrices [0, n_fast) are the unguarded class
+    uint32_t proj_tiles[2];    // per class: fast, guarded
+    uint32_t bp_tiles[2];
+    uint32_t no_R;             // 1 if some matrix has no R buffer
+    uint32_t pad_[3];
 };
+static_assert(sizeof(PlanHeader) % 16 == 0, "records must stay 16-byte aligned");
 
 __host__ __device__ inline const PlanMatrix* plan_matrices(const PlanHeader* h) {
     return reinterpret_cast<const PlanMatrix*>(h + 1);

@@ -81,15 +81,16 @@ def test_plan_build_on_host(L):
     buf = C.create_string_buffer(nbytes)
     assert L.qg_plan_build(2, descs, buf, nbytes - 1) == 5
     assert L.qg_plan_build(2, descs, buf, nbytes) == 0
-    hdr = (C.c_uint32 * 8).from_buffer(buf)
+    hdr = (C.c_uint32 * 12).from_buffer(buf)
     assert hdr[1] == 2                                       # count
     assert hdr[2] == 2 * (1024 * 4096) // 4096               # Adam chunks of 4096 elements
-    assert hdr[3] == 2 * 8 * 16                              # projection tiles 128 x 256 over r x n
-    assert hdr[4] == 32 * 16 + 86 * 16                       # back-projection tiles 128 x 256 over m x n
-    assert hdr[5] == 0                                       # nothing ragged
+    assert hdr[3] == 2                                       # both matrices fit the unguarded kernels
+    assert (hdr[4], hdr[5]) == (2 * 8 * 16, 0)               # projection tiles 128 x 256 over r x n, per class
+    assert (hdr[6], hdr[7]) == (32 * 16 + 86 * 16, 0)        # back-projection tiles 128 x 256 over m x n
     descs[1].n = 5461
     assert L.qg_plan_build(2, descs, buf, nbytes) == 0
-    assert (C.c_uint32 * 8).from_buffer(buf)[5] == 1
+    hdr = (C.c_uint32 * 12).from_buffer(buf)
+    assert hdr[3] == 1 and (hdr[4], hdr[5]) == (8 * 16, 8 * 22) and (hdr[6], hdr[7]) == (32 * 16, 86 * 22)
     descs[1].r = 12
     assert L.qg_plan_build(2, descs, buf, nbytes) == 2
     descs[1].r = 1024
