@@ -94,7 +94,7 @@ def step(Wq, Ws, Gbits, Pcodes, Ps, M, V, t, hp, seed):
     fp32-valued.  Returns dict of lists: R, M, V, Nb, U, Wq, Ws."""
     b1, b2, eps, lr, alpha = hp
     m, n, r = len(Wq), len(Wq[0]), len(Pcodes[0])
-    Pd = [[bf16(Pcodes[i][k] * Ps[(i * r + k) // GROUP]) for k in range(r)] for i in range(m)]
+    Pd = [[bf16(fl32(Pcodes[i][k] * Ps[(i * r + k) // GROUP])) for k in range(r)] for i in range(m)]
     G = [[bf16_from_bits(Gbits[i][j]) for j in range(n)] for i in range(m)]
     R = [[math.fsum(Pd[i][k] * G[i][j] for i in range(m)) for j in range(n)] for k in range(r)]
     M1 = [[b1 * M[k][j] + (1.0 - b1) * R[k][j] for j in range(n)] for k in range(r)]

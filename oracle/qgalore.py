@@ -260,8 +260,9 @@ class HParams:
 
 
 def dequant_p_bf16(Pq, Ps, m: int, r: int) -> np.ndarray:
-    """P as the GEMMs see it: code * scale (exact), rounded once to bf16."""
-    return bf16_rne(dequant_int4(Pq, Ps, m, r))
+    """P as the GEMMs see it: dequantized by a floating-point multiply, code * scale rounded to fp32 (the form of
+    the Appendix A dequantization, a product in a floating type), then stored as a bf16 GEMM operand (Sec. 3.1)."""
+    return bf16_rne(dequant_int4(Pq, Ps, m, r).astype(np.float32).astype(np.float64))
 
 
 def project(Pq, Ps, G_bits, m: int, n: int, r: int) -> np.ndarray:

@@ -60,8 +60,6 @@ def check_first_step_direction(gN, gR, o):
     eps = float(np.float32(1e-8))
     oR, oN = o["R"], o["Nb"]
     dR = float(np.abs(gR.astype(np.float64) - oR).max())
-    # the largest deviations come from elements of dequant(P) whose bf16 rounding differs (fp32-then-bf16 in the
-    # library, exact-then-bf16 in the oracle): one bf16 spacing of P times one element of G
     assert dR <= 1e-3 * float(np.sqrt(np.mean(oR ** 2)))
     band = np.abs(oR) < 64 * eps
     assert band.mean() < 0.05
@@ -301,6 +299,95 @@ def test_step_many_matches_oracle(shapes):
         assert rel_fro(host(s.M), o["M"]) <= 2e-5 and rel_fro(host(s.V), o["V"]) <= 4e-5
         check_codes(host(s.Wq), o["Wq"])
         check_scales_step(host(s.Ws), o["Ws"])
+
+
+def _check_many(mats, data, seed, t=1):
+    worst = 1.0
+    for i, (s, d) in enumerate(zip(mats, data)):
+        o = Q.step(d["Wq"], d["Ws"], d["Gb"], d["Pq"], d["Ps"], np.zeros((s.r, s.n)), np.zeros((s.r, s.n)), t, HP,
+                   seed=(seed + i * 0x9E3779B97F4A7C15) % 2 ** 64, r=s.r)
+        assert rel_fro(host(s.R), o["R"]) <= 2e-5
+        assert rel_fro(bf16_t_to_f64(s.N), o["Nb"]) <= 1e-3
+        assert rel_fro(host(s.M), o["M"]) <= 2e-5 and rel_fro(host(s.V), o["V"]) <= 4e-5
+        worst = min(worst, check_codes(host(s.Wq), o["Wq"]))
+        check_scales_step(host(s.Ws), o["Ws"], rel=5e-4)
+    return worst
+
+
+def test_config1_llama130m_full_step():
+    """Config 1: all 84 linear weights of the LLaMA-130M shapes (r = 256), one grouped step, every matrix checked
+    in full against the oracle."""
+    shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(1)]
+    mats, data = [], []
+    for (layer, kind, m, n, r) in I.config_matrices(1):
+        d = make_inputs(m, n, r, layer=layer, kind=kind)
+        data.append(d)
+        mats.append(qg.MatrixState(m, n, r, dev(d["Pq"]), dev(d["Ps"]), dev(d["Gb"]), dev(d["Wq"]), dev(d["Ws"]),
+                                   torch.zeros((r, n), dtype=torch.float32, device=DEV),
+                                   torch.zeros((r, n), dtype=torch.float32, device=DEV),
+                                   torch.empty((r, n), dtype=torch.float32, device=DEV),
+                                   torch.empty((r, n), dtype=torch.bfloat16, device=DEV)))
+    assert len(mats) == 84 and len(shapes) == 84
+    qg.step_many(qg.StepPlan(mats), qg.hparams(), 0, 1)
+    torch.cuda.synchronize()
+    print("lowest identical-code fraction over 84 matrices:", _check_many(mats, data, 0))
+
+
+@pytest.mark.parametrize("config", [2, 3])
+def test_one_layer_of_ragged_configs(config):
+    """One decoder layer (7 matrices) of the LLaMA-350M (ffn 2736) and LLaMA-1B (ffn 5461, r = 512) shapes: rows
+    and columns that are not multiples of the tile, rows of G and W that are not 16-byte aligned, short last
+    quantization blocks (176 and 85 columns), aligned and ragged matrices in one plan."""
+    _, _, _, r = I.LLAMA_SHAPES[config]
+    mats, data = [], []
+    for ki, (_, m, n) in enumerate(I.layer_shapes(config)):
+        d = make_inputs(m, n, r, kind=ki)
+        data.append(d)
+        mats.append(qg.MatrixState(m, n, r, dev(d["Pq"]), dev(d["Ps"]), dev(d["Gb"]), dev(d["Wq"]), dev(d["Ws"]),
+                                   torch.zeros((r, n), dtype=torch.float32, device=DEV),
+                                   torch.zeros((r, n), dtype=torch.float32, device=DEV),
+                                   torch.empty((r, n), dtype=torch.float32, device=DEV),
+                                   torch.empty((r, n), dtype=torch.bfloat16, device=DEV)))
+    qg.step_many(qg.StepPlan(mats), qg.hparams(), 7, 1)
+    torch.cuda.synchronize()
+    _check_many(mats, data, 7)
+
+
+def test_refresh_check_and_policy_between_steps():
+    """Config 1's schedule shortened: steps with a subspace check every 5 steps (instead of 200).  At a check the
+    new projection (a neighbour of the old one, or an unrelated one) is quantized by the library, compared with the
+    old one by qg_subspace_cossim, and the host policy decides the next interval; steps then continue with the new P.
+    Every GPU step starts from the oracle's state."""
+    m, n, r = 768, 768, 256
+    d = make_inputs(m, n, r)
+    Pf = d["P"]
+    Pq, Ps = d["Pq"], d["Ps"]
+    pol = qg.Policy(5, 0, 1, 5, 0.4, 0.0)
+    opol = Q.Policy(interval=5, k=1, threshold=0.4, next_refresh=5)
+    M = np.zeros((r, n), np.float32); V = np.zeros((r, n), np.float32)
+    Wq, Ws = d["Wq"], d["Ws"]
+    checks = 0
+    for t in range(1, 17):
+        if t == pol.next_refresh:
+            Pnew = I.perturbed_projection_f32(Pf, 0.02, layer=t) if checks == 0 else I.projection_f32(m, r, layer=t)
+            gq, gs = qg.quant_int4(dev(Pnew))
+            oq, os_ = Q.quant_int4(Pnew)
+            assert np.array_equal(host(gq), oq) and np.array_equal(host(gs), os_)
+            c = float(host(qg.subspace_cossim(dev(Pq), dev(Ps), gq, gs, m, r))[0])
+            oc = Q.subspace_cossim(Pq, Ps, oq, os_, m, r)
+            assert abs(c - oc) <= 1e-5
+            assert qg.policy_update(pol, c) == opol.update(float(np.float32(oc)))
+            assert (pol.interval, pol.next_refresh) == (opol.interval, opol.next_refresh)
+            Pf, Pq, Ps = Pnew, oq, os_
+            checks += 1
+        Gb = I.gradient_bf16(m, n, t)
+        o = Q.step(Wq, Ws, Gb, Pq, Ps, M, V, t, HP, seed=0, r=r)
+        g = _run_step_gpu(dict(Wq=Wq, Pq=Pq, Ps=Ps), dict(Wq=Wq, Ws=Ws, M=M, V=V, Gb=Gb), t, 0, r)
+        assert rel_fro(g["R"], o["R"]) <= 1e-3 and rel_fro(g["Nb"], o["Nb"]) <= 1e-3
+        check_codes(g["Wq"], o["Wq"])
+        Wq, Ws, M, V = o["Wq"], o["Ws"], o["M"].astype(np.float32), o["V"].astype(np.float32)
+    # first check: neighbouring subspace -> interval doubled (5 -> 10, next at 15); second: unrelated -> stays
+    assert checks == 2 and pol.interval == 10 and pol.next_refresh == 25
 
 
 # ------------------------------------------------------------------ full-size shapes, sampled

@@ -60,7 +60,7 @@ def test_project_is_transposed_product_not_plain():
         for j in (0, 100, 255):
             acc = 0.0
             for i in range(m):
-                acc += brute.bf16(float(codes[i, k]) * float(s[(i * r + k) // 256])) * G[i, j]
+                acc += brute.bf16(brute.fl32(float(codes[i, k]) * float(s[(i * r + k) // 256]))) * G[i, j]
             assert abs(R[k, j] - acc) <= 1e-12 * max(1.0, abs(acc))
 
 
