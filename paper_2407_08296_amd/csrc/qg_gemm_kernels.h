@@ -22,6 +22,10 @@
 namespace qg {
 
 constexpr int kPadK = 32;  // bf16 of padding per row of a K-major tile (64 B: rows k..k+3 hit distinct bank groups)
+#ifndef QG_MFMA_PRIO
+#define QG_MFMA_PRIO 1
+#endif
+constexpr int kMfmaPrio = QG_MFMA_PRIO;   // wave priority during the MFMA phase of a K step (0 outside)
 constexpr int kPadX = 8;   // bf16 of padding per row of a K-contiguous tile (16 B)
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -190,6 +194,9 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
         if (kt + 1 < KT) gload(kt + 1);
         const uint16_t* Ac = As + cur * S::A_STAGE + a_lane;
         const uint16_t* Bc = Bs + cur * S::B_STAGE + b_lane;
+        // With two workgroups per CU a SIMD holds two waves; the one in its MFMA phase gets issue priority so the
+        // matrix pipe stays fed while the other wave's staging instructions fill the gaps.
+        __builtin_amdgcn_s_setprio(kMfmaPrio);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 af[MB], bf[NB];
@@ -203,6 +210,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
                 for (int b = 0; b < NB; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
         if (kt + 1 < KT) sstore(cur ^ 1);
         __syncthreads();
     }
@@ -480,6 +488,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         if (kt + 1 < KT) gload(kt + 1);
         const uint16_t* Ac = As + cur * S::A_STAGE + a_lane;
         const uint16_t* Bc = Bs + cur * S::B_STAGE + b_lane;
+        __builtin_amdgcn_s_setprio(kMfmaPrio);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 af[IB], bf[JB];
@@ -494,6 +503,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
                 for (int b = 0; b < JB; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
         if (kt + 1 < KT) sstore(cur ^ 1);
         __syncthreads();
     }
