@@ -138,6 +138,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rsweep", action="store_true",
+                    help="time qg_project / qg_lowrank_adam / qg_backproject_update_sr on one 2048x5461 matrix for "
+                         "r in {128, 256, 512, 1024} (the roofline crossover of the LLaMA-1B shape) and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -163,6 +166,38 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
+        return
+
+    if args.rsweep:
+        m, n = 2048, 5461
+        rows = []
+        for r in (128, 256, 512, 1024):
+            P = torch.from_numpy(I.projection_f32(m, r)).to(device)
+            Pq, Ps = qg.quant_int4(P)
+            Wq, Ws = qg.quant_int8(torch.randn((m, n), device=device) * 0.02)
+            G = (torch.randn((m, n), device=device) * 1e-3).to(torch.bfloat16)
+            M = torch.zeros((r, n), device=device); V = torch.zeros((r, n), device=device)
+            R = torch.empty((r, n), device=device); N = torch.empty((r, n), dtype=torch.bfloat16, device=device)
+            hp = qg.hparams()
+            def run(f, reps=20):
+                f(); torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    f()
+                e1.record(); torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
+            tp = run(lambda: qg.project(Pq, Ps, G, m, n, r, R))
+            ta = run(lambda: qg.lowrank_adam(R, M, V, N, 2, hp))
+            tb = run(lambda: qg.backproject_update_sr(Pq, Ps, N, Wq, Ws, m, n, r, 0.25, 1e-3, 0, 2))
+            flops, b_proj, b_adam, b_bp = algorithmic_work([(m, n, r)])
+            rows.append({"r": r, "project_us": tp * 1e3, "project_TFLOP/s": flops / tp / 1e9,
+                         "project_GB/s": b_proj / tp / 1e6, "adam_us": ta * 1e3, "adam_GB/s": b_adam / ta / 1e6,
+                         "backproject_us": tb * 1e3, "backproject_TFLOP/s": flops / tb / 1e9,
+                         "backproject_GB/s": b_bp / tb / 1e6,
+                         "mfma_bound_us": flops / PEAK_BF16_TFLOPS / 1e6, "hbm_bound_project_us": b_proj / PEAK_HBM_GBS / 1e3,
+                         "hbm_bound_backproject_us": b_bp / PEAK_HBM_GBS / 1e3})
+        print(json.dumps({"rsweep": {"m": m, "n": n, "rows": rows}}))
         return
 
     shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(args.config)]

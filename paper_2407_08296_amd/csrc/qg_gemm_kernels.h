@@ -45,9 +45,19 @@ __device__ __forceinline__ bf16x8 read_kmajor_frag(const uint16_t* p, int pitch)
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// 8 consecutive bf16 starting at `src`, guarded per element (ragged shapes).
-__device__ __forceinline__ u32x4 load8_bf16_guarded(const uint16_t* src, int valid, bool vec) {
-    if (valid >= 8 && vec) return *reinterpret_cast<const u32x4*>(src);
+// Vector types with the alignment of their elements only: rows of a matrix with an odd (or merely not 8-aligned)
+// row length start at arbitrary element offsets.  Global memory accesses need no natural alignment on this target,
+// so these still compile to single wide loads and stores.
+typedef u32x4 __attribute__((aligned(2))) u32x4_align2;
+typedef u32x4 __attribute__((aligned(1))) u32x4_align1;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef u32x2 __attribute__((aligned(4))) u32x2_align4;
+typedef u32x4 __attribute__((aligned(4))) u32x4_align4;
+
+// 8 consecutive bf16 starting at `src`, of which the first `valid` lie inside the matrix (ragged shapes): one
+// 16-byte load when all do, element by element for the chunk that straddles the edge, zeros outside.
+__device__ __forceinline__ u32x4 load8_bf16_guarded(const uint16_t* src, int valid) {
+    if (valid >= 8) return *reinterpret_cast<const u32x4_align2*>(src);
     uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -71,12 +81,43 @@ __device__ __forceinline__ void load_words(const uint8_t* p, uint32_t (&w)[WPT])
     }
 }
 
-// Words of INT4 codes a thread fetches with one load when staging a P tile: as wide as the tile allows
-// (the unguarded kernels only; 8*WPT codes never straddle a block of 256 because tiles start at multiples of 32).
+// Guarded fetch of WPT words of INT4 codes starting at flat element index e (a multiple of 8), of which the first
+// `valid` codes lie inside the matrix.  Every word carries the scale of its own block: with r not a multiple of
+// 8*WPT the words of one fetch can fall into two blocks of 256.  Words outside read as code 0, scale 0.
+template <int WPT>
+__device__ __forceinline__ void load_p_guarded(const uint8_t* Pq, const float* Ps, int64_t e, int valid,
+                                               uint32_t (&w)[WPT], float (&sc)[WPT]) {
+    const uint8_t* p = Pq + (e >> 1);
+    if (valid >= 8 * WPT) {
+        if constexpr (WPT == 4) {
+            const u32x4 v = *reinterpret_cast<const u32x4_align4*>(p);
+            w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+        } else if constexpr (WPT == 2) {
+            const u32x2 v = *reinterpret_cast<const u32x2_align4*>(p);
+            w[0] = v[0]; w[1] = v[1];
+        } else {
+            w[0] = *reinterpret_cast<const uint32_t*>(p);
+        }
+#pragma unroll
+        for (int j = 0; j < WPT; ++j) sc[j] = Ps[(e + 8 * j) >> 8];
+    } else {
+#pragma unroll
+        for (int j = 0; j < WPT; ++j) {
+            const bool ok = valid > 8 * j;
+            w[j] = ok ? *reinterpret_cast<const uint32_t*>(p + 4 * j) : 0x88888888u;
+            sc[j] = ok ? Ps[(e + 8 * j) >> 8] : 0.f;
+        }
+    }
+}
+
+// Words of INT4 codes a thread fetches with one load when staging a P tile: as wide as the tile allows.  In the
+// unguarded kernels 8*WPT codes never straddle a block of 256 (tiles start at multiples of 32 and r is a multiple
+// of the tile), so one scale serves the fetch; the guarded kernels keep a scale per word.
 template <int WORDS, int NT, bool RAGGED>
 struct P_Task {
-    static constexpr int WPT = RAGGED ? 1 : (WORDS / NT >= 4 ? 4 : (WORDS / NT >= 2 ? 2 : 1));
+    static constexpr int WPT = WORDS / NT >= 4 ? 4 : (WORDS / NT >= 2 ? 2 : 1);
     static constexpr int PER = WORDS / (NT * WPT);
+    static constexpr int NSC = RAGGED ? WPT : 1;   // scales kept per fetch
     static_assert(WORDS % (NT * WPT) == 0 && PER >= 1, "staging must divide evenly");
 };
 
@@ -123,10 +164,8 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     uint16_t* Bs = smem + 2 * S::A_STAGE;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    const bool vec = (n & 7) == 0;
-
     uint32_t aw[A_PER][WPT];
-    float asc[A_PER];
+    float asc[A_PER][AT::NSC];
     u32x4 bv[B_PER];
 
     auto gload = [&](int kt) {
@@ -136,12 +175,11 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
             const int ti = t + p * NT;
             const int row = ti / A_TPR, c = (ti % A_TPR) * (8 * WPT);
             const int64_t e = (int64_t)(i0 + row) * r + r0 + c;
-            if (!RAGGED || (i0 + row < m && r0 + c < r)) {
+            if constexpr (!RAGGED) {
                 load_words<WPT>(Pq + (e >> 1), aw[p]);
-                asc[p] = Ps[e >> 8];
+                asc[p][0] = Ps[e >> 8];
             } else {
-                aw[p][0] = 0x88888888u;
-                asc[p] = 0.f;
+                load_p_guarded<WPT>(Pq, Ps, e, i0 + row < m ? r - (r0 + c) : 0, aw[p], asc[p]);
             }
         }
 #pragma unroll
@@ -153,7 +191,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
                 bv[p] = *reinterpret_cast<const u32x4*>(src);
             } else {
                 const int valid = (i0 + row < m) ? (n - (n0 + c8 * 8)) : 0;
-                bv[p] = load8_bf16_guarded(src, valid, vec);
+                bv[p] = load8_bf16_guarded(src, valid);
             }
         }
     };
@@ -164,7 +202,8 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
             const int row = ti / A_TPR, c = (ti % A_TPR) * (8 * WPT);
 #pragma unroll
             for (int j = 0; j < WPT; ++j)
-                *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c + 8 * j) = dequant8_bf16(aw[p][j], asc[p]);
+                *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c + 8 * j) =
+                    dequant8_bf16(aw[p][j], asc[p][RAGGED ? j : 0]);
         }
 #pragma unroll
         for (int p = 0; p < B_PER; ++p) {
@@ -393,7 +432,6 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     const int wn = wave / WGm, wm = wave % WGm;
     const int n0 = tile_n * BNn;
     const int ng = (n + kGroup - 1) / kGroup;
-    const bool vec8 = (n & 7) == 0;
 
     // ---- weight tile -> LDS (asynchronous direct loads where shapes allow) ----
     // whole tile inside the matrix and rows 16-byte aligned: the wide path works even in the guarded kernel
@@ -409,10 +447,25 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
                                              (__attribute__((address_space(3))) void*)(wt + rb * kGroup), 16, 0, 0);
         }
     } else {
-        for (int idx = t; idx < BMm * BNn; idx += NT) {
-            const int row = idx / BNn, col = idx % BNn;
-            const bool ok = m0 + row < m && n0 + col < n;
-            wt[wtile_offset(row, col)] = ok ? (uint8_t)Wq[(int64_t)(m0 + row) * n + n0 + col] : (uint8_t)0;
+        // same lane -> (row, chunk) map through registers: rows may start at any byte offset, and the chunk that
+        // straddles the matrix edge is fetched byte by byte
+#pragma unroll
+        for (int i = 0; i < W_ROUNDS; ++i) {
+            const int rb = (wave * W_ROUNDS + i) * 4;
+            const int row = rb + (lane >> 4), chunk = (lane ^ row) & 15;
+            const int8_t* src = Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16;
+            const int valid = m0 + row < m ? n - (n0 + chunk * 16) : 0;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (valid >= 16) {
+                v = *reinterpret_cast<const u32x4_align1*>(src);
+            } else {
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (j < valid) w[j >> 2] |= (uint32_t)(uint8_t)src[j] << (8 * (j & 3));
+                v[0] = w[0]; v[1] = w[1]; v[2] = w[2]; v[3] = w[3];
+            }
+            *reinterpret_cast<u32x4*>(wt + rb * kGroup + lane * 16) = v;
         }
     }
     };
@@ -420,7 +473,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
 
     u32x4 av[A_PER];
     uint32_t bw[B_PER][WPT];
-    float bsc[B_PER];
+    float bsc[B_PER][BT::NSC];
 
     auto gload = [&](int kt) {
         const int k0 = kt * BK;
@@ -433,7 +486,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
                 av[p] = *reinterpret_cast<const u32x4*>(src);
             } else {
                 const int valid = (k0 + row < r) ? (n - (n0 + c8 * 8)) : 0;
-                av[p] = load8_bf16_guarded(src, valid, vec8);
+                av[p] = load8_bf16_guarded(src, valid);
             }
         }
 #pragma unroll
@@ -441,12 +494,11 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
             const int ti = t + p * NT;
             const int row = ti / B_TPR, c = (ti % B_TPR) * (8 * WPT);
             const int64_t e = (int64_t)(m0 + row) * r + k0 + c;
-            if (!RAGGED || (m0 + row < m && k0 + c < r)) {
+            if constexpr (!RAGGED) {
                 load_words<WPT>(Pq + (e >> 1), bw[p]);
-                bsc[p] = Ps[e >> 8];
+                bsc[p][0] = Ps[e >> 8];
             } else {
-                bw[p][0] = 0x88888888u;
-                bsc[p] = 0.f;
+                load_p_guarded<WPT>(Pq, Ps, e, m0 + row < m ? r - (k0 + c) : 0, bw[p], bsc[p]);
             }
         }
     };
@@ -463,7 +515,8 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
             const int row = ti / B_TPR, c = (ti % B_TPR) * (8 * WPT);
 #pragma unroll
             for (int j = 0; j < WPT; ++j)
-                *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c + 8 * j) = dequant8_bf16(bw[p][j], bsc[p]);
+                *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c + 8 * j) =
+                    dequant8_bf16(bw[p][j], bsc[p][RAGGED ? j : 0]);
         }
     };
 
@@ -592,9 +645,19 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
             *reinterpret_cast<u32x4*>(Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16) = v;
         }
     } else {
-        for (int idx = t; idx < BMm * BNn; idx += NT) {
-            const int row = idx / BNn, col = idx % BNn;
-            if (m0 + row < m && n0 + col < n) Wq[(int64_t)(m0 + row) * n + n0 + col] = (int8_t)wt[wtile_offset(row, col)];
+#pragma unroll
+        for (int i = 0; i < W_ROUNDS; ++i) {
+            const int row = (wave * W_ROUNDS + i) * 4 + (lane >> 4), chunk = (lane ^ row) & 15;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(wt + row * kGroup + (lane & 15) * 16);
+            int8_t* dst = Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16;
+            const int valid = m0 + row < m ? n - (n0 + chunk * 16) : 0;
+            if (valid >= 16) {
+                *reinterpret_cast<u32x4_align1*>(dst) = v;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (j < valid) dst[j] = (int8_t)(v[j >> 2] >> (8 * (j & 3)));
+            }
         }
     }
 }
