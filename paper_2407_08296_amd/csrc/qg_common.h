@@ -60,9 +60,17 @@ __device__ inline uint16_t to_bf16(float a) { return (uint16_t)(pack_bf16x2(a, 0
 // fl32((nib - 8) * s) through one fma, then one rounding to bf16.
 __device__ inline u32x4 dequant8_bf16(uint32_t w, float s) {
     const float ms = -8.0f * s;
+    // even and odd nibbles spread to one byte each, so that each conversion is a single byte-to-float instruction
+    uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;
+    // (opaque to the optimizer, which would otherwise fold the masks back into eight 4-bit field extracts)
+    asm("" : "+v"(lo));
+    asm("" : "+v"(hi));
     float e[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) e[j] = __builtin_fmaf((float)((w >> (4 * j)) & 0xFu), s, ms);
+    for (int j = 0; j < 4; ++j) {
+        e[2 * j] = __builtin_fmaf((float)((lo >> (8 * j)) & 0xFFu), s, ms);
+        e[2 * j + 1] = __builtin_fmaf((float)((hi >> (8 * j)) & 0xFFu), s, ms);
+    }
     const u32x4 o = {pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]), pack_bf16x2(e[4], e[5]),
                      pack_bf16x2(e[6], e[7])};
     return o;

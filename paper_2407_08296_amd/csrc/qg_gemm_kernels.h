@@ -54,6 +54,25 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef u32x2 __attribute__((aligned(4))) u32x2_align4;
 typedef u32x4 __attribute__((aligned(4))) u32x4_align4;
 
+// Buffer resource over memory starting at `base`: loads through it take a scalar base, a scalar offset and a 32-bit
+// per-thread byte offset, so a loop that only moves the base spends no vector instructions on addresses.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
+}
+
+template <int WPT>
+__device__ __forceinline__ void buffer_load_words(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off, uint32_t (&w)[WPT]) {
+    if constexpr (WPT == 4) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, byte_off, 0, 0);
+        w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+    } else if constexpr (WPT == 2) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b64(rs, byte_off, 0, 0);
+        w[0] = v[0]; w[1] = v[1];
+    } else {
+        w[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, byte_off, 0, 0);
+    }
+}
+
 // 8 consecutive bf16 starting at `src`, of which the first `valid` lie inside the matrix (ragged shapes): one
 // 16-byte load when all do, element by element for the chunk that straddles the edge, zeros outside.
 __device__ __forceinline__ u32x4 load8_bf16_guarded(const uint16_t* src, int valid) {
@@ -85,7 +104,7 @@ __device__ __forceinline__ void load_words(const uint8_t* p, uint32_t (&w)[WPT])
 // `valid` codes lie inside the matrix.  Every word carries the scale of its own block: with r not a multiple of
 // 8*WPT the words of one fetch can fall into two blocks of 256.  Words outside read as code 0, scale 0.
 template <int WPT>
-__device__ __forceinline__ void load_p_guarded(const uint8_t* Pq, const float* Ps, int64_t e, int valid,
+__device__ __forceinline__ void load_p_guarded(const uint8_t* Pq, const float* Ps, uint32_t e, int valid,
                                                uint32_t (&w)[WPT], float (&sc)[WPT]) {
     const uint8_t* p = Pq + (e >> 1);
     if (valid >= 8 * WPT) {
@@ -168,30 +187,52 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     float asc[A_PER][AT::NSC];
     u32x4 bv[B_PER];
 
+    // Addresses are split into a part that is uniform over the workgroup and advances with the K step (scalar
+    // registers, scalar arithmetic) and a 32-bit per-thread offset fixed for the whole loop; the unguarded kernels
+    // load through buffer resources based at the uniform part, so their loop spends no vector instructions on
+    // address arithmetic.  A K step covers BK rows of P, i.e. BK*r codes: a multiple of 256 (r is a multiple of 8),
+    // so code bytes and block scales split the same way.
+    static_assert(BK % 32 == 0, "a K step must cover whole blocks of 256 codes");
+    uint32_t a_el[A_PER], b_byte[B_PER];   // P: element offset; G: byte offset
+#pragma unroll
+    for (int p = 0; p < A_PER; ++p) {
+        const int ti = t + p * NT;
+        a_el[p] = (uint32_t)((ti / A_TPR) * r + r0 + (ti % A_TPR) * (8 * WPT));
+    }
+#pragma unroll
+    for (int p = 0; p < B_PER; ++p) {
+        const int ci = t + p * NT;
+        b_byte[p] = 2u * (uint32_t)((ci / (BN / 8)) * n + (ci % (BN / 8)) * 8);
+    }
+
     auto gload = [&](int kt) {
         const int i0 = kt * BK;
+        const int64_t e0 = (int64_t)i0 * r;
+        const uint8_t* pq = Pq + (e0 >> 1);
+        const float* ps = Ps + (e0 >> 8);
+        const uint8_t* g = reinterpret_cast<const uint8_t*>(G + (int64_t)i0 * n + n0);
+        if constexpr (!RAGGED) {
+            const __amdgpu_buffer_rsrc_t rq = make_rsrc(pq), rs = make_rsrc(ps), rg = make_rsrc(g);
 #pragma unroll
-        for (int p = 0; p < A_PER; ++p) {
-            const int ti = t + p * NT;
-            const int row = ti / A_TPR, c = (ti % A_TPR) * (8 * WPT);
-            const int64_t e = (int64_t)(i0 + row) * r + r0 + c;
-            if constexpr (!RAGGED) {
-                load_words<WPT>(Pq + (e >> 1), aw[p]);
-                asc[p][0] = Ps[e >> 8];
-            } else {
-                load_p_guarded<WPT>(Pq, Ps, e, i0 + row < m ? r - (r0 + c) : 0, aw[p], asc[p]);
+            for (int p = 0; p < A_PER; ++p) {
+                buffer_load_words<WPT>(rq, a_el[p] >> 1, aw[p]);
+                asc[p][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (a_el[p] >> 8) << 2, 0, 0));
             }
-        }
 #pragma unroll
-        for (int p = 0; p < B_PER; ++p) {
-            const int ci = t + p * NT;
-            const int row = ci / (BN / 8), c8 = ci % (BN / 8);
-            const uint16_t* src = G + (int64_t)(i0 + row) * n + n0 + c8 * 8;
-            if (!RAGGED) {
-                bv[p] = *reinterpret_cast<const u32x4*>(src);
-            } else {
+            for (int p = 0; p < B_PER; ++p) bv[p] = __builtin_amdgcn_raw_buffer_load_b128(rg, b_byte[p], 0, 0);
+        } else {
+#pragma unroll
+            for (int p = 0; p < A_PER; ++p) {
+                const int ti = t + p * NT;
+                const int row = ti / A_TPR, c = (ti % A_TPR) * (8 * WPT);
+                load_p_guarded<WPT>(pq, ps, a_el[p], i0 + row < m ? r - (r0 + c) : 0, aw[p], asc[p]);
+            }
+#pragma unroll
+            for (int p = 0; p < B_PER; ++p) {
+                const int ci = t + p * NT;
+                const int row = ci / (BN / 8), c8 = ci % (BN / 8);
                 const int valid = (i0 + row < m) ? (n - (n0 + c8 * 8)) : 0;
-                bv[p] = load8_bf16_guarded(src, valid);
+                bv[p] = load8_bf16_guarded(reinterpret_cast<const uint16_t*>(g + b_byte[p]), valid);
             }
         }
     };
@@ -225,14 +266,9 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     const int b_lane = kmajor_lane_offset(PB, lane) + wn * WN;
     const int KT = (m + BK - 1) / BK;
 
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) gload(kt + 1);
-        const uint16_t* Ac = As + cur * S::A_STAGE + a_lane;
-        const uint16_t* Bc = Bs + cur * S::B_STAGE + b_lane;
+    auto mfma_step = [&](int stage) {
+        const uint16_t* Ac = As + stage * S::A_STAGE + a_lane;
+        const uint16_t* Bc = Bs + stage * S::B_STAGE + b_lane;
         // With two workgroups per CU a SIMD holds two waves; the one in its MFMA phase gets issue priority so the
         // matrix pipe stays fed while the other wave's staging instructions fill the gaps.
         __builtin_amdgcn_s_setprio(kMfmaPrio);
@@ -250,7 +286,22 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
         __builtin_amdgcn_s_setprio(0);
-        if (kt + 1 < KT) sstore(cur ^ 1);
+    };
+
+    // Unrolled by two so that the LDS stage of every access is a compile-time constant (no per-step address
+    // arithmetic).  Loads past the end re-read the last K slab (in bounds, never consumed), which keeps every load
+    // and store unconditional.
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {
+        gload(min(kt + 1, KT - 1));
+        mfma_step(0);
+        sstore(1);
+        __syncthreads();
+        gload(min(kt + 2, KT - 1));
+        if (kt + 1 < KT) mfma_step(1);
+        sstore(0);
         __syncthreads();
     }
 
@@ -406,6 +457,14 @@ __device__ __forceinline__ int wtile_offset(int row, int col) {
     return row * kGroup + ((((col >> 4) ^ row) & 15) << 4) + (col & 15);
 }
 
+// A lane's 4-element runs of an accumulator row sit at columns c0 + 32*a + 8*v4 (c0 = the lane's first column, a
+// multiple of 4 below 8 plus a multiple of the wave's column span).  Their tile offsets differ from that of c0 only
+// in bits that c0 leaves clear, so they are wtile_offset(row, c0) ^ wtile_run_bits(a, v4): one xor with a
+// compile-time constant per access instead of the full swizzle.
+__device__ __forceinline__ constexpr int wtile_run_bits(int a, int v4) {
+    return ((2 * a + (v4 >> 1)) << 4) | ((v4 & 1) << 3);
+}
+
 template <int BMm, int BK, int WGn, int WGm, bool RAGGED, bool DUMP_U, bool W_PREFETCH = true>
 __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
                                                  const uint16_t* __restrict__ N, int8_t* __restrict__ Wq,
@@ -425,6 +484,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     static_assert(A_CH % NT == 0, "staging must divide evenly");
     static_assert(WGn * BMm * 4 <= S::STAGING * 2, "row-max exchange must fit in the staging buffers");
     static_assert((BMm / 4) % NW == 0, "weight tile rows must divide evenly over the waves");
+    static_assert(SN % 32 == 0 && (SN & (SN - 1)) == 0, "a wave's column span must be a power of two (wtile_run_bits)");
     uint16_t* As = smem;
     uint16_t* Bs = smem + 2 * S::A_STAGE;
     uint8_t* wt = reinterpret_cast<uint8_t*>(smem + S::WOFF);
@@ -475,30 +535,51 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     uint32_t bw[B_PER][WPT];
     float bsc[B_PER][BT::NSC];
 
+    // Uniform bases that advance with the K step plus fixed 32-bit per-thread offsets, as in the projection.  The
+    // tile's first code, m0*r, starts a block of 256 (m0 is a multiple of 128, r of 8); the K offset k0 does not,
+    // so the index of a code's block scale takes one add and two shifts per step.
+    uint32_t a_byte[A_PER], b_el[B_PER];   // N: byte offset; P: element offset inside the tile's rows
+#pragma unroll
+    for (int p = 0; p < A_PER; ++p) {
+        const int ci = t + p * NT;
+        a_byte[p] = 2u * (uint32_t)((ci / (BNn / 8)) * n + (ci % (BNn / 8)) * 8);
+    }
+#pragma unroll
+    for (int p = 0; p < B_PER; ++p) {
+        const int ti = t + p * NT;
+        b_el[p] = (uint32_t)((ti / B_TPR) * r + (ti % B_TPR) * (8 * WPT));
+    }
+    const int64_t e_tile = (int64_t)m0 * r;
+
     auto gload = [&](int kt) {
         const int k0 = kt * BK;
+        const uint8_t* nb = reinterpret_cast<const uint8_t*>(N + (int64_t)k0 * n + n0);
+        const uint8_t* pq = Pq + ((e_tile + k0) >> 1);
+        const float* ps = Ps + (e_tile >> 8);
+        if constexpr (!RAGGED) {
+            const __amdgpu_buffer_rsrc_t rn = make_rsrc(nb), rq = make_rsrc(pq), rs = make_rsrc(ps);
 #pragma unroll
-        for (int p = 0; p < A_PER; ++p) {
-            const int ci = t + p * NT;
-            const int row = ci / (BNn / 8), c8 = ci % (BNn / 8);
-            const uint16_t* src = N + (int64_t)(k0 + row) * n + n0 + c8 * 8;
-            if (!RAGGED) {
-                av[p] = *reinterpret_cast<const u32x4*>(src);
-            } else {
-                const int valid = (k0 + row < r) ? (n - (n0 + c8 * 8)) : 0;
-                av[p] = load8_bf16_guarded(src, valid);
+            for (int p = 0; p < A_PER; ++p) av[p] = __builtin_amdgcn_raw_buffer_load_b128(rn, a_byte[p], 0, 0);
+#pragma unroll
+            for (int p = 0; p < B_PER; ++p) {
+                buffer_load_words<WPT>(rq, b_el[p] >> 1, bw[p]);
+                bsc[p][0] = __builtin_bit_cast(
+                    float, __builtin_amdgcn_raw_buffer_load_b32(rs, ((b_el[p] + (uint32_t)k0) >> 8) << 2, 0, 0));
             }
-        }
+        } else {
 #pragma unroll
-        for (int p = 0; p < B_PER; ++p) {
-            const int ti = t + p * NT;
-            const int row = ti / B_TPR, c = (ti % B_TPR) * (8 * WPT);
-            const int64_t e = (int64_t)(m0 + row) * r + k0 + c;
-            if constexpr (!RAGGED) {
-                load_words<WPT>(Pq + (e >> 1), bw[p]);
-                bsc[p][0] = Ps[e >> 8];
-            } else {
-                load_p_guarded<WPT>(Pq, Ps, e, m0 + row < m ? r - (k0 + c) : 0, bw[p], bsc[p]);
+            for (int p = 0; p < A_PER; ++p) {
+                const int ci = t + p * NT;
+                const int row = ci / (BNn / 8), c8 = ci % (BNn / 8);
+                const int valid = (k0 + row < r) ? (n - (n0 + c8 * 8)) : 0;
+                av[p] = load8_bf16_guarded(reinterpret_cast<const uint16_t*>(nb + a_byte[p]), valid);
+            }
+#pragma unroll
+            for (int p = 0; p < B_PER; ++p) {
+                const int ti = t + p * NT;
+                const int row = ti / B_TPR, c = (ti % B_TPR) * (8 * WPT);
+                load_p_guarded<WPT>(Pq + (e_tile >> 1), ps, b_el[p] + (uint32_t)k0, m0 + row < m ? r - (k0 + c) : 0,
+                                    bw[p], bsc[p]);
             }
         }
     };
@@ -533,14 +614,9 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     const int b_lane = (wm * SM + lrow) * PB + 8 * lhalf;
     const int KT = (r + BK - 1) / BK;
 
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) gload(kt + 1);
-        const uint16_t* Ac = As + cur * S::A_STAGE + a_lane;
-        const uint16_t* Bc = Bs + cur * S::B_STAGE + b_lane;
+    auto mfma_step = [&](int stage) {
+        const uint16_t* Ac = As + stage * S::A_STAGE + a_lane;
+        const uint16_t* Bc = Bs + stage * S::B_STAGE + b_lane;
         __builtin_amdgcn_s_setprio(kMfmaPrio);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
@@ -557,7 +633,20 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
         __builtin_amdgcn_s_setprio(0);
-        if (kt + 1 < KT) sstore(cur ^ 1);
+    };
+
+    // unrolled by two (constant LDS stages); loads past the end re-read the last K slab, see the projection
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {
+        gload(min(kt + 1, KT - 1));
+        mfma_step(0);
+        sstore(1);
+        __syncthreads();
+        gload(min(kt + 2, KT - 1));
+        if (kt + 1 < KT) mfma_step(1);
+        sstore(0);
         __syncthreads();
     }
 
@@ -577,12 +666,13 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         const bool row_ok = !RAGGED || mrow < m;
         const float s_old = row_ok ? Ws[(int64_t)mrow * ng + tile_n] : 0.f;
         float mx = 0.f;
+        const int wt_lane = wtile_offset(rl, wn * SN + 4 * lhalf);
 #pragma unroll
         for (int a = 0; a < IB; ++a)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
                 const int col = wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
-                const uint32_t w = *reinterpret_cast<const uint32_t*>(wt + wtile_offset(rl, col));
+                const uint32_t w = *reinterpret_cast<const uint32_t*>(wt + (wt_lane ^ wtile_run_bits(a, v4)));
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float cw = (float)(int)(int8_t)(w >> (8 * e)) * s_old;
@@ -616,6 +706,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         const float inv = amax > 0.f ? 127.0f / amax : 0.f;
         if (wn == 0 && lhalf == 0 && row_ok) Ws[(int64_t)mrow * ng + tile_n] = s_new;
         const uint32_t idx_row = (uint32_t)mrow * (uint32_t)n + (uint32_t)n0;   // m*n < 2^32
+        const int wt_lane = wtile_offset(rl, wn * SN + 4 * lhalf);
 #pragma unroll
         for (int a = 0; a < IB; ++a)
 #pragma unroll
@@ -628,10 +719,12 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
                     const uint32_t h = mix32(key ^ (idx_row + (uint32_t)(col + e)));
                     // fl32(tq + u) with u = (h >> 8) * 2^-24: the product is exact, so one fma rounds the same sum
                     const float v = __builtin_fmaf((float)(h >> 8), 0x1p-24f, tq);
-                    const float q = fminf(fmaxf(floorf(v), -128.f), 127.f);
-                    pk |= ((uint32_t)(int)q & 0xFFu) << (8 * e);
+                    // clamp(floor(v), -128, 127) as a byte: the saturating float -> u8 conversion of floor(v) + 128
+                    // (exact: |v| stays far below 2^23) packs straight into byte e; the bias comes off below
+                    pk = __builtin_amdgcn_cvt_pk_u8_f32(floorf(v) + 128.0f, e, pk);
                 }
-                *reinterpret_cast<uint32_t*>(wt + wtile_offset(rl, col)) = pk;
+                pk ^= 0x80808080u;
+                *reinterpret_cast<uint32_t*>(wt + (wt_lane ^ wtile_run_bits(a, v4))) = pk;
             }
     }
     __syncthreads();
