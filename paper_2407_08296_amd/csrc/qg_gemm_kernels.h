@@ -60,6 +60,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
 }
 
+// One wave-wide 16-byte-per-lane load straight into LDS: lane i's bytes land at lds + 16*i (lds is wave-uniform).
+__device__ __forceinline__ void buffer_load_lds16(__amdgpu_buffer_rsrc_t rs, void* lds, uint32_t byte_off) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)lds, 16, byte_off, 0, 0, 0);
+}
+
 template <int WPT>
 __device__ __forceinline__ void buffer_load_words(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off, uint32_t (&w)[WPT]) {
     if constexpr (WPT == 4) {
@@ -72,6 +77,34 @@ __device__ __forceinline__ void buffer_load_words(__amdgpu_buffer_rsrc_t rs, uin
         w[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, byte_off, 0, 0);
     }
 }
+
+// bf16 [K][X] operand tile of BK x BX elements whose rows are NOT padded: the unguarded kernels fill it with direct
+// global -> LDS loads (no registers, no LDS write instructions), and one wave-wide 16-byte load deposits 1 KB of
+// consecutive LDS.  Bank spreading comes from a swizzle instead: the 16-byte chunk c of row k sits at chunk position
+// c ^ ((k & 3) << 2), so the four rows a transpose read touches fall into four different 64-byte bank groups.  For a
+// transpose-read lane, k & 3 is a per-lane constant, and the swizzle is one xor on the (32-aligned) fragment column.
+template <int BX, int BK, int NT>
+struct KMajorSwizzled {
+    static constexpr int STAGE = BK * BX;        // uint16 elements per stage
+    static constexpr int CPR = BX / 8;           // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;         // rows per wave-wide load
+    static constexpr int PER = BK / (RPI * (NT / 64));   // loads per wave per stage
+    static_assert(CPR >= 16 && 64 % CPR == 0 && BK % (RPI * (NT / 64)) == 0 && PER >= 1, "tile shape");
+
+    // element offset of 16-byte chunk c of row k
+    __device__ static __forceinline__ int chunk_offset(int k, int c) { return k * BX + ((c ^ ((k & 3) << 2)) << 3); }
+    // byte offset (from the tile's first element in memory, row length ld) of the chunk that lane `lane` of wave
+    // `wave` fetches with its i-th load, and the tile row block that load fills
+    __device__ static __forceinline__ uint32_t lane_src_bytes(int wave, int i, int lane, int ld) {
+        const int row = (wave * PER + i) * RPI + lane / CPR;
+        const int c = (lane % CPR) ^ ((row & 3) << 2);
+        return 2u * (uint32_t)(row * ld + c * 8);
+    }
+    __device__ static __forceinline__ int load_row0(int wave, int i) { return (wave * PER + i) * RPI; }
+    // transpose-read lane offset and swizzle term (elements)
+    __device__ static __forceinline__ int lane_offset(int lane) { return kmajor_lane_offset(BX, lane); }
+    __device__ static __forceinline__ int lane_swizzle(int lane) { return ((lane & 15) >> 2) << 5; }
+};
 
 // 8 consecutive bf16 starting at `src`, of which the first `valid` lie inside the matrix (ragged shapes): one
 // 16-byte load when all do, element by element for the chunk that straddles the edge, zeros outside.
@@ -155,7 +188,7 @@ __device__ __forceinline__ uint32_t xcd_tile(uint32_t wg, uint32_t grid) {
 template <int BM, int BN, int BK, int WGM, int WGN>
 struct ProjShape {
     static constexpr int NT = WGM * WGN * 64;
-    static constexpr int PA = BM + kPadK, PB = BN + kPadK;
+    static constexpr int PA = BM + kPadK, PB = BN;   // P tile padded, G tile swizzled (KMajorSwizzled)
     static constexpr int A_STAGE = BK * PA, B_STAGE = BK * PB;
     static constexpr int SMEM = 2 * (A_STAGE + B_STAGE);  // uint16 elements
 };
@@ -176,16 +209,18 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     constexpr int A_WORDS = BK * BM / 8;
     using AT = P_Task<A_WORDS, NT, RAGGED>;
     constexpr int A_PER = AT::PER, WPT = AT::WPT, A_TPR = BM / (8 * WPT);   // tasks per tile row
-    constexpr int B_CH = BK * BN / 8, B_PER = B_CH / NT;
-    static_assert(B_CH % NT == 0, "staging must divide evenly");
+    using BD = KMajorSwizzled<BN, BK, NT>;
+    constexpr int B_PER = BD::PER;
+    static_assert(B_PER * NT * 8 == BK * BN, "staging must divide evenly");
     static_assert(BK % 16 == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     uint16_t* As = smem;
     uint16_t* Bs = smem + 2 * S::A_STAGE;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);   // wave-uniform: keeps everything derived from it scalar
     const int wm = wave / WGN, wn = wave % WGN;
     uint32_t aw[A_PER][WPT];
     float asc[A_PER][AT::NSC];
-    u32x4 bv[B_PER];
+    u32x4 bv[RAGGED ? B_PER : 1];   // the guarded kernels stage G through registers
 
     // Addresses are split into a part that is uniform over the workgroup and advances with the K step (scalar
     // registers, scalar arithmetic) and a 32-bit per-thread offset fixed for the whole loop; the unguarded kernels
@@ -201,11 +236,17 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     }
 #pragma unroll
     for (int p = 0; p < B_PER; ++p) {
-        const int ci = t + p * NT;
-        b_byte[p] = 2u * (uint32_t)((ci / (BN / 8)) * n + (ci % (BN / 8)) * 8);
+        if constexpr (!RAGGED) {
+            b_byte[p] = BD::lane_src_bytes(wave, p, lane, n);
+        } else {
+            const int ci = t + p * NT;
+            b_byte[p] = 2u * (uint32_t)((ci / BD::CPR) * n + (ci % BD::CPR) * 8);
+        }
     }
 
-    auto gload = [&](int kt) {
+    // Tile kt: P codes and scales into registers; G straight into LDS stage `stage` (unguarded kernels) or into
+    // registers (guarded kernels, stored by sstore).
+    auto gload = [&](int kt, int stage) {
         const int i0 = kt * BK;
         const int64_t e0 = (int64_t)i0 * r;
         const uint8_t* pq = Pq + (e0 >> 1);
@@ -214,12 +255,13 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
         if constexpr (!RAGGED) {
             const __amdgpu_buffer_rsrc_t rq = make_rsrc(pq), rs = make_rsrc(ps), rg = make_rsrc(g);
 #pragma unroll
+            for (int p = 0; p < B_PER; ++p)
+                buffer_load_lds16(rg, Bs + stage * S::B_STAGE + BD::load_row0(wave, p) * BN, b_byte[p]);
+#pragma unroll
             for (int p = 0; p < A_PER; ++p) {
                 buffer_load_words<WPT>(rq, a_el[p] >> 1, aw[p]);
                 asc[p][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (a_el[p] >> 8) << 2, 0, 0));
             }
-#pragma unroll
-            for (int p = 0; p < B_PER; ++p) bv[p] = __builtin_amdgcn_raw_buffer_load_b128(rg, b_byte[p], 0, 0);
         } else {
 #pragma unroll
             for (int p = 0; p < A_PER; ++p) {
@@ -230,12 +272,14 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
             for (int p = 0; p < B_PER; ++p) {
                 const int ci = t + p * NT;
-                const int row = ci / (BN / 8), c8 = ci % (BN / 8);
+                const int row = ci / BD::CPR, c8 = ci % BD::CPR;
                 const int valid = (i0 + row < m) ? (n - (n0 + c8 * 8)) : 0;
                 bv[p] = load8_bf16_guarded(reinterpret_cast<const uint16_t*>(g + b_byte[p]), valid);
             }
         }
     };
+    // Dequantized P tile (and, in the guarded kernels, the G tile) into LDS stage `stage`; returns once the stage's
+    // direct loads have landed too, so that the barrier that follows publishes the whole stage.
     auto sstore = [&](int stage) {
 #pragma unroll
         for (int p = 0; p < A_PER; ++p) {
@@ -246,11 +290,14 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
                 *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c + 8 * j) =
                     dequant8_bf16(aw[p][j], asc[p][RAGGED ? j : 0]);
         }
+        if constexpr (RAGGED) {
 #pragma unroll
-        for (int p = 0; p < B_PER; ++p) {
-            const int ci = t + p * NT;
-            const int row = ci / (BN / 8), c8 = ci % (BN / 8);
-            *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c8 * 8) = bv[p];
+            for (int p = 0; p < B_PER; ++p) {
+                const int ci = t + p * NT;
+                *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + BD::chunk_offset(ci / BD::CPR, ci % BD::CPR)) = bv[p];
+            }
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // direct loads are counted like any other load
         }
     };
 
@@ -263,12 +310,14 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
     const int a_lane = kmajor_lane_offset(PA, lane) + wm * WM;
-    const int b_lane = kmajor_lane_offset(PB, lane) + wn * WN;
+    int b_lane[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) b_lane[b] = BD::lane_offset(lane) + ((wn * WN + b * 32) ^ BD::lane_swizzle(lane));
     const int KT = (m + BK - 1) / BK;
 
     auto mfma_step = [&](int stage) {
         const uint16_t* Ac = As + stage * S::A_STAGE + a_lane;
-        const uint16_t* Bc = Bs + stage * S::B_STAGE + b_lane;
+        const uint16_t* Bc = Bs + stage * S::B_STAGE;
         // With two workgroups per CU a SIMD holds two waves; the one in its MFMA phase gets issue priority so the
         // matrix pipe stays fed while the other wave's staging instructions fill the gaps.
         __builtin_amdgcn_s_setprio(kMfmaPrio);
@@ -278,7 +327,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
             for (int a = 0; a < MB; ++a) af[a] = read_kmajor_frag(Ac + kk * 16 * PA + a * 32, PA);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) bf[b] = read_kmajor_frag(Bc + kk * 16 * PB + b * 32, PB);
+            for (int b = 0; b < NB; ++b) bf[b] = read_kmajor_frag(Bc + kk * 16 * BN + b_lane[b], BN);
 #pragma unroll
             for (int a = 0; a < MB; ++a)
 #pragma unroll
@@ -291,15 +340,15 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     // Unrolled by two so that the LDS stage of every access is a compile-time constant (no per-step address
     // arithmetic).  Loads past the end re-read the last K slab (in bounds, never consumed), which keeps every load
     // and store unconditional.
-    gload(0);
+    gload(0, 0);
     sstore(0);
     __syncthreads();
     for (int kt = 0; kt < KT; kt += 2) {
-        gload(min(kt + 1, KT - 1));
+        gload(min(kt + 1, KT - 1), 1);
         mfma_step(0);
         sstore(1);
         __syncthreads();
-        gload(min(kt + 2, KT - 1));
+        gload(min(kt + 2, KT - 1), 0);
         if (kt + 1 < KT) mfma_step(1);
         sstore(0);
         __syncthreads();
@@ -488,7 +537,8 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     uint16_t* As = smem;
     uint16_t* Bs = smem + 2 * S::A_STAGE;
     uint8_t* wt = reinterpret_cast<uint8_t*>(smem + S::WOFF);
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);   // wave-uniform: keeps everything derived from it scalar
     const int wn = wave / WGm, wm = wave % WGm;
     const int n0 = tile_n * BNn;
     const int ng = (n + kGroup - 1) / kGroup;
