@@ -489,8 +489,8 @@ template <int BMm, int BK, int WGn, int WGm, bool W_PREFETCH = true>
 struct BpShape {
     static constexpr int BNn = kGroup;
     static constexpr int NT = WGn * WGm * 64;
-    static constexpr int PA = BNn + kPadK;  // N tile, K-major
-    static constexpr int PB = BK + kPadX;   // P tile, [m][k]
+    static constexpr int PA = BNn;          // N tile, K-major, swizzled (KMajorSwizzled)
+    static constexpr int PB = BK + kPadX;   // P tile, [m][k], padded
     static constexpr int A_STAGE = BK * PA, B_STAGE = BMm * PB;
     static constexpr int STAGING = 2 * (A_STAGE + B_STAGE);   // uint16 elements
     static constexpr int WTILE = BMm * BNn / 2;                // INT8 weight tile, in uint16 elements
@@ -524,13 +524,14 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     constexpr int BNn = S::BNn, NT = S::NT, NW = WGn * WGm;
     constexpr int SN = BNn / WGn, SM = BMm / WGm, IB = SN / 32, JB = SM / 32;
     constexpr int PA = S::PA, PB = S::PB;
-    constexpr int A_CH = BK * BNn / 8, A_PER = A_CH / NT;
+    using AD = KMajorSwizzled<BNn, BK, NT>;
+    constexpr int A_PER = AD::PER;
     constexpr int B_WORDS = BMm * BK / 8;
     using BT = P_Task<B_WORDS, NT, RAGGED>;
     constexpr int B_PER = BT::PER, WPT = BT::WPT, B_TPR = BK / (8 * WPT);   // tasks per tile row
     static_assert(BK % (8 * WPT) == 0, "tile shape");
     constexpr int W_ROUNDS = BMm / 4 / NW;   // each wave-wide 16-byte access covers 4 tile rows
-    static_assert(A_CH % NT == 0, "staging must divide evenly");
+    static_assert(A_PER * NT * 8 == BK * BNn, "staging must divide evenly");
     static_assert(WGn * BMm * 4 <= S::STAGING * 2, "row-max exchange must fit in the staging buffers");
     static_assert((BMm / 4) % NW == 0, "weight tile rows must divide evenly over the waves");
     static_assert(SN % 32 == 0 && (SN & (SN - 1)) == 0, "a wave's column span must be a power of two (wtile_run_bits)");
@@ -581,7 +582,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     };
     if (W_PREFETCH) load_wtile();   // lands while the GEMM main loop runs
 
-    u32x4 av[A_PER];
+    u32x4 av[RAGGED ? A_PER : 1];   // the guarded kernels stage N through registers
     uint32_t bw[B_PER][WPT];
     float bsc[B_PER][BT::NSC];
 
@@ -591,8 +592,12 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     uint32_t a_byte[A_PER], b_el[B_PER];   // N: byte offset; P: element offset inside the tile's rows
 #pragma unroll
     for (int p = 0; p < A_PER; ++p) {
-        const int ci = t + p * NT;
-        a_byte[p] = 2u * (uint32_t)((ci / (BNn / 8)) * n + (ci % (BNn / 8)) * 8);
+        if constexpr (!RAGGED) {
+            a_byte[p] = AD::lane_src_bytes(wave, p, lane, n);
+        } else {
+            const int ci = t + p * NT;
+            a_byte[p] = 2u * (uint32_t)((ci / AD::CPR) * n + (ci % AD::CPR) * 8);
+        }
     }
 #pragma unroll
     for (int p = 0; p < B_PER; ++p) {
@@ -601,7 +606,9 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     }
     const int64_t e_tile = (int64_t)m0 * r;
 
-    auto gload = [&](int kt) {
+    // Tile kt: N straight into LDS stage `stage` (unguarded kernels) or into registers (guarded); P codes and scales
+    // into registers.
+    auto gload = [&](int kt, int stage) {
         const int k0 = kt * BK;
         const uint8_t* nb = reinterpret_cast<const uint8_t*>(N + (int64_t)k0 * n + n0);
         const uint8_t* pq = Pq + ((e_tile + k0) >> 1);
@@ -609,7 +616,8 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         if constexpr (!RAGGED) {
             const __amdgpu_buffer_rsrc_t rn = make_rsrc(nb), rq = make_rsrc(pq), rs = make_rsrc(ps);
 #pragma unroll
-            for (int p = 0; p < A_PER; ++p) av[p] = __builtin_amdgcn_raw_buffer_load_b128(rn, a_byte[p], 0, 0);
+            for (int p = 0; p < A_PER; ++p)
+                buffer_load_lds16(rn, As + stage * S::A_STAGE + AD::load_row0(wave, p) * BNn, a_byte[p]);
 #pragma unroll
             for (int p = 0; p < B_PER; ++p) {
                 buffer_load_words<WPT>(rq, b_el[p] >> 1, bw[p]);
@@ -620,7 +628,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
 #pragma unroll
             for (int p = 0; p < A_PER; ++p) {
                 const int ci = t + p * NT;
-                const int row = ci / (BNn / 8), c8 = ci % (BNn / 8);
+                const int row = ci / AD::CPR, c8 = ci % AD::CPR;
                 const int valid = (k0 + row < r) ? (n - (n0 + c8 * 8)) : 0;
                 av[p] = load8_bf16_guarded(reinterpret_cast<const uint16_t*>(nb + a_byte[p]), valid);
             }
@@ -635,12 +643,6 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     };
     auto sstore = [&](int stage) {
 #pragma unroll
-        for (int p = 0; p < A_PER; ++p) {
-            const int ci = t + p * NT;
-            const int row = ci / (BNn / 8), c8 = ci % (BNn / 8);
-            *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c8 * 8) = av[p];
-        }
-#pragma unroll
         for (int p = 0; p < B_PER; ++p) {
             const int ti = t + p * NT;
             const int row = ti / B_TPR, c = (ti % B_TPR) * (8 * WPT);
@@ -648,6 +650,15 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
             for (int j = 0; j < WPT; ++j)
                 *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c + 8 * j) =
                     dequant8_bf16(bw[p][j], bsc[p][RAGGED ? j : 0]);
+        }
+        if constexpr (RAGGED) {
+#pragma unroll
+            for (int p = 0; p < A_PER; ++p) {
+                const int ci = t + p * NT;
+                *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + AD::chunk_offset(ci / AD::CPR, ci % AD::CPR)) = av[p];
+            }
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the stage's direct loads have landed
         }
     };
 
@@ -660,19 +671,21 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int a_lane = kmajor_lane_offset(PA, lane) + wn * SN;
+    int a_lane[IB];
+#pragma unroll
+    for (int a = 0; a < IB; ++a) a_lane[a] = AD::lane_offset(lane) + ((wn * SN + a * 32) ^ AD::lane_swizzle(lane));
     const int b_lane = (wm * SM + lrow) * PB + 8 * lhalf;
     const int KT = (r + BK - 1) / BK;
 
     auto mfma_step = [&](int stage) {
-        const uint16_t* Ac = As + stage * S::A_STAGE + a_lane;
+        const uint16_t* Ac = As + stage * S::A_STAGE;
         const uint16_t* Bc = Bs + stage * S::B_STAGE + b_lane;
         __builtin_amdgcn_s_setprio(kMfmaPrio);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 af[IB], bf[JB];
 #pragma unroll
-            for (int a = 0; a < IB; ++a) af[a] = read_kmajor_frag(Ac + kk * 16 * PA + a * 32, PA);
+            for (int a = 0; a < IB; ++a) af[a] = read_kmajor_frag(Ac + kk * 16 * PA + a_lane[a], PA);
 #pragma unroll
             for (int b = 0; b < JB; ++b)
                 bf[b] = *reinterpret_cast<const bf16x8*>(Bc + b * 32 * PB + kk * 16);
@@ -686,15 +699,15 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     };
 
     // unrolled by two (constant LDS stages); loads past the end re-read the last K slab, see the projection
-    gload(0);
+    gload(0, 0);
     sstore(0);
     __syncthreads();
     for (int kt = 0; kt < KT; kt += 2) {
-        gload(min(kt + 1, KT - 1));
+        gload(min(kt + 1, KT - 1), 1);
         mfma_step(0);
         sstore(1);
         __syncthreads();
-        gload(min(kt + 2, KT - 1));
+        gload(min(kt + 2, KT - 1), 0);
         if (kt + 1 < KT) mfma_step(1);
         sstore(0);
         __syncthreads();
