@@ -88,9 +88,10 @@ static int launch_backproject_cfg(const uint8_t* Pq, const float* Ps, const uint
     const uint32_t tiles = tiles_m * tiles_n;
     const bool ragged = (m % BMm) || (n % kGroup) || (r % BK);
     const dim3 grid(grid8(tiles)), block(WGn * WGm * 64);
+    // the bounds-checked kernels need more registers: one workgroup fewer per CU
 #define QG_LAUNCH_BP(RAG, DUMP)                                                                                     \
-    hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, RAG, DUMP, PREF, MINWG>), grid, block, 0, stream, Pq, Ps, N, Wq, Ws, Udbg, \
-                       m, n, r, alpha, lr, key, tiles_m, tiles)
+    hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, RAG, DUMP, PREF, (RAG ? MINWG - 1 : MINWG)>), grid, block, 0,    \
+                       stream, Pq, Ps, N, Wq, Ws, Udbg, m, n, r, alpha, lr, key, tiles_m, tiles)
     if (ragged) {
         if (Udbg) QG_LAUNCH_BP(true, true); else QG_LAUNCH_BP(true, false);
     } else {
@@ -104,9 +105,9 @@ int launch_backproject(const uint8_t* Pq, const float* Ps, const uint16_t* N, in
                        int64_t m, int64_t n, int64_t r, float alpha, float lr, uint64_t seed, int64_t step,
                        hipStream_t stream) {
     const uint32_t key = sr_key(seed, (uint64_t)step, 0u);
-    // 128-row tiles, weight tile sharing the staging LDS, two workgroups per CU: the VALU-heavy update epilogue of
-    // one workgroup overlaps the MFMA main loop of the other.
-    return launch_backproject_cfg<128, 32, 2, 2, false, 2>(Pq, Ps, N, Wq, Ws, Udbg, (int)m, (int)n, (int)r, alpha, lr,
+    // 128-row tiles, weight tile sharing the staging LDS, three workgroups per CU: the VALU-heavy update epilogue of
+    // one workgroup overlaps the MFMA main loops of the others.
+    return launch_backproject_cfg<128, 32, 2, 2, false, 3>(Pq, Ps, N, Wq, Ws, Udbg, (int)m, (int)n, (int)r, alpha, lr,
                                                            key, stream);
 }
 
@@ -133,7 +134,7 @@ int launch_backproject_many(const PlanHeader* plan_host, const PlanHeader* plan_
         const uint32_t tiles = plan_host->bp_tiles[cls];
         if (cnt == 0 || tiles == 0) continue;
         if (cls == 0)
-            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, false, false, 2>), dim3(grid8(tiles)), dim3(256),
+            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, false, false, 3>), dim3(grid8(tiles)), dim3(256),
                                0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, alpha, lr, seed,
                                (uint64_t)step);
         else

@@ -61,8 +61,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
 }
 
 // One wave-wide 16-byte-per-lane load straight into LDS: lane i's bytes land at lds + 16*i (lds is wave-uniform).
-__device__ __forceinline__ void buffer_load_lds16(__amdgpu_buffer_rsrc_t rs, void* lds, uint32_t byte_off) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)lds, 16, byte_off, 0, 0, 0);
+// `byte_off` is per lane, `uniform_off` wave-uniform (a scalar register).
+__device__ __forceinline__ void buffer_load_lds16(__amdgpu_buffer_rsrc_t rs, void* lds, uint32_t byte_off,
+                                                  uint32_t uniform_off) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)lds, 16, byte_off,
+                                             uniform_off, 0, 0);
 }
 
 template <int WPT>
@@ -93,14 +96,19 @@ struct KMajorSwizzled {
 
     // element offset of 16-byte chunk c of row k
     __device__ static __forceinline__ int chunk_offset(int k, int c) { return k * BX + ((c ^ ((k & 3) << 2)) << 3); }
-    // byte offset (from the tile's first element in memory, row length ld) of the chunk that lane `lane` of wave
-    // `wave` fetches with its i-th load, and the tile row block that load fills
-    __device__ static __forceinline__ uint32_t lane_src_bytes(int wave, int i, int lane, int ld) {
-        const int row = (wave * PER + i) * RPI + lane / CPR;
-        const int c = (lane % CPR) ^ ((row & 3) << 2);
+    // A wave's i-th load fills tile rows load_row0(wave, i) .. +RPI-1.  Lane `lane` fetches the chunk at byte offset
+    // lane_src_bytes(lane, ld, v) + load_row0(wave, i) * ld * 2 from the tile's first element (row length ld).  The
+    // second summand is wave-uniform; the first depends on the load only through the residue v = load_row0 & 3 in
+    // the swizzle, which takes 4 / RPI values (at most two for the tiles used here): that many per-lane offsets
+    // serve all loads.
+    static constexpr int VARIANTS = RPI >= 4 ? 1 : 4 / RPI;
+    static_assert(PER % VARIANTS == 0, "every wave starts at a row that is a multiple of 4");
+    __device__ static __forceinline__ int load_row0(int wave, int i) { return (wave * PER + i) * RPI; }
+    __device__ static __forceinline__ uint32_t lane_src_bytes(int lane, int ld, int v) {
+        const int row = lane / CPR;   // row inside the load
+        const int c = (lane % CPR) ^ (((v * RPI + row) & 3) << 2);
         return 2u * (uint32_t)(row * ld + c * 8);
     }
-    __device__ static __forceinline__ int load_row0(int wave, int i) { return (wave * PER + i) * RPI; }
     // transpose-read lane offset and swizzle term (elements)
     __device__ static __forceinline__ int lane_offset(int lane) { return kmajor_lane_offset(BX, lane); }
     __device__ static __forceinline__ int lane_swizzle(int lane) { return ((lane & 15) >> 2) << 5; }
@@ -228,16 +236,17 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     // address arithmetic.  A K step covers BK rows of P, i.e. BK*r codes: a multiple of 256 (r is a multiple of 8),
     // so code bytes and block scales split the same way.
     static_assert(BK % 32 == 0, "a K step must cover whole blocks of 256 codes");
-    uint32_t a_el[A_PER], b_byte[B_PER];   // P: element offset; G: byte offset
+    constexpr int B_OFFS = RAGGED ? B_PER : BD::VARIANTS;
+    uint32_t a_el[A_PER], b_byte[B_OFFS];   // P: element offset; G: byte offset
 #pragma unroll
     for (int p = 0; p < A_PER; ++p) {
         const int ti = t + p * NT;
         a_el[p] = (uint32_t)((ti / A_TPR) * r + r0 + (ti % A_TPR) * (8 * WPT));
     }
 #pragma unroll
-    for (int p = 0; p < B_PER; ++p) {
+    for (int p = 0; p < B_OFFS; ++p) {
         if constexpr (!RAGGED) {
-            b_byte[p] = BD::lane_src_bytes(wave, p, lane, n);
+            b_byte[p] = BD::lane_src_bytes(lane, n, p);
         } else {
             const int ci = t + p * NT;
             b_byte[p] = 2u * (uint32_t)((ci / BD::CPR) * n + (ci % BD::CPR) * 8);
@@ -256,7 +265,8 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
             const __amdgpu_buffer_rsrc_t rq = make_rsrc(pq), rs = make_rsrc(ps), rg = make_rsrc(g);
 #pragma unroll
             for (int p = 0; p < B_PER; ++p)
-                buffer_load_lds16(rg, Bs + stage * S::B_STAGE + BD::load_row0(wave, p) * BN, b_byte[p]);
+                buffer_load_lds16(rg, Bs + stage * S::B_STAGE + BD::load_row0(wave, p) * BN, b_byte[p % BD::VARIANTS],
+                                  2u * (uint32_t)(BD::load_row0(wave, p) * n));
 #pragma unroll
             for (int p = 0; p < A_PER; ++p) {
                 buffer_load_words<WPT>(rq, a_el[p] >> 1, aw[p]);
@@ -333,6 +343,8 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+            // fragments of one 16-wide sub-step at a time (keeps the register count within three workgroups per CU)
+            __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_s_setprio(0);
     };
@@ -589,11 +601,12 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     // Uniform bases that advance with the K step plus fixed 32-bit per-thread offsets, as in the projection.  The
     // tile's first code, m0*r, starts a block of 256 (m0 is a multiple of 128, r of 8); the K offset k0 does not,
     // so the index of a code's block scale takes one add and two shifts per step.
-    uint32_t a_byte[A_PER], b_el[B_PER];   // N: byte offset; P: element offset inside the tile's rows
+    constexpr int A_OFFS = RAGGED ? A_PER : AD::VARIANTS;
+    uint32_t a_byte[A_OFFS], b_el[B_PER];   // N: byte offset; P: element offset inside the tile's rows
 #pragma unroll
-    for (int p = 0; p < A_PER; ++p) {
+    for (int p = 0; p < A_OFFS; ++p) {
         if constexpr (!RAGGED) {
-            a_byte[p] = AD::lane_src_bytes(wave, p, lane, n);
+            a_byte[p] = AD::lane_src_bytes(lane, n, p);
         } else {
             const int ci = t + p * NT;
             a_byte[p] = 2u * (uint32_t)((ci / AD::CPR) * n + (ci % AD::CPR) * 8);
@@ -617,7 +630,8 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
             const __amdgpu_buffer_rsrc_t rn = make_rsrc(nb), rq = make_rsrc(pq), rs = make_rsrc(ps);
 #pragma unroll
             for (int p = 0; p < A_PER; ++p)
-                buffer_load_lds16(rn, As + stage * S::A_STAGE + AD::load_row0(wave, p) * BNn, a_byte[p]);
+                buffer_load_lds16(rn, As + stage * S::A_STAGE + AD::load_row0(wave, p) * BNn, a_byte[p % AD::VARIANTS],
+                                  2u * (uint32_t)(AD::load_row0(wave, p) * n));
 #pragma unroll
             for (int p = 0; p < B_PER; ++p) {
                 buffer_load_words<WPT>(rq, b_el[p] >> 1, bw[p]);
