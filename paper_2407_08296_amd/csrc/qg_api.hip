@@ -32,6 +32,8 @@ int launch_adam_many(const PlanHeader*, const PlanHeader*, int64_t, const qg_hpa
 int launch_project_adam(const uint8_t*, const float*, const uint16_t*, float*, float*, float*, uint16_t*, int64_t, int64_t,
                         int64_t, int64_t, const qg_hparams*, hipStream_t);
 int launch_project_adam_many(const PlanHeader*, const PlanHeader*, int, int64_t, const qg_hparams*, hipStream_t);
+int project_mode(int64_t m, int64_t n, int64_t r);       // edge class the grouped projection needs for a matrix
+int backproject_mode(int64_t m, int64_t n, int64_t r);   // ... and the grouped back-projection
 constexpr int kAdamChunkElems = 256 * 4 * 4;  // must equal kAdamChunk of qg_adam.hip
 
 static int check_mnr(int64_t m, int64_t n, int64_t r, int group) {
@@ -140,16 +142,16 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
             !aligned16(d.M) || !aligned16(d.V) || (d.R && !aligned16(d.R)) || !aligned16(d.N))
             return QG_ERR_ALIGN;
     }
-    // shapes that fit the unguarded kernels: whole tiles everywhere and an even number of K steps
-    auto is_fast = [](const qg_matrix_desc& d) {
-        return (d.r % kManyProjBM) == 0 && (d.n % 256) == 0 && (d.m % 256) == 0;
+    auto matrix_class = [](const qg_matrix_desc& d) {
+        const int a = project_mode(d.m, d.n, d.r), b = backproject_mode(d.m, d.n, d.r);
+        return a > b ? a : b;
     };
-    uint64_t adam = 0, proj[2] = {0, 0}, bp[2] = {0, 0};
+    uint64_t adam = 0, proj[kPlanClasses] = {0, 0, 0}, bp[kPlanClasses] = {0, 0, 0};
     int out = 0;
-    for (int cls = 0; cls < 2; ++cls) {
+    for (int cls = 0; cls < kPlanClasses; ++cls) {
         for (int i = 0; i < count; ++i) {
             const qg_matrix_desc& d = descs[i];
-            if ((is_fast(d) ? 0 : 1) != cls) continue;
+            if (matrix_class(d) != cls) continue;
             PlanMatrix pm;
             std::memset(&pm, 0, sizeof pm);
             pm.m = d.m; pm.n = d.n; pm.r = d.r;
@@ -165,14 +167,13 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
             proj[cls] += (uint64_t)pm.proj_tiles_r * (uint64_t)((d.n + kManyProjBN - 1) / kManyProjBN);
             bp[cls] += (uint64_t)pm.bp_tiles_m * (uint64_t)((d.n + kManyBpBN - 1) / kManyBpBN);
             mats[out++] = pm;
+            ++h.class_count[cls];
         }
-        if (cls == 0) h.n_fast = out;
     }
-    if (adam > 0x7FFFFFF0ull || proj[0] > 0x7FFFFFF0ull || proj[1] > 0x7FFFFFF0ull || bp[0] > 0x7FFFFFF0ull ||
-        bp[1] > 0x7FFFFFF0ull)
-        return QG_ERR_SHAPE;
+    if (adam > 0x7FFFFFF0ull) return QG_ERR_SHAPE;
     h.adam_chunks = (uint32_t)adam;
-    for (int cls = 0; cls < 2; ++cls) {
+    for (int cls = 0; cls < kPlanClasses; ++cls) {
+        if (proj[cls] > 0x7FFFFFF0ull || bp[cls] > 0x7FFFFFF0ull) return QG_ERR_SHAPE;
         h.proj_tiles[cls] = (uint32_t)proj[cls];
         h.bp_tiles[cls] = (uint32_t)bp[cls];
     }

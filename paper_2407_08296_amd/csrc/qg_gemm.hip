@@ -8,18 +8,36 @@ namespace qg {
 // ---------------------------------------------------------------------------
 static inline unsigned grid8(uint32_t tiles) { return ((tiles + 7u) / 8u) * 8u; }
 
+// Edge mode of a matrix for tiles of TM (along r for the projection, along m for the back-projection) x TN and K
+// steps of BK over `kdim`.  The direct loads need 16-byte aligned rows (n % 8, and r % 16 for the 8-byte P fetches)
+// and 32-bit per-lane offsets.
+static inline int edge_mode(int64_t tiled, int TM, int64_t n, int TN, int64_t kdim, int BK, int64_t r) {
+    if (n > (int64_t(1) << 24) || (n % 8) != 0 || (r % 16) != 0) return kUnaligned;
+    if ((tiled % TM) == 0 && (n % TN) == 0 && (kdim % BK) == 0) return kExact;
+    return kMasked;
+}
+int project_mode(int64_t m, int64_t n, int64_t r) { return edge_mode(r, kManyProjBM, n, kManyProjBN, m, 32, r); }
+int backproject_mode(int64_t m, int64_t n, int64_t r) { return edge_mode(m, kManyBpBM, n, kManyBpBN, r, 32, r); }
+
 template <int BM, int BN, int BK, int WGM, int WGN, int MINWG>
 static int launch_project_cfg(const uint8_t* Pq, const float* Ps, const uint16_t* G, float* R, int m, int n, int r,
                               hipStream_t stream) {
     const uint32_t tiles_r = (uint32_t)((r + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
     const uint32_t tiles = tiles_r * tiles_n;
-    const bool ragged = (r % BM) || (n % BN) || (m % BK);
-    if (ragged)
-        hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, true, MINWG>), dim3(grid8(tiles)), dim3(WGM * WGN * 64), 0,
-                           stream, Pq, Ps, G, R, m, n, r, tiles_r, tiles);
-    else
-        hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, false, MINWG>), dim3(grid8(tiles)), dim3(WGM * WGN * 64), 0,
-                           stream, Pq, Ps, G, R, m, n, r, tiles_r, tiles);
+    const dim3 grid(grid8(tiles)), block(WGM * WGN * 64);
+    switch (edge_mode(r, BM, n, BN, m, BK, r)) {
+        case kExact:
+            hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, kExact, MINWG>), grid, block, 0, stream, Pq, Ps, G, R, m,
+                               n, r, tiles_r, tiles);
+            break;
+        case kMasked:
+            hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, kMasked, MINWG>), grid, block, 0, stream, Pq, Ps, G, R,
+                               m, n, r, tiles_r, tiles);
+            break;
+        default:
+            hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, kUnaligned, MINWG>), grid, block, 0, stream, Pq, Ps, G,
+                               R, m, n, r, tiles_r, tiles);
+    }
     return check_launch();
 }
 
@@ -28,13 +46,20 @@ static int launch_project_adam_cfg(const uint8_t* Pq, const float* Ps, const uin
                                    uint16_t* N, int m, int n, int r, const AdamCoef& coef, hipStream_t stream) {
     const uint32_t tiles_r = (uint32_t)((r + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
     const uint32_t tiles = tiles_r * tiles_n;
-    const bool ragged = (r % BM) || (n % BN) || (m % BK);
-    if (ragged)
-        hipLaunchKernelGGL((k_project_adam<BM, BN, BK, WGM, WGN, true, MINWG>), dim3(grid8(tiles)),
-                           dim3(WGM * WGN * 64), 0, stream, Pq, Ps, G, R, M, V, N, m, n, r, tiles_r, tiles, coef);
-    else
-        hipLaunchKernelGGL((k_project_adam<BM, BN, BK, WGM, WGN, false, MINWG>), dim3(grid8(tiles)),
-                           dim3(WGM * WGN * 64), 0, stream, Pq, Ps, G, R, M, V, N, m, n, r, tiles_r, tiles, coef);
+    const dim3 grid(grid8(tiles)), block(WGM * WGN * 64);
+    switch (edge_mode(r, BM, n, BN, m, BK, r)) {
+        case kExact:
+            hipLaunchKernelGGL((k_project_adam<BM, BN, BK, WGM, WGN, kExact, MINWG>), grid, block, 0, stream, Pq, Ps, G,
+                               R, M, V, N, m, n, r, tiles_r, tiles, coef);
+            break;
+        case kMasked:
+            hipLaunchKernelGGL((k_project_adam<BM, BN, BK, WGM, WGN, kMasked, MINWG>), grid, block, 0, stream, Pq, Ps,
+                               G, R, M, V, N, m, n, r, tiles_r, tiles, coef);
+            break;
+        default:
+            hipLaunchKernelGGL((k_project_adam<BM, BN, BK, WGM, WGN, kUnaligned, MINWG>), grid, block, 0, stream, Pq,
+                               Ps, G, R, M, V, N, m, n, r, tiles_r, tiles, coef);
+    }
     return check_launch();
 }
 
@@ -48,23 +73,32 @@ int launch_project_adam(const uint8_t* Pq, const float* Ps, const uint16_t* G, f
     return launch_project_adam_cfg<128, 128, 32, 2, 2, 2>(Pq, Ps, G, R, M, V, N, (int)m, (int)n, (int)r, coef, stream);
 }
 
-// Grouped launches: class 0 = matrices [0, n_fast) with the unguarded kernels, class 1 = the rest, guarded.
-static inline int class_first(const PlanHeader* h, int cls) { return cls == 0 ? 0 : h->n_fast; }
-static inline int class_count(const PlanHeader* h, int cls) { return cls == 0 ? h->n_fast : h->count - h->n_fast; }
+// Grouped launches: the plan stores the matrices class by class (kExact, kMasked, kUnaligned); each class that is
+// not empty gets a launch of its own kernel instance.
+static inline int class_first(const PlanHeader* h, int cls) {
+    int first = 0;
+    for (int c = 0; c < cls; ++c) first += h->class_count[c];
+    return first;
+}
+static inline int class_count(const PlanHeader* h, int cls) { return h->class_count[cls]; }
 
 int launch_project_adam_many(const PlanHeader* plan_host, const PlanHeader* plan_dev, int write_R, int64_t step,
                              const qg_hparams* hp, hipStream_t stream) {
     const AdamCoef coef = make_adam_coef(hp, step);
-    for (int cls = 0; cls < 2; ++cls) {
-        const int cnt = class_count(plan_host, cls);
+    for (int cls = 0; cls < kPlanClasses; ++cls) {
+        const int cnt = class_count(plan_host, cls), first = class_first(plan_host, cls);
         const uint32_t tiles = plan_host->proj_tiles[cls];
         if (cnt == 0 || tiles == 0) continue;
-        if (cls == 0)
-            hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, false, 2>), dim3(grid8(tiles)),
-                               dim3(256), 0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, write_R, coef);
+        const dim3 grid(grid8(tiles)), block(256);
+        if (cls == kExact)
+            hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, kExact, 2>), grid, block, 0,
+                               stream, plan_dev, first, cnt, tiles, write_R, coef);
+        else if (cls == kMasked)
+            hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, kMasked, 2>), grid, block, 0,
+                               stream, plan_dev, first, cnt, tiles, write_R, coef);
         else
-            hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, true, 2>), dim3(grid8(tiles)),
-                               dim3(256), 0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, write_R, coef);
+            hipLaunchKernelGGL((k_project_adam_many<kManyProjBM, kManyProjBN, 32, 2, 2, kUnaligned, 2>), grid, block, 0,
+                               stream, plan_dev, first, cnt, tiles, write_R, coef);
         if (int e = check_launch()) return e;
     }
     return QG_OK;
@@ -80,22 +114,28 @@ int launch_project(const uint8_t* Pq, const float* Ps, const uint16_t* G, float*
     return launch_project_cfg<128, 128, 32, 2, 2, 2>(Pq, Ps, G, R, (int)m, (int)n, (int)r, stream);
 }
 
-template <int BMm, int BK, int WGn, int WGm, bool PREF, int MINWG>
+// Workgroups per CU the back-projection instances are compiled for (the checked variants need more registers).
+static constexpr int kBpWgPerCu[3] = {3, 3, 2};
+
+template <int BMm, int BK, int WGn, int WGm, bool PREF>
 static int launch_backproject_cfg(const uint8_t* Pq, const float* Ps, const uint16_t* N, int8_t* Wq, float* Ws,
                                   float* Udbg, int m, int n, int r, float alpha, float lr, uint32_t key,
                                   hipStream_t stream) {
     const uint32_t tiles_m = (uint32_t)((m + BMm - 1) / BMm), tiles_n = (uint32_t)((n + kGroup - 1) / kGroup);
     const uint32_t tiles = tiles_m * tiles_n;
-    const bool ragged = (m % BMm) || (n % kGroup) || (r % BK);
     const dim3 grid(grid8(tiles)), block(WGn * WGm * 64);
-    // the bounds-checked kernels need more registers: one workgroup fewer per CU
-#define QG_LAUNCH_BP(RAG, DUMP)                                                                                     \
-    hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, RAG, DUMP, PREF, (RAG ? MINWG - 1 : MINWG)>), grid, block, 0,    \
-                       stream, Pq, Ps, N, Wq, Ws, Udbg, m, n, r, alpha, lr, key, tiles_m, tiles)
-    if (ragged) {
-        if (Udbg) QG_LAUNCH_BP(true, true); else QG_LAUNCH_BP(true, false);
-    } else {
-        if (Udbg) QG_LAUNCH_BP(false, true); else QG_LAUNCH_BP(false, false);
+#define QG_LAUNCH_BP(MODE, DUMP)                                                                                    \
+    hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, MODE, DUMP, PREF, kBpWgPerCu[MODE]>), grid, block, 0, stream, \
+                       Pq, Ps, N, Wq, Ws, Udbg, m, n, r, alpha, lr, key, tiles_m, tiles)
+    switch (edge_mode(m, BMm, n, kGroup, r, BK, r)) {
+        case kExact:
+            if (Udbg) QG_LAUNCH_BP(kExact, true); else QG_LAUNCH_BP(kExact, false);
+            break;
+        case kMasked:
+            if (Udbg) QG_LAUNCH_BP(kMasked, true); else QG_LAUNCH_BP(kMasked, false);
+            break;
+        default:
+            if (Udbg) QG_LAUNCH_BP(kUnaligned, true); else QG_LAUNCH_BP(kUnaligned, false);
     }
 #undef QG_LAUNCH_BP
     return check_launch();
@@ -105,23 +145,27 @@ int launch_backproject(const uint8_t* Pq, const float* Ps, const uint16_t* N, in
                        int64_t m, int64_t n, int64_t r, float alpha, float lr, uint64_t seed, int64_t step,
                        hipStream_t stream) {
     const uint32_t key = sr_key(seed, (uint64_t)step, 0u);
-    // 128-row tiles, weight tile sharing the staging LDS, three workgroups per CU: the VALU-heavy update epilogue of
-    // one workgroup overlaps the MFMA main loops of the others.
-    return launch_backproject_cfg<128, 32, 2, 2, false, 3>(Pq, Ps, N, Wq, Ws, Udbg, (int)m, (int)n, (int)r, alpha, lr,
+    // 128-row tiles, weight tile sharing the staging LDS, several workgroups per CU: the VALU-heavy update epilogue
+    // of one workgroup overlaps the MFMA main loops of the others.
+    return launch_backproject_cfg<128, 32, 2, 2, false>(Pq, Ps, N, Wq, Ws, Udbg, (int)m, (int)n, (int)r, alpha, lr,
                                                            key, stream);
 }
 
 int launch_project_many(const PlanHeader* plan_host, const PlanHeader* plan_dev, hipStream_t stream) {
-    for (int cls = 0; cls < 2; ++cls) {
-        const int cnt = class_count(plan_host, cls);
+    for (int cls = 0; cls < kPlanClasses; ++cls) {
+        const int cnt = class_count(plan_host, cls), first = class_first(plan_host, cls);
         const uint32_t tiles = plan_host->proj_tiles[cls];
         if (cnt == 0 || tiles == 0) continue;
-        if (cls == 0)
-            hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, false, 2>), dim3(grid8(tiles)),
-                               dim3(256), 0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles);
+        const dim3 grid(grid8(tiles)), block(256);
+        if (cls == kExact)
+            hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, kExact, 2>), grid, block, 0, stream,
+                               plan_dev, first, cnt, tiles);
+        else if (cls == kMasked)
+            hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, kMasked, 2>), grid, block, 0, stream,
+                               plan_dev, first, cnt, tiles);
         else
-            hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, true, 2>), dim3(grid8(tiles)),
-                               dim3(256), 0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles);
+            hipLaunchKernelGGL((k_project_many<kManyProjBM, kManyProjBN, 32, 2, 2, kUnaligned, 2>), grid, block, 0,
+                               stream, plan_dev, first, cnt, tiles);
         if (int e = check_launch()) return e;
     }
     return QG_OK;
@@ -129,18 +173,20 @@ int launch_project_many(const PlanHeader* plan_host, const PlanHeader* plan_dev,
 
 int launch_backproject_many(const PlanHeader* plan_host, const PlanHeader* plan_dev, float alpha, float lr,
                             uint64_t seed, int64_t step, hipStream_t stream) {
-    for (int cls = 0; cls < 2; ++cls) {
-        const int cnt = class_count(plan_host, cls);
+    for (int cls = 0; cls < kPlanClasses; ++cls) {
+        const int cnt = class_count(plan_host, cls), first = class_first(plan_host, cls);
         const uint32_t tiles = plan_host->bp_tiles[cls];
         if (cnt == 0 || tiles == 0) continue;
-        if (cls == 0)
-            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, false, false, 3>), dim3(grid8(tiles)), dim3(256),
-                               0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, alpha, lr, seed,
-                               (uint64_t)step);
+        const dim3 grid(grid8(tiles)), block(256);
+        if (cls == kExact)
+            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, kExact, false, kBpWgPerCu[kExact]>), grid, block,
+                               0, stream, plan_dev, first, cnt, tiles, alpha, lr, seed, (uint64_t)step);
+        else if (cls == kMasked)
+            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, kMasked, false, kBpWgPerCu[kMasked]>), grid,
+                               block, 0, stream, plan_dev, first, cnt, tiles, alpha, lr, seed, (uint64_t)step);
         else
-            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, true, false, 2>), dim3(grid8(tiles)), dim3(256),
-                               0, stream, plan_dev, class_first(plan_host, cls), cnt, tiles, alpha, lr, seed,
-                               (uint64_t)step);
+            hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, kUnaligned, false, kBpWgPerCu[kUnaligned]>),
+                               grid, block, 0, stream, plan_dev, first, cnt, tiles, alpha, lr, seed, (uint64_t)step);
         if (int e = check_launch()) return e;
     }
     return QG_OK;

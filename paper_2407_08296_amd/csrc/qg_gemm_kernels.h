@@ -54,10 +54,29 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef u32x2 __attribute__((aligned(4))) u32x2_align4;
 typedef u32x4 __attribute__((aligned(4))) u32x4_align4;
 
+// How a kernel instance treats the matrix edges.
+//   kExact:     every tile lies inside the matrix and the K extent is a whole number of steps: no checks at all.
+//   kMasked:    any m and r, rows 16-byte aligned (n a multiple of 8, r of 16).  Loads are the same wide buffer and
+//               direct-to-LDS loads as kExact, bounded by the end of the matrix: what lies past the end reads as
+//               zero, which is all the K tail needs; columns past a row's end read the next row (finite values that
+//               only reach output elements the masked epilogue never stores).
+//   kUnaligned: rows start at arbitrary element offsets (n not a multiple of 8): operands go through registers with
+//               per-chunk checks.
+enum : int { kExact = 0, kMasked = 1, kUnaligned = 2 };
+
+// Number of bytes a bounded buffer resource may cover: `bytes` (not negative, a multiple of 4, below 2^34) clamped
+// to what the 32-bit field holds; per-lane offsets stay far below that clamp.  Written with a shift and a 32-bit
+// minimum so that it stays on the scalar unit (which has no 64-bit ordered compare).
+__device__ __forceinline__ int bound_bytes(int64_t bytes) {
+    const uint32_t words = (uint32_t)((uint64_t)bytes >> 2);
+    return (int)((words < 0x1FFFFFFFu ? words : 0x1FFFFFFFu) << 2);
+}
+
 // Buffer resource over memory starting at `base`: loads through it take a scalar base, a scalar offset and a 32-bit
 // per-thread byte offset, so a loop that only moves the base spends no vector instructions on addresses.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
+// Offsets at or past `bytes` read as zero.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int bytes = 0x7FFFFFFF) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
 
 // One wave-wide 16-byte-per-lane load straight into LDS: lane i's bytes land at lds + 16*i (lds is wave-uniform).
@@ -170,14 +189,14 @@ __device__ __forceinline__ void load_p_guarded(const uint8_t* Pq, const float* P
     }
 }
 
-// Words of INT4 codes a thread fetches with one load when staging a P tile: as wide as the tile allows.  In the
-// unguarded kernels 8*WPT codes never straddle a block of 256 (tiles start at multiples of 32 and r is a multiple
-// of the tile), so one scale serves the fetch; the guarded kernels keep a scale per word.
-template <int WORDS, int NT, bool RAGGED>
+// Words of INT4 codes a thread fetches with one load when staging a P tile: as wide as the tile allows.  Where r is
+// a multiple of 8*WPT a fetch starts at a multiple of 8*WPT codes and never straddles a block of 256, so one scale
+// serves it; the kernels for unaligned shapes (r only a multiple of 8) keep a scale per word.
+template <int WORDS, int NT, bool PER_WORD_SCALES>
 struct P_Task {
     static constexpr int WPT = WORDS / NT >= 4 ? 4 : (WORDS / NT >= 2 ? 2 : 1);
     static constexpr int PER = WORDS / (NT * WPT);
-    static constexpr int NSC = RAGGED ? WPT : 1;   // scales kept per fetch
+    static constexpr int NSC = PER_WORD_SCALES ? WPT : 1;   // scales kept per fetch
     static_assert(WORDS % (NT * WPT) == 0 && PER >= 1, "staging must divide evenly");
 };
 
@@ -204,18 +223,21 @@ struct ProjShape {
 // With FUSE_ADAM the epilogue runs Adam on the tile while R is still in the accumulators: M and V are read and
 // written in place, N is stored as bf16 and R goes to memory only if the caller asked for it (R != nullptr), which
 // saves the 8 bytes per element of writing R and reading it back in a separate pass.
-template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, bool FUSE_ADAM = false>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, bool FUSE_ADAM = false>
 __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
                                              const uint16_t* __restrict__ G, float* __restrict__ R, int m, int n,
                                              int r, int r0, int n0, uint16_t* smem, float* __restrict__ Mo = nullptr,
                                              float* __restrict__ Vo = nullptr, uint16_t* __restrict__ No = nullptr,
                                              const AdamCoef* coef = nullptr) {
+    constexpr bool RAGGED = MODE != kExact;      // masked epilogue
+    constexpr bool DIRECT = MODE != kUnaligned;  // buffer / direct-to-LDS loads; a P fetch (8*WPT codes) starts at a
+                                                 // multiple of 8*WPT codes, so it lies in one block of 256
     using S = ProjShape<BM, BN, BK, WGM, WGN>;
     constexpr int NT = S::NT;
     constexpr int WM = BM / WGM, WN = BN / WGN, MB = WM / 32, NB = WN / 32;
     constexpr int PA = S::PA, PB = S::PB;
     constexpr int A_WORDS = BK * BM / 8;
-    using AT = P_Task<A_WORDS, NT, RAGGED>;
+    using AT = P_Task<A_WORDS, NT, !DIRECT>;
     constexpr int A_PER = AT::PER, WPT = AT::WPT, A_TPR = BM / (8 * WPT);   // tasks per tile row
     using BD = KMajorSwizzled<BN, BK, NT>;
     constexpr int B_PER = BD::PER;
@@ -228,7 +250,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     const int wm = wave / WGN, wn = wave % WGN;
     uint32_t aw[A_PER][WPT];
     float asc[A_PER][AT::NSC];
-    u32x4 bv[RAGGED ? B_PER : 1];   // the guarded kernels stage G through registers
+    u32x4 bv[DIRECT ? 1 : B_PER];   // the unaligned kernels stage G through registers
 
     // Addresses are split into a part that is uniform over the workgroup and advances with the K step (scalar
     // registers, scalar arithmetic) and a 32-bit per-thread offset fixed for the whole loop; the unguarded kernels
@@ -236,7 +258,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     // address arithmetic.  A K step covers BK rows of P, i.e. BK*r codes: a multiple of 256 (r is a multiple of 8),
     // so code bytes and block scales split the same way.
     static_assert(BK % 32 == 0, "a K step must cover whole blocks of 256 codes");
-    constexpr int B_OFFS = RAGGED ? B_PER : BD::VARIANTS;
+    constexpr int B_OFFS = DIRECT ? BD::VARIANTS : B_PER;
     uint32_t a_el[A_PER], b_byte[B_OFFS];   // P: element offset; G: byte offset
 #pragma unroll
     for (int p = 0; p < A_PER; ++p) {
@@ -245,7 +267,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     }
 #pragma unroll
     for (int p = 0; p < B_OFFS; ++p) {
-        if constexpr (!RAGGED) {
+        if constexpr (DIRECT) {
             b_byte[p] = BD::lane_src_bytes(lane, n, p);
         } else {
             const int ci = t + p * NT;
@@ -261,8 +283,16 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
         const uint8_t* pq = Pq + (e0 >> 1);
         const float* ps = Ps + (e0 >> 8);
         const uint8_t* g = reinterpret_cast<const uint8_t*>(G + (int64_t)i0 * n + n0);
-        if constexpr (!RAGGED) {
-            const __amdgpu_buffer_rsrc_t rq = make_rsrc(pq), rs = make_rsrc(ps), rg = make_rsrc(g);
+        if constexpr (DIRECT) {
+            __amdgpu_buffer_rsrc_t rq, rs, rg;
+            if constexpr (MODE == kExact) {
+                rq = make_rsrc(pq); rs = make_rsrc(ps); rg = make_rsrc(g);
+            } else {   // bounded by the end of each array: rows at or past m read as zero
+                const int64_t mr = (int64_t)m * r;
+                rq = make_rsrc(pq, bound_bytes((mr - e0) >> 1));
+                rs = make_rsrc(ps, bound_bytes((((mr + kGroup - 1) >> 8) - (e0 >> 8)) * 4));
+                rg = make_rsrc(g, bound_bytes(((int64_t)(m - i0) * n - n0) * 2));
+            }
 #pragma unroll
             for (int p = 0; p < B_PER; ++p)
                 buffer_load_lds16(rg, Bs + stage * S::B_STAGE + BD::load_row0(wave, p) * BN, b_byte[p % BD::VARIANTS],
@@ -270,7 +300,10 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
             for (int p = 0; p < A_PER; ++p) {
                 buffer_load_words<WPT>(rq, a_el[p] >> 1, aw[p]);
-                asc[p][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (a_el[p] >> 8) << 2, 0, 0));
+#pragma unroll
+                for (int j = 0; j < AT::NSC; ++j)
+                    asc[p][j] = __builtin_bit_cast(
+                        float, __builtin_amdgcn_raw_buffer_load_b32(rs, ((a_el[p] + 8 * j) >> 8) << 2, 0, 0));
             }
         } else {
 #pragma unroll
@@ -298,9 +331,9 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
             for (int j = 0; j < WPT; ++j)
                 *reinterpret_cast<u32x4*>(As + stage * S::A_STAGE + row * PA + c + 8 * j) =
-                    dequant8_bf16(aw[p][j], asc[p][RAGGED ? j : 0]);
+                    dequant8_bf16(aw[p][j], asc[p][DIRECT ? 0 : j]);
         }
-        if constexpr (RAGGED) {
+        if constexpr (!DIRECT) {
 #pragma unroll
             for (int p = 0; p < B_PER; ++p) {
                 const int ci = t + p * NT;
@@ -368,16 +401,31 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 
     const int lcol = lane & 31, lhalf = lane >> 5;
     if (!FUSE_ADAM) {
+        // R through buffer stores: the base of each 32-row block and the row inside it are scalars, the lane supplies
+        // one byte offset per 32-column block, and stores past the resource's end are dropped by the hardware.  That
+        // is the whole row mask (rows at or past r lie past the end of R); a column at or past n gets an offset no
+        // resource covers.
+        uint32_t voff[NB];
 #pragma unroll
-        for (int a = 0; a < MB; ++a)
+        for (int b = 0; b < NB; ++b) {
+            const int col = wn * WN + b * 32 + lcol;   // inside the tile
+            voff[b] = (!RAGGED || n0 + col < n) ? 4u * (uint32_t)(4 * lhalf * n + col) : 0x80000000u;
+        }
+#pragma unroll
+        for (int a = 0; a < MB; ++a) {
+            const int row0 = r0 + wm * WM + a * 32;
+            float* base = R + (int64_t)row0 * n + n0;
+            const __amdgpu_buffer_rsrc_t rr =
+                RAGGED ? make_rsrc(base, row0 < r ? bound_bytes(((int64_t)(r - row0) * n - n0) * 4) : 0) : make_rsrc(base);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = r0 + wm * WM + a * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                    const int col = n0 + wn * WN + b * 32 + lcol;
-                    if (!RAGGED || (row < r && col < n)) R[(int64_t)row * n + col] = acc[a][b][v];
+                    const float x = acc[a][b][v];   // (a copy: bit_cast of a vector element lvalue reads element 0)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, x), rr, voff[b],
+                                                          4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n), 0);
                 }
+        }
     } else {
         const AdamCoef c = *coef;
         const bool odd = (lane & 1) != 0;
@@ -422,7 +470,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project(const uint8_t* __restrict__ Pq,
                                                            const float* __restrict__ Ps,
                                                            const uint16_t* __restrict__ G, float* __restrict__ R,
@@ -430,11 +478,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project(const 
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    project_tile<BM, BN, BK, WGM, WGN, RAGGED>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
+    project_tile<BM, BN, BK, WGM, WGN, MODE>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
                                                (int)(tile / tiles_r) * BN, smem);
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam(
     const uint8_t* __restrict__ Pq, const float* __restrict__ Ps, const uint16_t* __restrict__ G,
     float* __restrict__ R, float* __restrict__ M, float* __restrict__ V, uint16_t* __restrict__ N, int m, int n, int r,
@@ -442,7 +490,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam(
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    project_tile<BM, BN, BK, WGM, WGN, RAGGED, true>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
+    project_tile<BM, BN, BK, WGM, WGN, MODE, true>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
                                                      (int)(tile / tiles_r) * BN, smem, M, V, N, &coef);
 }
 
@@ -456,7 +504,7 @@ __device__ __forceinline__ int plan_find(const PlanMatrix* mats, int count, uint
     return lo;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(const PlanHeader* __restrict__ plan, int first,
                                                                                int count, uint32_t tiles) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
@@ -465,12 +513,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(c
     const PlanMatrix* mats = plan_matrices(plan) + first;
     const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
     const uint32_t local = tile - d.proj_tile0;
-    project_tile<BM, BN, BK, WGM, WGN, RAGGED>(d.Pq, d.Ps, d.G, d.R, (int)d.m, (int)d.n, (int)d.r,
+    project_tile<BM, BN, BK, WGM, WGN, MODE>(d.Pq, d.Ps, d.G, d.R, (int)d.m, (int)d.n, (int)d.r,
                                                (int)(local % d.proj_tiles_r) * BM,
                                                (int)(local / d.proj_tiles_r) * BN, smem);
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool RAGGED, int MIN_WG_PER_CU = 1>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam_many(const PlanHeader* __restrict__ plan,
                                                                                      int first, int count,
                                                                                      uint32_t tiles, int write_R,
@@ -481,7 +529,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam_m
     const PlanMatrix* mats = plan_matrices(plan) + first;
     const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
     const uint32_t local = tile - d.proj_tile0;
-    project_tile<BM, BN, BK, WGM, WGN, RAGGED, true>(d.Pq, d.Ps, d.G, write_R ? d.R : nullptr, (int)d.m, (int)d.n,
+    project_tile<BM, BN, BK, WGM, WGN, MODE, true>(d.Pq, d.Ps, d.G, write_R ? d.R : nullptr, (int)d.m, (int)d.n,
                                                      (int)d.r, (int)(local % d.proj_tiles_r) * BM,
                                                      (int)(local / d.proj_tiles_r) * BN, smem, d.M, d.V, d.N, &coef);
 }
@@ -526,12 +574,15 @@ __device__ __forceinline__ constexpr int wtile_run_bits(int a, int v4) {
     return ((2 * a + (v4 >> 1)) << 4) | ((v4 & 1) << 3);
 }
 
-template <int BMm, int BK, int WGn, int WGm, bool RAGGED, bool DUMP_U, bool W_PREFETCH = true>
+template <int BMm, int BK, int WGn, int WGm, int MODE, bool DUMP_U, bool W_PREFETCH = true>
 __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
                                                  const uint16_t* __restrict__ N, int8_t* __restrict__ Wq,
                                                  float* __restrict__ Ws, float* __restrict__ Udbg, int m, int n, int r,
                                                  int m0, int tile_n, float alpha, float lr, uint32_t key,
                                                  uint16_t* smem) {
+    constexpr bool RAGGED = MODE != kExact;      // masked epilogue
+    constexpr bool DIRECT = MODE != kUnaligned;  // buffer / direct-to-LDS loads; a P fetch (8*WPT codes) starts at a
+                                                 // multiple of 8*WPT codes, so it lies in one block of 256
     using S = BpShape<BMm, BK, WGn, WGm, W_PREFETCH>;
     constexpr int BNn = S::BNn, NT = S::NT, NW = WGn * WGm;
     constexpr int SN = BNn / WGn, SM = BMm / WGm, IB = SN / 32, JB = SM / 32;
@@ -539,7 +590,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     using AD = KMajorSwizzled<BNn, BK, NT>;
     constexpr int A_PER = AD::PER;
     constexpr int B_WORDS = BMm * BK / 8;
-    using BT = P_Task<B_WORDS, NT, RAGGED>;
+    using BT = P_Task<B_WORDS, NT, !DIRECT>;
     constexpr int B_PER = BT::PER, WPT = BT::WPT, B_TPR = BK / (8 * WPT);   // tasks per tile row
     static_assert(BK % (8 * WPT) == 0, "tile shape");
     constexpr int W_ROUNDS = BMm / 4 / NW;   // each wave-wide 16-byte access covers 4 tile rows
@@ -594,18 +645,18 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     };
     if (W_PREFETCH) load_wtile();   // lands while the GEMM main loop runs
 
-    u32x4 av[RAGGED ? A_PER : 1];   // the guarded kernels stage N through registers
+    u32x4 av[DIRECT ? 1 : A_PER];   // the unaligned kernels stage N through registers
     uint32_t bw[B_PER][WPT];
     float bsc[B_PER][BT::NSC];
 
     // Uniform bases that advance with the K step plus fixed 32-bit per-thread offsets, as in the projection.  The
     // tile's first code, m0*r, starts a block of 256 (m0 is a multiple of 128, r of 8); the K offset k0 does not,
     // so the index of a code's block scale takes one add and two shifts per step.
-    constexpr int A_OFFS = RAGGED ? A_PER : AD::VARIANTS;
+    constexpr int A_OFFS = DIRECT ? AD::VARIANTS : A_PER;
     uint32_t a_byte[A_OFFS], b_el[B_PER];   // N: byte offset; P: element offset inside the tile's rows
 #pragma unroll
     for (int p = 0; p < A_OFFS; ++p) {
-        if constexpr (!RAGGED) {
+        if constexpr (DIRECT) {
             a_byte[p] = AD::lane_src_bytes(lane, n, p);
         } else {
             const int ci = t + p * NT;
@@ -626,8 +677,16 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         const uint8_t* nb = reinterpret_cast<const uint8_t*>(N + (int64_t)k0 * n + n0);
         const uint8_t* pq = Pq + ((e_tile + k0) >> 1);
         const float* ps = Ps + (e_tile >> 8);
-        if constexpr (!RAGGED) {
-            const __amdgpu_buffer_rsrc_t rn = make_rsrc(nb), rq = make_rsrc(pq), rs = make_rsrc(ps);
+        if constexpr (DIRECT) {
+            __amdgpu_buffer_rsrc_t rn, rq, rs;
+            if constexpr (MODE == kExact) {
+                rn = make_rsrc(nb); rq = make_rsrc(pq); rs = make_rsrc(ps);
+            } else {   // bounded by the end of each array: rows of N at or past r read as zero (the K tail)
+                const int64_t mr = (int64_t)m * r;
+                rn = make_rsrc(nb, bound_bytes(((int64_t)(r - k0) * n - n0) * 2));
+                rq = make_rsrc(pq, bound_bytes((mr - e_tile - k0) >> 1));
+                rs = make_rsrc(ps, bound_bytes((((mr + kGroup - 1) >> 8) - (e_tile >> 8)) * 4));
+            }
 #pragma unroll
             for (int p = 0; p < A_PER; ++p)
                 buffer_load_lds16(rn, As + stage * S::A_STAGE + AD::load_row0(wave, p) * BNn, a_byte[p % AD::VARIANTS],
@@ -635,8 +694,10 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
 #pragma unroll
             for (int p = 0; p < B_PER; ++p) {
                 buffer_load_words<WPT>(rq, b_el[p] >> 1, bw[p]);
-                bsc[p][0] = __builtin_bit_cast(
-                    float, __builtin_amdgcn_raw_buffer_load_b32(rs, ((b_el[p] + (uint32_t)k0) >> 8) << 2, 0, 0));
+#pragma unroll
+                for (int j = 0; j < BT::NSC; ++j)
+                    bsc[p][j] = __builtin_bit_cast(
+                        float, __builtin_amdgcn_raw_buffer_load_b32(rs, ((b_el[p] + (uint32_t)(k0 + 8 * j)) >> 8) << 2, 0, 0));
             }
         } else {
 #pragma unroll
@@ -663,9 +724,9 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
 #pragma unroll
             for (int j = 0; j < WPT; ++j)
                 *reinterpret_cast<u32x4*>(Bs + stage * S::B_STAGE + row * PB + c + 8 * j) =
-                    dequant8_bf16(bw[p][j], bsc[p][RAGGED ? j : 0]);
+                    dequant8_bf16(bw[p][j], bsc[p][DIRECT ? 0 : j]);
         }
-        if constexpr (RAGGED) {
+        if constexpr (!DIRECT) {
 #pragma unroll
             for (int p = 0; p < A_PER; ++p) {
                 const int ci = t + p * NT;
@@ -832,7 +893,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     }
 }
 
-template <int BMm, int BK, int WGn, int WGm, bool RAGGED, bool DUMP_U, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
+template <int BMm, int BK, int WGn, int WGm, int MODE, bool DUMP_U, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject(const uint8_t* __restrict__ Pq,
                                                                const float* __restrict__ Ps,
                                                                const uint16_t* __restrict__ N,
@@ -843,11 +904,11 @@ __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject(co
     __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    backproject_tile<BMm, BK, WGn, WGm, RAGGED, DUMP_U, W_PREFETCH>(Pq, Ps, N, Wq, Ws, Udbg, m, n, r, (int)(tile % tiles_m) * BMm,
+    backproject_tile<BMm, BK, WGn, WGm, MODE, DUMP_U, W_PREFETCH>(Pq, Ps, N, Wq, Ws, Udbg, m, n, r, (int)(tile % tiles_m) * BMm,
                                                 (int)(tile / tiles_m), alpha, lr, key, smem);
 }
 
-template <int BMm, int BK, int WGn, int WGm, bool RAGGED, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
+template <int BMm, int BK, int WGn, int WGm, int MODE, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_many(const PlanHeader* __restrict__ plan, int first,
                                                                                    int count, uint32_t tiles,
                                                                                    float alpha, float lr,
@@ -859,7 +920,7 @@ __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_ma
     const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.bp_tile0; })];
     const uint32_t local = tile - d.bp_tile0;
     const uint32_t key = sr_key(seed + (uint64_t)d.index * 0x9E3779B97F4A7C15ull, step, 0u);
-    backproject_tile<BMm, BK, WGn, WGm, RAGGED, false, W_PREFETCH>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.r,
+    backproject_tile<BMm, BK, WGn, WGm, MODE, false, W_PREFETCH>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.r,
                                                 (int)(local % d.bp_tiles_m) * BMm, (int)(local / d.bp_tiles_m),
                                                 alpha, lr, key, smem);
 }

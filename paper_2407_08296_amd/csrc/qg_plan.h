@@ -35,17 +35,19 @@ struct PlanMatrix {
     uint32_t index;         // position in the caller's descriptor array (selects the SR seed of the matrix)
 };
 
-// The records are stored in two classes, each served by its own launch: first the `n_fast` matrices whose
-// shapes fit the unguarded kernels, then the rest (bounds-checked kernels).  Tile indices (proj_tile0, bp_tile0)
-// count within a class; Adam chunks run over all matrices.
+// The records are stored class by class, each class served by its own launch: shapes that need no edge checks,
+// shapes with edges but 16-byte aligned rows, and the rest (see the kernels' edge modes).  A matrix takes the more
+// demanding of the classes its projection and its back-projection need.  Tile indices (proj_tile0, bp_tile0) count
+// within a class; Adam chunks run over all matrices.
+constexpr int kPlanClasses = 3;
 struct PlanHeader {
     uint32_t magic;
     int32_t count;
     uint32_t adam_chunks;
-    int32_t n_fast;            // matrices [0, n_fast) are the unguarded class
-    uint32_t proj_tiles[2];    // per class: fast, guarded
-    uint32_t bp_tiles[2];
-    uint32_t no_R;             // 1 if some matrix has no R buffer
+    uint32_t no_R;                        // 1 if some matrix has no R buffer
+    int32_t class_count[kPlanClasses];    // matrices per class, in storage order
+    uint32_t proj_tiles[kPlanClasses];
+    uint32_t bp_tiles[kPlanClasses];
     uint32_t pad_[3];
 };
 static_assert(sizeof(PlanHeader) % 16 == 0, "records must stay 16-byte aligned");

@@ -81,16 +81,26 @@ def test_plan_build_on_host(L):
     buf = C.create_string_buffer(nbytes)
     assert L.qg_plan_build(2, descs, buf, nbytes - 1) == 5
     assert L.qg_plan_build(2, descs, buf, nbytes) == 0
-    hdr = (C.c_uint32 * 12).from_buffer(buf)
+    # header: magic, count, Adam chunks, no_R, then per class (exact, masked, unaligned): matrices, projection
+    # tiles, back-projection tiles
+    hdr = (C.c_uint32 * 16).from_buffer(buf)
     assert hdr[1] == 2                                       # count
     assert hdr[2] == 2 * (1024 * 4096) // 4096               # Adam chunks of 4096 elements
-    assert hdr[3] == 2                                       # both matrices fit the unguarded kernels
-    assert (hdr[4], hdr[5]) == (2 * 8 * 16, 0)               # projection tiles 128 x 256 over r x n, per class
-    assert (hdr[6], hdr[7]) == (32 * 16 + 86 * 16, 0)        # back-projection tiles 128 x 256 over m x n
-    descs[1].n = 5461
+    assert hdr[3] == 0                                       # every matrix has an R buffer
+    assert list(hdr[4:7]) == [2, 0, 0]                       # both matrices need no edge checks
+    assert list(hdr[7:10]) == [2 * 8 * 16, 0, 0]             # projection tiles 128 x 256 over r x n
+    assert list(hdr[10:13]) == [32 * 16 + 86 * 16, 0, 0]     # back-projection tiles 128 x 256 over m x n
+    descs[1].n = 5461                                        # odd row length: rows not 16-byte aligned
     assert L.qg_plan_build(2, descs, buf, nbytes) == 0
-    hdr = (C.c_uint32 * 12).from_buffer(buf)
-    assert hdr[3] == 1 and (hdr[4], hdr[5]) == (8 * 16, 8 * 22) and (hdr[6], hdr[7]) == (32 * 16, 86 * 22)
+    hdr = (C.c_uint32 * 16).from_buffer(buf)
+    assert list(hdr[4:7]) == [1, 0, 1]
+    assert list(hdr[7:10]) == [8 * 16, 0, 8 * 22] and list(hdr[10:13]) == [32 * 16, 0, 86 * 22]
+    descs[1].n = 2736                                        # ragged but aligned rows; m = 11008 = 86 x 128
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 0
+    hdr = (C.c_uint32 * 16).from_buffer(buf)
+    assert list(hdr[4:7]) == [1, 1, 0]
+    assert list(hdr[7:10]) == [8 * 16, 8 * 11, 0] and list(hdr[10:13]) == [32 * 16, 86 * 11, 0]
+    descs[1].n = 5461
     descs[1].r = 12
     assert L.qg_plan_build(2, descs, buf, nbytes) == 2
     descs[1].r = 1024

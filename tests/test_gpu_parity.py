@@ -124,8 +124,10 @@ def test_sr_generator_known_answers_and_stream():
 
 
 # ------------------------------------------------------------------ projection
+# exact tiles; unaligned rows (n % 8, r % 16); aligned rows with a K tail / an r edge / an n edge (bounded loads)
 @pytest.mark.parametrize("m,n,r", [(512, 512, 128), (768, 768, 256), (2048, 768, 256), (768, 2048, 256),
-                                   (300, 700, 40), (1000, 264, 8), (2736, 1024, 256)])
+                                   (300, 700, 40), (1000, 264, 8), (2736, 1024, 256), (333, 264, 144),
+                                   (200, 520, 48), (1040, 1048, 272)])
 def test_project(m, n, r):
     d = make_inputs(m, n, r)
     R = qg.project(dev(d["Pq"]), dev(d["Ps"]), dev(d["Gb"]), m, n, r)
@@ -193,7 +195,8 @@ def test_project_adam_fused_equals_separate_calls(m, n, r):
 
 # ------------------------------------------------------------------ back-projection + SR update
 @pytest.mark.parametrize("m,n,r", [(512, 512, 128), (768, 768, 256), (2048, 768, 256), (768, 2048, 256),
-                                   (300, 700, 40), (1000, 264, 8), (4096, 4096, 64)])
+                                   (300, 700, 40), (1000, 264, 8), (4096, 4096, 64), (333, 264, 144),
+                                   (200, 520, 48), (1040, 1048, 272)])
 def test_backproject_update_sr(m, n, r):
     d = make_inputs(m, n, r)
     rs = np.random.default_rng(12)
@@ -283,7 +286,8 @@ def _state_for(kind_shapes, seed=0):
 
 @pytest.mark.parametrize("shapes", [
     [(512, 512, 256), (768, 768, 256), (2048, 768, 256), (768, 2048, 256)],        # aligned: fast grouped kernels
-    [(512, 512, 128), (300, 700, 40), (1024, 2736, 256)],                           # ragged: bounds-checked kernels
+    [(512, 512, 128), (300, 700, 40), (1024, 2736, 256)],                           # all three edge classes
+    [(333, 264, 144), (2736, 1024, 256), (200, 520, 48)],                           # aligned rows, edges everywhere
 ])
 def test_step_many_matches_oracle(shapes):
     mats, data = _state_for(shapes)
