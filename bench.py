@@ -227,6 +227,52 @@ def main():
     ms_per_step = wall * 1e3 / K
 
     dur = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)) / K for i in range(3)]   # ms per launch
+
+    # Outside the timed region: the shader clock each phase runs at (a one-wave probe on a second stream counts
+    # shader cycles against the constant 100 MHz counter for about half of the phase), and the two ceilings the
+    # fractions can be read against (a register-only MFMA loop, a plain device copy).
+    side = torch.cuda.Stream()
+    probe_out = torch.zeros((3, 2), dtype=torch.int64, device=device)
+    phases = [lambda: qg.project_many(plan), lambda: qg.lowrank_adam_many(plan, hp, t + 1),
+              lambda: qg.backproject_update_sr_many(plan, hp, 0, t + 1)]
+    main = torch.cuda.current_stream()
+    for i, launch in enumerate(phases):
+        ticks = max(int(dur[i] * 0.5 * 1e5), 1000)          # 1e5 ticks per ms
+        if dur[i] * 1e5 < 4000:                               # too short to sample
+            launch()
+            continue
+        start = torch.cuda.Event()
+        start.record(main)
+        launch()
+        with torch.cuda.stream(side):
+            side.wait_event(start)
+            qg.diag_clock_probe(ticks, probe_out[i])
+    torch.cuda.synchronize()
+    po = probe_out.cpu().tolist()
+    sclk = [(c / (w / 100.0)) if w > 0 else None for c, w in po]   # MHz
+    t += 1
+
+    def timed(f, reps):
+        f(); torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record(); torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+    sink = torch.empty((qg.DIAG_MFMA_WORKGROUPS * 512,), dtype=torch.float32, device=device)
+    mfma_iters = 256
+    mfma_flop = qg.DIAG_MFMA_WORKGROUPS * 8 * mfma_iters * 16 * 32768.0
+    ceil_const = mfma_flop / timed(lambda: qg.diag_mfma_loop(mfma_iters, False, sink), 5) / 1e9
+    ceil_random = mfma_flop / timed(lambda: qg.diag_mfma_loop(mfma_iters, True, sink), 5) / 1e9
+    csrc = torch.ones((1 << 27,), dtype=torch.float32, device=device)      # 512 MiB
+    cdst = torch.empty_like(csrc)
+    copy_gbs = 2 * csrc.numel() * 4 / timed(lambda: cdst.copy_(csrc), 5) / 1e6
+    del csrc, cdst
+    ceilings = {"mfma_loop_constant_operands_TFLOP/s": ceil_const, "mfma_loop_random_operands_TFLOP/s": ceil_random,
+                "device_copy_GB/s": copy_gbs,
+                "note": "register-only bf16 32x32x16 MFMA loop, two waves per SIMD; plain 512 MiB device copy "
+                        "(read + written bytes)"}
     flops, b_proj, b_adam, b_bp = algorithmic_work(shapes)
     kernels = {
         "project": {"ms": dur[0], "TFLOP/s": flops / dur[0] / 1e9, "frac_mfma": flops / dur[0] / 1e9 / PEAK_BF16_TFLOPS,
@@ -245,6 +291,12 @@ def main():
                     "achieved": kernels[name]["TFLOP/s"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": kernels[name]["frac_mfma"], "traffic": None}
 
+    if sclk[dom]:
+        roofline["sclk_mhz"] = sclk[dom]
+        if roofline["bound"] == "mfma":   # the published peak assumes 2400 MHz
+            roofline["frac_of_peak_at_measured_clock"] = roofline["frac"] * 2400.0 / sclk[dom]
+    for i, name in enumerate(("project", "lowrank_adam", "backproject_update_sr")):
+        kernels[name]["sclk_mhz"] = sclk[i]
     roofline["traffic"] = measured_traffic(roofline["kernel"], args.config)
     roofline["traffic_unit"] = "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, see profiles/)"
     roofline["algorithmic_bytes"] = [b_proj, b_adam, b_bp][dom]
@@ -253,7 +305,7 @@ def main():
         "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "launches_per_step": 3},
-        "roofline": roofline, "kernels": kernels,
+        "roofline": roofline, "kernels": kernels, "ceilings": ceilings,
     }
     if not args.no_cpu_baseline:
         del plan, mats

@@ -185,6 +185,21 @@ int qg_project_adam_many(int count, const void* plan_host, const void* plan_dev,
 int qg_backproject_update_sr_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
                                   const qg_hparams* hp, uint64_t seed, int64_t step, void* stream);
 
+/* ---- Measurement helpers (no part of the method; used by the benchmark to state what the machine sustains).
+ *
+ * qg_diag_clock_probe: enqueues a one-wave kernel that waits ticks_100mhz ticks (1 .. 10^8) of the constant
+ * 100 MHz counter and writes {shader clock cycles elapsed, ticks elapsed} to out2 (device, 2 x int64).  Launched
+ * on a second stream beside a kernel under test it gives the shader clock that kernel runs at.
+ *
+ * qg_diag_mfma_loop: QG_DIAG_MFMA_WORKGROUPS workgroups of 512 threads (8 waves, two per SIMD); each wave issues
+ * iters (1 .. 2^24) rounds of 16 independent bf16 32x32x16 MFMAs on register operands, i.e.
+ * QG_DIAG_MFMA_WORKGROUPS * 8 * iters * 16 * 32768 flop per launch: the ceiling of the matrix pipe with nothing else
+ * running.  random_operands != 0 fills the operands with varied finite bit patterns (the sustained clock depends on
+ * the data), 0 with constants.  sink: device, QG_DIAG_MFMA_WORKGROUPS * 512 floats (written so the loop is live). */
+#define QG_DIAG_MFMA_WORKGROUPS 512
+int qg_diag_clock_probe(int64_t ticks_100mhz, int64_t* out2, void* stream);
+int qg_diag_mfma_loop(int64_t iters, int random_operands, float* sink, void* stream);
+
 /* ---- Test helper: out[i] = u(seed, step, idx0 + i) for i < count, the uniform
  * draws of the stochastic-rounding generator, as fp32. */
 int qg_sr_uniform(uint64_t seed, int64_t step, uint64_t idx0, int64_t count, float* out, void* stream);

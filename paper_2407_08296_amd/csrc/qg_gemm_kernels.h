@@ -145,21 +145,6 @@ __device__ __forceinline__ u32x4 load8_bf16_guarded(const uint16_t* src, int val
     return o;
 }
 
-// WPT consecutive 32-bit words (WPT = 1, 2 or 4) from a pointer aligned to 4*WPT bytes.
-template <int WPT>
-__device__ __forceinline__ void load_words(const uint8_t* p, uint32_t (&w)[WPT]) {
-    if constexpr (WPT == 4) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(p);
-        w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
-    } else if constexpr (WPT == 2) {
-        typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-        const u32x2 v = *reinterpret_cast<const u32x2*>(p);
-        w[0] = v[0]; w[1] = v[1];
-    } else {
-        w[0] = *reinterpret_cast<const uint32_t*>(p);
-    }
-}
-
 // Guarded fetch of WPT words of INT4 codes starting at flat element index e (a multiple of 8), of which the first
 // `valid` codes lie inside the matrix.  Every word carries the scale of its own block: with r not a multiple of
 // 8*WPT the words of one fetch can fall into two blocks of 256.  Words outside read as code 0, scale 0.

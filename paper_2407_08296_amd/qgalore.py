@@ -23,7 +23,7 @@ EXPORTS = [
     "qg_project", "qg_lowrank_adam", "qg_backproject_update_sr", "qg_cossim_workspace_bytes", "qg_subspace_cossim",
     "qg_policy_update", "qg_workspace_bytes", "qg_step", "qg_plan_bytes", "qg_plan_build", "qg_step_many",
     "qg_sr_uniform", "qg_project_many", "qg_lowrank_adam_many", "qg_backproject_update_sr_many",
-    "qg_project_adam", "qg_project_adam_many",
+    "qg_project_adam", "qg_project_adam_many", "qg_diag_clock_probe", "qg_diag_mfma_loop",
 ]
 
 
@@ -87,6 +87,8 @@ def lib() -> C.CDLL:
         L.qg_backproject_update_sr_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), u64, i64, vp]
         L.qg_project_adam.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i64, C.POINTER(HParams), vp]
         L.qg_project_adam_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), i64, i32, vp]
+        L.qg_diag_clock_probe.argtypes = [i64, vp, vp]
+        L.qg_diag_mfma_loop.argtypes = [i64, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -264,6 +266,21 @@ def project_adam_many(plan: StepPlan, hp: HParams, step: int, write_R: bool = Fa
 def backproject_update_sr_many(plan: StepPlan, hp: HParams, seed: int, step: int) -> None:
     _check(lib().qg_backproject_update_sr_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
                                                C.byref(hp), seed, step, _stream()))
+
+
+DIAG_MFMA_WORKGROUPS = 512
+
+
+def diag_clock_probe(ticks_100mhz: int, out2: torch.Tensor) -> None:
+    """Enqueue the clock probe on the current stream; out2 (2 x int64, device) receives {shader cycles, ticks}."""
+    _check(lib().qg_diag_clock_probe(ticks_100mhz, _ptr(out2, (torch.int64,)), _stream()))
+
+
+def diag_mfma_loop(iters: int, random_operands: bool, sink: torch.Tensor) -> float:
+    """Enqueue the register-only MFMA loop; returns the flop it performs."""
+    assert sink.numel() >= DIAG_MFMA_WORKGROUPS * 512
+    _check(lib().qg_diag_mfma_loop(iters, int(random_operands), _ptr(sink, (torch.float32,)), _stream()))
+    return DIAG_MFMA_WORKGROUPS * 8 * iters * 16 * 32768.0
 
 
 def sr_uniform(seed: int, step: int, idx0: int, count: int, device="cuda") -> torch.Tensor:
