@@ -836,10 +836,14 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
             for (int v4 = 0; v4 < 4; ++v4) {
                 const int col = wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
                 uint32_t pk = 0;
+                // with aligned rows the run's first element index is a multiple of 4: index + e == index | e, and
+                // key ^ (index | e) == (key ^ index) ^ e, one xor per element instead of an add and an xor
+                const uint32_t run_key = key ^ (idx_row + (uint32_t)col);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float tq = acc[a][b][4 * v4 + e] * inv;
-                    const uint32_t h = mix32(key ^ (idx_row + (uint32_t)(col + e)));
+                    const uint32_t h = DIRECT ? mix32(run_key ^ (uint32_t)e)
+                                              : mix32(key ^ (idx_row + (uint32_t)(col + e)));
                     // fl32(tq + u) with u = (h >> 8) * 2^-24: the product is exact, so one fma rounds the same sum
                     const float v = __builtin_fmaf((float)(h >> 8), 0x1p-24f, tq);
                     // clamp(floor(v), -128, 127) as a byte: the saturating float -> u8 conversion of floor(v) + 128
