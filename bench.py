@@ -187,11 +187,27 @@ def main():
                     f()
                 e1.record(); torch.cuda.synchronize()
                 return e0.elapsed_time(e1) / reps
+            flops, b_proj, b_adam, b_bp = algorithmic_work([(m, n, r)])
             tp = run(lambda: qg.project(Pq, Ps, G, m, n, r, R))
             ta = run(lambda: qg.lowrank_adam(R, M, V, N, 2, hp))
             tb = run(lambda: qg.backproject_update_sr(Pq, Ps, N, Wq, Ws, m, n, r, 0.25, 1e-3, 0, 2))
-            flops, b_proj, b_adam, b_bp = algorithmic_work([(m, n, r)])
-            rows.append({"r": r, "project_us": tp * 1e3, "project_TFLOP/s": flops / tp / 1e9,
+            # steady state: the same matrix 24 times (the 24 `down` weights of the 1B model) through the grouped
+            # launches - what a training step sees; the single launches above are bound by launch and load latency
+            copies = 24
+            gm = []
+            for _ in range(copies):
+                gm.append(qg.MatrixState(m, n, r, Pq, Ps, G.clone(), Wq.clone(), Ws.clone(), torch.zeros_like(M),
+                                         torch.zeros_like(V), torch.empty_like(R), torch.empty_like(N)))
+            gplan = qg.StepPlan(gm)
+            gp = run(lambda: qg.project_many(gplan), 10) / copies
+            ga = run(lambda: qg.lowrank_adam_many(gplan, hp, 2), 10) / copies
+            gb = run(lambda: qg.backproject_update_sr_many(gplan, hp, 0, 2), 10) / copies
+            del gm, gplan
+            rows.append({"r": r, "grouped_project_us": gp * 1e3, "grouped_project_TFLOP/s": flops / gp / 1e9,
+                         "grouped_project_GB/s": b_proj / gp / 1e6, "grouped_adam_us": ga * 1e3,
+                         "grouped_adam_GB/s": b_adam / ga / 1e6, "grouped_backproject_us": gb * 1e3,
+                         "grouped_backproject_TFLOP/s": flops / gb / 1e9, "grouped_backproject_GB/s": b_bp / gb / 1e6,
+                         "project_us": tp * 1e3, "project_TFLOP/s": flops / tp / 1e9,
                          "project_GB/s": b_proj / tp / 1e6, "adam_us": ta * 1e3, "adam_GB/s": b_adam / ta / 1e6,
                          "backproject_us": tb * 1e3, "backproject_TFLOP/s": flops / tb / 1e9,
                          "backproject_GB/s": b_bp / tb / 1e6,
@@ -273,6 +289,8 @@ def main():
                 "device_copy_GB/s": copy_gbs,
                 "note": "register-only bf16 32x32x16 MFMA loop, two waves per SIMD; plain 512 MiB device copy "
                         "(read + written bytes)"}
+    per_step = sorted(ev[k][0].elapsed_time(ev[k][3]) for k in range(K))      # GPU time of each step, ms
+    step_stats = {"gpu_ms_min": per_step[0], "gpu_ms_median": per_step[len(per_step) // 2], "gpu_ms_max": per_step[-1]}
     flops, b_proj, b_adam, b_bp = algorithmic_work(shapes)
     kernels = {
         "project": {"ms": dur[0], "TFLOP/s": flops / dur[0] / 1e9, "frac_mfma": flops / dur[0] / 1e9 / PEAK_BF16_TFLOPS,
@@ -305,7 +323,7 @@ def main():
         "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "launches_per_step": 3},
-        "roofline": roofline, "kernels": kernels, "ceilings": ceilings,
+        "roofline": roofline, "kernels": kernels, "ceilings": ceilings, "step_stats": step_stats,
     }
     if not args.no_cpu_baseline:
         del plan, mats
