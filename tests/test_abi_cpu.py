@@ -68,6 +68,11 @@ def test_step_piece_argument_errors(L):
     assert L.qg_step(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 128, 256, C.byref(hp), 0, 0, None, 0, None) == 2
     assert L.qg_sr_uniform(0, 1, 0, 0, FAKE, None) == 2
     assert L.qg_sr_uniform(0, 1, 0, 16, None, None) == 1
+    assert L.qg_diag_clock_probe(0, FAKE, None) == 2
+    assert L.qg_diag_clock_probe(10 ** 9, FAKE, None) == 2      # more than a second of spinning is refused
+    assert L.qg_diag_clock_probe(1000, None, None) == 1
+    assert L.qg_diag_mfma_loop(0, 0, FAKE, None) == 2
+    assert L.qg_diag_mfma_loop(16, 1, None, None) == 1
 
 
 def test_plan_build_on_host(L):

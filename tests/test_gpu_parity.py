@@ -457,3 +457,19 @@ def test_subspace_cossim(m, r):
         got = float(host(qg.subspace_cossim(dev(pa[0]), dev(pa[1]), dev(pb[0]), dev(pb[1]), m, r))[0])
         want = Q.subspace_cossim(pa[0], pa[1], pb[0], pb[1], m, r)
         assert abs(got - want) <= 1e-5, (got, want)
+
+
+# ------------------------------------------------------------------ measurement helpers
+def test_diag_clock_probe_and_mfma_loop():
+    out = torch.zeros((2,), dtype=torch.int64, device="cuda")
+    qg.diag_clock_probe(20000, out)                    # 0.2 ms of the 100 MHz counter
+    torch.cuda.synchronize()
+    cycles, ticks = out.cpu().tolist()
+    assert 20000 <= ticks < 200000
+    assert 100.0 < cycles / (ticks / 100.0) < 3500.0   # shader clock in MHz
+    sink = torch.empty((qg.DIAG_MFMA_WORKGROUPS * 512,), dtype=torch.float32, device="cuda")
+    for random_operands in (False, True):
+        flop = qg.diag_mfma_loop(8, random_operands, sink)
+        torch.cuda.synchronize()
+        assert flop == qg.DIAG_MFMA_WORKGROUPS * 8 * 8 * 16 * 32768.0
+        assert bool(torch.isfinite(sink).all())
