@@ -15,14 +15,18 @@ __device__ inline void adam_chunk(const float* __restrict__ R, float* __restrict
                                   uint16_t* __restrict__ N, int64_t count, int64_t base, const AdamCoef& c) {
     const int t = threadIdx.x;
     if (base + kAdamChunk <= count) {
+        // every access is streaming (nothing here is re-read before it has left the caches): non-temporal loads and
+        // stores throughout, one array at a time
         f32x4 r[kAdamVec], m[kAdamVec], v[kAdamVec];
 #pragma unroll
-        for (int k = 0; k < kAdamVec; ++k) {
-            const int64_t e = base + (int64_t)(k * 256 + t) * 4;
-            r[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(R + e));
-            m[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(M + e));
-            v[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(V + e));
-        }
+        for (int k = 0; k < kAdamVec; ++k)
+            r[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(R + base + (int64_t)(k * 256 + t) * 4));
+#pragma unroll
+        for (int k = 0; k < kAdamVec; ++k)
+            m[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(M + base + (int64_t)(k * 256 + t) * 4));
+#pragma unroll
+        for (int k = 0; k < kAdamVec; ++k)
+            v[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(V + base + (int64_t)(k * 256 + t) * 4));
 #pragma unroll
         for (int k = 0; k < kAdamVec; ++k) {
             const int64_t e = base + (int64_t)(k * 256 + t) * 4;
@@ -36,10 +40,9 @@ __device__ inline void adam_chunk(const float* __restrict__ R, float* __restrict
             }
             __builtin_nontemporal_store(m[k], reinterpret_cast<f32x4*>(M + e));
             __builtin_nontemporal_store(v[k], reinterpret_cast<f32x4*>(V + e));
-            uint2 nb;
-            nb.x = pack_bf16x2(nn[0], nn[1]);
-            nb.y = pack_bf16x2(nn[2], nn[3]);
-            *reinterpret_cast<uint2*>(N + e) = nb;
+            typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+            const u32x2 nb = {pack_bf16x2(nn[0], nn[1]), pack_bf16x2(nn[2], nn[3])};
+            __builtin_nontemporal_store(nb, reinterpret_cast<u32x2*>(N + e));
         }
     } else {
         for (int64_t e = base + t; e < count && e < base + kAdamChunk; e += 256) {
