@@ -124,3 +124,24 @@ def test_policy_matches_oracle_tables(L):
             assert qg.policy_update(p, c) == o.update(float(C.c_float(c).value))
             assert (p.interval, p.streak, p.next_refresh) == (o.interval, o.streak, o.next_refresh)
     assert L.qg_policy_update(None, 0.5) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode != 0
+    assert "ONE GPU" in (p.stderr + p.stdout)
+
+
+def test_product_package_does_not_touch_the_oracle():
+    """The library and its binding may not import, read or call anything under oracle/ (test infrastructure)."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2407_08296_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|oracle[./]|#include.*oracle", text, re.M), \
+                    os.path.join(dirpath, f)
