@@ -23,7 +23,8 @@ namespace qg {
 
 constexpr int kPadK = 32;  // bf16 of padding per row of a K-major tile (64 B: rows k..k+3 hit distinct bank groups)
 // Cache policy of the R stores: non-temporal.  R is written once and read by a later kernel; kept out of the L2 it
-// leaves the G panels there for the other tiles that share them (measured: +13 % projection throughput).
+// leaves the operand panels there for the tiles that share them (+13 % on one large matrix alone, neutral inside
+// the full 7B step).
 constexpr int kAuxStream = 2;
 #ifndef QG_MFMA_PRIO
 #define QG_MFMA_PRIO 1
