@@ -2,8 +2,10 @@
 """Benchmark of the Q-GaLore optimizer step on one MI355X.
 
 A "step" is one pass of the whole hot path (project -> Adam -> back-project + INT8 stochastic-rounding
-update) over every linear weight of the workload, by the three grouped launches of qg_step_many.  The
-default workload is the one the headline metric is quoted on: LLaMA-7B shapes (224 matrices, r = 1024).
+update) over every linear weight of the workload, by the two grouped launches of qg_step_many (projection with
+Adam in its epilogue; back-projection with the update in its epilogue).  The unfused projection and Adam launches
+are timed too, after the timed region, for their own roofline fractions.  The default workload is the one the
+headline metric is quoted on: LLaMA-7B shapes (224 matrices, r = 1024).
 Inputs are synthetic, generated on the device before the timed region, and stay resident in HBM.
 
 Prints ONE JSON line (see README for the fields).
@@ -218,7 +220,11 @@ def main():
 
     shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(args.config)]
     mats = build_state(args.config, device)
-    plan = qg.StepPlan(mats)
+    import dataclasses
+    # The step needs no R buffers (the projected gradient stays in registers between the projection and Adam); the
+    # unfused pair of launches, timed after the step for its own roofline figures, does.
+    plan = qg.StepPlan([dataclasses.replace(s, R=None) for s in mats])
+    plan_unfused = qg.StepPlan(mats)
     hp = qg.hparams()
     K, W = args.steps, args.warmup
 
@@ -226,35 +232,47 @@ def main():
     for _ in range(W):
         t += 1
         qg.step_many(plan, hp, 0, t)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(K):
+    for k in range(K):                 # qg_step_many = these two grouped launches; events between them
         t += 1
         ev[k][0].record()
-        qg.project_many(plan)
+        qg.project_adam_many(plan, hp, t, False)
         ev[k][1].record()
-        qg.lowrank_adam_many(plan, hp, t)
-        ev[k][2].record()
         qg.backproject_update_sr_many(plan, hp, 0, t)
-        ev[k][3].record()
+        ev[k][2].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / K
+    dur2 = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)) / K for i in range(2)]   # ms per launch
 
-    dur = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)) / K for i in range(3)]   # ms per launch
+    # Outside the timed region.  (1) The unfused projection and Adam launches, for their own roofline fractions.
+    def timed(f, reps):
+        f(); torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record(); torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+    t += 1
+    d_proj = timed(lambda: qg.project_many(plan_unfused), 3)
+    d_adam = timed(lambda: qg.lowrank_adam_many(plan_unfused, hp, t), 3)
+    dur = [d_proj, d_adam, dur2[1]]
 
-    # Outside the timed region: the shader clock each phase runs at (a one-wave probe on a second stream counts
-    # shader cycles against the constant 100 MHz counter for about half of the phase), and the two ceilings the
-    # fractions can be read against (a register-only MFMA loop, a plain device copy).
+    # (2) The shader clock each kernel runs at (a one-wave probe on a second stream counts shader cycles against the
+    # constant 100 MHz counter for about half of the kernel), and (3) the two ceilings the fractions can be read
+    # against (a register-only MFMA loop, a plain device copy).
     side = torch.cuda.Stream()
-    probe_out = torch.zeros((3, 2), dtype=torch.int64, device=device)
-    phases = [lambda: qg.project_many(plan), lambda: qg.lowrank_adam_many(plan, hp, t + 1),
-              lambda: qg.backproject_update_sr_many(plan, hp, 0, t + 1)]
+    probe_out = torch.zeros((4, 2), dtype=torch.int64, device=device)
+    phases = [(d_proj, lambda: qg.project_many(plan_unfused)), (d_adam, lambda: qg.lowrank_adam_many(plan_unfused, hp, t)),
+              (dur2[1], lambda: qg.backproject_update_sr_many(plan, hp, 0, t)),
+              (dur2[0], lambda: qg.project_adam_many(plan, hp, t + 1, False))]
     main = torch.cuda.current_stream()
-    for i, launch in enumerate(phases):
-        ticks = max(int(dur[i] * 0.5 * 1e5), 1000)          # 1e5 ticks per ms
-        if dur[i] * 1e5 < 4000:                               # too short to sample
+    for i, (d, launch) in enumerate(phases):
+        ticks = max(int(d * 0.5 * 1e5), 1000)          # 1e5 ticks per ms
+        if d * 1e5 < 4000:                               # too short to sample
             launch()
             continue
         start = torch.cuda.Event()
@@ -268,14 +286,6 @@ def main():
     sclk = [(c / (w / 100.0)) if w > 0 else None for c, w in po]   # MHz
     t += 1
 
-    def timed(f, reps):
-        f(); torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            f()
-        b.record(); torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
     sink = torch.empty((qg.DIAG_MFMA_WORKGROUPS * 512,), dtype=torch.float32, device=device)
     mfma_iters = 256
     mfma_flop = qg.DIAG_MFMA_WORKGROUPS * 8 * mfma_iters * 16 * 32768.0
@@ -289,44 +299,43 @@ def main():
                 "device_copy_GB/s": copy_gbs,
                 "note": "register-only bf16 32x32x16 MFMA loop, two waves per SIMD; plain 512 MiB device copy "
                         "(read + written bytes)"}
-    per_step = sorted(ev[k][0].elapsed_time(ev[k][3]) for k in range(K))      # GPU time of each step, ms
+    per_step = sorted(ev[k][0].elapsed_time(ev[k][2]) for k in range(K))      # GPU time of each step, ms
     step_stats = {"gpu_ms_min": per_step[0], "gpu_ms_median": per_step[len(per_step) // 2], "gpu_ms_max": per_step[-1]}
     flops, b_proj, b_adam, b_bp = algorithmic_work(shapes)
+    b_fused = b_proj + b_adam - sum(8 * r * n for m, n, r in shapes)      # no R written, no R read back
+    mfma = lambda ms: {"TFLOP/s": flops / ms / 1e9, "frac_mfma": flops / ms / 1e9 / PEAK_BF16_TFLOPS}
     kernels = {
-        "project": {"ms": dur[0], "TFLOP/s": flops / dur[0] / 1e9, "frac_mfma": flops / dur[0] / 1e9 / PEAK_BF16_TFLOPS,
-                    "GB/s": b_proj / dur[0] / 1e6},
-        "lowrank_adam": {"ms": dur[1], "GB/s": b_adam / dur[1] / 1e6, "frac_hbm": b_adam / dur[1] / 1e6 / PEAK_HBM_GBS},
-        "backproject_update_sr": {"ms": dur[2], "TFLOP/s": flops / dur[2] / 1e9,
-                                  "frac_mfma": flops / dur[2] / 1e9 / PEAK_BF16_TFLOPS, "GB/s": b_bp / dur[2] / 1e6},
+        # the two launches of the step, timed inside the timed region
+        "project_adam": {"ms": dur2[0], **mfma(dur2[0]), "GB/s": b_fused / dur2[0] / 1e6, "sclk_mhz": sclk[3],
+                         "in_timed_region": True},
+        "backproject_update_sr": {"ms": dur2[1], **mfma(dur2[1]), "GB/s": b_bp / dur2[1] / 1e6, "sclk_mhz": sclk[2],
+                                  "in_timed_region": True},
+        # the unfused projection and Adam launches (same results), timed after the step
+        "project": {"ms": dur[0], **mfma(dur[0]), "GB/s": b_proj / dur[0] / 1e6, "sclk_mhz": sclk[0],
+                    "in_timed_region": False},
+        "lowrank_adam": {"ms": dur[1], "GB/s": b_adam / dur[1] / 1e6, "frac_hbm": b_adam / dur[1] / 1e6 / PEAK_HBM_GBS,
+                         "sclk_mhz": sclk[1], "in_timed_region": False},
     }
-    dom = max(range(3), key=lambda i: dur[i])
-    if dom == 1:
-        roofline = {"kernel": "k_lowrank_adam_many", "bound": "hbm", "achieved": kernels["lowrank_adam"]["GB/s"],
-                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": kernels["lowrank_adam"]["frac_hbm"], "traffic": None}
-    else:
-        name = "project" if dom == 0 else "backproject_update_sr"
-        roofline = {"kernel": "k_project_many" if dom == 0 else "k_backproject_many", "bound": "mfma",
-                    "achieved": kernels[name]["TFLOP/s"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": kernels[name]["frac_mfma"], "traffic": None}
-
-    if sclk[dom]:
-        roofline["sclk_mhz"] = sclk[dom]
-        if roofline["bound"] == "mfma":   # the published peak assumes 2400 MHz
-            roofline["frac_of_peak_at_measured_clock"] = roofline["frac"] * 2400.0 / sclk[dom]
-    for i, name in enumerate(("project", "lowrank_adam", "backproject_update_sr")):
-        kernels[name]["sclk_mhz"] = sclk[i]
+    dom_name, dom_kernel, dom_bytes = (("project_adam", "k_project_adam_many", b_fused) if dur2[0] >= dur2[1] else
+                                       ("backproject_update_sr", "k_backproject_many", b_bp))
+    roofline = {"kernel": dom_kernel, "bound": "mfma", "achieved": kernels[dom_name]["TFLOP/s"],
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dom_name]["frac_mfma"], "traffic": None}
+    if kernels[dom_name]["sclk_mhz"]:
+        roofline["sclk_mhz"] = kernels[dom_name]["sclk_mhz"]
+        # the published peak assumes 2400 MHz
+        roofline["frac_of_peak_at_measured_clock"] = roofline["frac"] * 2400.0 / roofline["sclk_mhz"]
     roofline["traffic"] = measured_traffic(roofline["kernel"], args.config)
     roofline["traffic_unit"] = "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, see profiles/)"
-    roofline["algorithmic_bytes"] = [b_proj, b_adam, b_bp][dom]
+    roofline["algorithmic_bytes"] = dom_bytes
     out = {
         "metric": "qgalore_step_ms_all_linear_weights", "value": ms_per_step, "unit": "ms", "n_gpus": 1,
         "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "launches_per_step": 3},
+        "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "launches_per_step": 2},
         "roofline": roofline, "kernels": kernels, "ceilings": ceilings, "step_stats": step_stats,
     }
     if not args.no_cpu_baseline:
-        del plan, mats
+        del plan, plan_unfused, mats
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(args.config, shapes)
     print(json.dumps(out), flush=True)

@@ -118,9 +118,8 @@ int qg_lowrank_adam(const float* R, float* M, float* V, uint16_t* N_bf16,
 /* ---- Projection and Adam fused (Sec. 3.5): the same arithmetic as qg_project followed by qg_lowrank_adam, with
  * Adam applied in the GEMM epilogue while R is still in registers.  M, V in/out, N out; R (nullable) receives the
  * projected gradient only if the caller wants to inspect it - leaving it NULL saves writing and re-reading
- * 8 bytes per low-rank element.  Results are bit-identical to the two separate calls.  At LLaMA-7B shapes the
- * separate calls are faster (the per-lane M/V accesses of the epilogue are latency-bound, the stand-alone Adam
- * pass streams at ~70 % of HBM peak); the fused form pays off where launches, not bytes, bound the step. */
+ * 8 bytes per low-rank element.  Results are bit-identical to the two separate calls.  This is the form qg_step
+ * and qg_step_many run (at LLaMA-7B shapes: 14.2 ms against 11.8 + 4.6 ms for the two separate launches). */
 int qg_project_adam(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
                     float* R /* nullable */, float* M, float* V, uint16_t* N_bf16,
                     int64_t m, int64_t n, int64_t r, int group, int64_t step, const qg_hparams* hp, void* stream);
@@ -152,8 +151,10 @@ int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB,
 int qg_policy_update(qg_policy* p, float cos);
 
 /* ---- One full step on one matrix (Sec. 3.5): project -> Adam -> back-project +
- * SR update, three kernels on `stream`.  R and N are caller-provided outputs
- * (r x n fp32 / bf16).  No subspace refresh happens inside. */
+ * SR update, as two kernels on `stream` (qg_project_adam, then
+ * qg_backproject_update_sr): the same results as the three separate calls.
+ * N is a caller-provided output (r x n bf16); R (r x n fp32) is written only
+ * if it is not NULL.  No subspace refresh happens inside. */
 size_t qg_workspace_bytes(int64_t m, int64_t n, int64_t r);
 int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
             int8_t* Wq, float* Ws, float* M, float* V, float* R, uint16_t* N_bf16,
@@ -162,8 +163,10 @@ int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
             void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- Grouped step over many matrices (the whole model's linear weights) in
- * three grouped launches (projection, Adam, back-projection + update).
- * A descriptor's R may be NULL only for plans used with qg_project_adam_many alone.  `descs` is a HOST array of `count` descriptors.
+ * two grouped launches per edge class (projection with Adam in its epilogue,
+ * back-projection + update).  R is written only if every descriptor supplies
+ * a buffer for it; qg_project_many and qg_lowrank_adam_many need every R.
+ * `descs` is a HOST array of `count` descriptors.
  * The library needs a device-resident launch plan: the caller provides
  * `plan_host` (host scratch) and `plan_dev` (device memory), each of
  * qg_plan_bytes(count, descs) bytes; qg_plan_build fills plan_host, the
@@ -176,7 +179,8 @@ int qg_step_many(int count, const void* plan_host, const void* plan_dev, size_t 
 
 /* The grouped launches one by one (same plan arguments): projection of every matrix, Adam over every matrix
  * (these two need every descriptor's R), their fusion (write_R != 0 also stores R), and back-projection + SR update
- * of every matrix.  qg_step_many(...) == qg_project_many, qg_lowrank_adam_many, qg_backproject_update_sr_many. */
+ * of every matrix.  qg_step_many(...) == qg_project_adam_many, qg_backproject_update_sr_many; the unfused pair
+ * qg_project_many, qg_lowrank_adam_many gives bit-identical M, V, N (and R). */
 int qg_project_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes, void* stream);
 int qg_lowrank_adam_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
                          const qg_hparams* hp, int64_t step, void* stream);

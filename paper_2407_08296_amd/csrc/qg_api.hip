@@ -92,15 +92,14 @@ extern "C" int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf1
                        void* stream) {
     (void)workspace;
     (void)workspace_bytes;
-    if (!Pq || !Ps || !G_bf16 || !Wq || !Ws || !M || !V || !R || !N_bf16 || !hp) return QG_ERR_NULL;
+    if (!Pq || !Ps || !G_bf16 || !Wq || !Ws || !M || !V || !N_bf16 || !hp) return QG_ERR_NULL;
     if (int e = check_mnr(m, n, r, group)) return e;
     if (step < 1) return QG_ERR_SHAPE;
     if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(G_bf16) || !aligned16(Wq) || !aligned16(Ws) || !aligned16(M) ||
-        !aligned16(V) || !aligned16(R) || !aligned16(N_bf16))
+        !aligned16(V) || (R && !aligned16(R)) || !aligned16(N_bf16))
         return QG_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
-    if (int e = launch_project(Pq, Ps, G_bf16, R, m, n, r, s)) return e;
-    if (int e = launch_adam(R, M, V, N_bf16, r * n, step, hp, s)) return e;
+    if (int e = launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, r, step, hp, s)) return e;
     return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, m, n, r, hp->alpha, hp->lr, seed, step, s);
 }
 
@@ -245,7 +244,9 @@ extern "C" int qg_project_adam_many(int count, const void* plan_host, const void
 
 extern "C" int qg_step_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,
                             const qg_hparams* hp, uint64_t seed, int64_t step, void* stream) {
-    if (int e = qg_project_many(count, plan_host, plan_dev, plan_bytes, stream)) return e;
-    if (int e = qg_lowrank_adam_many(count, plan_host, plan_dev, plan_bytes, hp, step, stream)) return e;
+    if (int e = check_plan(count, plan_host, plan_dev, plan_bytes)) return e;
+    // R is written only if every descriptor supplies a buffer for it
+    const int write_R = reinterpret_cast<const PlanHeader*>(plan_host)->no_R ? 0 : 1;
+    if (int e = qg_project_adam_many(count, plan_host, plan_dev, plan_bytes, hp, step, write_R, stream)) return e;
     return qg_backproject_update_sr_many(count, plan_host, plan_dev, plan_bytes, hp, seed, step, stream);
 }

@@ -415,44 +415,85 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
                                                           4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n), kAuxStream);
                 }
         }
-    } else {
+    } else if constexpr (DIRECT) {
+        // Adam on the tile while R is still in the accumulators.  M, V (and R, N) go through buffer resources like
+        // the R stores above: scalar base per 32-row block, scalar row offset, one per-lane offset per 32-column
+        // block; rows at or past r lie past the end of every array (loads return 0, stores are dropped), columns at
+        // or past n get an offset no resource covers.  Loads are issued eight rows at a time ahead of the
+        // arithmetic.  N: registers v and v+1 of a lane are rows i and i+1 of one column; even lanes store row i,
+        // odd lanes row i+1, each as one 4-byte bf16 pair with the value of the neighbouring column from lane ^ 1.
         const AdamCoef c = *coef;
         const bool odd = (lane & 1) != 0;
+        uint32_t voff[NB], voffn[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int col = wn * WN + b * 32 + lcol;   // inside the tile
+            const bool ok = !RAGGED || n0 + col < n;
+            voff[b] = ok ? 4u * (uint32_t)(4 * lhalf * n + col) : 0x80000000u;
+            voffn[b] = ok ? 2u * (uint32_t)(4 * lhalf * n + col + (odd ? n - 1 : 0)) : 0x80000000u;
+        }
+#pragma unroll
+        for (int a = 0; a < MB; ++a) {
+            const int row0 = r0 + wm * WM + a * 32;
+            const int64_t e0 = (int64_t)row0 * n + n0;
+            const int left4 = RAGGED ? (row0 < r ? bound_bytes(((int64_t)(r - row0) * n - n0) * 4) : 0) : 0x7FFFFFFF;
+            const __amdgpu_buffer_rsrc_t rm = make_rsrc(Mo + e0, left4), rv = make_rsrc(Vo + e0, left4);
+            const bool write_R = R != nullptr;
+            const __amdgpu_buffer_rsrc_t rr = make_rsrc(write_R ? R + e0 : Mo + e0, write_R ? left4 : 0);
+            const __amdgpu_buffer_rsrc_t rn = make_rsrc(No + e0, RAGGED ? left4 / 2 : 0x7FFFFFFF);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    float mm[8], vv[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const int v = 8 * h + q;
+                        const uint32_t so = 4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n);
+                        mm[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, voff[b], so, kAuxStream));
+                        vv[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, voff[b], so, kAuxStream));
+                    }
+#pragma unroll
+                    for (int q = 0; q < 8; q += 2) {
+                        float nn[2];
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            const int v = 8 * h + q + e;
+                            const uint32_t so = 4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n);
+                            const float rr_ = acc[a][b][v];
+                            nn[e] = adam_one(rr_, mm[q + e], vv[q + e], c);
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, mm[q + e]), rm, voff[b], so, kAuxStream);
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, vv[q + e]), rv, voff[b], so, kAuxStream);
+                            if (write_R)
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, rr_), rr, voff[b], so, kAuxStream);
+                        }
+                        const int v = 8 * h + q;   // rows i (v) and i + 1 (v + 1)
+                        const float recv = __shfl_xor(odd ? nn[0] : nn[1], 1, 64);
+                        const uint32_t pk = odd ? pack_bf16x2(recv, nn[1]) : pack_bf16x2(nn[0], recv);
+                        __builtin_amdgcn_raw_buffer_store_b32(pk, rn, voffn[b],
+                                                              2u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n), kAuxStream);
+                    }
+                }
+        }
+    } else {
+        const AdamCoef c = *coef;
 #pragma unroll
         for (int a = 0; a < MB; ++a)
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int col = n0 + wn * WN + b * 32 + lcol;
 #pragma unroll
-                for (int v = 0; v < 16; v += 2) {
-                    // registers v, v+1 of a lane are rows i, i+1 of one column
+                for (int v = 0; v < 16; ++v) {
                     const int row = r0 + wm * WM + a * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
                     const int64_t off = (int64_t)row * n + col;
-                    float nn[2];
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const bool ok = !RAGGED || (row + e < r && col < n);
-                        const float rr = acc[a][b][v + e];
-                        float mm = ok ? Mo[off + (int64_t)e * n] : 0.f;
-                        float vv = ok ? Vo[off + (int64_t)e * n] : 0.f;
-                        nn[e] = adam_one(rr, mm, vv, c);
-                        if (ok) {
-                            if (R != nullptr) R[off + (int64_t)e * n] = rr;
-                            Mo[off + (int64_t)e * n] = mm;
-                            Vo[off + (int64_t)e * n] = vv;
-                        }
-                    }
-                    if (!RAGGED) {
-                        // pair neighbouring columns into one 4-byte bf16x2 store: even lanes write row i, odd
-                        // lanes row i+1, each taking the value it lacks from its neighbour lane
-                        const float recv = __shfl_xor(odd ? nn[0] : nn[1], 1, 64);
-                        const uint32_t pk = odd ? pack_bf16x2(recv, nn[1]) : pack_bf16x2(nn[0], recv);
-                        const int64_t o2 = odd ? off + n - 1 : off;
-                        *reinterpret_cast<uint32_t*>(No + o2) = pk;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 2; ++e)
-                            if (row + e < r && col < n) No[off + (int64_t)e * n] = to_bf16(nn[e]);
+                    if (row < r && col < n) {
+                        const float rr_ = acc[a][b][v];
+                        float mm = Mo[off], vv = Vo[off];
+                        const float nn = adam_one(rr_, mm, vv, c);
+                        if (R != nullptr) R[off] = rr_;
+                        Mo[off] = mm;
+                        Vo[off] = vv;
+                        No[off] = to_bf16(nn);
                     }
                 }
             }
