@@ -98,7 +98,10 @@ __device__ inline float adam_one(float r, float& m, float& v, const AdamCoef& c)
     v = __builtin_fmaf(c.b2, v, c.omb2 * (r * r));
     const float mhat = m * c.rc1;
     const float vhat = v * c.rc2;
-    return mhat / (sqrtf(vhat) + c.eps);
+    // N is stored as bf16 (8 significant bits): the hardware square root and reciprocal (1 ulp of fp32 each) are
+    // exact enough, and a correctly rounded sqrt and divide would cost about 15 more instructions per element in
+    // the projection's epilogue.  M and V above are exact fp32 recurrences.
+    return mhat * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vhat) + c.eps);
 }
 
 AdamCoef make_adam_coef(const qg_hparams* hp, int64_t step);   // host, qg_adam.hip
