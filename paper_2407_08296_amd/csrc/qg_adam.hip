@@ -83,6 +83,7 @@ AdamCoef make_adam_coef(const qg_hparams* hp, int64_t step) {
     c.rc1 = (float)(1.0 / (1.0 - pow((double)hp->beta1, (double)step)));
     c.rc2 = (float)(1.0 / (1.0 - pow((double)hp->beta2, (double)step)));
     c.eps = hp->eps;
+    c.sqrt_rc2 = (float)sqrt(1.0 / (1.0 - pow((double)hp->beta2, (double)step)));
     return c;
 }
 

@@ -91,17 +91,17 @@ __device__ inline float wave_sum(float v) {
 // ---- Adam on one element (Sec. 3.5; Adam as cited in Sec. 4.1) ----
 struct AdamCoef {
     float b1, b2, omb1, omb2, rc1, rc2, eps;  // rc = 1/(1 - beta^t)
+    float sqrt_rc2;                           // sqrt(rc2): sqrt(V rc2) = sqrt(V) sqrt(rc2)
 };
 
 __device__ inline float adam_one(float r, float& m, float& v, const AdamCoef& c) {
     m = __builtin_fmaf(c.b1, m, c.omb1 * r);
     v = __builtin_fmaf(c.b2, v, c.omb2 * (r * r));
     const float mhat = m * c.rc1;
-    const float vhat = v * c.rc2;
     // N is stored as bf16 (8 significant bits): the hardware square root and reciprocal (1 ulp of fp32 each) are
     // exact enough, and a correctly rounded sqrt and divide would cost about 15 more instructions per element in
     // the projection's epilogue.  M and V above are exact fp32 recurrences.
-    return mhat * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vhat) + c.eps);
+    return mhat * __builtin_amdgcn_rcpf(__builtin_fmaf(__builtin_amdgcn_sqrtf(v), c.sqrt_rc2, c.eps));
 }
 
 AdamCoef make_adam_coef(const qg_hparams* hp, int64_t step);   // host, qg_adam.hip

@@ -424,6 +424,8 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
         // odd lanes row i+1, each as one 4-byte bf16 pair with the value of the neighbouring column from lane ^ 1.
         const AdamCoef c = *coef;
         const bool odd = (lane & 1) != 0;
+        // v_perm_b32 selector over {nbr (bytes 4..7), own (bytes 0..3)}: even lanes (own.lo, nbr.lo), odd (nbr.hi, own.hi)
+        const uint32_t pair_sel = odd ? 0x03020706u : 0x05040100u;
         uint32_t voff[NB], voffn[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
@@ -468,8 +470,12 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
                                 __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, rr_), rr, voff[b], so, kAuxStream);
                         }
                         const int v = 8 * h + q;   // rows i (v) and i + 1 (v + 1)
-                        const float recv = __shfl_xor(odd ? nn[0] : nn[1], 1, 64);
-                        const uint32_t pk = odd ? pack_bf16x2(recv, nn[1]) : pack_bf16x2(nn[0], recv);
+                        // own column as (row i, row i+1), the neighbour lane's the same way (one DPP move), then one
+                        // byte permute picks (own row i, neighbour row i) in even lanes and (neighbour row i+1, own
+                        // row i+1) in odd lanes
+                        const uint32_t own = pack_bf16x2(nn[0], nn[1]);
+                        const uint32_t nbr = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1, 0xF, 0xF, true);
+                        const uint32_t pk = __builtin_amdgcn_perm(nbr, own, pair_sel);
                         __builtin_amdgcn_raw_buffer_store_b32(pk, rn, voffn[b],
                                                               2u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n), kAuxStream);
                     }
