@@ -168,7 +168,9 @@ def test_lowrank_adam(count_shape, t):
         assert np.all(bf16_t_to_f64(dN)[0, :8] == 0.0)          # zero gradient, zero moments: 0/eps = 0
 
 
-@pytest.mark.parametrize("m,n,r", [(512, 512, 128), (2048, 768, 256), (300, 700, 40), (4096, 4096, 256)])
+# exact, unaligned, masked (K tail and r edge / n edge) classes; large-tile instance
+@pytest.mark.parametrize("m,n,r", [(512, 512, 128), (2048, 768, 256), (300, 700, 40), (4096, 4096, 256),
+                                   (333, 264, 144), (2736, 1024, 256), (1040, 1048, 272), (1024, 49152, 1024)])
 def test_project_adam_fused_equals_separate_calls(m, n, r):
     d = make_inputs(m, n, r)
     rs = np.random.default_rng(13)
@@ -188,6 +190,8 @@ def test_project_adam_fused_equals_separate_calls(m, n, r):
         assert torch.equal(N1.view(torch.int16), N2.view(torch.int16))
         if with_R:
             assert torch.equal(R1, R2)
+    if m * n * r > 5e9:       # the large-tile instance: the bit-identity above is the check (the oracle takes minutes)
+        return
     oM, oV, oN = Q.lowrank_adam(Q.project(d["Pq"], d["Ps"], d["Gb"], m, n, r), M0, V0, 5, HP)
     assert rel_fro(host(M1), oM) <= 2e-5 and rel_fro(host(V1), oV) <= 4e-5
     assert rel_fro(bf16_t_to_f64(N1), Q.bf16_rne(oN)) <= 1e-3
@@ -303,6 +307,21 @@ def test_step_many_matches_oracle(shapes):
         assert rel_fro(host(s.M), o["M"]) <= 2e-5 and rel_fro(host(s.V), o["V"]) <= 4e-5
         check_codes(host(s.Wq), o["Wq"])
         check_scales_step(host(s.Ws), o["Ws"])
+
+
+def test_step_many_without_R_buffers_gives_the_same_state():
+    """The grouped step writes R only if every matrix supplies a buffer; everything else must not depend on it."""
+    import dataclasses
+    shapes = [(512, 512, 128), (300, 700, 40), (1024, 2736, 256), (768, 2048, 256)]
+    a, _ = _state_for(shapes)
+    b, _ = _state_for(shapes)
+    qg.step_many(qg.StepPlan(a), qg.hparams(), 9, 3)
+    qg.step_many(qg.StepPlan([dataclasses.replace(s, R=None) for s in b]), qg.hparams(), 9, 3)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.M, y.M) and torch.equal(x.V, y.V)
+        assert torch.equal(x.N.view(torch.int16), y.N.view(torch.int16))
+        assert torch.equal(x.Wq, y.Wq) and torch.equal(x.Ws, y.Ws)
 
 
 def _check_many(mats, data, seed, t=1):
