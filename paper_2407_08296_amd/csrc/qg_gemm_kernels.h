@@ -104,7 +104,7 @@ __device__ __forceinline__ void buffer_load_words(__amdgpu_buffer_rsrc_t rs, uin
     }
 }
 
-// bf16 [K][X] operand tile of BK x BX elements whose rows are NOT padded: the unguarded kernels fill it with direct
+// bf16 [K][X] operand tile of BK x BX elements whose rows are NOT padded: the kExact and kMasked kernels fill it with direct
 // global -> LDS loads (no registers, no LDS write instructions), and one wave-wide 16-byte load deposits 1 KB of
 // consecutive LDS.  Bank spreading comes from a swizzle instead: the 16-byte chunk c of row k sits at chunk position
 // c ^ ((k & 3) << 2), so the four rows a transpose read touches fall into four different 64-byte bank groups.  For a
@@ -224,7 +224,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     using S = ProjShape<BM, BN, BK, WGM, WGN>;
     constexpr int NT = S::NT;
     constexpr int WM = BM / WGM, WN = BN / WGN, MB = WM / 32, NB = WN / 32;
-    constexpr int PA = S::PA, PB = S::PB;
+    constexpr int PA = S::PA;
     constexpr int A_WORDS = BK * BM / 8;
     using AT = P_Task<A_WORDS, NT, !DIRECT>;
     constexpr int A_PER = AT::PER, WPT = AT::WPT, A_TPR = BM / (8 * WPT);   // tasks per tile row
@@ -242,7 +242,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     u32x4 bv[DIRECT ? 1 : B_PER];   // the unaligned kernels stage G through registers
 
     // Addresses are split into a part that is uniform over the workgroup and advances with the K step (scalar
-    // registers, scalar arithmetic) and a 32-bit per-thread offset fixed for the whole loop; the unguarded kernels
+    // registers, scalar arithmetic) and a 32-bit per-thread offset fixed for the whole loop; the kExact and kMasked kernels
     // load through buffer resources based at the uniform part, so their loop spends no vector instructions on
     // address arithmetic.  A K step covers BK rows of P, i.e. BK*r codes: a multiple of 256 (r is a multiple of 8),
     // so code bytes and block scales split the same way.
@@ -264,8 +264,8 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
         }
     }
 
-    // Tile kt: P codes and scales into registers; G straight into LDS stage `stage` (unguarded kernels) or into
-    // registers (guarded kernels, stored by sstore).
+    // Tile kt: P codes and scales into registers; G straight into LDS stage `stage` (kExact, kMasked) or into
+    // registers (kUnaligned, stored by sstore).
     auto gload = [&](int kt, int stage) {
         const int i0 = kt * BK;
         const int64_t e0 = (int64_t)i0 * r;
@@ -310,7 +310,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
             }
         }
     };
-    // Dequantized P tile (and, in the guarded kernels, the G tile) into LDS stage `stage`; returns once the stage's
+    // Dequantized P tile (and, in the kUnaligned kernels, the G tile) into LDS stage `stage`; returns once the stage's
     // direct loads have landed too, so that the barrier that follows publishes the whole stage.
     auto sstore = [&](int stage) {
 #pragma unroll
@@ -350,8 +350,8 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
     auto mfma_step = [&](int stage) {
         const uint16_t* Ac = As + stage * S::A_STAGE + a_lane;
         const uint16_t* Bc = Bs + stage * S::B_STAGE;
-        // With two workgroups per CU a SIMD holds two waves; the one in its MFMA phase gets issue priority so the
-        // matrix pipe stays fed while the other wave's staging instructions fill the gaps.
+        // With several workgroups per CU a SIMD holds several waves; the one in its MFMA phase gets issue priority so the
+        // matrix pipe stays fed while the other waves' staging instructions fill the gaps.
         __builtin_amdgcn_s_setprio(kMfmaPrio);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
@@ -644,7 +644,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     const int ng = (n + kGroup - 1) / kGroup;
 
     // ---- weight tile -> LDS (asynchronous direct loads where shapes allow) ----
-    // whole tile inside the matrix and rows 16-byte aligned: the wide path works even in the guarded kernel
+    // whole tile inside the matrix and rows 16-byte aligned: the direct loads work in the edge-checking kernels too
     const bool w_fast = !RAGGED || (m0 + BMm <= m && n0 + BNn <= n && (n & 15) == 0);
     auto load_wtile = [&]() {
     if (w_fast) {
@@ -706,7 +706,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     }
     const int64_t e_tile = (int64_t)m0 * r;
 
-    // Tile kt: N straight into LDS stage `stage` (unguarded kernels) or into registers (guarded); P codes and scales
+    // Tile kt: N straight into LDS stage `stage` (kExact, kMasked) or into registers (kUnaligned); P codes and scales
     // into registers.
     auto gload = [&](int kt, int stage) {
         const int k0 = kt * BK;
