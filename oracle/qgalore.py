@@ -377,3 +377,59 @@ class Policy:
             doubled = True
         self.next_refresh += self.interval
         return doubled
+
+
+# --------------------------------------------------------------------------
+# Subspace refresh (Sec. 3.2, Sec. 3.5: the projection matrix is recomputed
+# from the current gradient every `interval` steps and stored as INT4)
+# --------------------------------------------------------------------------
+def refresh_svd(G_bits, m: int, n: int, r: int):
+    """The definition the paper inherits from GaLore (Sec. 1, Sec. 3.2): P is
+    made of the first r left singular vectors of the gradient.  Returns
+    (P m x r, singular values).  Column signs are the library's (an SVD fixes
+    them only up to sign): compare subspaces, not columns."""
+    G = bf16_bits_to_f64(np.asarray(G_bits)).reshape(m, n)
+    U, s, _ = np.linalg.svd(G, full_matrices=False)
+    return U[:, :r], s
+
+
+def orthonormalize(Y) -> np.ndarray:
+    """Q of the QR factorisation Y = Q T with T upper triangular and a
+    positive diagonal, i.e. Gram-Schmidt on the columns of Y in order.  For Y
+    of full column rank this Q is unique.  The library's Householder QR is the
+    step; its sign convention is normalised afterwards."""
+    Y = np.asarray(Y, dtype=np.float64)
+    Q, T = np.linalg.qr(Y, mode="reduced")
+    sgn = np.where(np.diag(T) < 0, -1.0, 1.0)
+    return Q * sgn[None, :]
+
+
+def range_apply(G_bits, Z_bits, m: int, n: int, r: int) -> np.ndarray:
+    """Y = G Z^T for the bf16 gradient G (m x n) and a bf16 r x n matrix Z
+    (the projected gradient stored in BFloat16 like the gradient itself,
+    Sec. 3.1): with Z = P^T G this is (G G^T) P, one step of the power
+    method on the left singular subspace."""
+    G = bf16_bits_to_f64(np.asarray(G_bits)).reshape(m, n)
+    Z = bf16_bits_to_f64(np.asarray(Z_bits)).reshape(r, n)
+    return G @ Z.T
+
+
+def subspace_refresh(Pq, Ps, G_bits, m: int, n: int, r: int, iters: int = 1):
+    """Replacement for the SVD of Sec. 3.2 (reading: the paper only asks for
+    the dominant left singular subspace; orthogonal iteration started from the
+    stored projection converges to the same singular vectors, in the same
+    order, at the rate (sigma_{r+1}/sigma_r)^2 per pass).  One pass:
+        R = dequant(P)^T G        (the projection of Sec. 3.5)
+        Z = bf16(R)
+        Y = G Z^T
+        Q = orthonormalize(Y)
+        P <- quant_int4(fl32(Q))  (Sec. 3.3: the projection is kept in INT4)
+    Returns (Pq, Ps, Q of the last pass in fp64)."""
+    Q = None
+    for _ in range(iters):
+        R = project(Pq, Ps, G_bits, m, n, r)
+        Z_bits = f64_to_bf16_bits(R)
+        Y = range_apply(G_bits, Z_bits, m, n, r)
+        Q = orthonormalize(Y)
+        Pq, Ps = quant_int4(Q.astype(np.float32))
+    return Pq, Ps, Q

@@ -1,0 +1,169 @@
+"""Pins of the oracle's subspace refresh (Sec. 3.2: the projection is recomputed from the gradient; the paper
+takes the first r left singular vectors) against the SVD, the symmetric eigenproblem, the Eckart-Young identity,
+the contraction rate of orthogonal iteration and a pure-Python Gram-Schmidt."""
+import numpy as np
+import pytest
+
+from oracle import qgalore as Q
+from paper_2407_08296_amd import inputs as I
+
+
+def _spectrum_matrix(m, n, sig, seed):
+    """G = U diag(sig) V^T with seeded orthonormal U, V, rounded to bf16 (what the gradient buffer holds)."""
+    g = np.random.default_rng(seed)
+    U, _ = np.linalg.qr(g.standard_normal((m, len(sig))))
+    V, _ = np.linalg.qr(g.standard_normal((n, len(sig))))
+    return Q.f64_to_bf16_bits((U * np.asarray(sig)[None, :]) @ V.T), U
+
+
+def _sin_theta(A, B):
+    """Largest principal-angle sine between the column spaces of two orthonormal bases."""
+    return np.linalg.norm(B - A @ (A.T @ B), 2)
+
+
+# ---------------------------------------------------------------- orthonormalize
+def test_orthonormalize_is_gram_schmidt_by_hand():
+    Y = np.random.default_rng(1).standard_normal((7, 4))
+    want = []
+    for j in range(4):                              # textbook Gram-Schmidt, scalar loops
+        v = [Y[i][j] for i in range(7)]
+        for q in want:
+            d = sum(q[i] * Y[i][j] for i in range(7))
+            v = [v[i] - d * q[i] for i in range(7)]
+        nrm = sum(x * x for x in v) ** 0.5
+        want.append([x / nrm for x in v])
+    got = Q.orthonormalize(Y)
+    assert np.abs(got - np.array(want).T).max() < 1e-12
+
+
+def test_orthonormalize_invariants_and_uniqueness():
+    Y = np.random.default_rng(2).standard_normal((300, 40)) * np.logspace(0, -3, 40)[None, :]
+    Qm = Q.orthonormalize(Y)
+    assert np.abs(Qm.T @ Qm - np.eye(40)).max() < 1e-12
+    T = Qm.T @ Y
+    assert np.abs(np.tril(T, -1)).max() < 1e-12 and (np.diag(T) > 0).all()      # upper triangular, positive diagonal
+    assert np.abs(Qm @ T - Y).max() < 1e-12
+    # scaling columns by positive numbers and adding earlier columns to later ones leaves Q unchanged
+    S = np.triu(np.random.default_rng(3).standard_normal((40, 40)), 1) * 0.1 + np.diag(np.linspace(0.5, 2, 40))
+    assert np.abs(Q.orthonormalize(Y @ S) - Qm).max() < 1e-8
+    # flipping a column of Y flips that column of Q only
+    Y2 = Y.copy(); Y2[:, 5] *= -1
+    Q2 = Q.orthonormalize(Y2)
+    assert np.abs(Q2[:, 5] + Qm[:, 5]).max() < 1e-12 and np.abs(np.delete(Q2 - Qm, 5, axis=1)).max() < 1e-12
+    # orthogonal columns: only normalisation
+    D = np.linalg.qr(np.random.default_rng(4).standard_normal((50, 6)))[0]
+    assert np.abs(Q.orthonormalize(D * np.array([3, .1, 2, 5, 1, .7])) - D).max() < 1e-12
+
+
+# ---------------------------------------------------------------- the SVD definition
+def test_refresh_svd_matches_eigenvectors_and_eckart_young():
+    m, n, r = 96, 160, 8
+    Gb, U = _spectrum_matrix(m, n, np.r_[np.linspace(4, 2, r), np.linspace(0.2, 0.05, 24)], seed=5)
+    P, s = Q.refresh_svd(Gb, m, n, r)
+    G = Q.bf16_bits_to_f64(Gb).reshape(m, n)
+    assert np.abs(P.T @ P - np.eye(r)).max() < 1e-12
+    w, E = np.linalg.eigh(G @ G.T)                   # same subspace from the symmetric eigenproblem
+    assert _sin_theta(E[:, -r:], P) < 1e-10 and np.allclose(np.sqrt(w[::-1][:r]), s[:r], rtol=1e-10)
+    assert _sin_theta(U[:, :r], P) < 5e-2            # the planted vectors, up to the bf16 rounding of G
+    # Eckart-Young: the residual of the rank-r projection is the tail of the spectrum, and no other
+    # r-dimensional subspace does better
+    res = np.linalg.norm(G - P @ (P.T @ G)) ** 2
+    assert np.isclose(res, np.sum(s[r:] ** 2), rtol=1e-10)
+    other = np.linalg.qr(np.random.default_rng(6).standard_normal((m, r)))[0]
+    assert np.linalg.norm(G - other @ (other.T @ G)) ** 2 > res
+
+
+def test_range_apply_is_the_gram_operator():
+    m, n, r = 64, 96, 16
+    Gb = I.gradient_bf16(m, n, 1)
+    G = Q.bf16_bits_to_f64(Gb).reshape(m, n)
+    Zb = Q.f64_to_bf16_bits(np.random.default_rng(7).standard_normal((r, n)))
+    Z = Q.bf16_bits_to_f64(Zb).reshape(r, n)
+    Y = Q.range_apply(Gb, Zb, m, n, r)
+    want = np.array([[sum(G[i, k] * Z[j, k] for k in range(n)) for j in range(r)] for i in range(m)])
+    assert Y.shape == (m, r) and np.abs(Y - want).max() < 1e-15
+    # with Z = P^T G exactly, Y = (G G^T) P
+    P = np.linalg.qr(np.random.default_rng(8).standard_normal((m, r)))[0]
+    Zx = P.T @ G
+    Yx = Q.range_apply(Gb, Q.f64_to_bf16_bits(Zx), m, n, r)
+    assert np.linalg.norm(Yx - G @ G.T @ P) / np.linalg.norm(Yx) < 4e-3       # bf16 rounding of Z only
+
+
+# ---------------------------------------------------------------- the iteration
+def _start(m, r, seed=0):
+    return Q.quant_int4(I.projection_f32(m, r, seed=seed))
+
+
+def test_exact_rank_gradient_is_captured_in_one_pass():
+    """rank(G) = r: (G G^T) P spans range(G) after a single pass whatever the start."""
+    m, n, r = 256, 384, 16
+    Gb, _ = _spectrum_matrix(m, n, np.linspace(3, 1, r), seed=9)
+    Pq, Ps = _start(m, r)
+    _, _, Qm = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+    Psvd, s = Q.refresh_svd(Gb, m, n, r)
+    # G's bf16 rounding adds a tail of relative size 2^-9: the angle is of that order, not zero
+    assert _sin_theta(Psvd, Qm) < 2e-2
+    G = Q.bf16_bits_to_f64(Gb).reshape(m, n)
+    assert np.linalg.norm(Qm.T @ G) ** 2 / np.sum(s[:r] ** 2) > 1 - 1e-4
+
+
+def test_contraction_rate_of_one_pass():
+    """tan(theta) to the dominant subspace shrinks at least by (sigma_{r+1}/sigma_r)^2 per pass (orthogonal
+    iteration on G G^T), up to the bf16 and INT4 roundings of the pass."""
+    m, n, r = 192, 256, 12
+    gap = 0.25
+    sig = np.r_[np.linspace(2, 1, r), np.linspace(gap, 0.05, 30)]
+    Gb, _ = _spectrum_matrix(m, n, sig, seed=10)
+    Psvd, s = Q.refresh_svd(Gb, m, n, r)
+    Pq, Ps = _start(m, r, seed=3)
+    P0 = Q.dequant_p_bf16(Pq, Ps, m, r)
+    Q0 = Q.orthonormalize(P0)
+
+    def tan_theta(B):
+        c = np.linalg.svd(Psvd.T @ B, compute_uv=False).min()
+        return np.sqrt(max(1 - c * c, 0)) / c
+    t0 = tan_theta(Q0)
+    _, _, Q1 = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+    t1 = tan_theta(Q1)
+    rate = (s[r] / s[r - 1]) ** 2
+    assert t1 <= rate * t0 * 1.05 + 5e-3, (t0, t1, rate)
+    assert t1 < t0 / 8
+
+
+def test_passes_converge_to_the_singular_vectors_in_order():
+    """With distinct singular values the columns themselves converge (not only the span): column k approaches
+    +-u_k, which is what makes the column-wise cosine of Sec. 3.2 meaningful between refreshes."""
+    m, n, r = 128, 128, 6
+    sig = np.r_[[8, 5, 3, 2, 1.2, 0.8], np.full(20, 0.02)]
+    Gb, _ = _spectrum_matrix(m, n, sig, seed=11)
+    Psvd, _ = Q.refresh_svd(Gb, m, n, r)
+    Pq, Ps = _start(m, r, seed=4)
+    for _ in range(12):
+        Pq, Ps, Qm = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+    cos = np.abs(np.sum(Psvd * Qm, axis=0))
+    assert (cos > 0.98).all(), cos                   # INT4 storage between passes sets the floor
+    # a converged basis is a fixed point: the refresh reproduces the stored P and the cosine check reads ~1
+    Pq2, Ps2, _ = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+    assert Q.subspace_cossim(Pq, Ps, Pq2, Ps2, m, r) > 0.97
+
+
+def test_refresh_on_the_synthetic_gradient_captures_the_planted_signal():
+    """Config-0 recipe (rank-16 signal + noise): after one pass from an unrelated start the INT4 projection holds
+    the signal's energy nearly as well as the SVD's first r vectors do."""
+    m, n, r = 512, 512, 128
+    Gb = I.gradient_bf16(m, n, 1)
+    Pq, Ps = _start(m, r)
+    Pq1, Ps1, Qm = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+    Psvd, s = Q.refresh_svd(Gb, m, n, r)
+    G = Q.bf16_bits_to_f64(Gb).reshape(m, n)
+    best = np.sum(s[:r] ** 2)
+    assert np.abs(Qm.T @ Qm - np.eye(r)).max() < 1e-10
+    assert np.linalg.norm(Qm.T @ G) ** 2 / best > 0.97
+    e0 = np.linalg.norm(Q.project(Pq, Ps, Gb, m, n, r)) ** 2 / best
+    e1 = np.linalg.norm(Q.project(Pq1, Ps1, Gb, m, n, r)) ** 2 / best
+    assert e0 < 0.5 and e1 > 0.93, (e0, e1)
+    # the basis keeps moving less from pass to pass on a fixed gradient (the saturation the cosine check looks for)
+    Pq2, Ps2, _ = Q.subspace_refresh(Pq1, Ps1, Gb, m, n, r, iters=1)
+    c1 = Q.subspace_cossim(Pq, Ps, Pq1, Ps1, m, r)
+    c2 = Q.subspace_cossim(Pq1, Ps1, Pq2, Ps2, m, r)
+    assert c1 < 0.9 and c2 > c1 + 0.05, (c1, c2)
