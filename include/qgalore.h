@@ -143,6 +143,40 @@ int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB,
                        int64_t m, int64_t r, int group, float* cos_out,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Subspace refresh (Sec. 3.2: every `interval` steps the projection is recomputed from the current gradient;
+ * the paper takes the first r left singular vectors of G).  One pass of orthogonal iteration started from the stored
+ * projection stands in for the SVD; it converges to the same singular vectors, in the same order, at the rate
+ * (sigma_{r+1} / sigma_r)^2 per pass:
+ *     R = dequant(P)^T G (qg_project);  Z = bf16(R);  Y = G Z^T;  Q = orthonormalize(Y);  P_new = quant_int4(Q)
+ * and, after the last pass, *cos_out = qg_subspace_cossim(P, P_new).
+ *
+ * qg_range_apply: Y (fp32 [m][r], overwritten) = G (bf16 [m][n]) * Z^T (Z bf16 [r][n]); bf16 MFMA, fp32 accumulation.
+ *
+ * qg_orthonormalize: Q (fp32 [m][r]) = the orthonormal factor of Y = Q T with T upper triangular and a positive
+ * diagonal (Gram-Schmidt on the columns of Y in order), computed in fp64 as Q = Y L^-T from the Cholesky factor
+ * of Y^T Y, twice in a row (the second round removes the cond(Y)^2 loss of orthogonality of the first; accurate to
+ * fp32 rounding for cond(Y) up to about 1e7).  *info (device int32) receives 0, or 1 + the index of the first
+ * column whose pivot was not positive (Y numerically rank deficient: Q is then meaningless, but every kernel still
+ * completes).  Y and Q may not alias.
+ * workspace: qg_orthonormalize_workspace_bytes(m, r) bytes, 16-byte aligned.
+ *
+ * qg_subspace_refresh: `passes` (1 .. 64) passes as above.  Pq/Ps hold the old projection (unchanged); Pq_new/Ps_new
+ * (same sizes, distinct buffers) receive the new one; cos_out is one device float; info as for qg_orthonormalize
+ * (first failure over all passes).  workspace: qg_refresh_workspace_bytes(m, n, r) bytes, 16-byte aligned; after
+ * the call it starts with R (fp32 [r][n]) of the last pass.
+ *
+ * All three require r % 8 == 0, r <= m, m*r < 2^31 and m*n < 2^32 (QG_ERR_SHAPE otherwise). */
+int qg_range_apply(const uint16_t* G_bf16, const uint16_t* Z_bf16, int64_t m, int64_t n, int64_t r, float* Y,
+                   void* stream);
+size_t qg_orthonormalize_workspace_bytes(int64_t m, int64_t r);
+int qg_orthonormalize(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info,
+                      void* workspace, size_t workspace_bytes, void* stream);
+size_t qg_refresh_workspace_bytes(int64_t m, int64_t n, int64_t r);
+int qg_subspace_refresh(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
+                        int64_t m, int64_t n, int64_t r, int group, int passes,
+                        uint8_t* Pq_new, float* Ps_new, float* cos_out, int32_t* info,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- Adaptive lazy update policy (Sec. 3.2), HOST ONLY (p is a host pointer):
  * streak counts consecutive checks with cos >= threshold; at k in a row the
  * interval doubles and the streak restarts; next_refresh advances by the

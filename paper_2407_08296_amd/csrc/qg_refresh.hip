@@ -1,0 +1,572 @@
+// Subspace refresh (Sec. 3.2: the projection matrix is recomputed from the current gradient; the paper takes the
+// first r left singular vectors from an SVD).  Here one pass of orthogonal iteration started from the stored INT4
+// projection replaces the SVD:
+//     R = dequant(P)^T G  (the projection kernel of the optimizer step)      bf16 MFMA
+//     Z = bf16(R)
+//     Y = G Z^T           (m x r)                                            bf16 MFMA, fp32 accumulation
+//     Q = Y T^-1          with Y = Q T, T upper triangular, diag(T) > 0      fp64 MFMA (Cholesky QR)
+//     P <- quant_int4(Q)  (Sec. 3.3)
+// followed by the cosine check of Sec. 3.2 between the old and the new P.
+//
+// The orthonormalisation works on the r x r Gram matrix S = Y^T Y in fp64: S = L L^T (blocked Cholesky, 64-wide
+// blocks), X = L^-1, Q = Y X^T, and all of that a second time on the result (Cholesky QR twice): one round leaves
+// |Q^T Q - I| ~ 1e-16 * cond(Y)^2, which for the low-rank-plus-noise gradients this is made for (cond(Y) up to 1e7)
+// is far from orthonormal; the second round starts from a matrix with cond ~ 1 and lands within fp32 rounding of
+// the Gram-Schmidt factor, because multiplying Y from the right by a triangular matrix with a positive diagonal
+// does not change that factor.  A pivot that is not positive (cond(Y) beyond ~1e8, or Y rank deficient) is reported
+// through `info` and replaced by 1 so that every kernel still runs to completion.
+#include "qg_common.h"
+#include "qg_gemm_kernels.h"
+
+namespace qg {
+
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kNB = 64;               // block size of the fp64 kernels: one workgroup (4 waves) per 64 x 64 block
+constexpr int kKC = 32;               // K extent staged in LDS per barrier pair
+constexpr int kPitchKF = kKC + 4;     // LDS pitch of a [64][k] chunk (k fastest)
+constexpr int kPitchKS = kNB + 16;    // LDS pitch of a [k][64] chunk (k slowest)
+constexpr int kPitchT = kNB + 2;      // LDS pitch of a 64 x 64 intermediate
+
+// ROWS x COLS block at (row0, col0) of a row-major matrix (fp32 or fp64) -> registers -> LDS doubles.  Elements
+// outside [0, rows) x [0, cols) read as zero.  col0 and cols are even, so an element pair never straddles the edge.
+template <int ROWS, int COLS, int PITCH, typename T>
+struct BlockStage {
+    static constexpr int PER = ROWS * COLS / 2 / 256;
+    static_assert(ROWS * COLS % 512 == 0, "256 threads, two elements each");
+    double v[PER][2];
+    __device__ __forceinline__ void fetch(const T* __restrict__ src, int64_t ld, int row0, int col0, int rows, int cols) {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int idx = threadIdx.x + 256 * q;
+            const int gr = row0 + idx / (COLS / 2), gc = col0 + (idx % (COLS / 2)) * 2;
+            v[q][0] = v[q][1] = 0.0;
+            if (gr < rows && gc < cols) {
+                typedef T pair_t __attribute__((ext_vector_type(2)));
+                const pair_t p = *reinterpret_cast<const pair_t*>(src + (int64_t)gr * ld + gc);
+                v[q][0] = (double)p[0];
+                v[q][1] = (double)p[1];
+            }
+        }
+    }
+    __device__ __forceinline__ void commit(double* dst) const {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int idx = threadIdx.x + 256 * q;
+            double* d = dst + (idx / (COLS / 2)) * PITCH + (idx % (COLS / 2)) * 2;
+            d[0] = v[q][0];
+            d[1] = v[q][1];
+        }
+    }
+};
+
+// One K chunk of the workgroup's 64 x 64 product on the fp64 matrix cores.  Wave (wi, wj) owns the 32 x 32 quadrant
+// as 2 x 2 blocks of v_mfma_f64_16x16x4: lane l supplies A[i = l % 16][k = l / 16] and B[k = l / 16][j = l % 16];
+// register v of the result is element (i = 4 v + l / 16, j = l % 16).  Operand element (i, k) of A sits at
+// At[i * a_pi + k * a_pk], element (k, j) of B at Bt[j * b_pj + k * b_pk].
+__device__ __forceinline__ void mma_chunk(const double* At, int a_pi, int a_pk, const double* Bt, int b_pj, int b_pk,
+                                          f64x4 (&acc)[2][2], int lane, int wi, int wj) {
+    const double* ap = At + (wi * 32 + (lane & 15)) * a_pi + (lane >> 4) * a_pk;
+    const double* bp = Bt + (wj * 32 + (lane & 15)) * b_pj + (lane >> 4) * b_pk;
+#pragma unroll
+    for (int k0 = 0; k0 < kKC; k0 += 4) {
+        double af[2], bf[2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a) af[a] = ap[a * 16 * a_pi + k0 * a_pk];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) bf[b] = bp[b * 16 * b_pj + k0 * b_pk];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[a], bf[b], acc[a][b], 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void zero_acc(f64x4 (&acc)[2][2]) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = f64x4{0.0, 0.0, 0.0, 0.0};
+}
+
+// f(row, col, value) for every element of the wave's quadrant, row and col inside the 64 x 64 block.
+template <typename F>
+__device__ __forceinline__ void for_each_acc(const f64x4 (&acc)[2][2], int lane, int wi, int wj, F f) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) f(wi * 32 + a * 16 + 4 * v + (lane >> 4), wj * 32 + b * 16 + (lane & 15), acc[a][b][v]);
+}
+
+// (bi, bj) with bi >= bj of the idx-th block of a lower block triangle, rows first.
+__device__ __forceinline__ void lower_pair(int idx, int& bi, int& bj) {
+    int i = 0;
+    while ((i + 1) * (i + 2) / 2 <= idx) ++i;
+    bi = i;
+    bj = idx - i * (i + 1) / 2;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Z = bf16(R), round to nearest even
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_f32_to_bf16(const float* __restrict__ x, uint16_t* __restrict__ y, int64_t quads) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < quads; i += (int64_t)gridDim.x * 256) {
+        const f32x4 v = reinterpret_cast<const f32x4*>(x)[i];
+        u32x2 o;
+        o[0] = pack_bf16x2(v[0], v[1]);
+        o[1] = pack_bf16x2(v[2], v[3]);
+        reinterpret_cast<u32x2*>(y)[i] = o;
+    }
+}
+
+__global__ void k_set_i32(int32_t* p, int32_t v) { *p = v; }
+
+// ---------------------------------------------------------------------------------------------------------------
+// Y = G Z^T : G m x n and Z r x n, both bf16 row-major (the contraction index n is the fast one in both), Y fp32
+// m x r.  128 x 128 tile per workgroup, 4 waves of 64 x 64, v_mfma_f32_32x32x16_bf16; operands go through
+// registers into [row][k] LDS tiles one 64-deep K step ahead of the MFMAs.
+// ---------------------------------------------------------------------------------------------------------------
+constexpr int kRgT = 128, kRgK = 64, kRgPitch = kRgK + kPadX;
+
+__global__ __launch_bounds__(256) void k_range(const uint16_t* __restrict__ G, const uint16_t* __restrict__ Z,
+                                               float* __restrict__ Y, int m, int n, int r, int tiles_r) {
+    __shared__ __attribute__((aligned(16))) uint16_t Gs[kRgT * kRgPitch];
+    __shared__ __attribute__((aligned(16))) uint16_t Zs[kRgT * kRgPitch];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = (int)(blockIdx.x / tiles_r) * kRgT, r0 = (int)(blockIdx.x % tiles_r) * kRgT;
+    constexpr int PER = kRgT * (kRgK / 8) / 256;   // 16-byte chunks per thread and operand
+    u32x4 gv[PER], zv[PER];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int idx = t + 256 * q;
+            const int row = idx / (kRgK / 8), c = k0 + (idx % (kRgK / 8)) * 8;
+            gv[q] = load8_bf16_guarded(G + (int64_t)(m0 + row) * n + c, m0 + row < m ? n - c : 0);
+            zv[q] = load8_bf16_guarded(Z + (int64_t)(r0 + row) * n + c, r0 + row < r ? n - c : 0);
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int idx = t + 256 * q;
+            const int row = idx / (kRgK / 8), c = (idx % (kRgK / 8)) * 8;
+            *reinterpret_cast<u32x4*>(Gs + row * kRgPitch + c) = gv[q];
+            *reinterpret_cast<u32x4*>(Zs + row * kRgPitch + c) = zv[q];
+        }
+    };
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    // lane l supplies row l % 32 of its 32-row block and the 8 contraction elements starting at 8 * (l / 32)
+    const uint16_t* gl = Gs + (wm * 64 + (lane & 31)) * kRgPitch + 8 * (lane >> 5);
+    const uint16_t* zl = Zs + (wn * 64 + (lane & 31)) * kRgPitch + 8 * (lane >> 5);
+    const int KT = (n + kRgK - 1) / kRgK;
+    fetch(0);
+    for (int kt = 0; kt < KT; ++kt) {
+        commit();
+        __syncthreads();
+        if (kt + 1 < KT) fetch((kt + 1) * kRgK);
+#pragma unroll
+        for (int kk = 0; kk < kRgK / 16; ++kk) {
+            bf16x8 gf[2], zf[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) gf[a] = *reinterpret_cast<const bf16x8*>(gl + a * 32 * kRgPitch + kk * 16);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) zf[b] = *reinterpret_cast<const bf16x8*>(zl + b * 32 * kRgPitch + kk * 16);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[a], zf[b], acc[a][b], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // register v of a 32 x 32 block: row 8 (v / 4) + 4 (l / 32) + v % 4 (G's index), column l % 32 (Z's index)
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int col = r0 + wn * 64 + b * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (row < m && col < r) Y[(int64_t)row * r + col] = acc[a][b][v];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// S = Y^T Y in fp64, lower block triangle only (Y fp32 m x r; S r x r row-major)
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_gram(const float* __restrict__ Y, double* __restrict__ S, int m, int r) {
+    __shared__ double At[kKC * kPitchKS];
+    __shared__ double Bt[kKC * kPitchKS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
+    int bi, bj;
+    lower_pair(blockIdx.x, bi, bj);
+    const bool diag = bi == bj;
+    BlockStage<kKC, kNB, kPitchKS, float> sa, sb;
+    f64x4 acc[2][2];
+    zero_acc(acc);
+    const int KT = (m + kKC - 1) / kKC;
+    sa.fetch(Y, r, 0, bi * kNB, m, r);
+    if (!diag) sb.fetch(Y, r, 0, bj * kNB, m, r);
+    for (int kt = 0; kt < KT; ++kt) {
+        sa.commit(At);
+        if (!diag) sb.commit(Bt);
+        __syncthreads();
+        if (kt + 1 < KT) {
+            sa.fetch(Y, r, (kt + 1) * kKC, bi * kNB, m, r);
+            if (!diag) sb.fetch(Y, r, (kt + 1) * kKC, bj * kNB, m, r);
+        }
+        mma_chunk(At, 1, kPitchKS, diag ? At : Bt, 1, kPitchKS, acc, lane, wi, wj);
+        __syncthreads();
+    }
+    for_each_acc(acc, lane, wi, wj, [&](int row, int col, double x) {
+        const int gi = bi * kNB + row, gj = bj * kNB + col;
+        if (gi < r && gj < r) S[(int64_t)gi * r + gj] = x;
+    });
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Blocked Cholesky S = L L^T in place (lower triangle), right-looking, one block column per step kb:
+//   k_chol_diag:   L_kk from the diagonal block, and X_kk = L_kk^-1 (to Dinv[kb] and to the diagonal block of X)
+//   k_chol_panel:  L_ik = S_ik X_kk^T for the blocks below
+//   k_chol_update: S_ij -= L_ik L_jk^T for i >= j > kb
+// Rows and columns at or past r (r not a multiple of 64) behave like an identity block.
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r, int kb, double* __restrict__ Dinv,
+                                                   double* __restrict__ X, int32_t* __restrict__ info) {
+    constexpr int P = kNB + 1;
+    __shared__ double T[kNB * P];
+    __shared__ double dg[kNB];
+    __shared__ double vcol[kNB];
+    const int t = threadIdx.x;
+    const int base = kb * kNB;
+    for (int e = t; e < kNB * kNB; e += 256) {     // consecutive threads along a row
+        const int i = e >> 6, c = e & 63;
+        const int gi = base + i, gc = base + c;
+        T[i * P + c] = (gi < r && gc < r) ? S[(int64_t)gi * r + gc] : (i == c ? 1.0 : 0.0);
+    }
+    const int i = t & 63, cg = t >> 6;              // row i, columns cg, cg + 4, ...
+    for (int j = 0; j < kNB; ++j) {
+        __syncthreads();
+        double d = T[j * P + j];
+        if (!(d > 0.0)) {                           // not positive, or NaN
+            if (t == 0) atomicCAS(info, 0, base + j + 1);
+            d = 1.0;
+        }
+        const double s = sqrt(d);
+        if (cg == 0) {
+            if (i > j) T[i * P + j] = T[i * P + j] / s;
+            if (i == j) dg[j] = s;                  // T[j][j] itself stays until every thread has read it
+        }
+        __syncthreads();
+        const double lij = T[i * P + j];
+        for (int c = j + 1 + ((cg - (j + 1)) & 3); c <= i; c += 4) T[i * P + c] -= lij * T[c * P + j];
+    }
+    __syncthreads();
+    if (t < kNB) T[t * P + t] = dg[t];
+    __syncthreads();
+    for (int e = t; e < kNB * kNB; e += 256) {
+        const int ii = e >> 6, c = e & 63;
+        if (c <= ii && base + ii < r) S[(int64_t)(base + ii) * r + base + c] = T[ii * P + c];
+    }
+    // in-place inverse of the lower triangular block, last column first: with the trailing block already
+    // inverted, X[j+1.., j] = -X[j+1.., j+1..] L[j+1.., j] / L_jj
+    for (int j = kNB - 1; j >= 0; --j) {
+        __syncthreads();
+        const double xjj = 1.0 / T[j * P + j];
+        if (t < kNB) vcol[t] = t > j ? T[t * P + j] : 0.0;
+        __syncthreads();
+        if (t < kNB) {
+            if (t > j) {
+                double sum = 0.0;
+                for (int k = j + 1; k <= t; ++k) sum = fma(T[t * P + k], vcol[k], sum);
+                T[t * P + j] = -sum * xjj;
+            } else if (t == j) {
+                T[j * P + j] = xjj;
+            }
+        }
+    }
+    __syncthreads();
+    for (int e = t; e < kNB * kNB; e += 256) {
+        const int ii = e >> 6, c = e & 63;
+        const double x = c <= ii ? T[ii * P + c] : 0.0;
+        Dinv[(int64_t)kb * kNB * kNB + e] = x;
+        if (base + ii < r && base + c < r) X[(int64_t)(base + ii) * r + base + c] = x;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_chol_panel(double* __restrict__ S, int r, int kb, const double* __restrict__ Dinv) {
+    __shared__ double At[kNB * kPitchKF];
+    __shared__ double Bt[kNB * kPitchKF];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
+    const int ib = kb + 1 + blockIdx.x;
+    const double* D = Dinv + (int64_t)kb * kNB * kNB;
+    BlockStage<kNB, kKC, kPitchKF, double> sa, sb;
+    f64x4 acc[2][2];
+    zero_acc(acc);
+    for (int kc = 0; kc < kNB; kc += kKC) {
+        sa.fetch(S, r, ib * kNB, kb * kNB + kc, r, r);
+        sb.fetch(D, kNB, 0, kc, kNB, kNB);
+        sa.commit(At);
+        sb.commit(Bt);
+        __syncthreads();
+        mma_chunk(At, kPitchKF, 1, Bt, kPitchKF, 1, acc, lane, wi, wj);
+        __syncthreads();
+    }
+    for_each_acc(acc, lane, wi, wj, [&](int row, int col, double x) {
+        const int gi = ib * kNB + row, gj = kb * kNB + col;
+        if (gi < r && gj < r) S[(int64_t)gi * r + gj] = x;
+    });
+}
+
+__global__ __launch_bounds__(256) void k_chol_update(double* __restrict__ S, int r, int kb) {
+    __shared__ double At[kNB * kPitchKF];
+    __shared__ double Bt[kNB * kPitchKF];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
+    int pi, pj;
+    lower_pair(blockIdx.x, pi, pj);
+    const int ib = kb + 1 + pi, jb = kb + 1 + pj;
+    BlockStage<kNB, kKC, kPitchKF, double> sa, sb;
+    f64x4 acc[2][2];
+    zero_acc(acc);
+    for (int kc = 0; kc < kNB; kc += kKC) {
+        sa.fetch(S, r, ib * kNB, kb * kNB + kc, r, r);
+        sb.fetch(S, r, jb * kNB, kb * kNB + kc, r, r);
+        sa.commit(At);
+        sb.commit(Bt);
+        __syncthreads();
+        mma_chunk(At, kPitchKF, 1, Bt, kPitchKF, 1, acc, lane, wi, wj);
+        __syncthreads();
+    }
+    for_each_acc(acc, lane, wi, wj, [&](int row, int col, double x) {
+        const int gi = ib * kNB + row, gj = jb * kNB + col;
+        if (gi < r && gj < r) S[(int64_t)gi * r + gj] -= x;
+    });
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// X = L^-1, block row ib (all block rows above are complete):  X_ik = -X_ii (sum_{j=k}^{i-1} L_ij X_jk),  k < i
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_trinv_row(const double* __restrict__ S, double* __restrict__ X,
+                                                   const double* __restrict__ Dinv, int r, int ib) {
+    // phase 1: At (L chunk, k fast) and Bt (X chunk, k slow); phase 2: Tm (the sum) and At (X_ii chunk)
+    __shared__ double At[kNB * kPitchKF];
+    __shared__ double Bt[kNB * kPitchT];
+    static_assert(kNB * kPitchT >= kKC * kPitchKS, "the intermediate reuses the X chunk's buffer");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
+    const int kb = blockIdx.x;
+    f64x4 acc[2][2];
+    zero_acc(acc);
+    BlockStage<kNB, kKC, kPitchKF, double> sa;
+    BlockStage<kKC, kNB, kPitchKS, double> sb;
+    for (int kc = kb * kNB; kc < ib * kNB; kc += kKC) {
+        sa.fetch(S, r, ib * kNB, kc, r, r);
+        sb.fetch(X, r, kc, kb * kNB, r, r);
+        sa.commit(At);
+        sb.commit(Bt);
+        __syncthreads();
+        mma_chunk(At, kPitchKF, 1, Bt, 1, kPitchKS, acc, lane, wi, wj);
+        __syncthreads();
+    }
+    double* Tm = Bt;
+    for_each_acc(acc, lane, wi, wj, [&](int row, int col, double x) { Tm[row * kPitchT + col] = x; });
+    zero_acc(acc);
+    const double* D = Dinv + (int64_t)ib * kNB * kNB;
+    for (int kc = 0; kc < kNB; kc += kKC) {
+        sa.fetch(D, kNB, 0, kc, kNB, kNB);
+        sa.commit(At);
+        __syncthreads();       // also publishes Tm on the first pass
+        mma_chunk(At, kPitchKF, 1, Tm + kc * kPitchT, 1, kPitchT, acc, lane, wi, wj);
+        __syncthreads();
+    }
+    for_each_acc(acc, lane, wi, wj, [&](int row, int col, double x) {
+        const int gi = ib * kNB + row, gj = kb * kNB + col;
+        if (gi < r && gj < r) X[(int64_t)gi * r + gj] = -x;
+    });
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Q = Y X^T (X lower triangular: column block jb needs the contraction index up to the end of that block only)
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_apply(const float* __restrict__ Y, const double* __restrict__ X,
+                                               float* __restrict__ Q, int m, int r) {
+    __shared__ double At[kNB * kPitchKF];
+    __shared__ double Bt[kNB * kPitchKF];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
+    const int a0 = blockIdx.x * kNB, jb = blockIdx.y;
+    const int kend = min(r, (jb + 1) * kNB);
+    BlockStage<kNB, kKC, kPitchKF, float> sa;
+    BlockStage<kNB, kKC, kPitchKF, double> sb;
+    f64x4 acc[2][2];
+    zero_acc(acc);
+    sa.fetch(Y, r, a0, 0, m, r);
+    sb.fetch(X, r, jb * kNB, 0, r, r);
+    for (int kc = 0; kc < kend; kc += kKC) {
+        sa.commit(At);
+        sb.commit(Bt);
+        __syncthreads();
+        if (kc + kKC < kend) {
+            sa.fetch(Y, r, a0, kc + kKC, m, r);
+            sb.fetch(X, r, jb * kNB, kc + kKC, r, r);
+        }
+        mma_chunk(At, kPitchKF, 1, Bt, kPitchKF, 1, acc, lane, wi, wj);
+        __syncthreads();
+    }
+    for_each_acc(acc, lane, wi, wj, [&](int row, int col, double x) {
+        const int gi = a0 + row, gj = jb * kNB + col;
+        if (gi < m && gj < r) Q[(int64_t)gi * r + gj] = (float)x;
+    });
+}
+
+static size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+
+struct OrthLayout {
+    size_t S, X, Dinv, T, total;
+};
+static OrthLayout orth_layout(int64_t m, int64_t r) {
+    const int64_t nt = (r + kNB - 1) / kNB;
+    OrthLayout L;
+    L.S = 0;
+    L.X = L.S + align256((size_t)r * r * 8);
+    L.Dinv = L.X + align256((size_t)r * r * 8);
+    L.T = L.Dinv + align256((size_t)nt * kNB * kNB * 8);     // result of the first round, fp32 m x r
+    L.total = L.T + align256((size_t)m * r * 4);
+    return L;
+}
+
+struct RefreshLayout {
+    size_t R, Z, Y, Q, orth, cos, total;
+};
+static RefreshLayout refresh_layout(int64_t m, int64_t n, int64_t r) {
+    RefreshLayout L;
+    L.R = 0;
+    L.Z = L.R + align256((size_t)r * n * 4);
+    L.Y = L.Z + align256((size_t)r * n * 2);
+    L.Q = L.Y + align256((size_t)m * r * 4);
+    L.orth = L.Q + align256((size_t)m * r * 4);
+    L.cos = L.orth + orth_layout(m, r).total;
+    L.total = L.cos + align256(qg_cossim_workspace_bytes(m, r));
+    return L;
+}
+
+static int check_mr(int64_t m, int64_t r) {
+    if (m <= 0 || r <= 0 || (r & 7) || r > m || m >= (int64_t(1) << 31) / r) return QG_ERR_SHAPE;
+    return QG_OK;
+}
+
+static int launch_range(const uint16_t* G, const uint16_t* Z, float* Y, int64_t m, int64_t n, int64_t r, hipStream_t st) {
+    const int64_t tiles_m = (m + kRgT - 1) / kRgT, tiles_r = (r + kRgT - 1) / kRgT;
+    hipLaunchKernelGGL(k_range, dim3((unsigned)(tiles_m * tiles_r)), dim3(256), 0, st, G, Z, Y, (int)m, (int)n, (int)r,
+                       (int)tiles_r);
+    return check_launch();
+}
+
+// One round: Q = Y L^-T with L the Cholesky factor of Y^T Y.
+static void launch_cholqr(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info, double* S, double* X,
+                          double* Dinv, hipStream_t st) {
+    const int nt = (int)((r + kNB - 1) / kNB);
+    hipLaunchKernelGGL(k_gram, dim3(nt * (nt + 1) / 2), dim3(256), 0, st, Y, S, (int)m, (int)r);
+    for (int kb = 0; kb < nt; ++kb) {
+        hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), 0, st, S, (int)r, kb, Dinv, X, info);
+        const int below = nt - kb - 1;
+        if (below > 0) {
+            hipLaunchKernelGGL(k_chol_panel, dim3(below), dim3(256), 0, st, S, (int)r, kb, Dinv);
+            hipLaunchKernelGGL(k_chol_update, dim3(below * (below + 1) / 2), dim3(256), 0, st, S, (int)r, kb);
+        }
+    }
+    for (int ib = 1; ib < nt; ++ib)
+        hipLaunchKernelGGL(k_trinv_row, dim3(ib), dim3(256), 0, st, S, X, Dinv, (int)r, ib);
+    hipLaunchKernelGGL(k_apply, dim3((unsigned)((m + kNB - 1) / kNB), nt), dim3(256), 0, st, Y, X, Q, (int)m, (int)r);
+}
+
+static int launch_orth(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info, bool reset_info, char* ws,
+                       hipStream_t st) {
+    const OrthLayout L = orth_layout(m, r);
+    double* S = reinterpret_cast<double*>(ws + L.S);
+    double* X = reinterpret_cast<double*>(ws + L.X);
+    double* Dinv = reinterpret_cast<double*>(ws + L.Dinv);
+    float* T = reinterpret_cast<float*>(ws + L.T);
+    if (reset_info) hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, st, info, 0);
+    launch_cholqr(Y, m, r, T, info, S, X, Dinv, st);
+    launch_cholqr(T, m, r, Q, info, S, X, Dinv, st);
+    return check_launch();
+}
+
+}  // namespace qg
+
+using namespace qg;
+
+extern "C" int qg_range_apply(const uint16_t* G_bf16, const uint16_t* Z_bf16, int64_t m, int64_t n, int64_t r, float* Y,
+                              void* stream) {
+    if (!G_bf16 || !Z_bf16 || !Y) return QG_ERR_NULL;
+    if (int e = check_mr(m, r)) return e;
+    if (n <= 0 || m * n >= (int64_t(1) << 32) || r * n >= (int64_t(1) << 32)) return QG_ERR_SHAPE;
+    if (!aligned16(G_bf16) || !aligned16(Z_bf16) || !aligned16(Y)) return QG_ERR_ALIGN;
+    return launch_range(G_bf16, Z_bf16, Y, m, n, r, (hipStream_t)stream);
+}
+
+extern "C" size_t qg_orthonormalize_workspace_bytes(int64_t m, int64_t r) {
+    if (check_mr(m, r) != QG_OK) return 0;
+    return orth_layout(m, r).total;
+}
+
+extern "C" int qg_orthonormalize(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (!Y || !Q || !info) return QG_ERR_NULL;
+    if (int e = check_mr(m, r)) return e;
+    if (!aligned16(Y) || !aligned16(Q) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(info) & 3)) return QG_ERR_ALIGN;
+    if (Y == Q) return QG_ERR_SHAPE;
+    if (!workspace || workspace_bytes < orth_layout(m, r).total) return QG_ERR_WORKSPACE;
+    return launch_orth(Y, m, r, Q, info, true, static_cast<char*>(workspace), (hipStream_t)stream);
+}
+
+extern "C" size_t qg_refresh_workspace_bytes(int64_t m, int64_t n, int64_t r) {
+    if (check_mr(m, r) != QG_OK || n <= 0 || m * n >= (int64_t(1) << 32)) return 0;
+    return refresh_layout(m, n, r).total;
+}
+
+extern "C" int qg_subspace_refresh(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int64_t m, int64_t n,
+                                   int64_t r, int group, int passes, uint8_t* Pq_new, float* Ps_new, float* cos_out,
+                                   int32_t* info, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!Pq || !Ps || !G_bf16 || !Pq_new || !Ps_new || !cos_out || !info) return QG_ERR_NULL;
+    if (int e = check_mr(m, r)) return e;
+    if (n <= 0 || m * n >= (int64_t(1) << 32) || passes < 1 || passes > 64) return QG_ERR_SHAPE;
+    if (group != kGroup) return QG_ERR_GROUP;
+    if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(G_bf16) || !aligned16(Pq_new) || !aligned16(Ps_new) ||
+        !aligned16(workspace) || (reinterpret_cast<uintptr_t>(cos_out) & 3) || (reinterpret_cast<uintptr_t>(info) & 3))
+        return QG_ERR_ALIGN;
+    if (Pq == Pq_new || Ps == Ps_new) return QG_ERR_SHAPE;   // the cosine check needs the old P intact
+    const RefreshLayout L = refresh_layout(m, n, r);
+    if (!workspace || workspace_bytes < L.total) return QG_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    float* R = reinterpret_cast<float*>(ws + L.R);
+    uint16_t* Z = reinterpret_cast<uint16_t*>(ws + L.Z);
+    float* Y = reinterpret_cast<float*>(ws + L.Y);
+    float* Q = reinterpret_cast<float*>(ws + L.Q);
+    hipStream_t st = (hipStream_t)stream;
+    const uint8_t* pq = Pq;
+    const float* ps = Ps;
+    for (int pass = 0; pass < passes; ++pass) {
+        if (int e = qg_project(pq, ps, G_bf16, m, n, r, group, R, nullptr, 0, stream)) return e;
+        const int64_t quads = r * n / 4;   // r is a multiple of 8
+        const int64_t blocks = (quads + 255) / 256;
+        hipLaunchKernelGGL(k_f32_to_bf16, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, st, R, Z, quads);
+        if (int e = launch_range(G_bf16, Z, Y, m, n, r, st)) return e;
+        if (int e = launch_orth(Y, m, r, Q, info, pass == 0, ws + L.orth, st)) return e;
+        if (int e = qg_quant_int4(Q, m, r, group, Pq_new, Ps_new, stream)) return e;
+        pq = Pq_new;
+        ps = Ps_new;
+    }
+    return qg_subspace_cossim(Pq, Ps, Pq_new, Ps_new, m, r, group, cos_out, ws + L.cos, workspace_bytes - L.cos, stream);
+}

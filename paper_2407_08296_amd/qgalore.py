@@ -24,6 +24,8 @@ EXPORTS = [
     "qg_policy_update", "qg_workspace_bytes", "qg_step", "qg_plan_bytes", "qg_plan_build", "qg_step_many",
     "qg_sr_uniform", "qg_project_many", "qg_lowrank_adam_many", "qg_backproject_update_sr_many",
     "qg_project_adam", "qg_project_adam_many", "qg_diag_clock_probe", "qg_diag_mfma_loop",
+    "qg_range_apply", "qg_orthonormalize_workspace_bytes", "qg_orthonormalize", "qg_refresh_workspace_bytes",
+    "qg_subspace_refresh",
 ]
 
 
@@ -89,6 +91,13 @@ def lib() -> C.CDLL:
         L.qg_project_adam_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), i64, i32, vp]
         L.qg_diag_clock_probe.argtypes = [i64, vp, vp]
         L.qg_diag_mfma_loop.argtypes = [i64, i32, vp, vp]
+        L.qg_range_apply.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+        L.qg_orthonormalize_workspace_bytes.restype = sz
+        L.qg_orthonormalize_workspace_bytes.argtypes = [i64, i64]
+        L.qg_orthonormalize.argtypes = [vp, i64, i64, vp, vp, vp, sz, vp]
+        L.qg_refresh_workspace_bytes.restype = sz
+        L.qg_refresh_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qg_subspace_refresh.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -266,6 +275,42 @@ def project_adam_many(plan: StepPlan, hp: HParams, step: int, write_R: bool = Fa
 def backproject_update_sr_many(plan: StepPlan, hp: HParams, seed: int, step: int) -> None:
     _check(lib().qg_backproject_update_sr_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
                                                C.byref(hp), seed, step, _stream()))
+
+
+# ---------------------------------------------------------------- subspace refresh
+def range_apply(G: torch.Tensor, Z: torch.Tensor, m: int, n: int, r: int) -> torch.Tensor:
+    Y = torch.empty((m, r), dtype=torch.float32, device=G.device)
+    _check(lib().qg_range_apply(_ptr(G, _BF16), _ptr(Z, _BF16), m, n, r, _ptr(Y), _stream()))
+    return Y
+
+
+def orthonormalize(Y: torch.Tensor):
+    """Returns (Q, info): Q fp32 [m][r], info a device int32 (0 = every pivot positive)."""
+    m, r = Y.shape
+    nbytes = lib().qg_orthonormalize_workspace_bytes(m, r)
+    if nbytes == 0:
+        raise QGError("libqgalore: shape out of range")
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=Y.device)
+    Q = torch.empty_like(Y)
+    info = torch.empty((1,), dtype=torch.int32, device=Y.device)
+    _check(lib().qg_orthonormalize(_ptr(Y, (torch.float32,)), m, r, _ptr(Q), _ptr(info), _ptr(ws), nbytes, _stream()))
+    return Q, info
+
+
+def subspace_refresh(Pq, Ps, G, m: int, n: int, r: int, passes: int = 1, workspace: torch.Tensor | None = None):
+    """Returns (Pq_new, Ps_new, cos, info, workspace); cos and info are device tensors of one element."""
+    nbytes = lib().qg_refresh_workspace_bytes(m, n, r)
+    if nbytes == 0:
+        raise QGError("libqgalore: shape out of range")
+    if workspace is None:
+        workspace = torch.empty((nbytes,), dtype=torch.uint8, device=G.device)
+    Pq_new, Ps_new = torch.empty_like(Pq), torch.empty_like(Ps)
+    cos = torch.empty((1,), dtype=torch.float32, device=G.device)
+    info = torch.empty((1,), dtype=torch.int32, device=G.device)
+    _check(lib().qg_subspace_refresh(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(G, _BF16), m, n, r,
+                                     GROUP, passes, _ptr(Pq_new), _ptr(Ps_new), _ptr(cos), _ptr(info),
+                                     _ptr(workspace), workspace.numel(), _stream()))
+    return Pq_new, Ps_new, cos, info, workspace
 
 
 DIAG_MFMA_WORKGROUPS = 512

@@ -75,6 +75,38 @@ def test_step_piece_argument_errors(L):
     assert L.qg_diag_mfma_loop(16, 1, None, None) == 1
 
 
+def test_refresh_argument_errors(L):
+    assert L.qg_range_apply(None, FAKE, 512, 512, 128, FAKE, None) == 1
+    assert L.qg_range_apply(FAKE, FAKE, 512, 512, 132, FAKE, None) == 2                      # r % 8 != 0
+    assert L.qg_range_apply(FAKE, FAKE, 64, 512, 128, FAKE, None) == 2                       # r > m
+    assert L.qg_range_apply(FAKE, FAKE, 1 << 17, 1 << 17, 128, FAKE, None) == 2              # m*n >= 2^32
+    assert L.qg_range_apply(FAKE, FAKE + 2, 512, 512, 128, FAKE, None) == 4
+    ob = L.qg_orthonormalize_workspace_bytes(512, 128)
+    assert ob >= 2 * 128 * 128 * 8 + 2 * 64 * 64 * 8 + 512 * 128 * 4 and ob % 256 == 0
+    assert L.qg_orthonormalize_workspace_bytes(64, 128) == 0
+    assert L.qg_orthonormalize(FAKE, 512, 128, FAKE + 4096, None, FAKE, ob, None) == 1
+    assert L.qg_orthonormalize(FAKE, 512, 128, FAKE, FAKE, FAKE, ob, None) == 2              # Y and Q alias
+    assert L.qg_orthonormalize(FAKE, 512, 128, FAKE + 4096, FAKE, FAKE, ob - 1, None) == 5
+    assert L.qg_orthonormalize(FAKE, 512, 128, FAKE + 4096, FAKE, None, 0, None) == 5
+    assert L.qg_orthonormalize(FAKE, 1 << 22, 1024, FAKE + 4096, FAKE, FAKE, 1 << 40, None) == 2   # m*r >= 2^31
+    rb = L.qg_refresh_workspace_bytes(512, 512, 128)
+    assert rb >= 128 * 512 * 6 + 2 * 512 * 128 * 4 + ob + L.qg_cossim_workspace_bytes(512, 128)
+    assert L.qg_refresh_workspace_bytes(512, 0, 128) == 0
+    args = (FAKE, FAKE, FAKE, 512, 512, 128, 256, 1, FAKE + 4096, FAKE + 8192, FAKE, FAKE, FAKE, rb, None)
+
+    def call(**kw):
+        a = list(args)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return L.qg_subspace_refresh(*a)
+    assert call(a0=None) == 1 and call(a10=None) == 1 and call(a11=None) == 1
+    assert call(a7=0) == 2 and call(a7=65) == 2                                              # passes
+    assert call(a6=128) == 3
+    assert call(a8=FAKE) == 2                                                                # new P aliases the old
+    assert call(a2=FAKE + 2) == 4
+    assert call(a13=rb - 1) == 5 and call(a12=None) == 5
+
+
 def test_plan_build_on_host(L):
     descs = (qg.MatrixDesc * 2)()
     for d, (m, n, r) in zip(descs, [(4096, 4096, 1024), (11008, 4096, 1024)]):

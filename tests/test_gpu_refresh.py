@@ -1,0 +1,205 @@
+"""GPU parity of the subspace refresh (Sec. 3.2) against the CPU oracle.
+
+What is compared, and to what bar:
+  * Y = G Z^T: 1e-4 relative Frobenius (bf16 products are exact in fp32; only the fp32 accumulation order differs).
+  * Q = orthonormalize(Y) on the SAME fp32 Y: element-wise 1e-6 (the library works in fp64 and rounds Q to fp32
+    once), and |Q^T Q - I| <= 1e-6.
+  * the whole pass: the library's Y differs from the oracle's by dY (fp32 accumulation, a few bf16 roundings of Z
+    that land on the other side), and the QR factor moves by at most sqrt(2) cond(Y) |dY|_F / |Y|_2 to first
+    order, so Q is held to that bound; the INT4 codes of the new P then agree except where Q sits within that
+    distance of a rounding boundary (>= 99 % identical, never off by more than one code), and the quantities the
+    method uses downstream (the energy the new P captures, the cosine of Sec. 3.2) agree to 1e-3.
+  * the composite entry point equals the chain of the separate entry points bit for bit.
+Every oracle input comes from the seeded generators or from the oracle itself.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qgalore as Q
+from paper_2407_08296_amd import inputs as I
+from paper_2407_08296_amd import qgalore as qg
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+SHAPES = [(512, 512, 128), (333, 264, 144), (200, 521, 48), (1040, 1048, 272), (2048, 768, 256)]
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def bits_t(bits):
+    """uint16 bf16 patterns -> device tensor the binding accepts."""
+    return dev(np.ascontiguousarray(bits).view(np.int16))
+
+
+def rel_fro(a, b):
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(np.asarray(a, dtype=np.float64) - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def start(m, n, r, seed=0):
+    Gb = I.gradient_bf16(m, n, 1, seed)
+    Pq, Ps = Q.quant_int4(I.projection_f32(m, r, seed))
+    return Gb, Pq, Ps
+
+
+# ---------------------------------------------------------------- Y = G Z^T
+@pytest.mark.parametrize("m,n,r", SHAPES + [(2048, 5461, 512)])
+def test_range_apply(m, n, r):
+    Gb, Pq, Ps = start(m, n, r)
+    Zb = Q.f64_to_bf16_bits(Q.project(Pq, Ps, Gb, m, n, r))
+    want = Q.range_apply(Gb, Zb, m, n, r)
+    got = host(qg.range_apply(bits_t(Gb), bits_t(Zb), m, n, r))
+    assert got.shape == (m, r)
+    assert rel_fro(got, want) <= 1e-4
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+
+
+# ---------------------------------------------------------------- Q = orthonormalize(Y)
+def _oracle_y(m, n, r):
+    Gb, Pq, Ps = start(m, n, r)
+    Zb = Q.f64_to_bf16_bits(Q.project(Pq, Ps, Gb, m, n, r))
+    return Q.range_apply(Gb, Zb, m, n, r).astype(np.float32)
+
+
+@pytest.mark.parametrize("m,n,r", SHAPES + [(4096, 1024, 1024)])
+def test_orthonormalize_matches_the_positive_diagonal_qr(m, n, r):
+    Y = _oracle_y(m, n, r)
+    want = Q.orthonormalize(Y)
+    Qd, info = qg.orthonormalize(dev(Y))
+    got = host(Qd).astype(np.float64)
+    assert int(host(info)[0]) == 0
+    assert np.abs(got - want).max() <= 1e-6
+    assert np.abs(got.T @ got - np.eye(r)).max() <= 1e-6
+
+
+def test_orthonormalize_graded_columns():
+    """Column norms spread over four decades and strong correlation: cond(Y) ~ 1e5."""
+    m, r = 777, 200
+    g = np.random.default_rng(21)
+    Y = (g.standard_normal((m, r)) + 3.0 * g.standard_normal((m, 1))) * np.logspace(0, -4, r)[None, :]
+    Y = Y.astype(np.float32)
+    assert 1e4 < np.linalg.cond(Y.astype(np.float64)) < 1e7
+    want = Q.orthonormalize(Y)
+    Qd, info = qg.orthonormalize(dev(Y))
+    got = host(Qd).astype(np.float64)
+    assert int(host(info)[0]) == 0
+    assert np.abs(got - want).max() <= 1e-5
+    assert np.abs(got.T @ got - np.eye(r)).max() <= 1e-5
+
+
+def test_orthonormalize_reports_a_zero_pivot():
+    m, r = 300, 136
+    Y = np.random.default_rng(22).standard_normal((m, r)).astype(np.float32)
+    Y[:, 70] = 0.0
+    Qd, info = qg.orthonormalize(dev(Y))
+    assert int(host(info)[0]) == 71
+    got = host(Qd).astype(np.float64)
+    assert np.isfinite(got).all()
+    want = Q.orthonormalize(Y[:, :70])                       # the columns before the failure are still right
+    assert np.abs(got[:, :70] - want).max() <= 1e-6
+
+
+# ---------------------------------------------------------------- the whole pass
+def _chain(Gb, Pq, Ps, m, n, r):
+    """One pass through the separate entry points; returns every intermediate."""
+    Gd, Pqd, Psd = bits_t(Gb), dev(Pq), dev(Ps)
+    R = qg.project(Pqd, Psd, Gd, m, n, r)
+    Z = R.to(torch.bfloat16)                                  # round to nearest even, as the library's conversion
+    Y = qg.range_apply(Gd, Z, m, n, r)
+    Qd, info = qg.orthonormalize(Y)
+    Pq1, Ps1 = qg.quant_int4(Qd)
+    return dict(R=R, Y=Y, Q=Qd, info=info, Pq=Pq1, Ps=Ps1)
+
+
+@pytest.mark.parametrize("m,n,r", SHAPES)
+def test_refresh_pass_against_the_oracle(m, n, r):
+    Gb, Pq, Ps = start(m, n, r)
+    oR = Q.project(Pq, Ps, Gb, m, n, r)
+    oY = Q.range_apply(Gb, Q.f64_to_bf16_bits(oR), m, n, r)
+    oPq, oPs, oQ = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+    c = _chain(Gb, Pq, Ps, m, n, r)
+    assert int(host(c["info"])[0]) == 0
+    gY, gQ = host(c["Y"]).astype(np.float64), host(c["Q"]).astype(np.float64)
+    assert rel_fro(gY, oY) <= 1e-3
+    sv = np.linalg.svd(oY, compute_uv=False)
+    bound = 1.5 * np.sqrt(2.0) * (sv[0] / sv[-1]) * np.linalg.norm(gY - oY) / sv[0] + 1e-6 * np.sqrt(r)
+    assert np.linalg.norm(gQ - oQ) <= bound, (np.linalg.norm(gQ - oQ), bound, sv[0] / sv[-1])
+    assert np.abs(gQ.T @ gQ - np.eye(r)).max() <= 1e-6
+    # the stored projection
+    gc, oc = Q.unpack_int4(host(c["Pq"]), m * r).astype(np.int32), Q.unpack_int4(oPq, m * r).astype(np.int32)
+    assert np.abs(gc - oc).max() <= 1 and np.mean(gc == oc) >= 0.99, np.mean(gc == oc)
+    assert np.allclose(host(c["Ps"]), oPs, rtol=2e-3)
+    G = Q.bf16_bits_to_f64(Gb).reshape(m, n)
+    e_got = np.linalg.norm(Q.project(host(c["Pq"]), host(c["Ps"]), Gb, m, n, r)) ** 2
+    e_want = np.linalg.norm(Q.project(oPq, oPs, Gb, m, n, r)) ** 2
+    assert abs(e_got - e_want) <= 1e-3 * e_want
+    assert e_got >= 0.9 * np.linalg.norm(oQ.T @ G) ** 2      # and INT4 storage keeps most of what Q captures
+
+
+@pytest.mark.parametrize("m,n,r,passes", [(512, 512, 128, 1), (333, 264, 144, 1), (200, 521, 48, 2), (1040, 1048, 272, 3)])
+def test_subspace_refresh_equals_its_parts_and_the_oracle(m, n, r, passes):
+    Gb, Pq, Ps = start(m, n, r)
+    Pq1, Ps1, cos, info, ws = qg.subspace_refresh(dev(Pq), dev(Ps), bits_t(Gb), m, n, r, passes)
+    assert int(host(info)[0]) == 0
+    # bit for bit the chain of the separate calls
+    pq, ps = Pq, Ps
+    for _ in range(passes):
+        c = _chain(Gb, pq, ps, m, n, r)
+        pq, ps = host(c["Pq"]), host(c["Ps"])
+    assert np.array_equal(host(Pq1), pq) and np.array_equal(host(Ps1), ps)
+    R_ws = host(ws[: r * n * 4].view(torch.float32)).reshape(r, n)
+    assert np.array_equal(R_ws, host(c["R"]))
+    want_cos = Q.subspace_cossim(Pq, Ps, pq, ps, m, r)        # the library's own new P: isolates the cosine kernel
+    assert abs(float(host(cos)[0]) - want_cos) <= 1e-5
+    # against the oracle's passes: what the method uses downstream
+    oPq, oPs, _ = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=passes)
+    assert abs(float(host(cos)[0]) - Q.subspace_cossim(Pq, Ps, oPq, oPs, m, r)) <= 2e-3 * passes
+    e_got = np.linalg.norm(Q.project(pq, ps, Gb, m, n, r)) ** 2
+    e_want = np.linalg.norm(Q.project(oPq, oPs, Gb, m, n, r)) ** 2
+    assert abs(e_got - e_want) <= 1e-3 * passes * e_want
+    # the input projection is untouched and a second call on the same workspace gives the same answer
+    again = qg.subspace_refresh(dev(Pq), dev(Ps), bits_t(Gb), m, n, r, passes, workspace=ws)
+    assert np.array_equal(host(again[0]), pq) and np.array_equal(host(again[1]), ps)
+
+
+def test_refresh_at_llama7b_shapes_by_properties():
+    """Full-size matrices of the 7B configuration (r = 1024): sampled entries of Y against fp64 dot products, Q
+    orthonormal and spanning Y, the new P capturing more of G than the start."""
+    for (m, n) in [(4096, 4096), (11008, 4096)]:
+        r = 1024
+        g = torch.Generator(device=DEV).manual_seed(5)
+        A = torch.randn((m, 16), generator=g, device=DEV) * 0.01
+        B = torch.randn((n, 16), generator=g, device=DEV) * 0.01
+        G = (A @ B.T + torch.randn((m, n), generator=g, device=DEV) * 1e-4).to(torch.bfloat16)
+        Pq, Ps = qg.quant_int4(torch.linalg.qr(torch.randn((m, r), generator=g, device=DEV))[0].contiguous())
+        R = qg.project(Pq, Ps, G, m, n, r)
+        Z = R.to(torch.bfloat16)
+        Y = qg.range_apply(G, Z, m, n, r)
+        rows = np.random.default_rng(6).integers(0, m, 64)
+        cols = np.random.default_rng(7).integers(0, r, 64)
+        Gh = host(G[rows].to(torch.float32)).astype(np.float64)
+        Zh = host(Z[cols].to(torch.float32)).astype(np.float64)
+        want = np.sum(Gh * Zh, axis=1)
+        got = host(Y[rows, cols]).astype(np.float64)
+        assert np.abs(got - want).max() <= 1e-4 * np.abs(host(Y)).max()
+        Qd, info = qg.orthonormalize(Y)
+        assert int(host(info)[0]) == 0
+        Q64, Y64 = Qd.to(torch.float64), Y.to(torch.float64)
+        assert float((Q64.T @ Q64 - torch.eye(r, device=DEV, dtype=torch.float64)).abs().max()) <= 1e-6
+        T = Q64.T @ Y64                                       # upper triangular, positive diagonal, Q T = Y
+        assert float(torch.tril(T, -1).abs().max()) <= 1e-6 * float(T.abs().max())
+        assert bool((torch.diagonal(T) > 0).all())
+        assert float((Q64 @ T - Y64).abs().max()) <= 1e-6 * float(Y64.abs().max())
+        Pq1, Ps1, cos, info, _ = qg.subspace_refresh(Pq, Ps, G, m, n, r, 1)
+        assert int(host(info)[0]) == 0 and 0.0 < float(host(cos)[0]) < 1.0
+        e0 = float(qg.project(Pq, Ps, G, m, n, r).norm()) ** 2
+        e1 = float(qg.project(Pq1, Ps1, G, m, n, r).norm()) ** 2
+        assert e1 > 1.5 * e0
