@@ -133,6 +133,89 @@ def cpu_baseline(config: int, shapes):
             "sample": note, "sample_seconds": total, "host_cpus": len(os.sched_getaffinity(0))}
 
 
+PEAK_FP64_TFLOPS = 78.6      # MI355X fp64 matrix (and vector) peak, published
+
+
+def refresh_bench(args, shapes, mats):
+    """One subspace refresh (one pass of orthogonal iteration, Cholesky QR twice, INT4 requantization, cosine check)
+    of every matrix of the workload, one qg_subspace_refresh call per matrix on one shared workspace."""
+    import torch
+
+    from paper_2407_08296_amd import qgalore as qg
+
+    L = qg.lib()
+    dev = mats[0].G.device
+    ws = torch.empty((max(L.qg_refresh_workspace_bytes(m, n, r) for m, n, r in shapes),), dtype=torch.uint8, device=dev)
+
+    def one_round(read_info=False):
+        bad = 0
+        for s in mats:
+            _, _, _, info, _ = qg.subspace_refresh(s.Pq, s.Ps, s.G, s.m, s.n, s.r, 1, workspace=ws)
+            if read_info:
+                bad += int(info.item() != 0)
+        return bad
+
+    bad = one_round(read_info=True)                     # warm-up, and the only round that reads `info` back
+    torch.cuda.synchronize()
+    rounds = max(1, min(args.steps, 3))
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(rounds):
+        one_round()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / rounds * 1e3
+    ms = e0.elapsed_time(e1) / rounds
+    per_shape = {}
+    for (m, n, r) in sorted(set(shapes)):
+        s = next(x for x in mats if (x.m, x.n, x.r) == (m, n, r))
+        qg.subspace_refresh(s.Pq, s.Ps, s.G, m, n, r, 1, workspace=ws)
+        torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            qg.subspace_refresh(s.Pq, s.Ps, s.G, m, n, r, 1, workspace=ws)
+        b.record(); torch.cuda.synchronize()
+        per_shape[f"{m}x{n} r{r}"] = {"ms": a.elapsed_time(b) / 5, "count": shapes.count((m, n, r))}
+    bf16_flop = sum(4.0 * m * n * r for m, n, r in shapes)                 # R = P^T G and Y = G Z^T
+    fp64_flop = sum(2 * (m * r * r + r ** 3 / 3 + r ** 3 / 3 + m * r * r) for m, n, r in shapes)   # two rounds
+    out = {"metric": "Q-GaLore subspace refresh ms over all linear weights", "value": ms, "unit": "ms",
+           "n_gpus": 1, "rounds": rounds, "higher_is_better": False, "dtype": "bf16 GEMMs + fp64 orthonormalisation",
+           "data": "synthetic", "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "passes": 1},
+           "wall_ms": wall, "per_shape": per_shape, "info_nonzero": bad,
+           "work": {"bf16_TFLOP": bf16_flop / 1e12, "fp64_TFLOP": fp64_flop / 1e12,
+                    "bf16_bound_ms": bf16_flop / PEAK_BF16_TFLOPS / 1e9, "fp64_bound_ms": fp64_flop / PEAK_FP64_TFLOPS / 1e9},
+           "amortized_ms_per_step_at_interval_200": ms / 200.0,
+           "context": "the paper reports about 10 minutes per SVD refresh of LLaMA-7B on one RTX A6000 (Sec. 4.3)"}
+    if not args.no_cpu_baseline:
+        import numpy as np
+
+        from oracle import qgalore as Q
+        from paper_2407_08296_amd import inputs as I
+        m, n, r = 768, 768, 256
+        Pq, Ps = Q.quant_int4(I.projection_f32(m, r))
+        Gb = I.gradient_bf16(m, n, 1)
+        t0 = time.perf_counter()
+        Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+        t_or = time.perf_counter() - t0
+        t1 = time.perf_counter()
+        Q.refresh_svd(Gb, m, n, r)
+        t_svd = time.perf_counter() - t1
+        Pqd, Psd = torch.from_numpy(Pq).to(dev), torch.from_numpy(Ps).to(dev)
+        Gd = torch.from_numpy(Gb.view(np.int16)).to(dev)
+        qg.subspace_refresh(Pqd, Psd, Gd, m, n, r, 1); torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            qg.subspace_refresh(Pqd, Psd, Gd, m, n, r, 1)
+        b.record(); torch.cuda.synchronize()
+        out["cpu_baseline"] = {"kind": "oracle", "sample": "one 768x768 matrix, r=256 (LLaMA-130M attention shape)",
+                               "oracle_pass_ms": t_or * 1e3, "oracle_svd_ms": t_svd * 1e3,
+                               "gpu_ms_same_matrix": a.elapsed_time(b) / 5, "host_cpus": len(os.sched_getaffinity(0))}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -143,6 +226,9 @@ def main():
     ap.add_argument("--rsweep", action="store_true",
                     help="time qg_project / qg_lowrank_adam / qg_backproject_update_sr on one 2048x5461 matrix for "
                          "r in {128, 256, 512, 1024} (the roofline crossover of the LLaMA-1B shape) and exit")
+    ap.add_argument("--refresh", action="store_true",
+                    help="time the subspace refresh (qg_subspace_refresh, one pass) over every matrix of the workload "
+                         "instead of the optimizer step, print its own JSON line and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -220,6 +306,10 @@ def main():
 
     shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(args.config)]
     mats = build_state(args.config, device)
+
+    if args.refresh:
+        print(json.dumps(refresh_bench(args, shapes, mats)))
+        return
     import dataclasses
     # The step needs no R buffers (the projected gradient stays in registers between the projection and Adam); the
     # unfused pair of launches, timed after the step for its own roofline figures, does.

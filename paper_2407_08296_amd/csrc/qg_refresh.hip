@@ -101,6 +101,18 @@ __device__ __forceinline__ void for_each_acc(const f64x4 (&acc)[2][2], int lane,
             for (int v = 0; v < 4; ++v) f(wi * 32 + a * 16 + 4 * v + (lane >> 4), wj * 32 + b * 16 + (lane & 15), acc[a][b][v]);
 }
 
+// 1 / sqrt(d) for d > 0 to fp64 accuracy: the hardware estimate and two Newton steps (the correctly rounded sqrt
+// and divide of the library cost an order of magnitude more instructions, on the critical path of every column).
+__device__ __forceinline__ double rsqrt_f64(double d) {
+    double y = __builtin_amdgcn_rsq(d);
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const double e = fma(-d * y, y, 1.0);      // 1 - d y^2
+        y = fma(0.5 * y, e, y);
+    }
+    return y;
+}
+
 // (bi, bj) with bi >= bj of the idx-th block of a lower block triangle, rows first.
 __device__ __forceinline__ void lower_pair(int idx, int& bi, int& bj) {
     int i = 0;
@@ -204,28 +216,34 @@ __global__ __launch_bounds__(256) void k_range(const uint16_t* __restrict__ G, c
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// S = Y^T Y in fp64, lower block triangle only (Y fp32 m x r; S r x r row-major)
+// S = Y^T Y in fp64, lower block triangle only (Y fp32 m x r; S r x r row-major).  The m rows are cut into
+// gridDim.y slices so that the launch fills the chip; slice s writes its partial sums to part + s * r * r and
+// k_gram_reduce adds the slices in a fixed order (the result does not depend on scheduling).
 // ---------------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_gram(const float* __restrict__ Y, double* __restrict__ S, int m, int r) {
+constexpr int kGramMaxSlices = 8;
+
+__global__ __launch_bounds__(256) void k_gram(const float* __restrict__ Y, double* __restrict__ part, int m, int r,
+                                              int slice_rows) {
     __shared__ double At[kKC * kPitchKS];
     __shared__ double Bt[kKC * kPitchKS];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
     int bi, bj;
     lower_pair(blockIdx.x, bi, bj);
     const bool diag = bi == bj;
+    const int k_begin = blockIdx.y * slice_rows, k_end = min(m, k_begin + slice_rows);
+    double* S = part + (int64_t)blockIdx.y * r * r;
     BlockStage<kKC, kNB, kPitchKS, float> sa, sb;
     f64x4 acc[2][2];
     zero_acc(acc);
-    const int KT = (m + kKC - 1) / kKC;
-    sa.fetch(Y, r, 0, bi * kNB, m, r);
-    if (!diag) sb.fetch(Y, r, 0, bj * kNB, m, r);
-    for (int kt = 0; kt < KT; ++kt) {
+    sa.fetch(Y, r, k_begin, bi * kNB, k_end, r);
+    if (!diag) sb.fetch(Y, r, k_begin, bj * kNB, k_end, r);
+    for (int k0 = k_begin; k0 < k_end; k0 += kKC) {
         sa.commit(At);
         if (!diag) sb.commit(Bt);
         __syncthreads();
-        if (kt + 1 < KT) {
-            sa.fetch(Y, r, (kt + 1) * kKC, bi * kNB, m, r);
-            if (!diag) sb.fetch(Y, r, (kt + 1) * kKC, bj * kNB, m, r);
+        if (k0 + kKC < k_end) {
+            sa.fetch(Y, r, k0 + kKC, bi * kNB, k_end, r);
+            if (!diag) sb.fetch(Y, r, k0 + kKC, bj * kNB, k_end, r);
         }
         mma_chunk(At, 1, kPitchKS, diag ? At : Bt, 1, kPitchKS, acc, lane, wi, wj);
         __syncthreads();
@@ -234,6 +252,17 @@ __global__ __launch_bounds__(256) void k_gram(const float* __restrict__ Y, doubl
         const int gi = bi * kNB + row, gj = bj * kNB + col;
         if (gi < r && gj < r) S[(int64_t)gi * r + gj] = x;
     });
+}
+
+__global__ __launch_bounds__(256) void k_gram_reduce(const double* __restrict__ part, double* __restrict__ S, int r,
+                                                     int slices) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)r * r) return;
+    const int i = (int)(e / r), j = (int)(e % r);
+    if (j / kNB > i / kNB) return;                 // above the lower block triangle: never written, never read
+    double sum = 0.0;
+    for (int s = 0; s < slices; ++s) sum += part[(int64_t)s * r * r + e];
+    S[e] = sum;
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -247,8 +276,7 @@ __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r
                                                    double* __restrict__ X, int32_t* __restrict__ info) {
     constexpr int P = kNB + 1;
     __shared__ double T[kNB * P];
-    __shared__ double dg[kNB];
-    __shared__ double vcol[kNB];
+    __shared__ double dg[kNB], rdg[kNB];
     const int t = threadIdx.x;
     const int base = kb * kNB;
     for (int e = t; e < kNB * kNB; e += 256) {     // consecutive threads along a row
@@ -264,10 +292,13 @@ __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r
             if (t == 0) atomicCAS(info, 0, base + j + 1);
             d = 1.0;
         }
-        const double s = sqrt(d);
+        const double rs = rsqrt_f64(d);             // column j is scaled by 1 / L_jj, kept for the inverse below
         if (cg == 0) {
-            if (i > j) T[i * P + j] = T[i * P + j] / s;
-            if (i == j) dg[j] = s;                  // T[j][j] itself stays until every thread has read it
+            if (i > j) T[i * P + j] *= rs;
+            if (i == j) {
+                dg[j] = d * rs;                     // T[j][j] itself stays until every thread has read it
+                rdg[j] = rs;
+            }
         }
         __syncthreads();
         const double lij = T[i * P + j];
@@ -280,27 +311,28 @@ __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r
         const int ii = e >> 6, c = e & 63;
         if (c <= ii && base + ii < r) S[(int64_t)(base + ii) * r + base + c] = T[ii * P + c];
     }
-    // in-place inverse of the lower triangular block, last column first: with the trailing block already
-    // inverted, X[j+1.., j] = -X[j+1.., j+1..] L[j+1.., j] / L_jj
-    for (int j = kNB - 1; j >= 0; --j) {
+    // X = L^-1 by forward substitution on all 64 columns of the identity at once, right-looking: once row j of X is
+    // final, every later row's residual loses its L[i][j] X[j][.] term.  The residuals (and then X) live transposed
+    // in the strict upper triangle of T, which the factor does not use: X[i][c] at T[c][i] for c < i; the diagonal
+    // of X is 1 / L_jj (rdg).
+    for (int e = t; e < kNB * kNB; e += 256) {
+        const int ii = e >> 6, c = e & 63;
+        if (c > ii) T[ii * P + c] = 0.0;
+    }
+    for (int j = 0; j < kNB; ++j) {
         __syncthreads();
-        const double xjj = 1.0 / T[j * P + j];
-        if (t < kNB) vcol[t] = t > j ? T[t * P + j] : 0.0;
+        const double xjj = rdg[j];
+        if (t < j) T[t * P + j] *= xjj;             // row j of X: residual / L_jj
         __syncthreads();
-        if (t < kNB) {
-            if (t > j) {
-                double sum = 0.0;
-                for (int k = j + 1; k <= t; ++k) sum = fma(T[t * P + k], vcol[k], sum);
-                T[t * P + j] = -sum * xjj;
-            } else if (t == j) {
-                T[j * P + j] = xjj;
-            }
+        if (i > j) {
+            const double lij = T[i * P + j];
+            for (int c = cg; c <= j; c += 4) T[c * P + i] -= lij * (c < j ? T[c * P + j] : xjj);
         }
     }
     __syncthreads();
     for (int e = t; e < kNB * kNB; e += 256) {
         const int ii = e >> 6, c = e & 63;
-        const double x = c <= ii ? T[ii * P + c] : 0.0;
+        const double x = c < ii ? T[c * P + ii] : (c == ii ? rdg[ii] : 0.0);
         Dinv[(int64_t)kb * kNB * kNB + e] = x;
         if (base + ii < r && base + c < r) X[(int64_t)(base + ii) * r + base + c] = x;
     }
@@ -315,12 +347,16 @@ __global__ __launch_bounds__(256) void k_chol_panel(double* __restrict__ S, int 
     BlockStage<kNB, kKC, kPitchKF, double> sa, sb;
     f64x4 acc[2][2];
     zero_acc(acc);
+    sa.fetch(S, r, ib * kNB, kb * kNB, r, r);
+    sb.fetch(D, kNB, 0, 0, kNB, kNB);
     for (int kc = 0; kc < kNB; kc += kKC) {
-        sa.fetch(S, r, ib * kNB, kb * kNB + kc, r, r);
-        sb.fetch(D, kNB, 0, kc, kNB, kNB);
         sa.commit(At);
         sb.commit(Bt);
         __syncthreads();
+        if (kc + kKC < kNB) {
+            sa.fetch(S, r, ib * kNB, kb * kNB + kc + kKC, r, r);
+            sb.fetch(D, kNB, 0, kc + kKC, kNB, kNB);
+        }
         mma_chunk(At, kPitchKF, 1, Bt, kPitchKF, 1, acc, lane, wi, wj);
         __syncthreads();
     }
@@ -340,12 +376,16 @@ __global__ __launch_bounds__(256) void k_chol_update(double* __restrict__ S, int
     BlockStage<kNB, kKC, kPitchKF, double> sa, sb;
     f64x4 acc[2][2];
     zero_acc(acc);
+    sa.fetch(S, r, ib * kNB, kb * kNB, r, r);
+    sb.fetch(S, r, jb * kNB, kb * kNB, r, r);
     for (int kc = 0; kc < kNB; kc += kKC) {
-        sa.fetch(S, r, ib * kNB, kb * kNB + kc, r, r);
-        sb.fetch(S, r, jb * kNB, kb * kNB + kc, r, r);
         sa.commit(At);
         sb.commit(Bt);
         __syncthreads();
+        if (kc + kKC < kNB) {
+            sa.fetch(S, r, ib * kNB, kb * kNB + kc + kKC, r, r);
+            sb.fetch(S, r, jb * kNB, kb * kNB + kc + kKC, r, r);
+        }
         mma_chunk(At, kPitchKF, 1, Bt, kPitchKF, 1, acc, lane, wi, wj);
         __syncthreads();
     }
@@ -370,23 +410,30 @@ __global__ __launch_bounds__(256) void k_trinv_row(const double* __restrict__ S,
     zero_acc(acc);
     BlockStage<kNB, kKC, kPitchKF, double> sa;
     BlockStage<kKC, kNB, kPitchKS, double> sb;
-    for (int kc = kb * kNB; kc < ib * kNB; kc += kKC) {
-        sa.fetch(S, r, ib * kNB, kc, r, r);
-        sb.fetch(X, r, kc, kb * kNB, r, r);
+    const double* D = Dinv + (int64_t)ib * kNB * kNB;
+    const int k_end = ib * kNB;
+    sa.fetch(S, r, ib * kNB, kb * kNB, r, r);
+    sb.fetch(X, r, kb * kNB, kb * kNB, r, r);
+    for (int kc = kb * kNB; kc < k_end; kc += kKC) {
         sa.commit(At);
         sb.commit(Bt);
         __syncthreads();
+        if (kc + kKC < k_end) {
+            sa.fetch(S, r, ib * kNB, kc + kKC, r, r);
+            sb.fetch(X, r, kc + kKC, kb * kNB, r, r);
+        } else {
+            sa.fetch(D, kNB, 0, 0, kNB, kNB);     // first chunk of the second product
+        }
         mma_chunk(At, kPitchKF, 1, Bt, 1, kPitchKS, acc, lane, wi, wj);
         __syncthreads();
     }
     double* Tm = Bt;
     for_each_acc(acc, lane, wi, wj, [&](int row, int col, double x) { Tm[row * kPitchT + col] = x; });
     zero_acc(acc);
-    const double* D = Dinv + (int64_t)ib * kNB * kNB;
     for (int kc = 0; kc < kNB; kc += kKC) {
-        sa.fetch(D, kNB, 0, kc, kNB, kNB);
         sa.commit(At);
         __syncthreads();       // also publishes Tm on the first pass
+        if (kc + kKC < kNB) sa.fetch(D, kNB, 0, kc + kKC, kNB, kNB);
         mma_chunk(At, kPitchKF, 1, Tm + kc * kPitchT, 1, kPitchT, acc, lane, wi, wj);
         __syncthreads();
     }
@@ -432,7 +479,7 @@ __global__ __launch_bounds__(256) void k_apply(const float* __restrict__ Y, cons
 static size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 
 struct OrthLayout {
-    size_t S, X, Dinv, T, total;
+    size_t S, X, Dinv, T, part, total;
 };
 static OrthLayout orth_layout(int64_t m, int64_t r) {
     const int64_t nt = (r + kNB - 1) / kNB;
@@ -441,7 +488,8 @@ static OrthLayout orth_layout(int64_t m, int64_t r) {
     L.X = L.S + align256((size_t)r * r * 8);
     L.Dinv = L.X + align256((size_t)r * r * 8);
     L.T = L.Dinv + align256((size_t)nt * kNB * kNB * 8);     // result of the first round, fp32 m x r
-    L.total = L.T + align256((size_t)m * r * 4);
+    L.part = L.T + align256((size_t)m * r * 4);                 // Gram partial sums, kGramMaxSlices x r x r fp64
+    L.total = L.part + align256((size_t)kGramMaxSlices * r * r * 8);
     return L;
 }
 
@@ -474,9 +522,18 @@ static int launch_range(const uint16_t* G, const uint16_t* Z, float* Y, int64_t 
 
 // One round: Q = Y L^-T with L the Cholesky factor of Y^T Y.
 static void launch_cholqr(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info, double* S, double* X,
-                          double* Dinv, hipStream_t st) {
+                          double* Dinv, double* part, hipStream_t st) {
     const int nt = (int)((r + kNB - 1) / kNB);
-    hipLaunchKernelGGL(k_gram, dim3(nt * (nt + 1) / 2), dim3(256), 0, st, Y, S, (int)m, (int)r);
+    const int pairs = nt * (nt + 1) / 2;
+    // about two workgroups per CU, at least 256 rows per slice
+    int slices = (512 + pairs - 1) / pairs;
+    const int by_rows = (int)((m + 255) / 256);
+    slices = slices < by_rows ? slices : by_rows;
+    slices = slices < kGramMaxSlices ? slices : kGramMaxSlices;
+    const int slice_rows = (int)(((m + slices - 1) / slices + kKC - 1) / kKC) * kKC;
+    slices = (int)((m + slice_rows - 1) / slice_rows);
+    hipLaunchKernelGGL(k_gram, dim3(pairs, slices), dim3(256), 0, st, Y, part, (int)m, (int)r, slice_rows);
+    hipLaunchKernelGGL(k_gram_reduce, dim3((unsigned)((r * r + 255) / 256)), dim3(256), 0, st, part, S, (int)r, slices);
     for (int kb = 0; kb < nt; ++kb) {
         hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), 0, st, S, (int)r, kb, Dinv, X, info);
         const int below = nt - kb - 1;
@@ -498,8 +555,9 @@ static int launch_orth(const float* Y, int64_t m, int64_t r, float* Q, int32_t* 
     double* Dinv = reinterpret_cast<double*>(ws + L.Dinv);
     float* T = reinterpret_cast<float*>(ws + L.T);
     if (reset_info) hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, st, info, 0);
-    launch_cholqr(Y, m, r, T, info, S, X, Dinv, st);
-    launch_cholqr(T, m, r, Q, info, S, X, Dinv, st);
+    double* part = reinterpret_cast<double*>(ws + L.part);
+    launch_cholqr(Y, m, r, T, info, S, X, Dinv, part, st);
+    launch_cholqr(T, m, r, Q, info, S, X, Dinv, part, st);
     return check_launch();
 }
 
