@@ -145,44 +145,54 @@ def refresh_bench(args, shapes, mats):
 
     L = qg.lib()
     dev = mats[0].G.device
-    ws = torch.empty((max(L.qg_refresh_workspace_bytes(m, n, r) for m, n, r in shapes),), dtype=torch.uint8, device=dev)
+    groups = {}
+    for s in mats:
+        groups.setdefault((s.m, s.n, s.r), []).append(s)
+    ws = torch.empty((max(L.qg_refresh_workspace_bytes(len(g), m, n, r) for (m, n, r), g in groups.items()),),
+                     dtype=torch.uint8, device=dev)
+    outs = {k: ([torch.empty_like(s.Pq) for s in g], [torch.empty_like(s.Ps) for s in g]) for k, g in groups.items()}
 
     def one_round(read_info=False):
+        """Every matrix of the workload once: one batched call per distinct shape."""
         bad = 0
-        for s in mats:
-            _, _, _, info, _ = qg.subspace_refresh(s.Pq, s.Ps, s.G, s.m, s.n, s.r, 1, workspace=ws)
+        for (m, n, r), g in groups.items():
+            _, _, _, info, _ = qg.subspace_refresh_many([s.Pq for s in g], [s.Ps for s in g], [s.G for s in g], m, n, r,
+                                                        1, workspace=ws, out=outs[(m, n, r)])
             if read_info:
-                bad += int(info.item() != 0)
+                bad += int((info != 0).sum().item())
         return bad
+
+    def timed(f, reps):
+        f()
+        torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
 
     bad = one_round(read_info=True)                     # warm-up, and the only round that reads `info` back
     torch.cuda.synchronize()
     rounds = max(1, min(args.steps, 3))
-    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    e0.record()
-    for _ in range(rounds):
-        one_round()
-    e1.record()
-    torch.cuda.synchronize()
-    wall = (time.perf_counter() - t0) / rounds * 1e3
-    ms = e0.elapsed_time(e1) / rounds
+    ms = timed(one_round, rounds)
+    wall = (time.perf_counter() - t0) / (rounds + 1) * 1e3
     per_shape = {}
-    for (m, n, r) in sorted(set(shapes)):
-        s = next(x for x in mats if (x.m, x.n, x.r) == (m, n, r))
-        qg.subspace_refresh(s.Pq, s.Ps, s.G, m, n, r, 1, workspace=ws)
-        torch.cuda.synchronize()
-        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(5):
-            qg.subspace_refresh(s.Pq, s.Ps, s.G, m, n, r, 1, workspace=ws)
-        b.record(); torch.cuda.synchronize()
-        per_shape[f"{m}x{n} r{r}"] = {"ms": a.elapsed_time(b) / 5, "count": shapes.count((m, n, r))}
+    for (m, n, r), g in groups.items():
+        s = g[0]
+        one = timed(lambda: qg.subspace_refresh(s.Pq, s.Ps, s.G, m, n, r, 1, workspace=ws), 3)
+        many = timed(lambda: qg.subspace_refresh_many([x.Pq for x in g], [x.Ps for x in g], [x.G for x in g], m, n, r, 1,
+                                                      workspace=ws, out=outs[(m, n, r)]), 1)
+        per_shape[f"{m}x{n} r{r}"] = {"count": len(g), "single_call_ms": one, "batched_ms_per_matrix": many / len(g)}
     bf16_flop = sum(4.0 * m * n * r for m, n, r in shapes)                 # R = P^T G and Y = G Z^T
     fp64_flop = sum(2 * (m * r * r + r ** 3 / 3 + r ** 3 / 3 + m * r * r) for m, n, r in shapes)   # two rounds
     out = {"metric": "Q-GaLore subspace refresh ms over all linear weights", "value": ms, "unit": "ms",
            "n_gpus": 1, "rounds": rounds, "higher_is_better": False, "dtype": "bf16 GEMMs + fp64 orthonormalisation",
-           "data": "synthetic", "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "passes": 1},
+           "data": "synthetic", "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "passes": 1,
+                                           "calls": "one qg_subspace_refresh_many per distinct shape"},
+           "workspace_GB": ws.numel() / 1e9,
            "wall_ms": wall, "per_shape": per_shape, "info_nonzero": bad,
            "work": {"bf16_TFLOP": bf16_flop / 1e12, "fp64_TFLOP": fp64_flop / 1e12,
                     "bf16_bound_ms": bf16_flop / PEAK_BF16_TFLOPS / 1e9, "fp64_bound_ms": fp64_flop / PEAK_FP64_TFLOPS / 1e9},

@@ -160,18 +160,32 @@ int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB,
  * completes).  Y and Q may not alias.
  * workspace: qg_orthonormalize_workspace_bytes(m, r) bytes, 16-byte aligned.
  *
- * qg_subspace_refresh: `passes` (1 .. 64) passes as above.  Pq/Ps hold the old projection (unchanged); Pq_new/Ps_new
- * (same sizes, distinct buffers) receive the new one; cos_out is one device float; info as for qg_orthonormalize
- * (first failure over all passes).  workspace: qg_refresh_workspace_bytes(m, n, r) bytes, 16-byte aligned; after
- * the call it starts with R (fp32 [r][n]) of the last pass.
+ * qg_subspace_refresh_many: `passes` (1 .. 64) passes as above on `count` matrices of ONE shape (m, n, r).  descs
+ * is a HOST array; Pq/Ps hold each matrix's old projection (unchanged), Pq_new/Ps_new (same sizes, distinct
+ * buffers) receive the new one.  cos_out and info are device arrays of `count` elements (info as for
+ * qg_orthonormalize, first failure over all passes).  The fp64 stages run batched over the matrices, as many at a
+ * time as the workspace holds: qg_refresh_workspace_bytes(count, m, n, r) bytes let all of them run in one batch,
+ * qg_refresh_workspace_bytes(1, m, n, r) is the minimum; results do not depend on the batch size.  workspace is
+ * 16-byte aligned; after the call it starts with R (fp32 [r][n]) of the last matrix's last pass.
+ * qg_subspace_refresh: the same for one matrix.
  *
- * All three require r % 8 == 0, r <= m, m*r < 2^31 and m*n < 2^32 (QG_ERR_SHAPE otherwise). */
+ * All require r % 8 == 0, r <= m, m*r < 2^31 and m*n < 2^32 (QG_ERR_SHAPE otherwise). */
+typedef struct {
+    const uint8_t*  Pq;      /* old projection, INT4 packed  */
+    const float*    Ps;      /* old projection, block scales */
+    const uint16_t* G;       /* bf16 gradient m x n          */
+    uint8_t*        Pq_new;  /* out */
+    float*          Ps_new;  /* out */
+} qg_refresh_desc;
 int qg_range_apply(const uint16_t* G_bf16, const uint16_t* Z_bf16, int64_t m, int64_t n, int64_t r, float* Y,
                    void* stream);
 size_t qg_orthonormalize_workspace_bytes(int64_t m, int64_t r);
 int qg_orthonormalize(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info,
                       void* workspace, size_t workspace_bytes, void* stream);
-size_t qg_refresh_workspace_bytes(int64_t m, int64_t n, int64_t r);
+size_t qg_refresh_workspace_bytes(int count, int64_t m, int64_t n, int64_t r);
+int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs, int64_t m, int64_t n, int64_t r, int group,
+                             int passes, float* cos_out, int32_t* info,
+                             void* workspace, size_t workspace_bytes, void* stream);
 int qg_subspace_refresh(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
                         int64_t m, int64_t n, int64_t r, int group, int passes,
                         uint8_t* Pq_new, float* Ps_new, float* cos_out, int32_t* info,

@@ -101,6 +101,13 @@ __device__ __forceinline__ void for_each_acc(const f64x4 (&acc)[2][2], int lane,
             for (int v = 0; v < 4; ++v) f(wi * 32 + a * 16 + 4 * v + (lane >> 4), wj * 32 + b * 16 + (lane & 15), acc[a][b][v]);
 }
 
+// A batch of matrices with the same m and r runs through the fp64 kernels in one launch each, matrix b =
+// blockIdx.z; its pieces sit at these element strides from matrix 0's (all zero for a single matrix).  The in and
+// out matrices of a round share the stride Y/Q (both are m x r fp32 arrays of the same batch layout).
+struct BatchStride {
+    int64_t Y, Q, S, X, D, part;
+};
+
 // 1 / sqrt(d) for d > 0 to fp64 accuracy: the hardware estimate and two Newton steps (the correctly rounded sqrt
 // and divide of the library cost an order of magnitude more instructions, on the critical path of every column).
 __device__ __forceinline__ double rsqrt_f64(double d) {
@@ -134,7 +141,10 @@ __global__ __launch_bounds__(256) void k_f32_to_bf16(const float* __restrict__ x
     }
 }
 
-__global__ void k_set_i32(int32_t* p, int32_t v) { *p = v; }
+__global__ void k_set_i32(int32_t* p, int32_t v, int count) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = v;
+}
 
 // ---------------------------------------------------------------------------------------------------------------
 // Y = G Z^T : G m x n and Z r x n, both bf16 row-major (the contraction index n is the fast one in both), Y fp32
@@ -223,7 +233,9 @@ __global__ __launch_bounds__(256) void k_range(const uint16_t* __restrict__ G, c
 constexpr int kGramMaxSlices = 8;
 
 __global__ __launch_bounds__(256) void k_gram(const float* __restrict__ Y, double* __restrict__ part, int m, int r,
-                                              int slice_rows) {
+                                              int slice_rows, BatchStride st) {
+    Y += blockIdx.z * st.Y;
+    part += blockIdx.z * st.part;
     __shared__ double At[kKC * kPitchKS];
     __shared__ double Bt[kKC * kPitchKS];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
@@ -255,7 +267,9 @@ __global__ __launch_bounds__(256) void k_gram(const float* __restrict__ Y, doubl
 }
 
 __global__ __launch_bounds__(256) void k_gram_reduce(const double* __restrict__ part, double* __restrict__ S, int r,
-                                                     int slices) {
+                                                     int slices, BatchStride st) {
+    part += blockIdx.z * st.part;
+    S += blockIdx.z * st.S;
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= (int64_t)r * r) return;
     const int i = (int)(e / r), j = (int)(e % r);
@@ -273,7 +287,11 @@ __global__ __launch_bounds__(256) void k_gram_reduce(const double* __restrict__ 
 // Rows and columns at or past r (r not a multiple of 64) behave like an identity block.
 // ---------------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r, int kb, double* __restrict__ Dinv,
-                                                   double* __restrict__ X, int32_t* __restrict__ info) {
+                                                   double* __restrict__ X, int32_t* __restrict__ info, BatchStride st) {
+    S += blockIdx.z * st.S;
+    Dinv += blockIdx.z * st.D;
+    X += blockIdx.z * st.X;
+    info += blockIdx.z;
     constexpr int P = kNB + 1;
     __shared__ double T[kNB * P];
     __shared__ double dg[kNB], rdg[kNB];
@@ -338,7 +356,10 @@ __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r
     }
 }
 
-__global__ __launch_bounds__(256) void k_chol_panel(double* __restrict__ S, int r, int kb, const double* __restrict__ Dinv) {
+__global__ __launch_bounds__(256) void k_chol_panel(double* __restrict__ S, int r, int kb, const double* __restrict__ Dinv,
+                                                    BatchStride st) {
+    S += blockIdx.z * st.S;
+    Dinv += blockIdx.z * st.D;
     __shared__ double At[kNB * kPitchKF];
     __shared__ double Bt[kNB * kPitchKF];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
@@ -366,7 +387,8 @@ __global__ __launch_bounds__(256) void k_chol_panel(double* __restrict__ S, int 
     });
 }
 
-__global__ __launch_bounds__(256) void k_chol_update(double* __restrict__ S, int r, int kb) {
+__global__ __launch_bounds__(256) void k_chol_update(double* __restrict__ S, int r, int kb, BatchStride st) {
+    S += blockIdx.z * st.S;
     __shared__ double At[kNB * kPitchKF];
     __shared__ double Bt[kNB * kPitchKF];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
@@ -399,7 +421,10 @@ __global__ __launch_bounds__(256) void k_chol_update(double* __restrict__ S, int
 // X = L^-1, block row ib (all block rows above are complete):  X_ik = -X_ii (sum_{j=k}^{i-1} L_ij X_jk),  k < i
 // ---------------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_trinv_row(const double* __restrict__ S, double* __restrict__ X,
-                                                   const double* __restrict__ Dinv, int r, int ib) {
+                                                   const double* __restrict__ Dinv, int r, int ib, BatchStride st) {
+    S += blockIdx.z * st.S;
+    X += blockIdx.z * st.X;
+    Dinv += blockIdx.z * st.D;
     // phase 1: At (L chunk, k fast) and Bt (X chunk, k slow); phase 2: Tm (the sum) and At (X_ii chunk)
     __shared__ double At[kNB * kPitchKF];
     __shared__ double Bt[kNB * kPitchT];
@@ -447,7 +472,10 @@ __global__ __launch_bounds__(256) void k_trinv_row(const double* __restrict__ S,
 // Q = Y X^T (X lower triangular: column block jb needs the contraction index up to the end of that block only)
 // ---------------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_apply(const float* __restrict__ Y, const double* __restrict__ X,
-                                               float* __restrict__ Q, int m, int r) {
+                                               float* __restrict__ Q, int m, int r, BatchStride st) {
+    Y += blockIdx.z * st.Y;
+    X += blockIdx.z * st.X;
+    Q += blockIdx.z * st.Q;
     __shared__ double At[kNB * kPitchKF];
     __shared__ double Bt[kNB * kPitchKF];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wi = wave >> 1, wj = wave & 1;
@@ -478,32 +506,59 @@ __global__ __launch_bounds__(256) void k_apply(const float* __restrict__ Y, cons
 
 static size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 
+// Number of row slices of the Gram kernel: a function of the shape only (never of the batch size), so that a
+// matrix gets bit-identical results alone and inside a batch.  About two workgroups per CU for a single matrix,
+// at least 256 rows per slice.
+static int gram_slices(int64_t m, int64_t r, int* slice_rows) {
+    const int nt = (int)((r + kNB - 1) / kNB);
+    const int pairs = nt * (nt + 1) / 2;
+    int slices = (512 + pairs - 1) / pairs;
+    const int by_rows = (int)((m + 255) / 256);
+    slices = slices < by_rows ? slices : by_rows;
+    slices = slices < kGramMaxSlices ? slices : kGramMaxSlices;
+    *slice_rows = (int)(((m + slices - 1) / slices + kKC - 1) / kKC) * kKC;
+    return (int)((m + *slice_rows - 1) / *slice_rows);
+}
+
+// Workspace of the orthonormalisation of `batch` matrices of one shape: per matrix S and X (r x r fp64), the
+// inverted diagonal blocks, the result of the first round T (fp32 m x r) and the Gram slices.
 struct OrthLayout {
     size_t S, X, Dinv, T, part, total;
+    BatchStride st;   // element strides between consecutive matrices; st.Y = st.Q = stride of T
 };
-static OrthLayout orth_layout(int64_t m, int64_t r) {
+static OrthLayout orth_layout(int64_t m, int64_t r, int64_t batch) {
     const int64_t nt = (r + kNB - 1) / kNB;
+    int slice_rows;
+    const int slices = gram_slices(m, r, &slice_rows);
+    const size_t bS = align256((size_t)r * r * 8), bD = align256((size_t)nt * kNB * kNB * 8),
+                 bT = align256((size_t)m * r * 4), bP = align256((size_t)slices * r * r * 8);
     OrthLayout L;
     L.S = 0;
-    L.X = L.S + align256((size_t)r * r * 8);
-    L.Dinv = L.X + align256((size_t)r * r * 8);
-    L.T = L.Dinv + align256((size_t)nt * kNB * kNB * 8);     // result of the first round, fp32 m x r
-    L.part = L.T + align256((size_t)m * r * 4);                 // Gram partial sums, kGramMaxSlices x r x r fp64
-    L.total = L.part + align256((size_t)kGramMaxSlices * r * r * 8);
+    L.X = L.S + bS * batch;
+    L.Dinv = L.X + bS * batch;
+    L.T = L.Dinv + bD * batch;
+    L.part = L.T + bT * batch;
+    L.total = L.part + bP * batch;
+    L.st = BatchStride{(int64_t)(bT / 4), (int64_t)(bT / 4), (int64_t)(bS / 8), (int64_t)(bS / 8), (int64_t)(bD / 8),
+                       (int64_t)(bP / 8)};
     return L;
 }
 
+// Workspace of the refresh of `batch` matrices of one shape: R and Z of the matrix in flight (shared: the
+// per-matrix launches are ordered on the stream), per matrix Y (which also receives Q), then the orthonormalisation's
+// and the cosine check's.
 struct RefreshLayout {
-    size_t R, Z, Y, Q, orth, cos, total;
+    size_t R, Z, Y, orth, cos, total;
+    size_t y_bytes;   // per matrix
 };
-static RefreshLayout refresh_layout(int64_t m, int64_t n, int64_t r) {
+static RefreshLayout refresh_layout(int64_t m, int64_t n, int64_t r, int64_t batch) {
     RefreshLayout L;
+    L.y_bytes = align256((size_t)m * r * 4);
     L.R = 0;
     L.Z = L.R + align256((size_t)r * n * 4);
     L.Y = L.Z + align256((size_t)r * n * 2);
-    L.Q = L.Y + align256((size_t)m * r * 4);
-    L.orth = L.Q + align256((size_t)m * r * 4);
-    L.cos = L.orth + orth_layout(m, r).total;
+    L.orth = L.Y + 2 * L.y_bytes * batch;        // Y and Q of every matrix
+    L.cos = L.orth + orth_layout(m, r, batch).total;
     L.total = L.cos + align256(qg_cossim_workspace_bytes(m, r));
     return L;
 }
@@ -520,44 +575,53 @@ static int launch_range(const uint16_t* G, const uint16_t* Z, float* Y, int64_t 
     return check_launch();
 }
 
-// One round: Q = Y L^-T with L the Cholesky factor of Y^T Y.
-static void launch_cholqr(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info, double* S, double* X,
-                          double* Dinv, double* part, hipStream_t st) {
-    const int nt = (int)((r + kNB - 1) / kNB);
-    const int pairs = nt * (nt + 1) / 2;
-    // about two workgroups per CU, at least 256 rows per slice
-    int slices = (512 + pairs - 1) / pairs;
-    const int by_rows = (int)((m + 255) / 256);
-    slices = slices < by_rows ? slices : by_rows;
-    slices = slices < kGramMaxSlices ? slices : kGramMaxSlices;
-    const int slice_rows = (int)(((m + slices - 1) / slices + kKC - 1) / kKC) * kKC;
-    slices = (int)((m + slice_rows - 1) / slice_rows);
-    hipLaunchKernelGGL(k_gram, dim3(pairs, slices), dim3(256), 0, st, Y, part, (int)m, (int)r, slice_rows);
-    hipLaunchKernelGGL(k_gram_reduce, dim3((unsigned)((r * r + 255) / 256)), dim3(256), 0, st, part, S, (int)r, slices);
-    for (int kb = 0; kb < nt; ++kb) {
-        hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), 0, st, S, (int)r, kb, Dinv, X, info);
-        const int below = nt - kb - 1;
-        if (below > 0) {
-            hipLaunchKernelGGL(k_chol_panel, dim3(below), dim3(256), 0, st, S, (int)r, kb, Dinv);
-            hipLaunchKernelGGL(k_chol_update, dim3(below * (below + 1) / 2), dim3(256), 0, st, S, (int)r, kb);
-        }
-    }
-    for (int ib = 1; ib < nt; ++ib)
-        hipLaunchKernelGGL(k_trinv_row, dim3(ib), dim3(256), 0, st, S, X, Dinv, (int)r, ib);
-    hipLaunchKernelGGL(k_apply, dim3((unsigned)((m + kNB - 1) / kNB), nt), dim3(256), 0, st, Y, X, Q, (int)m, (int)r);
-}
-
-static int launch_orth(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info, bool reset_info, char* ws,
-                       hipStream_t st) {
-    const OrthLayout L = orth_layout(m, r);
+// One round on `batch` matrices (matrix b at Y + b * sYin, result at Q + b * sQout): Q = Y L^-T with L the Cholesky
+// factor of Y^T Y.
+static void launch_cholqr(const float* Y, int64_t sYin, float* Q, int64_t sQout, int64_t m, int64_t r, int batch,
+                          int32_t* info, char* ws, const OrthLayout& L, hipStream_t stream) {
     double* S = reinterpret_cast<double*>(ws + L.S);
     double* X = reinterpret_cast<double*>(ws + L.X);
     double* Dinv = reinterpret_cast<double*>(ws + L.Dinv);
-    float* T = reinterpret_cast<float*>(ws + L.T);
-    if (reset_info) hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, st, info, 0);
     double* part = reinterpret_cast<double*>(ws + L.part);
-    launch_cholqr(Y, m, r, T, info, S, X, Dinv, part, st);
-    launch_cholqr(T, m, r, Q, info, S, X, Dinv, part, st);
+    BatchStride st = L.st;
+    st.Y = sYin;
+    st.Q = sQout;
+    const int nt = (int)((r + kNB - 1) / kNB);
+    const int pairs = nt * (nt + 1) / 2;
+    int slice_rows;
+    const int slices = gram_slices(m, r, &slice_rows);
+    const dim3 blk(256);
+    const unsigned B = (unsigned)batch;
+    hipLaunchKernelGGL(k_gram, dim3(pairs, slices, B), blk, 0, stream, Y, part, (int)m, (int)r, slice_rows, st);
+    hipLaunchKernelGGL(k_gram_reduce, dim3((unsigned)((r * r + 255) / 256), 1, B), blk, 0, stream, part, S, (int)r, slices, st);
+    for (int kb = 0; kb < nt; ++kb) {
+        hipLaunchKernelGGL(k_chol_diag, dim3(1, 1, B), blk, 0, stream, S, (int)r, kb, Dinv, X, info, st);
+        const int below = nt - kb - 1;
+        if (below > 0) {
+            hipLaunchKernelGGL(k_chol_panel, dim3(below, 1, B), blk, 0, stream, S, (int)r, kb, Dinv, st);
+            hipLaunchKernelGGL(k_chol_update, dim3(below * (below + 1) / 2, 1, B), blk, 0, stream, S, (int)r, kb, st);
+        }
+    }
+    for (int ib = 1; ib < nt; ++ib)
+        hipLaunchKernelGGL(k_trinv_row, dim3(ib, 1, B), blk, 0, stream, S, X, Dinv, (int)r, ib, st);
+    hipLaunchKernelGGL(k_apply, dim3((unsigned)((m + kNB - 1) / kNB), nt, B), blk, 0, stream, Y, X, Q, (int)m, (int)r, st);
+}
+
+// Cholesky QR twice: Y -> T -> Q.  info: `batch` consecutive device ints.
+static int launch_orth(const float* Y, int64_t sY, float* Q, int64_t sQ, int64_t m, int64_t r, int batch, int32_t* info,
+                       bool reset_info, char* ws, hipStream_t stream) {
+    const OrthLayout L = orth_layout(m, r, batch);
+    float* T = reinterpret_cast<float*>(ws + L.T);
+    if (reset_info)
+        hipLaunchKernelGGL(k_set_i32, dim3((batch + 255) / 256), dim3(256), 0, stream, info, 0, batch);
+    launch_cholqr(Y, sY, T, L.st.Y, m, r, batch, info, ws, L, stream);
+    launch_cholqr(T, L.st.Y, Q, sQ, m, r, batch, info, ws, L, stream);
+    return check_launch();
+}
+
+static int launch_to_bf16(const float* R, uint16_t* Z, int64_t count, hipStream_t st) {
+    const int64_t quads = count / 4, blocks = (quads + 255) / 256;
+    hipLaunchKernelGGL(k_f32_to_bf16, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, st, R, Z, quads);
     return check_launch();
 }
 
@@ -576,7 +640,7 @@ extern "C" int qg_range_apply(const uint16_t* G_bf16, const uint16_t* Z_bf16, in
 
 extern "C" size_t qg_orthonormalize_workspace_bytes(int64_t m, int64_t r) {
     if (check_mr(m, r) != QG_OK) return 0;
-    return orth_layout(m, r).total;
+    return orth_layout(m, r, 1).total;
 }
 
 extern "C" int qg_orthonormalize(const float* Y, int64_t m, int64_t r, float* Q, int32_t* info, void* workspace,
@@ -585,46 +649,75 @@ extern "C" int qg_orthonormalize(const float* Y, int64_t m, int64_t r, float* Q,
     if (int e = check_mr(m, r)) return e;
     if (!aligned16(Y) || !aligned16(Q) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(info) & 3)) return QG_ERR_ALIGN;
     if (Y == Q) return QG_ERR_SHAPE;
-    if (!workspace || workspace_bytes < orth_layout(m, r).total) return QG_ERR_WORKSPACE;
-    return launch_orth(Y, m, r, Q, info, true, static_cast<char*>(workspace), (hipStream_t)stream);
+    if (!workspace || workspace_bytes < orth_layout(m, r, 1).total) return QG_ERR_WORKSPACE;
+    return launch_orth(Y, 0, Q, 0, m, r, 1, info, true, static_cast<char*>(workspace), (hipStream_t)stream);
 }
 
-extern "C" size_t qg_refresh_workspace_bytes(int64_t m, int64_t n, int64_t r) {
-    if (check_mr(m, r) != QG_OK || n <= 0 || m * n >= (int64_t(1) << 32)) return 0;
-    return refresh_layout(m, n, r).total;
+extern "C" size_t qg_refresh_workspace_bytes(int count, int64_t m, int64_t n, int64_t r) {
+    if (count < 1 || check_mr(m, r) != QG_OK || n <= 0 || m * n >= (int64_t(1) << 32)) return 0;
+    return refresh_layout(m, n, r, count).total;
+}
+
+extern "C" int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs, int64_t m, int64_t n, int64_t r, int group,
+                                        int passes, float* cos_out, int32_t* info, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+    if (!descs || !cos_out || !info) return QG_ERR_NULL;
+    if (count < 1 || passes < 1 || passes > 64) return QG_ERR_SHAPE;
+    if (int e = check_mr(m, r)) return e;
+    if (n <= 0 || m * n >= (int64_t(1) << 32)) return QG_ERR_SHAPE;
+    if (group != kGroup) return QG_ERR_GROUP;
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(cos_out) & 3) || (reinterpret_cast<uintptr_t>(info) & 3))
+        return QG_ERR_ALIGN;
+    for (int i = 0; i < count; ++i) {
+        const qg_refresh_desc& d = descs[i];
+        if (!d.Pq || !d.Ps || !d.G || !d.Pq_new || !d.Ps_new) return QG_ERR_NULL;
+        if (!aligned16(d.Pq) || !aligned16(d.Ps) || !aligned16(d.G) || !aligned16(d.Pq_new) || !aligned16(d.Ps_new))
+            return QG_ERR_ALIGN;
+        if (d.Pq == d.Pq_new || d.Ps == d.Ps_new) return QG_ERR_SHAPE;   // the cosine check needs the old P intact
+    }
+    if (!workspace) return QG_ERR_WORKSPACE;
+    // as many matrices per batch as the workspace holds
+    int batch = count;
+    while (batch > 1 && refresh_layout(m, n, r, batch).total > workspace_bytes) batch = (batch + 1) / 2;
+    const RefreshLayout L = refresh_layout(m, n, r, batch);
+    if (L.total > workspace_bytes) return QG_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    float* R = reinterpret_cast<float*>(ws + L.R);
+    uint16_t* Z = reinterpret_cast<uint16_t*>(ws + L.Z);
+    float* Y = reinterpret_cast<float*>(ws + L.Y);
+    float* Q = reinterpret_cast<float*>(ws + L.Y + L.y_bytes * batch);
+    const int64_t sY = (int64_t)(L.y_bytes / 4);
+    hipStream_t st = (hipStream_t)stream;
+    for (int first = 0; first < count; first += batch) {
+        const int nb = count - first < batch ? count - first : batch;
+        for (int pass = 0; pass < passes; ++pass) {
+            for (int b = 0; b < nb; ++b) {
+                const qg_refresh_desc& d = descs[first + b];
+                const uint8_t* pq = pass == 0 ? d.Pq : d.Pq_new;
+                const float* ps = pass == 0 ? d.Ps : d.Ps_new;
+                if (int e = qg_project(pq, ps, d.G, m, n, r, group, R, nullptr, 0, stream)) return e;
+                if (int e = launch_to_bf16(R, Z, r * n, st)) return e;
+                if (int e = launch_range(d.G, Z, Y + b * sY, m, n, r, st)) return e;
+            }
+            if (int e = launch_orth(Y, sY, Q, sY, m, r, nb, info + first, pass == 0, ws + L.orth, st)) return e;
+            for (int b = 0; b < nb; ++b) {
+                const qg_refresh_desc& d = descs[first + b];
+                if (int e = qg_quant_int4(Q + b * sY, m, r, group, d.Pq_new, d.Ps_new, stream)) return e;
+            }
+        }
+        for (int b = 0; b < nb; ++b) {
+            const qg_refresh_desc& d = descs[first + b];
+            if (int e = qg_subspace_cossim(d.Pq, d.Ps, d.Pq_new, d.Ps_new, m, r, group, cos_out + first + b, ws + L.cos,
+                                           workspace_bytes - L.cos, stream))
+                return e;
+        }
+    }
+    return QG_OK;
 }
 
 extern "C" int qg_subspace_refresh(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int64_t m, int64_t n,
                                    int64_t r, int group, int passes, uint8_t* Pq_new, float* Ps_new, float* cos_out,
                                    int32_t* info, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!Pq || !Ps || !G_bf16 || !Pq_new || !Ps_new || !cos_out || !info) return QG_ERR_NULL;
-    if (int e = check_mr(m, r)) return e;
-    if (n <= 0 || m * n >= (int64_t(1) << 32) || passes < 1 || passes > 64) return QG_ERR_SHAPE;
-    if (group != kGroup) return QG_ERR_GROUP;
-    if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(G_bf16) || !aligned16(Pq_new) || !aligned16(Ps_new) ||
-        !aligned16(workspace) || (reinterpret_cast<uintptr_t>(cos_out) & 3) || (reinterpret_cast<uintptr_t>(info) & 3))
-        return QG_ERR_ALIGN;
-    if (Pq == Pq_new || Ps == Ps_new) return QG_ERR_SHAPE;   // the cosine check needs the old P intact
-    const RefreshLayout L = refresh_layout(m, n, r);
-    if (!workspace || workspace_bytes < L.total) return QG_ERR_WORKSPACE;
-    char* ws = static_cast<char*>(workspace);
-    float* R = reinterpret_cast<float*>(ws + L.R);
-    uint16_t* Z = reinterpret_cast<uint16_t*>(ws + L.Z);
-    float* Y = reinterpret_cast<float*>(ws + L.Y);
-    float* Q = reinterpret_cast<float*>(ws + L.Q);
-    hipStream_t st = (hipStream_t)stream;
-    const uint8_t* pq = Pq;
-    const float* ps = Ps;
-    for (int pass = 0; pass < passes; ++pass) {
-        if (int e = qg_project(pq, ps, G_bf16, m, n, r, group, R, nullptr, 0, stream)) return e;
-        const int64_t quads = r * n / 4;   // r is a multiple of 8
-        const int64_t blocks = (quads + 255) / 256;
-        hipLaunchKernelGGL(k_f32_to_bf16, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, st, R, Z, quads);
-        if (int e = launch_range(G_bf16, Z, Y, m, n, r, st)) return e;
-        if (int e = launch_orth(Y, m, r, Q, info, pass == 0, ws + L.orth, st)) return e;
-        if (int e = qg_quant_int4(Q, m, r, group, Pq_new, Ps_new, stream)) return e;
-        pq = Pq_new;
-        ps = Ps_new;
-    }
-    return qg_subspace_cossim(Pq, Ps, Pq_new, Ps_new, m, r, group, cos_out, ws + L.cos, workspace_bytes - L.cos, stream);
+    const qg_refresh_desc d = {Pq, Ps, G_bf16, Pq_new, Ps_new};
+    return qg_subspace_refresh_many(1, &d, m, n, r, group, passes, cos_out, info, workspace, workspace_bytes, stream);
 }

@@ -25,7 +25,7 @@ EXPORTS = [
     "qg_sr_uniform", "qg_project_many", "qg_lowrank_adam_many", "qg_backproject_update_sr_many",
     "qg_project_adam", "qg_project_adam_many", "qg_diag_clock_probe", "qg_diag_mfma_loop",
     "qg_range_apply", "qg_orthonormalize_workspace_bytes", "qg_orthonormalize", "qg_refresh_workspace_bytes",
-    "qg_subspace_refresh",
+    "qg_subspace_refresh", "qg_subspace_refresh_many",
 ]
 
 
@@ -47,6 +47,11 @@ class MatrixDesc(C.Structure):
     _fields_ = [("m", C.c_int64), ("n", C.c_int64), ("r", C.c_int64),
                 ("Pq", C.c_void_p), ("Ps", C.c_void_p), ("G", C.c_void_p), ("Wq", C.c_void_p), ("Ws", C.c_void_p),
                 ("M", C.c_void_p), ("V", C.c_void_p), ("R", C.c_void_p), ("N", C.c_void_p)]
+
+
+class RefreshDesc(C.Structure):
+    _fields_ = [("Pq", C.c_void_p), ("Ps", C.c_void_p), ("G", C.c_void_p), ("Pq_new", C.c_void_p),
+                ("Ps_new", C.c_void_p)]
 
 
 _lib = None
@@ -96,8 +101,9 @@ def lib() -> C.CDLL:
         L.qg_orthonormalize_workspace_bytes.argtypes = [i64, i64]
         L.qg_orthonormalize.argtypes = [vp, i64, i64, vp, vp, vp, sz, vp]
         L.qg_refresh_workspace_bytes.restype = sz
-        L.qg_refresh_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qg_refresh_workspace_bytes.argtypes = [i32, i64, i64, i64]
         L.qg_subspace_refresh.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.qg_subspace_refresh_many.argtypes = [i32, C.POINTER(RefreshDesc), i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -299,7 +305,7 @@ def orthonormalize(Y: torch.Tensor):
 
 def subspace_refresh(Pq, Ps, G, m: int, n: int, r: int, passes: int = 1, workspace: torch.Tensor | None = None):
     """Returns (Pq_new, Ps_new, cos, info, workspace); cos and info are device tensors of one element."""
-    nbytes = lib().qg_refresh_workspace_bytes(m, n, r)
+    nbytes = lib().qg_refresh_workspace_bytes(1, m, n, r)
     if nbytes == 0:
         raise QGError("libqgalore: shape out of range")
     if workspace is None:
@@ -311,6 +317,31 @@ def subspace_refresh(Pq, Ps, G, m: int, n: int, r: int, passes: int = 1, workspa
                                      GROUP, passes, _ptr(Pq_new), _ptr(Ps_new), _ptr(cos), _ptr(info),
                                      _ptr(workspace), workspace.numel(), _stream()))
     return Pq_new, Ps_new, cos, info, workspace
+
+
+def subspace_refresh_many(Pqs, Pss, Gs, m: int, n: int, r: int, passes: int = 1,
+                          workspace: torch.Tensor | None = None, out=None):
+    """Refresh of several matrices of one shape.  Pqs, Pss, Gs: lists of device tensors.  `out`: optional
+    (list of Pq_new, list of Ps_new) to write into.  Returns (Pq_news, Ps_news, cos[count], info[count], workspace)."""
+    count = len(Gs)
+    if count == 0 or len(Pqs) != count or len(Pss) != count:
+        raise QGError("libqgalore: one Pq and one Ps per gradient expected")
+    if workspace is None:
+        nbytes = lib().qg_refresh_workspace_bytes(count, m, n, r)
+        if nbytes == 0:
+            raise QGError("libqgalore: shape out of range")
+        workspace = torch.empty((nbytes,), dtype=torch.uint8, device=Gs[0].device)
+    if out is None:
+        out = ([torch.empty_like(p) for p in Pqs], [torch.empty_like(p) for p in Pss])
+    descs = (RefreshDesc * count)()
+    for i in range(count):
+        descs[i] = RefreshDesc(_ptr(Pqs[i], (torch.uint8,)), _ptr(Pss[i], (torch.float32,)), _ptr(Gs[i], _BF16),
+                               _ptr(out[0][i], (torch.uint8,)), _ptr(out[1][i], (torch.float32,)))
+    cos = torch.empty((count,), dtype=torch.float32, device=Gs[0].device)
+    info = torch.empty((count,), dtype=torch.int32, device=Gs[0].device)
+    _check(lib().qg_subspace_refresh_many(count, descs, m, n, r, GROUP, passes, _ptr(cos), _ptr(info),
+                                          _ptr(workspace), workspace.numel(), _stream()))
+    return out[0], out[1], cos, info, workspace
 
 
 DIAG_MFMA_WORKGROUPS = 512

@@ -89,9 +89,11 @@ def test_refresh_argument_errors(L):
     assert L.qg_orthonormalize(FAKE, 512, 128, FAKE + 4096, FAKE, FAKE, ob - 1, None) == 5
     assert L.qg_orthonormalize(FAKE, 512, 128, FAKE + 4096, FAKE, None, 0, None) == 5
     assert L.qg_orthonormalize(FAKE, 1 << 22, 1024, FAKE + 4096, FAKE, FAKE, 1 << 40, None) == 2   # m*r >= 2^31
-    rb = L.qg_refresh_workspace_bytes(512, 512, 128)
+    rb = L.qg_refresh_workspace_bytes(1, 512, 512, 128)
     assert rb >= 128 * 512 * 6 + 2 * 512 * 128 * 4 + ob + L.qg_cossim_workspace_bytes(512, 128)
-    assert L.qg_refresh_workspace_bytes(512, 0, 128) == 0
+    assert L.qg_refresh_workspace_bytes(1, 512, 0, 128) == 0 and L.qg_refresh_workspace_bytes(0, 512, 512, 128) == 0
+    rb4 = L.qg_refresh_workspace_bytes(4, 512, 512, 128)
+    assert rb < rb4 < 4 * rb                                                                 # R and Z are shared
     args = (FAKE, FAKE, FAKE, 512, 512, 128, 256, 1, FAKE + 4096, FAKE + 8192, FAKE, FAKE, FAKE, rb, None)
 
     def call(**kw):
@@ -105,6 +107,12 @@ def test_refresh_argument_errors(L):
     assert call(a8=FAKE) == 2                                                                # new P aliases the old
     assert call(a2=FAKE + 2) == 4
     assert call(a13=rb - 1) == 5 and call(a12=None) == 5
+    descs = (qg.RefreshDesc * 2)(qg.RefreshDesc(FAKE, FAKE, FAKE, FAKE + 4096, FAKE + 8192),
+                                 qg.RefreshDesc(FAKE, FAKE, FAKE, FAKE + 4096, None))
+    assert L.qg_subspace_refresh_many(2, descs, 512, 512, 128, 256, 1, FAKE, FAKE, FAKE, rb4, None) == 1
+    assert L.qg_subspace_refresh_many(0, descs, 512, 512, 128, 256, 1, FAKE, FAKE, FAKE, rb4, None) == 2
+    assert L.qg_subspace_refresh_many(1, None, 512, 512, 128, 256, 1, FAKE, FAKE, FAKE, rb4, None) == 1
+    assert L.qg_subspace_refresh_many(1, descs, 512, 512, 128, 256, 1, FAKE, FAKE + 2, FAKE, rb4, None) == 4
 
 
 def test_plan_build_on_host(L):

@@ -170,6 +170,27 @@ def test_subspace_refresh_equals_its_parts_and_the_oracle(m, n, r, passes):
     assert np.array_equal(host(again[0]), pq) and np.array_equal(host(again[1]), ps)
 
 
+@pytest.mark.parametrize("m,n,r,passes", [(512, 512, 128, 1), (333, 264, 144, 2)])
+def test_batched_refresh_equals_the_single_matrix_calls(m, n, r, passes):
+    """Three matrices of one shape through qg_subspace_refresh_many, in one batch and with a workspace that only
+    holds two at a time: bit for bit what qg_subspace_refresh gives for each of them."""
+    ins = [start(m, n, r, seed=s) for s in (0, 1, 2)]
+    Gs = [bits_t(Gb) for Gb, _, _ in ins]
+    Pqs = [dev(Pq) for _, Pq, _ in ins]
+    Pss = [dev(Ps) for _, _, Ps in ins]
+    single = [qg.subspace_refresh(Pqs[i], Pss[i], Gs[i], m, n, r, passes) for i in range(3)]
+    L = qg.lib()
+    for holds in (3, 2):
+        ws = torch.empty((L.qg_refresh_workspace_bytes(holds, m, n, r),), dtype=torch.uint8, device=DEV)
+        pq, ps, cos, info, _ = qg.subspace_refresh_many(Pqs, Pss, Gs, m, n, r, passes, workspace=ws)
+        assert host(info).tolist() == [0, 0, 0]
+        for i in range(3):
+            assert np.array_equal(host(pq[i]), host(single[i][0])) and np.array_equal(host(ps[i]), host(single[i][1]))
+            assert float(host(cos)[i]) == float(host(single[i][2])[0])
+    # the matrices are different problems: the results differ from one another
+    assert not np.array_equal(host(pq[0]), host(pq[1]))
+
+
 def test_refresh_at_llama7b_shapes_by_properties():
     """Full-size matrices of the 7B configuration (r = 1024): sampled entries of Y against fp64 dot products, Q
     orthonormal and spanning Y, the new P capturing more of G than the start."""
