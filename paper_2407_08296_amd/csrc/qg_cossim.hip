@@ -1,6 +1,6 @@
 // Subspace convergence check (Sec. 3.2, Fig. 2): mean over the r columns of the
 // cosine between corresponding columns of two INT4 projection matrices.
-// Two deterministic passes: per-row-chunk partial sums, then a fixed-order finish.
+// Deterministic: per-row-chunk partial sums, then per-column cosines and their mean, all in fixed orders.
 #include "qg_common.h"
 
 namespace qg {
@@ -47,28 +47,49 @@ __global__ __launch_bounds__(256) void k_cossim_partial(const uint8_t* __restric
     }
 }
 
-__global__ __launch_bounds__(256) void k_cossim_finish(const float* __restrict__ partial, int r, int chunks,
-                                                       float* __restrict__ cos_out) {
-    __shared__ float red[256];
-    const int t = threadIdx.x;
-    float acc = 0.f;
-    for (int k = t; k < r; k += 256) {
-        float dot = 0.f, na = 0.f, nb = 0.f;
-        for (int c = 0; c < chunks; ++c) {
+// Columns of one 64-wide group per workgroup: four threads per column add the chunks' partial sums (thread p takes
+// chunks p, p + 4, ...), the four are combined in a fixed order, the column's cosine is formed and the group's 64
+// cosines are added by a fixed tree -> group_sum[blockIdx.x].
+constexpr int kCosGroup = 64;
+
+__global__ __launch_bounds__(256) void k_cossim_columns(const float* __restrict__ partial, int r, int chunks,
+                                                        float* __restrict__ group_sum) {
+    __shared__ float sh[3][4][kCosGroup];
+    __shared__ float cosv[kCosGroup];
+    const int t = threadIdx.x, cl = t & 63, part = t >> 6;
+    const int k = blockIdx.x * kCosGroup + cl;
+    float dot = 0.f, na = 0.f, nb = 0.f;
+    if (k < r) {
+#pragma unroll 4
+        for (int c = part; c < chunks; c += 4) {
             const float* p = partial + (int64_t)c * 3 * r + k;
             dot += p[0];
             na += p[r];
             nb += p[2 * r];
         }
-        acc += dot / fmaxf(sqrtf(na) * sqrtf(nb), 1e-8f);
     }
-    red[t] = acc;
+    sh[0][part][cl] = dot;
+    sh[1][part][cl] = na;
+    sh[2][part][cl] = nb;
     __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (t < s) red[t] += red[t + s];
+    if (part == 0) {
+        float v[3];
+#pragma unroll
+        for (int q = 0; q < 3; ++q) v[q] = ((sh[q][0][cl] + sh[q][1][cl]) + sh[q][2][cl]) + sh[q][3][cl];
+        cosv[cl] = k < r ? v[0] / fmaxf(sqrtf(v[1]) * sqrtf(v[2]), 1e-8f) : 0.f;
+    }
+    __syncthreads();
+    for (int s = kCosGroup / 2; s > 0; s >>= 1) {
+        if (t < s) cosv[t] += cosv[t + s];
         __syncthreads();
     }
-    if (t == 0) cos_out[0] = red[0] / (float)r;
+    if (t == 0) group_sum[blockIdx.x] = cosv[0];
+}
+
+__global__ void k_cossim_mean(const float* __restrict__ group_sum, int groups, int r, float* __restrict__ cos_out) {
+    float acc = 0.f;
+    for (int g = 0; g < groups; ++g) acc += group_sum[g];
+    cos_out[0] = acc / (float)r;
 }
 
 }  // namespace qg
@@ -78,7 +99,8 @@ using namespace qg;
 extern "C" size_t qg_cossim_workspace_bytes(int64_t m, int64_t r) {
     if (m <= 0 || r <= 0) return 0;
     const int64_t chunks = (m + kCosRows - 1) / kCosRows;
-    return (size_t)(chunks * 3 * r * (int64_t)sizeof(float));
+    const int64_t groups = (r + kCosGroup - 1) / kCosGroup;
+    return (size_t)((chunks * 3 * r + groups) * (int64_t)sizeof(float));   // partial sums, then one sum per column group
 }
 
 extern "C" int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB, const float* PsB, int64_t m,
@@ -99,7 +121,11 @@ extern "C" int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const ui
     hipLaunchKernelGGL(k_cossim_partial, dim3(blocks), dim3(256), 0, (hipStream_t)stream, PqA, PsA, PqB, PsB, (int)m,
                        (int)r, wpr, lanes_rows, chunks, (float*)workspace);
     if (int e = check_launch()) return e;
-    hipLaunchKernelGGL(k_cossim_finish, dim3(1), dim3(256), 0, (hipStream_t)stream, (const float*)workspace, (int)r,
-                       chunks, cos_out);
+    const int groups = (int)((r + kCosGroup - 1) / kCosGroup);
+    float* group_sum = (float*)workspace + (int64_t)chunks * 3 * r;
+    hipLaunchKernelGGL(k_cossim_columns, dim3(groups), dim3(256), 0, (hipStream_t)stream, (const float*)workspace, (int)r,
+                       chunks, group_sum);
+    hipLaunchKernelGGL(k_cossim_mean, dim3(1), dim3(1), 0, (hipStream_t)stream, (const float*)group_sum, groups, (int)r,
+                       cos_out);
     return check_launch();
 }
