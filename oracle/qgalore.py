@@ -433,3 +433,39 @@ def subspace_refresh(Pq, Ps, G_bits, m: int, n: int, r: int, iters: int = 1):
         Q = orthonormalize(Y)
         Pq, Ps = quant_int4(Q.astype(np.float32))
     return Pq, Ps, Q
+
+
+# --------------------------------------------------------------------------
+# INT8 linear layer (Appendix A: forward and backward of a layer whose weight
+# is kept in INT8; the backward pass produces the gradient G the optimizer
+# step consumes)
+# --------------------------------------------------------------------------
+def dequant_w_bf16(Wq, Ws) -> np.ndarray:
+    """The weight as the layer's GEMMs see it (Appendix A: codes times scales in
+    the activation dtype, zeros = 0): code * scale rounded to fp32, then stored
+    as a bf16 operand - the same reading as for the projection matrix."""
+    return bf16_rne(dequant_int8(Wq, Ws).astype(np.float32).astype(np.float64))
+
+
+def int8_linear_forward(x_bits, Wq, Ws, bias_bits=None) -> np.ndarray:
+    """y = x W^T (+ bias) (Appendix A, forward): x bf16 [tokens][n], W the m x n
+    INT8 weight, y [tokens][m].  Returned unrounded in fp64; the layer stores it
+    in the activation dtype (bf16)."""
+    Wq = np.asarray(Wq)
+    m, n = Wq.shape
+    x = bf16_bits_to_f64(np.asarray(x_bits)).reshape(-1, n)
+    y = x @ dequant_w_bf16(Wq, Ws).T
+    if bias_bits is not None:
+        y = y + bf16_bits_to_f64(np.asarray(bias_bits)).reshape(1, m)
+    return y
+
+
+def int8_linear_backward(dy_bits, x_bits, Wq, Ws):
+    """(grad_input, grad_W) = (dy W, dy^T x) (Appendix A, backward): dy bf16
+    [tokens][m], x bf16 [tokens][n].  Returned unrounded in fp64; both are
+    stored in bf16 (Sec. 3.1: activations and gradients are BFloat16)."""
+    Wq = np.asarray(Wq)
+    m, n = Wq.shape
+    dy = bf16_bits_to_f64(np.asarray(dy_bits)).reshape(-1, m)
+    x = bf16_bits_to_f64(np.asarray(x_bits)).reshape(-1, n)
+    return dy @ dequant_w_bf16(Wq, Ws), dy.T @ x
