@@ -191,6 +191,21 @@ int qg_subspace_refresh(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf
                         uint8_t* Pq_new, float* Ps_new, float* cos_out, int32_t* info,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- INT8 linear layer (Appendix A): the layer whose weight the step updates; its backward pass produces the
+ * gradient G the step consumes.  W is the m x n INT8 weight (codes + block scales as above, zero point 0),
+ * dequantized inside the GEMMs as bf16(fl32(code * scale)); bf16 MFMA, fp32 accumulation, outputs rounded once
+ * to bf16 (activations and gradients are BFloat16, Sec. 3.1).
+ * qg_int8_linear_forward:  y [tokens][m] = x [tokens][n] * W^T (+ bias [m], bf16, nullable).
+ * qg_int8_linear_backward: dx [tokens][n] = dy [tokens][m] * W and G [m][n] = dy^T * x; either output may be NULL
+ *   (then it is not computed, and the inputs only it needs - Wq/Ws for dx, x for G - may be NULL too).
+ * Any tokens, m, n >= 1 with tokens*m, tokens*n and m*n below 2^31; base pointers 16-byte aligned (rows need not
+ * be).  Outputs may not alias inputs. */
+int qg_int8_linear_forward(const uint16_t* x_bf16, const int8_t* Wq, const float* Ws, const uint16_t* bias_bf16,
+                           int64_t tokens, int64_t m, int64_t n, int group, uint16_t* y_bf16, void* stream);
+int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
+                            int64_t tokens, int64_t m, int64_t n, int group,
+                            uint16_t* dx_bf16, uint16_t* G_bf16, void* stream);
+
 /* ---- Adaptive lazy update policy (Sec. 3.2), HOST ONLY (p is a host pointer):
  * streak counts consecutive checks with cos >= threshold; at k in a row the
  * interval doubles and the streak restarts; next_refresh advances by the

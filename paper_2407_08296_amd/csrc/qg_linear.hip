@@ -1,0 +1,217 @@
+// INT8 linear layer (Appendix A): the layer whose weight the optimizer step updates, and whose backward pass
+// produces the gradient G that the step consumes.
+//     forward:   y  = x W^T (+ bias)       x bf16 [tokens][n], W INT8 [m][n] + block scales, y bf16 [tokens][m]
+//     backward:  dx = dy W                 dy bf16 [tokens][m], dx bf16 [tokens][n]
+//                G  = dy^T x               bf16 [m][n]
+// W is dequantized while its tile is staged into LDS (code * scale in fp32, rounded once to bf16: the operand the
+// projection GEMM of the step sees for P); all three products are bf16 MFMA GEMMs with fp32 accumulation and one
+// rounding to bf16 at the store.
+//
+// One kernel template covers the three products.  The contraction index is the fast (contiguous) one of x and W in
+// the forward pass, of dy only in grad_input, of neither in grad_W; an operand whose contraction index is fast is
+// staged as a [128][k] tile and read with 16-byte LDS reads, one whose contraction index is slow as a [k][128] tile
+// read with the transposing LDS reads of the step's kernels.  Rows may start at any element offset (n = 5461 in the
+// LLaMA-1B shapes): chunks of eight elements are fetched with under-aligned wide loads, element by element only
+// where a chunk straddles the edge of the matrix.
+#include "qg_common.h"
+#include "qg_gemm_kernels.h"
+
+namespace qg {
+
+enum : int { kBf16KFast = 0, kBf16KSlow = 1, kInt8KFast = 2, kInt8KSlow = 3 };
+
+constexpr int kLinT = 128;                 // output tile: 128 x 128, 4 waves of 64 x 64
+constexpr int kLinK = 64;                  // contraction depth per step
+constexpr int kLinPF = kLinK + kPadX;      // pitch of a [128][k] tile
+constexpr int kLinPS = kLinT + kPadK;      // pitch of a [k][128] tile
+constexpr int kLinTile = kLinT * kLinPF > kLinK * kLinPS ? kLinT * kLinPF : kLinK * kLinPS;
+constexpr int kLinPer = kLinT * kLinK / 8 / 256;   // 8-element chunks per thread and operand
+
+typedef u32x2 __attribute__((aligned(1))) u32x2_align1;
+
+// 8 consecutive INT8 codes starting at `src`, of which the first `valid` lie inside the matrix.
+__device__ __forceinline__ u32x2 load8_i8_guarded(const int8_t* src, int valid) {
+    if (valid >= 8) return *reinterpret_cast<const u32x2_align1*>(src);
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j < valid) w[j >> 2] |= (uint32_t)(uint8_t)src[j] << (8 * (j & 3));
+    const u32x2 o = {w[0], w[1]};
+    return o;
+}
+
+// bf16(fl32(code * s)) of 8 codes
+__device__ __forceinline__ u32x4 dequant8_i8_bf16(u32x2 c, float s) {
+    float e[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) e[j] = (float)(int)(int8_t)(c[j >> 2] >> (8 * (j & 3))) * s;
+    const u32x4 o = {pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]), pack_bf16x2(e[4], e[5]), pack_bf16x2(e[6], e[7])};
+    return o;
+}
+
+// One GEMM operand: a row-major matrix (bf16, or INT8 codes with one fp32 scale per block of 256 elements of a
+// row) of which the kernel needs the 128 "x" indices starting at x0 (X of them exist) against the contraction
+// index k (K of them).  LAYOUT says which of the two is the column (fast) index of the matrix in memory.
+struct LinOperand {
+    const void* base;
+    const float* scales;   // INT8 only: [rows][sgroups]
+    int64_t ld;            // row length in elements
+    int sgroups;
+};
+
+template <int LAYOUT>
+struct LinStage {
+    static constexpr bool kFast = LAYOUT == kBf16KFast || LAYOUT == kInt8KFast;
+    static constexpr bool kInt8 = LAYOUT == kInt8KFast || LAYOUT == kInt8KSlow;
+    static constexpr int CPR = kFast ? kLinK / 8 : kLinT / 8;   // chunks per tile row
+    u32x4 v[kInt8 ? 1 : kLinPer];
+    u32x2 c[kInt8 ? kLinPer : 1];
+    float s[kInt8 ? kLinPer : 1];
+
+    __device__ __forceinline__ void fetch(const LinOperand& op, int x0, int X, int k0, int K) {
+#pragma unroll
+        for (int q = 0; q < kLinPer; ++q) {
+            const int idx = threadIdx.x + 256 * q;
+            const int tr = idx / CPR, tc = (idx % CPR) * 8;          // row and first column inside the tile
+            const int row = kFast ? x0 + tr : k0 + tr;               // ... and inside the matrix
+            const int col = kFast ? k0 + tc : x0 + tc;
+            const int rows = kFast ? X : K, cols = kFast ? K : X;
+            const int valid = row < rows ? cols - col : 0;
+            const int64_t off = (int64_t)row * op.ld + col;
+            if constexpr (kInt8) {
+                c[q] = load8_i8_guarded(static_cast<const int8_t*>(op.base) + off, valid);
+                s[q] = valid > 0 ? op.scales[(int64_t)row * op.sgroups + (col >> 8)] : 0.f;
+            } else {
+                v[q] = load8_bf16_guarded(static_cast<const uint16_t*>(op.base) + off, valid);
+            }
+        }
+    }
+    __device__ __forceinline__ void commit(uint16_t* tile) const {
+#pragma unroll
+        for (int q = 0; q < kLinPer; ++q) {
+            const int idx = threadIdx.x + 256 * q;
+            const int tr = idx / CPR, tc = (idx % CPR) * 8;
+            u32x4 w;
+            if constexpr (kInt8) w = dequant8_i8_bf16(c[q], s[q]); else w = v[q];
+            *reinterpret_cast<u32x4*>(tile + tr * (kFast ? kLinPF : kLinPS) + tc) = w;
+        }
+    }
+    // MFMA operand fragment of the 32 x indices starting at xb for the 16-deep sub-step kk
+    __device__ static __forceinline__ bf16x8 frag(const uint16_t* tile, int xb, int kk, int lane) {
+        if constexpr (kFast)
+            return *reinterpret_cast<const bf16x8*>(tile + (xb + (lane & 31)) * kLinPF + kk * 16 + 8 * (lane >> 5));
+        else
+            return read_kmajor_frag(tile + kk * 16 * kLinPS + xb + kmajor_lane_offset(kLinPS, lane), kLinPS);
+    }
+};
+
+// C[M][N] (bf16) = sum_k A(i, k) B(k, j) (+ bias[j]); A's x index runs over the rows of C, B's over its columns.
+template <int AL, int BL>
+__global__ __launch_bounds__(256) void k_linear(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
+                                                uint16_t* __restrict__ C, int M, int N, int K, int tiles_n) {
+    __shared__ __attribute__((aligned(16))) uint16_t At[kLinTile];
+    __shared__ __attribute__((aligned(16))) uint16_t Bt[kLinTile];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+    const int i0 = (int)(blockIdx.x / tiles_n) * kLinT, j0 = (int)(blockIdx.x % tiles_n) * kLinT;
+    LinStage<AL> sa;
+    LinStage<BL> sb;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    const int KT = (K + kLinK - 1) / kLinK;
+    sa.fetch(A, i0, M, 0, K);
+    sb.fetch(B, j0, N, 0, K);
+    for (int kt = 0; kt < KT; ++kt) {
+        sa.commit(At);
+        sb.commit(Bt);
+        __syncthreads();
+        if (kt + 1 < KT) {
+            sa.fetch(A, i0, M, (kt + 1) * kLinK, K);
+            sb.fetch(B, j0, N, (kt + 1) * kLinK, K);
+        }
+#pragma unroll
+        for (int kk = 0; kk < kLinK / 16; ++kk) {
+            bf16x8 af[2], bf[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) af[a] = LinStage<AL>::frag(At, wm * 64 + a * 32, kk, lane);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) bf[b] = LinStage<BL>::frag(Bt, wn * 64 + b * 32, kk, lane);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // register v of a 32 x 32 block: row 8 (v / 4) + 4 (l / 32) + v % 4 (A's index), column l % 32 (B's index)
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int col = j0 + wn * 64 + b * 32 + (lane & 31);
+            const float bj = (bias != nullptr && col < N) ? __builtin_bit_cast(float, (uint32_t)bias[col] << 16) : 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const float x = acc[a][b][v];
+                if (row < M && col < N) C[(int64_t)row * N + col] = to_bf16(x + bj);
+            }
+        }
+}
+
+template <int AL, int BL>
+static int launch_linear(const LinOperand& A, const LinOperand& B, const uint16_t* bias, uint16_t* C, int64_t M, int64_t N,
+                         int64_t K, hipStream_t st) {
+    const int64_t tiles_m = (M + kLinT - 1) / kLinT, tiles_n = (N + kLinT - 1) / kLinT;
+    hipLaunchKernelGGL((k_linear<AL, BL>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, st, A, B, bias, C, (int)M,
+                       (int)N, (int)K, (int)tiles_n);
+    return check_launch();
+}
+
+static int check_linear(int64_t tokens, int64_t m, int64_t n, int group) {
+    const int64_t lim = int64_t(1) << 31;
+    if (tokens <= 0 || m <= 0 || n <= 0 || tokens >= lim / m || tokens >= lim / n || m >= lim / n) return QG_ERR_SHAPE;
+    if (group != kGroup) return QG_ERR_GROUP;
+    return QG_OK;
+}
+
+}  // namespace qg
+
+using namespace qg;
+
+extern "C" int qg_int8_linear_forward(const uint16_t* x_bf16, const int8_t* Wq, const float* Ws, const uint16_t* bias_bf16,
+                                      int64_t tokens, int64_t m, int64_t n, int group, uint16_t* y_bf16, void* stream) {
+    if (!x_bf16 || !Wq || !Ws || !y_bf16) return QG_ERR_NULL;
+    if (int e = check_linear(tokens, m, n, group)) return e;
+    if (!aligned16(x_bf16) || !aligned16(Wq) || !aligned16(Ws) || !aligned16(y_bf16) || (bias_bf16 && !aligned16(bias_bf16)))
+        return QG_ERR_ALIGN;
+    const int sg = (int)((n + kGroup - 1) / kGroup);
+    const LinOperand A = {x_bf16, nullptr, n, 0}, B = {Wq, Ws, n, sg};
+    return launch_linear<kBf16KFast, kInt8KFast>(A, B, bias_bf16, y_bf16, tokens, m, n, (hipStream_t)stream);
+}
+
+extern "C" int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
+                                       int64_t tokens, int64_t m, int64_t n, int group, uint16_t* dx_bf16,
+                                       uint16_t* G_bf16, void* stream) {
+    if (!dy_bf16 || (!dx_bf16 && !G_bf16)) return QG_ERR_NULL;
+    if ((dx_bf16 && (!Wq || !Ws)) || (G_bf16 && !x_bf16)) return QG_ERR_NULL;
+    if (int e = check_linear(tokens, m, n, group)) return e;
+    if (!aligned16(dy_bf16) || (x_bf16 && !aligned16(x_bf16)) || (Wq && !aligned16(Wq)) || (Ws && !aligned16(Ws)) ||
+        (dx_bf16 && !aligned16(dx_bf16)) || (G_bf16 && !aligned16(G_bf16)))
+        return QG_ERR_ALIGN;
+    const int sg = (int)((n + kGroup - 1) / kGroup);
+    if (dx_bf16) {   // dx[t][i] = sum_o dy[t][o] W[o][i]
+        const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {Wq, Ws, n, sg};
+        if (int e = launch_linear<kBf16KFast, kInt8KSlow>(A, B, nullptr, dx_bf16, tokens, n, m, (hipStream_t)stream)) return e;
+    }
+    if (G_bf16) {    // G[o][i] = sum_t dy[t][o] x[t][i]
+        const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {x_bf16, nullptr, n, 0};
+        if (int e = launch_linear<kBf16KSlow, kBf16KSlow>(A, B, nullptr, G_bf16, m, n, tokens, (hipStream_t)stream)) return e;
+    }
+    return QG_OK;
+}

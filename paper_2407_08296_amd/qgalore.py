@@ -25,7 +25,7 @@ EXPORTS = [
     "qg_sr_uniform", "qg_project_many", "qg_lowrank_adam_many", "qg_backproject_update_sr_many",
     "qg_project_adam", "qg_project_adam_many", "qg_diag_clock_probe", "qg_diag_mfma_loop",
     "qg_range_apply", "qg_orthonormalize_workspace_bytes", "qg_orthonormalize", "qg_refresh_workspace_bytes",
-    "qg_subspace_refresh", "qg_subspace_refresh_many",
+    "qg_subspace_refresh", "qg_subspace_refresh_many", "qg_int8_linear_forward", "qg_int8_linear_backward",
 ]
 
 
@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
         L.qg_refresh_workspace_bytes.restype = sz
         L.qg_refresh_workspace_bytes.argtypes = [i32, i64, i64, i64]
         L.qg_subspace_refresh.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.qg_int8_linear_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
+        L.qg_int8_linear_backward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp]
         L.qg_subspace_refresh_many.argtypes = [i32, C.POINTER(RefreshDesc), i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
@@ -281,6 +283,26 @@ def project_adam_many(plan: StepPlan, hp: HParams, step: int, write_R: bool = Fa
 def backproject_update_sr_many(plan: StepPlan, hp: HParams, seed: int, step: int) -> None:
     _check(lib().qg_backproject_update_sr_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
                                                C.byref(hp), seed, step, _stream()))
+
+
+# ---------------------------------------------------------------- INT8 linear layer
+def int8_linear_forward(x: torch.Tensor, Wq: torch.Tensor, Ws: torch.Tensor, bias: torch.Tensor | None = None):
+    tokens, n = x.shape
+    m = Wq.shape[0]
+    y = torch.empty((tokens, m), dtype=torch.bfloat16, device=x.device)
+    _check(lib().qg_int8_linear_forward(_ptr(x, _BF16), _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)),
+                                        _ptr(bias, _BF16), tokens, m, n, GROUP, _ptr(y), _stream()))
+    return y
+
+
+def int8_linear_backward(dy: torch.Tensor, x: torch.Tensor | None, Wq: torch.Tensor | None, Ws: torch.Tensor | None,
+                         m: int, n: int, want_dx: bool = True, want_G: bool = True):
+    tokens = dy.shape[0]
+    dx = torch.empty((tokens, n), dtype=torch.bfloat16, device=dy.device) if want_dx else None
+    G = torch.empty((m, n), dtype=torch.bfloat16, device=dy.device) if want_G else None
+    _check(lib().qg_int8_linear_backward(_ptr(dy, _BF16), _ptr(x, _BF16), _ptr(Wq, (torch.int8,)),
+                                         _ptr(Ws, (torch.float32,)), tokens, m, n, GROUP, _ptr(dx), _ptr(G), _stream()))
+    return dx, G
 
 
 # ---------------------------------------------------------------- subspace refresh

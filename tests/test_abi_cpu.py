@@ -115,6 +115,19 @@ def test_refresh_argument_errors(L):
     assert L.qg_subspace_refresh_many(1, descs, 512, 512, 128, 256, 1, FAKE, FAKE + 2, FAKE, rb4, None) == 4
 
 
+def test_int8_linear_argument_errors(L):
+    assert L.qg_int8_linear_forward(None, FAKE, FAKE, None, 16, 512, 512, 256, FAKE, None) == 1
+    assert L.qg_int8_linear_forward(FAKE, FAKE, FAKE, None, 0, 512, 512, 256, FAKE, None) == 2
+    assert L.qg_int8_linear_forward(FAKE, FAKE, FAKE, None, 1 << 20, 1 << 12, 512, 256, FAKE, None) == 2   # tokens*m >= 2^31
+    assert L.qg_int8_linear_forward(FAKE, FAKE, FAKE, None, 16, 512, 512, 128, FAKE, None) == 3
+    assert L.qg_int8_linear_forward(FAKE, FAKE, FAKE, FAKE + 2, 16, 512, 512, 256, FAKE, None) == 4
+    assert L.qg_int8_linear_backward(FAKE, FAKE, FAKE, FAKE, 16, 512, 512, 256, None, None, None) == 1     # no output asked for
+    assert L.qg_int8_linear_backward(FAKE, None, FAKE, FAKE, 16, 512, 512, 256, FAKE, FAKE, None) == 1     # G needs x
+    assert L.qg_int8_linear_backward(FAKE, FAKE, None, FAKE, 16, 512, 512, 256, FAKE, None, None) == 1     # dx needs W
+    assert L.qg_int8_linear_backward(FAKE, FAKE, FAKE, FAKE, 16, 512, 0, 256, FAKE, FAKE, None) == 2
+    assert L.qg_int8_linear_backward(FAKE + 8, FAKE, FAKE, FAKE, 16, 512, 512, 256, FAKE, FAKE, None) == 4
+
+
 def test_plan_build_on_host(L):
     descs = (qg.MatrixDesc * 2)()
     for d, (m, n, r) in zip(descs, [(4096, 4096, 1024), (11008, 4096, 1024)]):
