@@ -133,6 +133,61 @@ def cpu_baseline(config: int, shapes):
             "sample": note, "sample_seconds": total, "host_cpus": len(os.sched_getaffinity(0))}
 
 
+def linear_bench(args, device):
+    """Forward and backward of the INT8 linear layer over the seven weights of one decoder layer."""
+    import torch
+
+    from paper_2407_08296_amd import inputs as I
+    from paper_2407_08296_amd import qgalore as qg
+
+    T = args.tokens
+    layer = [(m, n) for (l, _, m, n, _) in I.config_matrices(args.config) if l == 0]
+    g = torch.Generator(device=device).manual_seed(0)
+    ops = []
+    for (m, n) in layer:
+        Wq, Ws = qg.quant_int8(torch.randn((m, n), generator=g, device=device) * 0.02)
+        x = torch.randn((T, n), generator=g, device=device).to(torch.bfloat16)
+        dy = (torch.randn((T, m), generator=g, device=device) * 0.05).to(torch.bfloat16)
+        ops.append((m, n, Wq, Ws, x, dy))
+
+    def timed(f, reps):
+        f()
+        torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    reps = max(1, args.steps)
+    flop = sum(2.0 * T * m * n for m, n in layer)
+    legs = {
+        "forward": lambda: [qg.int8_linear_forward(x, Wq, Ws) for (m, n, Wq, Ws, x, dy) in ops],
+        "grad_input": lambda: [qg.int8_linear_backward(dy, None, Wq, Ws, m, n, want_G=False) for (m, n, Wq, Ws, x, dy) in ops],
+        "grad_W": lambda: [qg.int8_linear_backward(dy, x, None, None, m, n, want_dx=False) for (m, n, Wq, Ws, x, dy) in ops],
+    }
+    out = {"metric": "INT8 linear layer ms per decoder layer (forward + backward)", "unit": "ms", "n_gpus": 1,
+           "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": WORKLOADS[args.config], "tokens": T, "weights": [f"{m}x{n}" for m, n in layer]},
+           "kernels": {}}
+    total = 0.0
+    for name, f in legs.items():
+        ms = timed(f, reps)
+        total += ms
+        out["kernels"][name] = {"ms": ms, "TFLOP/s": flop / ms / 1e9, "frac_mfma": flop / ms / 1e9 / PEAK_BF16_TFLOPS}
+    out["value"] = total
+    out["mfma_bound_ms"] = 3 * flop / PEAK_BF16_TFLOPS / 1e9
+    # the vendor GEMM (torch.mm -> hipBLASLt) on the same shapes with a bf16 weight, no dequantization: for scale
+    Wb = [(x, (torch.randn((m, n), generator=g, device=device) * 0.02).to(torch.bfloat16), dy) for (m, n, _, _, x, dy) in ops]
+    out["vendor_bf16_gemm_ms"] = {
+        "forward": timed(lambda: [torch.mm(x, W.t()) for (x, W, dy) in Wb], reps),
+        "grad_input": timed(lambda: [torch.mm(dy, W) for (x, W, dy) in Wb], reps),
+        "grad_W": timed(lambda: [torch.mm(dy.t(), x) for (x, W, dy) in Wb], reps)}
+    return out
+
+
 PEAK_FP64_TFLOPS = 78.6      # MI355X fp64 matrix (and vector) peak, published
 
 
@@ -239,6 +294,10 @@ def main():
     ap.add_argument("--refresh", action="store_true",
                     help="time the subspace refresh (qg_subspace_refresh, one pass) over every matrix of the workload "
                          "instead of the optimizer step, print its own JSON line and exit")
+    ap.add_argument("--linear", action="store_true",
+                    help="time the INT8 linear layer (forward, grad_input, grad_W) over the seven weights of one decoder "
+                         "layer of the workload at --tokens tokens, print its own JSON line and exit")
+    ap.add_argument("--tokens", type=int, default=4096, help="tokens per micro-batch for --linear (16 sequences of 256)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -312,6 +371,10 @@ def main():
                          "mfma_bound_us": flops / PEAK_BF16_TFLOPS / 1e6, "hbm_bound_project_us": b_proj / PEAK_HBM_GBS / 1e3,
                          "hbm_bound_backproject_us": b_bp / PEAK_HBM_GBS / 1e3})
         print(json.dumps({"rsweep": {"m": m, "n": n, "rows": rows}}))
+        return
+
+    if args.linear:
+        print(json.dumps(linear_bench(args, device)))
         return
 
     shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(args.config)]

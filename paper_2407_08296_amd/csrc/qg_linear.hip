@@ -26,6 +26,7 @@ constexpr int kLinPF = kLinK + kPadX;      // pitch of a [128][k] tile
 constexpr int kLinPS = kLinT + kPadK;      // pitch of a [k][128] tile
 constexpr int kLinTile = kLinT * kLinPF > kLinK * kLinPS ? kLinT * kLinPF : kLinK * kLinPS;
 constexpr int kLinPer = kLinT * kLinK / 8 / 256;   // 8-element chunks per thread and operand
+constexpr int kLinStrip = 8;               // row tiles per strip of the tile numbering
 
 typedef u32x2 __attribute__((aligned(1))) u32x2_align1;
 
@@ -108,11 +109,17 @@ struct LinStage {
 // C[M][N] (bf16) = sum_k A(i, k) B(k, j) (+ bias[j]); A's x index runs over the rows of C, B's over its columns.
 template <int AL, int BL>
 __global__ __launch_bounds__(256) void k_linear(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
-                                                uint16_t* __restrict__ C, int M, int N, int K, int tiles_n) {
+                                                uint16_t* __restrict__ C, int M, int N, int K, int tiles_m, int tiles_n) {
     __shared__ __attribute__((aligned(16))) uint16_t At[kLinTile];
     __shared__ __attribute__((aligned(16))) uint16_t Bt[kLinTile];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
-    const int i0 = (int)(blockIdx.x / tiles_n) * kLinT, j0 = (int)(blockIdx.x % tiles_n) * kLinT;
+    // Each XCD (own L2) takes a contiguous range of tiles, and tiles are numbered in strips eight row tiles tall,
+    // column tile by column tile: the tiles in flight on an XCD share eight A panels and a few B panels.
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= (uint32_t)(tiles_m * tiles_n)) return;
+    const int strip = (int)(tile / (uint32_t)(kLinStrip * tiles_n)), in_strip = (int)(tile % (uint32_t)(kLinStrip * tiles_n));
+    const int strip_rows = min(kLinStrip, tiles_m - strip * kLinStrip);
+    const int i0 = (strip * kLinStrip + in_strip % strip_rows) * kLinT, j0 = (in_strip / strip_rows) * kLinT;
     LinStage<AL> sa;
     LinStage<BL> sb;
     f32x16 acc[2][2];
@@ -133,6 +140,7 @@ __global__ __launch_bounds__(256) void k_linear(LinOperand A, LinOperand B, cons
             sa.fetch(A, i0, M, (kt + 1) * kLinK, K);
             sb.fetch(B, j0, N, (kt + 1) * kLinK, K);
         }
+        __builtin_amdgcn_s_setprio(kMfmaPrio);     // the wave in its MFMA phase goes first (several workgroups per CU)
 #pragma unroll
         for (int kk = 0; kk < kLinK / 16; ++kk) {
             bf16x8 af[2], bf[2];
@@ -146,6 +154,7 @@ __global__ __launch_bounds__(256) void k_linear(LinOperand A, LinOperand B, cons
                 for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
         __syncthreads();
     }
     // register v of a 32 x 32 block: row 8 (v / 4) + 4 (l / 32) + v % 4 (A's index), column l % 32 (B's index)
@@ -168,8 +177,9 @@ template <int AL, int BL>
 static int launch_linear(const LinOperand& A, const LinOperand& B, const uint16_t* bias, uint16_t* C, int64_t M, int64_t N,
                          int64_t K, hipStream_t st) {
     const int64_t tiles_m = (M + kLinT - 1) / kLinT, tiles_n = (N + kLinT - 1) / kLinT;
-    hipLaunchKernelGGL((k_linear<AL, BL>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, st, A, B, bias, C, (int)M,
-                       (int)N, (int)K, (int)tiles_n);
+    const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);   // a multiple of the 8 XCDs
+    hipLaunchKernelGGL((k_linear<AL, BL>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M, (int)N, (int)K,
+                       (int)tiles_m, (int)tiles_n);
     return check_launch();
 }
 
