@@ -9,7 +9,7 @@
 //
 // One kernel template covers the three products.  The contraction index is the fast (contiguous) one of x and W in
 // the forward pass, of dy only in grad_input, of neither in grad_W; an operand whose contraction index is fast is
-// staged as a [128][k] tile and read with 16-byte LDS reads, one whose contraction index is slow as a [k][128] tile
+// staged as an [x][k] tile and read with 16-byte LDS reads, one whose contraction index is slow as a [k][x] tile
 // read with the transposing LDS reads of the step's kernels.  Rows may start at any element offset (n = 5461 in the
 // LLaMA-1B shapes): chunks of eight elements are fetched with under-aligned wide loads, element by element only
 // where a chunk straddles the edge of the matrix.
@@ -20,39 +20,38 @@ namespace qg {
 
 enum : int { kBf16KFast = 0, kBf16KSlow = 1, kInt8KFast = 2, kInt8KSlow = 3 };
 
-constexpr int kLinT = 128;                 // output tile: 128 x 128, 4 waves of 64 x 64
-constexpr int kLinK = 64;                  // contraction depth per step
-constexpr int kLinPF = kLinK + kPadX;      // pitch of a [128][k] tile
-constexpr int kLinPS = kLinT + kPadK;      // pitch of a [k][128] tile
-constexpr int kLinTile = kLinT * kLinPF > kLinK * kLinPS ? kLinT * kLinPF : kLinK * kLinPS;
-constexpr int kLinPer = kLinT * kLinK / 8 / 256;   // 8-element chunks per thread and operand
+constexpr int kLinTM = 128;                // output tile: 128 (A's index) x 256 (B's index), 4 waves of 64 x 128
+constexpr int kLinTN = 256;
+constexpr int kLinK = 32;                  // contraction depth per step
+constexpr int kLinPF = kLinK + kPadX;      // pitch of an [x][k] tile
 constexpr int kLinStrip = 8;               // row tiles per strip of the tile numbering
 
-typedef u32x2 __attribute__((aligned(1))) u32x2_align1;
-
-// 8 consecutive INT8 codes starting at `src`, of which the first `valid` lie inside the matrix.
-__device__ __forceinline__ u32x2 load8_i8_guarded(const int8_t* src, int valid) {
-    if (valid >= 8) return *reinterpret_cast<const u32x2_align1*>(src);
-    uint32_t w[2] = {0u, 0u};
+// 16 consecutive INT8 codes starting at `src`, of which the first `valid` lie inside the matrix.
+__device__ __forceinline__ u32x4 load16_i8_guarded(const int8_t* src, int valid) {
+    if (valid >= 16) return *reinterpret_cast<const u32x4_align1*>(src);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < 16; ++j)
         if (j < valid) w[j >> 2] |= (uint32_t)(uint8_t)src[j] << (8 * (j & 3));
-    const u32x2 o = {w[0], w[1]};
+    const u32x4 o = {w[0], w[1], w[2], w[3]};
     return o;
 }
 
-// bf16(fl32(code * s)) of 8 codes
-__device__ __forceinline__ u32x4 dequant8_i8_bf16(u32x2 c, float s) {
+// bf16(fl32(code * s)) of the 8 codes in two words
+__device__ __forceinline__ u32x4 dequant8_i8_bf16(uint32_t c0, uint32_t c1, float s) {
     float e[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) e[j] = (float)(int)(int8_t)(c[j >> 2] >> (8 * (j & 3))) * s;
+    for (int j = 0; j < 4; ++j) {
+        e[j] = (float)(int)(int8_t)(c0 >> (8 * j)) * s;
+        e[4 + j] = (float)(int)(int8_t)(c1 >> (8 * j)) * s;
+    }
     const u32x4 o = {pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]), pack_bf16x2(e[4], e[5]), pack_bf16x2(e[6], e[7])};
     return o;
 }
 
 // One GEMM operand: a row-major matrix (bf16, or INT8 codes with one fp32 scale per block of 256 elements of a
-// row) of which the kernel needs the 128 "x" indices starting at x0 (X of them exist) against the contraction
-// index k (K of them).  LAYOUT says which of the two is the column (fast) index of the matrix in memory.
+// row) of which a workgroup needs XT "x" indices starting at x0 (X of them exist) against the contraction index k
+// (K of them).  LAYOUT says which of the two is the column (fast) index of the matrix in memory.
 struct LinOperand {
     const void* base;
     const float* scales;   // INT8 only: [rows][sgroups]
@@ -60,115 +59,140 @@ struct LinOperand {
     int sgroups;
 };
 
-template <int LAYOUT>
+// Staging of one operand tile: global -> registers (fetch) -> LDS (commit; INT8 is dequantized here).  EXACT: the
+// tile lies inside the matrix, K is a whole number of steps and rows are 16-byte aligned - no checks.
+template <int LAYOUT, int XT, bool EXACT>
 struct LinStage {
     static constexpr bool kFast = LAYOUT == kBf16KFast || LAYOUT == kInt8KFast;
     static constexpr bool kInt8 = LAYOUT == kInt8KFast || LAYOUT == kInt8KSlow;
-    static constexpr int CPR = kFast ? kLinK / 8 : kLinT / 8;   // chunks per tile row
-    u32x4 v[kInt8 ? 1 : kLinPer];
-    u32x2 c[kInt8 ? kLinPer : 1];
-    float s[kInt8 ? kLinPer : 1];
+    static constexpr int CH = kInt8 ? 16 : 8;                   // elements per 16-byte chunk (one block scale each)
+    static constexpr int CPR = (kFast ? kLinK : XT) / CH;       // chunks per tile row
+    static constexpr int PITCH = kFast ? kLinPF : XT + kPadK;   // LDS pitch: [x][k] or [k][x]
+    static constexpr int ELEMS = (kFast ? XT : kLinK) * PITCH;
+    static constexpr int PER = XT * kLinK / CH / 256;           // chunks per thread
+    u32x4 v[PER];
+    float s[kInt8 ? PER : 1];
 
     __device__ __forceinline__ void fetch(const LinOperand& op, int x0, int X, int k0, int K) {
 #pragma unroll
-        for (int q = 0; q < kLinPer; ++q) {
+        for (int q = 0; q < PER; ++q) {
             const int idx = threadIdx.x + 256 * q;
-            const int tr = idx / CPR, tc = (idx % CPR) * 8;          // row and first column inside the tile
+            const int tr = idx / CPR, tc = (idx % CPR) * CH;         // row and first column inside the tile
             const int row = kFast ? x0 + tr : k0 + tr;               // ... and inside the matrix
             const int col = kFast ? k0 + tc : x0 + tc;
             const int rows = kFast ? X : K, cols = kFast ? K : X;
-            const int valid = row < rows ? cols - col : 0;
+            const int valid = EXACT ? CH : (row < rows ? cols - col : 0);
             const int64_t off = (int64_t)row * op.ld + col;
             if constexpr (kInt8) {
-                c[q] = load8_i8_guarded(static_cast<const int8_t*>(op.base) + off, valid);
+                const int8_t* src = static_cast<const int8_t*>(op.base) + off;
+                if constexpr (EXACT) v[q] = *reinterpret_cast<const u32x4*>(src); else v[q] = load16_i8_guarded(src, valid);
                 s[q] = valid > 0 ? op.scales[(int64_t)row * op.sgroups + (col >> 8)] : 0.f;
             } else {
-                v[q] = load8_bf16_guarded(static_cast<const uint16_t*>(op.base) + off, valid);
+                const uint16_t* src = static_cast<const uint16_t*>(op.base) + off;
+                if constexpr (EXACT) v[q] = *reinterpret_cast<const u32x4*>(src); else v[q] = load8_bf16_guarded(src, valid);
             }
         }
     }
     __device__ __forceinline__ void commit(uint16_t* tile) const {
 #pragma unroll
-        for (int q = 0; q < kLinPer; ++q) {
+        for (int q = 0; q < PER; ++q) {
             const int idx = threadIdx.x + 256 * q;
-            const int tr = idx / CPR, tc = (idx % CPR) * 8;
-            u32x4 w;
-            if constexpr (kInt8) w = dequant8_i8_bf16(c[q], s[q]); else w = v[q];
-            *reinterpret_cast<u32x4*>(tile + tr * (kFast ? kLinPF : kLinPS) + tc) = w;
+            uint16_t* dst = tile + (idx / CPR) * PITCH + (idx % CPR) * CH;
+            if constexpr (kInt8) {
+                *reinterpret_cast<u32x4*>(dst) = dequant8_i8_bf16(v[q][0], v[q][1], s[q]);
+                *reinterpret_cast<u32x4*>(dst + 8) = dequant8_i8_bf16(v[q][2], v[q][3], s[q]);
+            } else {
+                *reinterpret_cast<u32x4*>(dst) = v[q];
+            }
         }
     }
     // MFMA operand fragment of the 32 x indices starting at xb for the 16-deep sub-step kk
     __device__ static __forceinline__ bf16x8 frag(const uint16_t* tile, int xb, int kk, int lane) {
         if constexpr (kFast)
-            return *reinterpret_cast<const bf16x8*>(tile + (xb + (lane & 31)) * kLinPF + kk * 16 + 8 * (lane >> 5));
+            return *reinterpret_cast<const bf16x8*>(tile + (xb + (lane & 31)) * PITCH + kk * 16 + 8 * (lane >> 5));
         else
-            return read_kmajor_frag(tile + kk * 16 * kLinPS + xb + kmajor_lane_offset(kLinPS, lane), kLinPS);
+            return read_kmajor_frag(tile + kk * 16 * PITCH + xb + kmajor_lane_offset(PITCH, lane), PITCH);
     }
 };
 
 // C[M][N] (bf16) = sum_k A(i, k) B(k, j) (+ bias[j]); A's x index runs over the rows of C, B's over its columns.
-template <int AL, int BL>
-__global__ __launch_bounds__(256) void k_linear(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
-                                                uint16_t* __restrict__ C, int M, int N, int K, int tiles_m, int tiles_n) {
-    __shared__ __attribute__((aligned(16))) uint16_t At[kLinTile];
-    __shared__ __attribute__((aligned(16))) uint16_t Bt[kLinTile];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+// Two LDS stages: while the MFMAs of step kt read stage kt & 1, the operands of step kt + 1 (fetched into registers
+// before those MFMAs) are written to the other stage; one barrier per step.
+template <int AL, int BL, bool EXACT>
+__global__ __launch_bounds__(256, 2) void k_linear(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
+                                                   uint16_t* __restrict__ C, int M, int N, int K, int tiles_m,
+                                                   int tiles_n) {
+    using SA = LinStage<AL, kLinTM, EXACT>;
+    using SB = LinStage<BL, kLinTN, EXACT>;
+    __shared__ __attribute__((aligned(16))) uint16_t At[2][SA::ELEMS];
+    __shared__ __attribute__((aligned(16))) uint16_t Bt[2][SB::ELEMS];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
     // Each XCD (own L2) takes a contiguous range of tiles, and tiles are numbered in strips eight row tiles tall,
     // column tile by column tile: the tiles in flight on an XCD share eight A panels and a few B panels.
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= (uint32_t)(tiles_m * tiles_n)) return;
     const int strip = (int)(tile / (uint32_t)(kLinStrip * tiles_n)), in_strip = (int)(tile % (uint32_t)(kLinStrip * tiles_n));
     const int strip_rows = min(kLinStrip, tiles_m - strip * kLinStrip);
-    const int i0 = (strip * kLinStrip + in_strip % strip_rows) * kLinT, j0 = (in_strip / strip_rows) * kLinT;
-    LinStage<AL> sa;
-    LinStage<BL> sb;
-    f32x16 acc[2][2];
+    const int i0 = (strip * kLinStrip + in_strip % strip_rows) * kLinTM, j0 = (in_strip / strip_rows) * kLinTN;
+    SA sa;
+    SB sb;
+    constexpr int MB = 2, NB = 4;              // 32 x 32 blocks of the wave's 64 x 128
+    f32x16 acc[MB][NB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MB; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
     const int KT = (K + kLinK - 1) / kLinK;
     sa.fetch(A, i0, M, 0, K);
     sb.fetch(B, j0, N, 0, K);
+    sa.commit(At[0]);
+    sb.commit(Bt[0]);
+    __syncthreads();
     for (int kt = 0; kt < KT; ++kt) {
-        sa.commit(At);
-        sb.commit(Bt);
-        __syncthreads();
-        if (kt + 1 < KT) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < KT;
+        if (more) {
             sa.fetch(A, i0, M, (kt + 1) * kLinK, K);
             sb.fetch(B, j0, N, (kt + 1) * kLinK, K);
         }
-        __builtin_amdgcn_s_setprio(kMfmaPrio);     // the wave in its MFMA phase goes first (several workgroups per CU)
+        __builtin_amdgcn_s_setprio(kMfmaPrio);     // the wave in its MFMA phase goes first (two workgroups per CU)
 #pragma unroll
         for (int kk = 0; kk < kLinK / 16; ++kk) {
-            bf16x8 af[2], bf[2];
+            bf16x8 af[MB], bf[NB];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) af[a] = LinStage<AL>::frag(At, wm * 64 + a * 32, kk, lane);
+            for (int a = 0; a < MB; ++a) af[a] = SA::frag(At[cur], wm * 64 + a * 32, kk, lane);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) bf[b] = LinStage<BL>::frag(Bt, wn * 64 + b * 32, kk, lane);
+            for (int b = 0; b < NB; ++b) bf[b] = SB::frag(Bt[cur], wn * 128 + b * 32, kk, lane);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < MB; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
+                for (int b = 0; b < NB; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);     // fragments of one sub-step at a time
         }
         __builtin_amdgcn_s_setprio(0);
+        if (more) {
+            sa.commit(At[cur ^ 1]);
+            sb.commit(Bt[cur ^ 1]);
+        }
         __syncthreads();
     }
     // register v of a 32 x 32 block: row 8 (v / 4) + 4 (l / 32) + v % 4 (A's index), column l % 32 (B's index)
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MB; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int col = j0 + wn * 64 + b * 32 + (lane & 31);
-            const float bj = (bias != nullptr && col < N) ? __builtin_bit_cast(float, (uint32_t)bias[col] << 16) : 0.f;
+        for (int b = 0; b < NB; ++b) {
+            const int col = j0 + wn * 128 + b * 32 + (lane & 31);
+            const bool col_ok = EXACT || col < N;
+            const float bj = (bias != nullptr && col_ok) ? __builtin_bit_cast(float, (uint32_t)bias[col] << 16) : 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 const float x = acc[a][b][v];
-                if (row < M && col < N) C[(int64_t)row * N + col] = to_bf16(x + bj);
+                if (EXACT || (row < M && col_ok)) C[(int64_t)row * N + col] = to_bf16(x + bj);
             }
         }
 }
@@ -176,10 +200,16 @@ __global__ __launch_bounds__(256) void k_linear(LinOperand A, LinOperand B, cons
 template <int AL, int BL>
 static int launch_linear(const LinOperand& A, const LinOperand& B, const uint16_t* bias, uint16_t* C, int64_t M, int64_t N,
                          int64_t K, hipStream_t st) {
-    const int64_t tiles_m = (M + kLinT - 1) / kLinT, tiles_n = (N + kLinT - 1) / kLinT;
+    const int64_t tiles_m = (M + kLinTM - 1) / kLinTM, tiles_n = (N + kLinTN - 1) / kLinTN;
     const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);   // a multiple of the 8 XCDs
-    hipLaunchKernelGGL((k_linear<AL, BL>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M, (int)N, (int)K,
-                       (int)tiles_m, (int)tiles_n);
+    // no checks at all when every tile and every step is whole and rows start 16-byte aligned
+    const bool exact = M % kLinTM == 0 && N % kLinTN == 0 && K % kLinK == 0 && A.ld % 8 == 0 && B.ld % 16 == 0;
+    if (exact)
+        hipLaunchKernelGGL((k_linear<AL, BL, true>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M, (int)N, (int)K,
+                           (int)tiles_m, (int)tiles_n);
+    else
+        hipLaunchKernelGGL((k_linear<AL, BL, false>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M, (int)N, (int)K,
+                           (int)tiles_m, (int)tiles_n);
     return check_launch();
 }
 
