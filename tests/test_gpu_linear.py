@@ -17,7 +17,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 # (tokens, m, n): whole tiles; ragged everything; odd n (unaligned rows); odd m; one token; LLaMA-130M FFN shape
-CASES = [(256, 512, 512), (130, 333, 264), (77, 200, 521), (64, 519, 256), (1, 768, 768), (300, 2048, 768)]
+CASES = [(256, 512, 512), (130, 333, 264), (77, 200, 521), (64, 519, 256), (1, 768, 768), (300, 2048, 768), (1, 1, 1),
+         (3, 5, 7)]
 
 
 def dev(a):

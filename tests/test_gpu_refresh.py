@@ -23,7 +23,8 @@ from paper_2407_08296_amd import qgalore as qg
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
-SHAPES = [(512, 512, 128), (333, 264, 144), (200, 521, 48), (1040, 1048, 272), (2048, 768, 256)]
+# whole tiles; ragged in every dimension; odd n; r not a multiple of 64 above 256; a 130M shape; the smallest legal r
+SHAPES = [(512, 512, 128), (333, 264, 144), (200, 521, 48), (1040, 1048, 272), (2048, 768, 256), (24, 40, 8)]
 
 
 def dev(a):
