@@ -7,211 +7,11 @@
 // projection GEMM of the step sees for P); all three products are bf16 MFMA GEMMs with fp32 accumulation and one
 // rounding to bf16 at the store.
 //
-// One kernel template covers the three products.  The contraction index is the fast (contiguous) one of x and W in
-// the forward pass, of dy only in grad_input, of neither in grad_W; an operand whose contraction index is fast is
-// staged as an [x][k] tile and read with 16-byte LDS reads, one whose contraction index is slow as a [k][x] tile
-// read with the transposing LDS reads of the step's kernels.  Rows may start at any element offset (n = 5461 in the
-// LLaMA-1B shapes): chunks of eight elements are fetched with under-aligned wide loads, element by element only
-// where a chunk straddles the edge of the matrix.
-#include "qg_common.h"
-#include "qg_gemm_kernels.h"
+// The three products are instances of the tile GEMM of qg_tile_gemm.h: the contraction index is the fast one of x and
+// W in the forward pass, of dy only in grad_input, of neither in grad_W.
+#include "qg_tile_gemm.h"
 
 namespace qg {
-
-enum : int { kBf16KFast = 0, kBf16KSlow = 1, kInt8KFast = 2, kInt8KSlow = 3 };
-
-constexpr int kLinTM = 128;                // output tile: 128 (A's index) x 256 (B's index), 4 waves of 64 x 128
-constexpr int kLinTN = 256;
-constexpr int kLinK = 32;                  // contraction depth per step
-constexpr int kLinPF = kLinK + kPadX;      // pitch of an [x][k] tile
-constexpr int kLinStrip = 8;               // row tiles per strip of the tile numbering
-
-// 16 consecutive INT8 codes starting at `src`, of which the first `valid` lie inside the matrix.
-__device__ __forceinline__ u32x4 load16_i8_guarded(const int8_t* src, int valid) {
-    if (valid >= 16) return *reinterpret_cast<const u32x4_align1*>(src);
-    uint32_t w[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int j = 0; j < 16; ++j)
-        if (j < valid) w[j >> 2] |= (uint32_t)(uint8_t)src[j] << (8 * (j & 3));
-    const u32x4 o = {w[0], w[1], w[2], w[3]};
-    return o;
-}
-
-// bf16(fl32(code * s)) of the 8 codes in two words
-__device__ __forceinline__ u32x4 dequant8_i8_bf16(uint32_t c0, uint32_t c1, float s) {
-    float e[8];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        e[j] = (float)(int)(int8_t)(c0 >> (8 * j)) * s;
-        e[4 + j] = (float)(int)(int8_t)(c1 >> (8 * j)) * s;
-    }
-    const u32x4 o = {pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]), pack_bf16x2(e[4], e[5]), pack_bf16x2(e[6], e[7])};
-    return o;
-}
-
-// One GEMM operand: a row-major matrix (bf16, or INT8 codes with one fp32 scale per block of 256 elements of a
-// row) of which a workgroup needs XT "x" indices starting at x0 (X of them exist) against the contraction index k
-// (K of them).  LAYOUT says which of the two is the column (fast) index of the matrix in memory.
-struct LinOperand {
-    const void* base;
-    const float* scales;   // INT8 only: [rows][sgroups]
-    int64_t ld;            // row length in elements
-    int sgroups;
-};
-
-// Staging of one operand tile: global -> registers (fetch) -> LDS (commit; INT8 is dequantized here).  EXACT: the
-// tile lies inside the matrix, K is a whole number of steps and rows are 16-byte aligned - no checks.
-template <int LAYOUT, int XT, bool EXACT>
-struct LinStage {
-    static constexpr bool kFast = LAYOUT == kBf16KFast || LAYOUT == kInt8KFast;
-    static constexpr bool kInt8 = LAYOUT == kInt8KFast || LAYOUT == kInt8KSlow;
-    static constexpr int CH = kInt8 ? 16 : 8;                   // elements per 16-byte chunk (one block scale each)
-    static constexpr int CPR = (kFast ? kLinK : XT) / CH;       // chunks per tile row
-    static constexpr int PITCH = kFast ? kLinPF : XT + kPadK;   // LDS pitch: [x][k] or [k][x]
-    static constexpr int ELEMS = (kFast ? XT : kLinK) * PITCH;
-    static constexpr int PER = XT * kLinK / CH / 256;           // chunks per thread
-    u32x4 v[PER];
-    float s[kInt8 ? PER : 1];
-
-    __device__ __forceinline__ void fetch(const LinOperand& op, int x0, int X, int k0, int K) {
-#pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int idx = threadIdx.x + 256 * q;
-            const int tr = idx / CPR, tc = (idx % CPR) * CH;         // row and first column inside the tile
-            const int row = kFast ? x0 + tr : k0 + tr;               // ... and inside the matrix
-            const int col = kFast ? k0 + tc : x0 + tc;
-            const int rows = kFast ? X : K, cols = kFast ? K : X;
-            const int valid = EXACT ? CH : (row < rows ? cols - col : 0);
-            const int64_t off = (int64_t)row * op.ld + col;
-            if constexpr (kInt8) {
-                const int8_t* src = static_cast<const int8_t*>(op.base) + off;
-                if constexpr (EXACT) v[q] = *reinterpret_cast<const u32x4*>(src); else v[q] = load16_i8_guarded(src, valid);
-                s[q] = valid > 0 ? op.scales[(int64_t)row * op.sgroups + (col >> 8)] : 0.f;
-            } else {
-                const uint16_t* src = static_cast<const uint16_t*>(op.base) + off;
-                if constexpr (EXACT) v[q] = *reinterpret_cast<const u32x4*>(src); else v[q] = load8_bf16_guarded(src, valid);
-            }
-        }
-    }
-    __device__ __forceinline__ void commit(uint16_t* tile) const {
-#pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int idx = threadIdx.x + 256 * q;
-            uint16_t* dst = tile + (idx / CPR) * PITCH + (idx % CPR) * CH;
-            if constexpr (kInt8) {
-                *reinterpret_cast<u32x4*>(dst) = dequant8_i8_bf16(v[q][0], v[q][1], s[q]);
-                *reinterpret_cast<u32x4*>(dst + 8) = dequant8_i8_bf16(v[q][2], v[q][3], s[q]);
-            } else {
-                *reinterpret_cast<u32x4*>(dst) = v[q];
-            }
-        }
-    }
-    // MFMA operand fragment of the 32 x indices starting at xb for the 16-deep sub-step kk
-    __device__ static __forceinline__ bf16x8 frag(const uint16_t* tile, int xb, int kk, int lane) {
-        if constexpr (kFast)
-            return *reinterpret_cast<const bf16x8*>(tile + (xb + (lane & 31)) * PITCH + kk * 16 + 8 * (lane >> 5));
-        else
-            return read_kmajor_frag(tile + kk * 16 * PITCH + xb + kmajor_lane_offset(PITCH, lane), PITCH);
-    }
-};
-
-// C[M][N] (bf16) = sum_k A(i, k) B(k, j) (+ bias[j]); A's x index runs over the rows of C, B's over its columns.
-// Two LDS stages: while the MFMAs of step kt read stage kt & 1, the operands of step kt + 1 (fetched into registers
-// before those MFMAs) are written to the other stage; one barrier per step.
-template <int AL, int BL, bool EXACT>
-__global__ __launch_bounds__(256, 2) void k_linear(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
-                                                   uint16_t* __restrict__ C, int M, int N, int K, int tiles_m,
-                                                   int tiles_n) {
-    using SA = LinStage<AL, kLinTM, EXACT>;
-    using SB = LinStage<BL, kLinTN, EXACT>;
-    __shared__ __attribute__((aligned(16))) uint16_t At[2][SA::ELEMS];
-    __shared__ __attribute__((aligned(16))) uint16_t Bt[2][SB::ELEMS];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
-    // Each XCD (own L2) takes a contiguous range of tiles, and tiles are numbered in strips eight row tiles tall,
-    // column tile by column tile: the tiles in flight on an XCD share eight A panels and a few B panels.
-    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
-    if (tile >= (uint32_t)(tiles_m * tiles_n)) return;
-    const int strip = (int)(tile / (uint32_t)(kLinStrip * tiles_n)), in_strip = (int)(tile % (uint32_t)(kLinStrip * tiles_n));
-    const int strip_rows = min(kLinStrip, tiles_m - strip * kLinStrip);
-    const int i0 = (strip * kLinStrip + in_strip % strip_rows) * kLinTM, j0 = (in_strip / strip_rows) * kLinTN;
-    SA sa;
-    SB sb;
-    constexpr int MB = 2, NB = 4;              // 32 x 32 blocks of the wave's 64 x 128
-    f32x16 acc[MB][NB];
-#pragma unroll
-    for (int a = 0; a < MB; ++a)
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-    const int KT = (K + kLinK - 1) / kLinK;
-    sa.fetch(A, i0, M, 0, K);
-    sb.fetch(B, j0, N, 0, K);
-    sa.commit(At[0]);
-    sb.commit(Bt[0]);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            sa.fetch(A, i0, M, (kt + 1) * kLinK, K);
-            sb.fetch(B, j0, N, (kt + 1) * kLinK, K);
-        }
-        __builtin_amdgcn_s_setprio(kMfmaPrio);     // the wave in its MFMA phase goes first (two workgroups per CU)
-#pragma unroll
-        for (int kk = 0; kk < kLinK / 16; ++kk) {
-            bf16x8 af[MB], bf[NB];
-#pragma unroll
-            for (int a = 0; a < MB; ++a) af[a] = SA::frag(At[cur], wm * 64 + a * 32, kk, lane);
-#pragma unroll
-            for (int b = 0; b < NB; ++b) bf[b] = SB::frag(Bt[cur], wn * 128 + b * 32, kk, lane);
-#pragma unroll
-            for (int a = 0; a < MB; ++a)
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);     // fragments of one sub-step at a time
-        }
-        __builtin_amdgcn_s_setprio(0);
-        if (more) {
-            sa.commit(At[cur ^ 1]);
-            sb.commit(Bt[cur ^ 1]);
-        }
-        __syncthreads();
-    }
-    // register v of a 32 x 32 block: row 8 (v / 4) + 4 (l / 32) + v % 4 (A's index), column l % 32 (B's index)
-#pragma unroll
-    for (int a = 0; a < MB; ++a)
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int col = j0 + wn * 128 + b * 32 + (lane & 31);
-            const bool col_ok = EXACT || col < N;
-            const float bj = (bias != nullptr && col_ok) ? __builtin_bit_cast(float, (uint32_t)bias[col] << 16) : 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                const float x = acc[a][b][v];
-                if (EXACT || (row < M && col_ok)) C[(int64_t)row * N + col] = to_bf16(x + bj);
-            }
-        }
-}
-
-template <int AL, int BL>
-static int launch_linear(const LinOperand& A, const LinOperand& B, const uint16_t* bias, uint16_t* C, int64_t M, int64_t N,
-                         int64_t K, hipStream_t st) {
-    const int64_t tiles_m = (M + kLinTM - 1) / kLinTM, tiles_n = (N + kLinTN - 1) / kLinTN;
-    const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);   // a multiple of the 8 XCDs
-    // no checks at all when every tile and every step is whole and rows start 16-byte aligned
-    const bool exact = M % kLinTM == 0 && N % kLinTN == 0 && K % kLinK == 0 && A.ld % 8 == 0 && B.ld % 16 == 0;
-    if (exact)
-        hipLaunchKernelGGL((k_linear<AL, BL, true>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M, (int)N, (int)K,
-                           (int)tiles_m, (int)tiles_n);
-    else
-        hipLaunchKernelGGL((k_linear<AL, BL, false>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M, (int)N, (int)K,
-                           (int)tiles_m, (int)tiles_n);
-    return check_launch();
-}
 
 static int check_linear(int64_t tokens, int64_t m, int64_t n, int group) {
     const int64_t lim = int64_t(1) << 31;
@@ -232,7 +32,7 @@ extern "C" int qg_int8_linear_forward(const uint16_t* x_bf16, const int8_t* Wq, 
         return QG_ERR_ALIGN;
     const int sg = (int)((n + kGroup - 1) / kGroup);
     const LinOperand A = {x_bf16, nullptr, n, 0}, B = {Wq, Ws, n, sg};
-    return launch_linear<kBf16KFast, kInt8KFast>(A, B, bias_bf16, y_bf16, tokens, m, n, (hipStream_t)stream);
+    return launch_tile_gemm<kBf16KFast, kInt8KFast, uint16_t>(A, B, bias_bf16, y_bf16, tokens, m, n, (hipStream_t)stream);
 }
 
 extern "C" int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
@@ -247,11 +47,11 @@ extern "C" int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* 
     const int sg = (int)((n + kGroup - 1) / kGroup);
     if (dx_bf16) {   // dx[t][i] = sum_o dy[t][o] W[o][i]
         const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {Wq, Ws, n, sg};
-        if (int e = launch_linear<kBf16KFast, kInt8KSlow>(A, B, nullptr, dx_bf16, tokens, n, m, (hipStream_t)stream)) return e;
+        if (int e = launch_tile_gemm<kBf16KFast, kInt8KSlow, uint16_t>(A, B, nullptr, dx_bf16, tokens, n, m, (hipStream_t)stream)) return e;
     }
     if (G_bf16) {    // G[o][i] = sum_t dy[t][o] x[t][i]
         const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {x_bf16, nullptr, n, 0};
-        if (int e = launch_linear<kBf16KSlow, kBf16KSlow>(A, B, nullptr, G_bf16, m, n, tokens, (hipStream_t)stream)) return e;
+        if (int e = launch_tile_gemm<kBf16KSlow, kBf16KSlow, uint16_t>(A, B, nullptr, G_bf16, m, n, tokens, (hipStream_t)stream)) return e;
     }
     return QG_OK;
 }

@@ -3,7 +3,7 @@
 // projection replaces the SVD:
 //     R = dequant(P)^T G  (the projection kernel of the optimizer step)      bf16 MFMA
 //     Z = bf16(R)
-//     Y = G Z^T           (m x r)                                            bf16 MFMA, fp32 accumulation
+//     Y = G Z^T           (m x r)                                            bf16 MFMA, fp32 accumulation (qg_tile_gemm.h)
 //     Q = Y T^-1          with Y = Q T, T upper triangular, diag(T) > 0      fp64 MFMA (Cholesky QR)
 //     P <- quant_int4(Q)  (Sec. 3.3)
 // followed by the cosine check of Sec. 3.2 between the old and the new P.
@@ -15,8 +15,7 @@
 // the Gram-Schmidt factor, because multiplying Y from the right by a triangular matrix with a positive diagonal
 // does not change that factor.  A pivot that is not positive (cond(Y) beyond ~1e8, or Y rank deficient) is reported
 // through `info` and replaced by 1 so that every kernel still runs to completion.
-#include "qg_common.h"
-#include "qg_gemm_kernels.h"
+#include "qg_tile_gemm.h"
 
 namespace qg {
 
@@ -144,85 +143,6 @@ __global__ __launch_bounds__(256) void k_f32_to_bf16(const float* __restrict__ x
 __global__ void k_set_i32(int32_t* p, int32_t v, int count) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i < count) p[i] = v;
-}
-
-// ---------------------------------------------------------------------------------------------------------------
-// Y = G Z^T : G m x n and Z r x n, both bf16 row-major (the contraction index n is the fast one in both), Y fp32
-// m x r.  128 x 128 tile per workgroup, 4 waves of 64 x 64, v_mfma_f32_32x32x16_bf16; operands go through
-// registers into [row][k] LDS tiles one 64-deep K step ahead of the MFMAs.
-// ---------------------------------------------------------------------------------------------------------------
-constexpr int kRgT = 128, kRgK = 64, kRgPitch = kRgK + kPadX;
-
-__global__ __launch_bounds__(256) void k_range(const uint16_t* __restrict__ G, const uint16_t* __restrict__ Z,
-                                               float* __restrict__ Y, int m, int n, int r, int tiles_r) {
-    __shared__ __attribute__((aligned(16))) uint16_t Gs[kRgT * kRgPitch];
-    __shared__ __attribute__((aligned(16))) uint16_t Zs[kRgT * kRgPitch];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = (int)(blockIdx.x / tiles_r) * kRgT, r0 = (int)(blockIdx.x % tiles_r) * kRgT;
-    constexpr int PER = kRgT * (kRgK / 8) / 256;   // 16-byte chunks per thread and operand
-    u32x4 gv[PER], zv[PER];
-    auto fetch = [&](int k0) {
-#pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int idx = t + 256 * q;
-            const int row = idx / (kRgK / 8), c = k0 + (idx % (kRgK / 8)) * 8;
-            gv[q] = load8_bf16_guarded(G + (int64_t)(m0 + row) * n + c, m0 + row < m ? n - c : 0);
-            zv[q] = load8_bf16_guarded(Z + (int64_t)(r0 + row) * n + c, r0 + row < r ? n - c : 0);
-        }
-    };
-    auto commit = [&]() {
-#pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int idx = t + 256 * q;
-            const int row = idx / (kRgK / 8), c = (idx % (kRgK / 8)) * 8;
-            *reinterpret_cast<u32x4*>(Gs + row * kRgPitch + c) = gv[q];
-            *reinterpret_cast<u32x4*>(Zs + row * kRgPitch + c) = zv[q];
-        }
-    };
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-    // lane l supplies row l % 32 of its 32-row block and the 8 contraction elements starting at 8 * (l / 32)
-    const uint16_t* gl = Gs + (wm * 64 + (lane & 31)) * kRgPitch + 8 * (lane >> 5);
-    const uint16_t* zl = Zs + (wn * 64 + (lane & 31)) * kRgPitch + 8 * (lane >> 5);
-    const int KT = (n + kRgK - 1) / kRgK;
-    fetch(0);
-    for (int kt = 0; kt < KT; ++kt) {
-        commit();
-        __syncthreads();
-        if (kt + 1 < KT) fetch((kt + 1) * kRgK);
-#pragma unroll
-        for (int kk = 0; kk < kRgK / 16; ++kk) {
-            bf16x8 gf[2], zf[2];
-#pragma unroll
-            for (int a = 0; a < 2; ++a) gf[a] = *reinterpret_cast<const bf16x8*>(gl + a * 32 * kRgPitch + kk * 16);
-#pragma unroll
-            for (int b = 0; b < 2; ++b) zf[b] = *reinterpret_cast<const bf16x8*>(zl + b * 32 * kRgPitch + kk * 16);
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[a], zf[b], acc[a][b], 0, 0, 0);
-        }
-        __syncthreads();
-    }
-    // register v of a 32 x 32 block: row 8 (v / 4) + 4 (l / 32) + v % 4 (G's index), column l % 32 (Z's index)
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int col = r0 + wn * 64 + b * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (row < m && col < r) Y[(int64_t)row * r + col] = acc[a][b][v];
-            }
-        }
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -568,11 +488,10 @@ static int check_mr(int64_t m, int64_t r) {
     return QG_OK;
 }
 
+// Y = G Z^T: G m x n and Z r x n, both bf16 with the contraction index n as their fast index; Y fp32 m x r.
 static int launch_range(const uint16_t* G, const uint16_t* Z, float* Y, int64_t m, int64_t n, int64_t r, hipStream_t st) {
-    const int64_t tiles_m = (m + kRgT - 1) / kRgT, tiles_r = (r + kRgT - 1) / kRgT;
-    hipLaunchKernelGGL(k_range, dim3((unsigned)(tiles_m * tiles_r)), dim3(256), 0, st, G, Z, Y, (int)m, (int)n, (int)r,
-                       (int)tiles_r);
-    return check_launch();
+    const LinOperand A = {G, nullptr, n, 0}, B = {Z, nullptr, n, 0};
+    return launch_tile_gemm<kBf16KFast, kBf16KFast, float>(A, B, nullptr, Y, m, r, n, st);
 }
 
 // One round on `batch` matrices (matrix b at Y + b * sYin, result at Q + b * sQout): Q = Y L^-T with L the Cholesky
