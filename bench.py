@@ -180,6 +180,25 @@ def linear_bench(args, device):
     out["value"] = total
     out["mfma_bound_ms"] = 3 * flop / PEAK_BF16_TFLOPS / 1e9
     # the vendor GEMM (torch.mm -> hipBLASLt) on the same shapes with a bf16 weight, no dequantization: for scale
+    if not args.no_cpu_baseline:                # the oracle as it stands on one small layer, next to the library on the same
+        import numpy as np
+
+        from oracle import qgalore as Q
+        tk, mk, nk = 256, 768, 768
+        Wq_h, Ws_h = Q.quant_int8(I.weight_f32(mk, nk))
+        rs = np.random.default_rng(0)
+        xb = Q.f64_to_bf16_bits(rs.standard_normal((tk, nk)))
+        dyb = Q.f64_to_bf16_bits(rs.standard_normal((tk, mk)) * 0.05)
+        t0 = time.perf_counter()
+        Q.int8_linear_forward(xb, Wq_h, Ws_h)
+        Q.int8_linear_backward(dyb, xb, Wq_h, Ws_h)
+        t_or = time.perf_counter() - t0
+        xd = torch.from_numpy(xb.view(np.int16).reshape(tk, nk)).to(device)
+        dyd = torch.from_numpy(dyb.view(np.int16).reshape(tk, mk)).to(device)
+        Wqd, Wsd = torch.from_numpy(Wq_h).to(device), torch.from_numpy(Ws_h).to(device)
+        t_gpu = timed(lambda: (qg.int8_linear_forward(xd, Wqd, Wsd), qg.int8_linear_backward(dyd, xd, Wqd, Wsd, mk, nk)), 10)
+        out["cpu_baseline"] = {"kind": "oracle", "sample": "forward + backward of one 768x768 weight at 256 tokens",
+                               "oracle_ms": t_or * 1e3, "gpu_ms_same_sample": t_gpu, "host_cpus": len(os.sched_getaffinity(0))}
     Wb = [(x, (torch.randn((m, n), generator=g, device=device) * 0.02).to(torch.bfloat16), dy) for (m, n, _, _, x, dy) in ops]
     out["vendor_bf16_gemm_ms"] = {
         "forward": timed(lambda: [torch.mm(x, W.t()) for (x, W, dy) in Wb], reps),

@@ -222,6 +222,11 @@ def test_refresh_at_llama7b_shapes_by_properties():
         assert float((Q64 @ T - Y64).abs().max()) <= 1e-6 * float(Y64.abs().max())
         Pq1, Ps1, cos, info, _ = qg.subspace_refresh(Pq, Ps, G, m, n, r, 1)
         assert int(host(info)[0]) == 0 and 0.0 < float(host(cos)[0]) < 1.0
+        # the batched call, as bench.py --refresh issues it, gives the same bits for every copy
+        pqs, pss, cosb, infob, _ = qg.subspace_refresh_many([Pq] * 3, [Ps] * 3, [G] * 3, m, n, r, 1)
+        assert host(infob).tolist() == [0, 0, 0]
+        for i in range(3):
+            assert torch.equal(pqs[i], Pq1) and torch.equal(pss[i], Ps1) and float(cosb[i]) == float(cos[0])
         e0 = float(qg.project(Pq, Ps, G, m, n, r).norm()) ** 2
         e1 = float(qg.project(Pq1, Ps1, G, m, n, r).norm()) ** 2
         assert e1 > 1.5 * e0
