@@ -155,9 +155,10 @@ int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB,
  * qg_orthonormalize: Q (fp32 [m][r]) = the orthonormal factor of Y = Q T with T upper triangular and a positive
  * diagonal (Gram-Schmidt on the columns of Y in order), computed in fp64 as Q = Y L^-T from the Cholesky factor
  * of Y^T Y, twice in a row (the second round removes the cond(Y)^2 loss of orthogonality of the first; accurate to
- * fp32 rounding for cond(Y) up to about 1e7).  *info (device int32) receives 0, or 1 + the index of the first
- * column whose pivot was not positive (Y numerically rank deficient: Q is then meaningless, but every kernel still
- * completes).  Y and Q may not alias.
+ * fp32 rounding of what Householder QR gives for cond(Y) up to several 1e8; a shift of 2^-46 trace(Y^T Y) on the
+ * Gram diagonal keeps the pivots positive).  *info (device int32) receives 0, or 1 + the index of the first column
+ * found numerically dependent on its predecessors (Y rank deficient: that column of Q and the later ones are then
+ * meaningless, but every kernel still completes).  Y and Q may not alias.
  * workspace: qg_orthonormalize_workspace_bytes(m, r) bytes, 16-byte aligned.
  *
  * qg_subspace_refresh_many: `passes` (1 .. 64) passes as above on `count` matrices of ONE shape (m, n, r).  descs

@@ -13,8 +13,10 @@
 // |Q^T Q - I| ~ 1e-16 * cond(Y)^2, which for the low-rank-plus-noise gradients this is made for (cond(Y) up to 1e7)
 // is far from orthonormal; the second round starts from a matrix with cond ~ 1 and lands within fp32 rounding of
 // the Gram-Schmidt factor, because multiplying Y from the right by a triangular matrix with a positive diagonal
-// does not change that factor.  A pivot that is not positive (cond(Y) beyond ~1e8, or Y rank deficient) is reported
-// through `info` and replaced by 1 so that every kernel still runs to completion.
+// does not change that factor.  Each Gram matrix gets a shift of 2^-46 of its trace on the diagonal, which keeps
+// the first round's pivots positive for cond(Y) well beyond 1e8 at no cost in the result.  A column that is
+// numerically dependent on its predecessors (a last-round pivot no larger than the shift) is reported through
+// `info`; every kernel runs to completion whatever the data.
 #include "qg_tile_gemm.h"
 
 namespace qg {
@@ -104,7 +106,7 @@ __device__ __forceinline__ void for_each_acc(const f64x4 (&acc)[2][2], int lane,
 // blockIdx.z; its pieces sit at these element strides from matrix 0's (all zero for a single matrix).  The in and
 // out matrices of a round share the stride Y/Q (both are m x r fp32 arrays of the same batch layout).
 struct BatchStride {
-    int64_t Y, Q, S, X, D, part;
+    int64_t Y, Q, S, X, D, part, shift;
 };
 
 // 1 / sqrt(d) for d > 0 to fp64 accuracy: the hardware estimate and two Newton steps (the correctly rounded sqrt
@@ -199,15 +201,43 @@ __global__ __launch_bounds__(256) void k_gram_reduce(const double* __restrict__ 
     S[e] = sum;
 }
 
+// S += sigma I with sigma = 2^-46 trace(S) (at least 128 units of fp64 roundoff of the largest eigenvalue): keeps
+// the pivots of a Gram matrix with cond(Y) beyond ~1e8 positive.  The shift changes L, not the factor Q in exact
+// arithmetic (Y X^T for any triangular X with a positive diagonal has the same Gram-Schmidt factor); the second
+// round, on a matrix with a far smaller condition number, removes what it costs in orthogonality.  sigma is kept
+// for the pivot check of k_chol_diag.
+__global__ __launch_bounds__(256) void k_gram_shift(double* __restrict__ S, int r, double* __restrict__ shift, BatchStride st) {
+    __shared__ double red[256];
+    S += blockIdx.z * st.S;
+    shift += blockIdx.z * st.shift;
+    const int t = threadIdx.x;
+    double acc = 0.0;
+    for (int i = t; i < r; i += 256) acc += S[(int64_t)i * r + i];
+    red[t] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (t < w) red[t] += red[t + w];
+        __syncthreads();
+    }
+    const double sigma = red[0] > 0.0 ? 0x1p-46 * red[0] : 0.0;
+    for (int i = t; i < r; i += 256) S[(int64_t)i * r + i] += sigma;
+    if (t == 0) shift[0] = sigma;
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // Blocked Cholesky S = L L^T in place (lower triangle), right-looking, one block column per step kb:
 //   k_chol_diag:   L_kk from the diagonal block, and X_kk = L_kk^-1 (to Dinv[kb] and to the diagonal block of X)
 //   k_chol_panel:  L_ik = S_ik X_kk^T for the blocks below
 //   k_chol_update: S_ij -= L_ik L_jk^T for i >= j > kb
-// Rows and columns at or past r (r not a multiple of 64) behave like an identity block.
+// Rows and columns at or past r (r not a multiple of 64) behave like an identity block.  A pivot that is not positive
+// is replaced by 1 so that the factorization runs to completion whatever the data.
 // ---------------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r, int kb, double* __restrict__ Dinv,
-                                                   double* __restrict__ X, int32_t* __restrict__ info, BatchStride st) {
+                                                   double* __restrict__ X, int32_t* __restrict__ info,
+                                                   const double* __restrict__ shift, double flag_factor, BatchStride st) {
+    // a pivot at or below flag_factor * sigma is reported: 0 in the first round (only pivots that are not positive),
+    // 16 in the last, where a pivot that small is the shift alone, i.e. a column that is numerically dependent
+    const double floor_d = flag_factor * shift[blockIdx.z * st.shift];
     S += blockIdx.z * st.S;
     Dinv += blockIdx.z * st.D;
     X += blockIdx.z * st.X;
@@ -226,9 +256,9 @@ __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r
     for (int j = 0; j < kNB; ++j) {
         __syncthreads();
         double d = T[j * P + j];
-        if (!(d > 0.0)) {                           // not positive, or NaN
-            if (t == 0) atomicCAS(info, 0, base + j + 1);
-            d = 1.0;
+        if (!(d > floor_d)) {                       // too small, not positive, or NaN
+            if (t == 0 && base + j < r) atomicCAS(info, 0, base + j + 1);
+            if (!(d > 0.0)) d = 1.0;
         }
         const double rs = rsqrt_f64(d);             // column j is scaled by 1 / L_jj, kept for the inverse below
         if (cg == 0) {
@@ -443,7 +473,7 @@ static int gram_slices(int64_t m, int64_t r, int* slice_rows) {
 // Workspace of the orthonormalisation of `batch` matrices of one shape: per matrix S and X (r x r fp64), the
 // inverted diagonal blocks, the result of the first round T (fp32 m x r) and the Gram slices.
 struct OrthLayout {
-    size_t S, X, Dinv, T, part, total;
+    size_t S, X, Dinv, T, part, shift, total;
     BatchStride st;   // element strides between consecutive matrices; st.Y = st.Q = stride of T
 };
 static OrthLayout orth_layout(int64_t m, int64_t r, int64_t batch) {
@@ -458,9 +488,10 @@ static OrthLayout orth_layout(int64_t m, int64_t r, int64_t batch) {
     L.Dinv = L.X + bS * batch;
     L.T = L.Dinv + bD * batch;
     L.part = L.T + bT * batch;
-    L.total = L.part + bP * batch;
+    L.shift = L.part + bP * batch;
+    L.total = L.shift + 256 * (size_t)batch;     // one double per matrix, 256 bytes apart
     L.st = BatchStride{(int64_t)(bT / 4), (int64_t)(bT / 4), (int64_t)(bS / 8), (int64_t)(bS / 8), (int64_t)(bD / 8),
-                       (int64_t)(bP / 8)};
+                       (int64_t)(bP / 8), 256 / 8};
     return L;
 }
 
@@ -497,11 +528,12 @@ static int launch_range(const uint16_t* G, const uint16_t* Z, float* Y, int64_t 
 // One round on `batch` matrices (matrix b at Y + b * sYin, result at Q + b * sQout): Q = Y L^-T with L the Cholesky
 // factor of Y^T Y.
 static void launch_cholqr(const float* Y, int64_t sYin, float* Q, int64_t sQout, int64_t m, int64_t r, int batch,
-                          int32_t* info, char* ws, const OrthLayout& L, hipStream_t stream) {
+                          int32_t* info, double flag_factor, char* ws, const OrthLayout& L, hipStream_t stream) {
     double* S = reinterpret_cast<double*>(ws + L.S);
     double* X = reinterpret_cast<double*>(ws + L.X);
     double* Dinv = reinterpret_cast<double*>(ws + L.Dinv);
     double* part = reinterpret_cast<double*>(ws + L.part);
+    double* shift = reinterpret_cast<double*>(ws + L.shift);
     BatchStride st = L.st;
     st.Y = sYin;
     st.Q = sQout;
@@ -513,8 +545,9 @@ static void launch_cholqr(const float* Y, int64_t sYin, float* Q, int64_t sQout,
     const unsigned B = (unsigned)batch;
     hipLaunchKernelGGL(k_gram, dim3(pairs, slices, B), blk, 0, stream, Y, part, (int)m, (int)r, slice_rows, st);
     hipLaunchKernelGGL(k_gram_reduce, dim3((unsigned)((r * r + 255) / 256), 1, B), blk, 0, stream, part, S, (int)r, slices, st);
+    hipLaunchKernelGGL(k_gram_shift, dim3(1, 1, B), blk, 0, stream, S, (int)r, shift, st);
     for (int kb = 0; kb < nt; ++kb) {
-        hipLaunchKernelGGL(k_chol_diag, dim3(1, 1, B), blk, 0, stream, S, (int)r, kb, Dinv, X, info, st);
+        hipLaunchKernelGGL(k_chol_diag, dim3(1, 1, B), blk, 0, stream, S, (int)r, kb, Dinv, X, info, shift, flag_factor, st);
         const int below = nt - kb - 1;
         if (below > 0) {
             hipLaunchKernelGGL(k_chol_panel, dim3(below, 1, B), blk, 0, stream, S, (int)r, kb, Dinv, st);
@@ -533,8 +566,8 @@ static int launch_orth(const float* Y, int64_t sY, float* Q, int64_t sQ, int64_t
     float* T = reinterpret_cast<float*>(ws + L.T);
     if (reset_info)
         hipLaunchKernelGGL(k_set_i32, dim3((batch + 255) / 256), dim3(256), 0, stream, info, 0, batch);
-    launch_cholqr(Y, sY, T, L.st.Y, m, r, batch, info, ws, L, stream);
-    launch_cholqr(T, L.st.Y, Q, sQ, m, r, batch, info, ws, L, stream);
+    launch_cholqr(Y, sY, T, L.st.Y, m, r, batch, info, 0.0, ws, L, stream);
+    launch_cholqr(T, L.st.Y, Q, sQ, m, r, batch, info, 16.0, ws, L, stream);
     return check_launch();
 }
 

@@ -96,6 +96,30 @@ def test_orthonormalize_graded_columns():
     assert np.abs(got.T @ got - np.eye(r)).max() <= 1e-5
 
 
+def test_orthonormalize_decaying_singular_values():
+    """Singular values over ten decades with mixed columns (what a low-rank gradient gives): after rounding to fp32
+    cond(Y) ~ 4e8, where the unshifted Gram matrix is not positive definite in fp64."""
+    m, r = 600, 128
+    g = np.random.default_rng(23)
+    U = np.linalg.qr(g.standard_normal((m, r)))[0]
+    V = np.linalg.qr(g.standard_normal((r, r)))[0]
+    Y = ((U * np.logspace(0, -10, r)[None, :]) @ V.T).astype(np.float32)
+    Y64 = Y.astype(np.float64)
+    assert np.linalg.cond(Y64) > 1e8
+    with pytest.raises(np.linalg.LinAlgError):
+        np.linalg.cholesky(Y64.T @ Y64)
+    want = Q.orthonormalize(Y)
+    Qd, info = qg.orthonormalize(dev(Y))
+    got = host(Qd).astype(np.float64)
+    assert int(host(info)[0]) == 0
+    assert np.abs(got.T @ got - np.eye(r)).max() <= 1e-6
+    assert np.abs(got[:, :32] - want[:, :32]).max() <= 1e-6           # the well-determined leading columns
+    assert np.abs(got - want).max() <= 1e-5                           # Householder itself is good to cond * 1e-16
+    T = got.T @ Y64                                                   # Q spans Y, in order
+    assert np.abs(np.tril(T, -1)).max() <= 1e-6 * np.abs(T).max()
+    assert np.linalg.norm(got @ T - Y64) <= 1e-6 * np.linalg.norm(Y64)
+
+
 def test_orthonormalize_reports_a_zero_pivot():
     m, r = 300, 136
     Y = np.random.default_rng(22).standard_normal((m, r)).astype(np.float32)
