@@ -469,3 +469,84 @@ def int8_linear_backward(dy_bits, x_bits, Wq, Ws):
     dy = bf16_bits_to_f64(np.asarray(dy_bits)).reshape(-1, m)
     x = bf16_bits_to_f64(np.asarray(x_bits)).reshape(-1, n)
     return dy @ dequant_w_bf16(Wq, Ws), dy.T @ x
+
+
+# --------------------------------------------------------------------------
+# 8-bit Adam states (Sec. 3.5: "an 8-bit version of the Adam optimizer" is the
+# inner optimizer).  The paper takes the format from a third-party library
+# and does not define it; the format below is designed here after the
+# published idea of block-wise dynamic quantization (a data type whose
+# resolution is relative: a dynamic exponent plus a linear fraction, scaled by
+# the block's absolute maximum).  Parity unpinned against the paper.
+#
+#   block      256 consecutive elements of the flattened r x n state
+#   scale      fp32 absmax of the block (0 for an all-zero block)
+#   code       index into a sorted table of 8-bit values in [-1, 1] (first
+#              moment) or [0, 1] (second moment), the nearest entry to
+#              x / scale; ties go to the lower index
+#   table      entry p >= 1 of the unsigned table: level L = floor(log2 p),
+#              k = p - 2^L, value = 10^-(7-L) * (0.1 + 0.9 (k+1) / 2^L);
+#              entry 0 is 0.  That is 2^L values spaced linearly over each
+#              decade (10^-(8-L), 10^-(7-L)], 255 values from 1e-7 to 1.
+#              The signed table has 7 magnitude bits (levels 0..6, 1e-6 to 1):
+#              indices 0..126 the negatives from -1 up, 127 zero, 128..254 the
+#              positives; index 255 is not used.
+# --------------------------------------------------------------------------
+def state8_table(signed: bool) -> np.ndarray:
+    """The sorted table of representable values, as fp32 (255 entries signed, 256 unsigned)."""
+    top = 6 if signed else 7
+    pos = []
+    for p in range(1, 2 ** (top + 1)):
+        L = p.bit_length() - 1
+        k = p - (1 << L)
+        pos.append(10.0 ** -(top - L) * (0.1 + 0.9 * (k + 1) / (1 << L)))
+    pos = np.array(pos, dtype=np.float64)
+    full = np.concatenate([-pos[::-1], [0.0], pos]) if signed else np.concatenate([[0.0], pos])
+    return full.astype(np.float32)
+
+
+def _state8_mids(table32: np.ndarray) -> np.ndarray:
+    t = table32.astype(np.float64)
+    return (0.5 * (t[:-1] + t[1:])).astype(np.float32)
+
+
+def state8_quant(x, signed: bool):
+    """Block-wise dynamic 8-bit quantization of a flat state; all decisions in fp32.  Returns (codes uint8, scales fp32)."""
+    x32 = np.asarray(x, dtype=np.float32).reshape(-1)
+    nb = (x32.size + GROUP - 1) // GROUP
+    mids = _state8_mids(state8_table(signed))
+    codes = np.zeros(x32.size, dtype=np.uint8)
+    scales = np.zeros(nb, dtype=np.float32)
+    zero_code = 127 if signed else 0
+    for b in range(nb):
+        blk = x32[b * GROUP:(b + 1) * GROUP]
+        a = np.float32(np.max(np.abs(blk)))
+        scales[b] = a
+        if a == 0:
+            codes[b * GROUP:(b + 1) * GROUP] = zero_code
+            continue
+        inv = np.float32(1.0) / a                       # correctly rounded fp32 quotient
+        xn = (blk * inv).astype(np.float32)
+        codes[b * GROUP:(b + 1) * GROUP] = np.searchsorted(mids, xn, side="left").astype(np.uint8)
+    return codes, scales
+
+
+def state8_dequant(codes, scales, signed: bool) -> np.ndarray:
+    """table[code] * scale as an fp32 product, returned in fp64."""
+    t = state8_table(signed)
+    c = np.asarray(codes).reshape(-1)
+    s = np.repeat(np.asarray(scales, dtype=np.float32), GROUP)[:c.size]
+    return (t[np.minimum(c, t.size - 1)] * s).astype(np.float32).astype(np.float64)
+
+
+def lowrank_adam8(R, Mq, Ms, Vq, Vs, t: int, hp: HParams):
+    """Adam on the low-rank gradient with 8-bit states (Sec. 3.5): the states are dequantized, updated exactly
+    as in lowrank_adam, and quantized again.  Returns (Mq', Ms', Vq', Vs', N, M', V') with N, M', V' in fp64
+    (M', V' before quantization)."""
+    R = np.asarray(R, dtype=np.float64)
+    M = state8_dequant(Mq, Ms, True).reshape(R.shape)
+    V = state8_dequant(Vq, Vs, False).reshape(R.shape)
+    M1, V1, N = lowrank_adam(R, M, V, t, hp)
+    Mq1, Ms1 = state8_quant(M1, True)
+    Vq1, Vs1 = state8_quant(V1, False)
+    return Mq1, Ms1, Vq1, Vs1, N, M1, V1
