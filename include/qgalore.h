@@ -115,6 +115,23 @@ int qg_project(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
 int qg_lowrank_adam(const float* R, float* M, float* V, uint16_t* N_bf16,
                     int64_t count, int64_t step, const qg_hparams* hp, void* stream);
 
+/* ---- Adam with 8-bit states (Sec. 3.5: an 8-bit Adam is the paper's inner optimizer; it takes the state format from
+ * a third-party library and does not define it - this format is this library's own design).
+ * State format: block = 256 consecutive elements of the flattened r x n state; scales [ceil(count/256)] fp32 = the
+ * block's absolute maximum; codes uint8 [count] = index of the entry nearest to x/scale (ties to the lower index) in
+ * a sorted table with relative resolution.  Unsigned table (second moment): entry 0 is 0, entry p >= 1 has level
+ * L = floor(log2 p), k = p - 2^L and value 10^-(7-L) * (0.1 + 0.9 (k+1) / 2^L) (2^L values spaced linearly over each
+ * decade from 1e-7 to 1).  Signed table (first moment): levels 0..6 (1e-6 to 1), indices 0..126 the negatives from
+ * -1 up, 127 zero, 128..254 the positives, 255 unused.
+ * qg_state8_quant / qg_state8_dequant: fp32 [count] <-> (codes, scales); is_signed selects the table.
+ * qg_lowrank_adam8: as qg_lowrank_adam, with M and V held in this format (Mq/Ms signed, Vq/Vs unsigned, updated in
+ * place): dequantize (table[code] * scale), the same update and direction N, quantize again.
+ * count >= 1, a multiple of 4, below 2^40; step >= 1. */
+int qg_state8_quant(const float* x, int64_t count, int is_signed, uint8_t* codes, float* scales, void* stream);
+int qg_state8_dequant(const uint8_t* codes, const float* scales, int64_t count, int is_signed, float* x, void* stream);
+int qg_lowrank_adam8(const float* R, uint8_t* Mq, float* Ms, uint8_t* Vq, float* Vs, uint16_t* N_bf16,
+                     int64_t count, int64_t step, const qg_hparams* hp, void* stream);
+
 /* ---- Projection and Adam fused (Sec. 3.5): the same arithmetic as qg_project followed by qg_lowrank_adam, with
  * Adam applied in the GEMM epilogue while R is still in registers.  M, V in/out, N out; R (nullable) receives the
  * projected gradient only if the caller wants to inspect it - leaving it NULL saves writing and re-reading

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqgalore.so")
-SOURCES = ["qg_api.hip", "qg_quant.hip", "qg_adam.hip", "qg_gemm.hip", "qg_cossim.hip", "qg_diag.hip", "qg_refresh.hip", "qg_linear.hip"]
+SOURCES = ["qg_api.hip", "qg_quant.hip", "qg_adam.hip", "qg_gemm.hip", "qg_cossim.hip", "qg_diag.hip", "qg_refresh.hip", "qg_linear.hip", "qg_adam8.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                                   # fused multiply-adds only where written

@@ -26,6 +26,7 @@ EXPORTS = [
     "qg_project_adam", "qg_project_adam_many", "qg_diag_clock_probe", "qg_diag_mfma_loop",
     "qg_range_apply", "qg_orthonormalize_workspace_bytes", "qg_orthonormalize", "qg_refresh_workspace_bytes",
     "qg_subspace_refresh", "qg_subspace_refresh_many", "qg_int8_linear_forward", "qg_int8_linear_backward",
+    "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8",
 ]
 
 
@@ -103,6 +104,9 @@ def lib() -> C.CDLL:
         L.qg_refresh_workspace_bytes.restype = sz
         L.qg_refresh_workspace_bytes.argtypes = [i32, i64, i64, i64]
         L.qg_subspace_refresh.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.qg_state8_quant.argtypes = [vp, i64, i32, vp, vp, vp]
+        L.qg_state8_dequant.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.qg_lowrank_adam8.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, C.POINTER(HParams), vp]
         L.qg_int8_linear_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
         L.qg_int8_linear_backward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp]
         L.qg_subspace_refresh_many.argtypes = [i32, C.POINTER(RefreshDesc), i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
@@ -283,6 +287,28 @@ def project_adam_many(plan: StepPlan, hp: HParams, step: int, write_R: bool = Fa
 def backproject_update_sr_many(plan: StepPlan, hp: HParams, seed: int, step: int) -> None:
     _check(lib().qg_backproject_update_sr_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
                                                C.byref(hp), seed, step, _stream()))
+
+
+# ---------------------------------------------------------------- 8-bit Adam states
+def state8_quant(x: torch.Tensor, signed: bool):
+    count = x.numel()
+    codes = torch.empty((count,), dtype=torch.uint8, device=x.device)
+    scales = torch.empty(((count + GROUP - 1) // GROUP,), dtype=torch.float32, device=x.device)
+    _check(lib().qg_state8_quant(_ptr(x, (torch.float32,)), count, int(signed), _ptr(codes), _ptr(scales), _stream()))
+    return codes, scales
+
+
+def state8_dequant(codes: torch.Tensor, scales: torch.Tensor, signed: bool) -> torch.Tensor:
+    x = torch.empty((codes.numel(),), dtype=torch.float32, device=codes.device)
+    _check(lib().qg_state8_dequant(_ptr(codes, (torch.uint8,)), _ptr(scales, (torch.float32,)), codes.numel(),
+                                   int(signed), _ptr(x), _stream()))
+    return x
+
+
+def lowrank_adam8(R, Mq, Ms, Vq, Vs, N, step: int, hp: HParams) -> None:
+    _check(lib().qg_lowrank_adam8(_ptr(R, (torch.float32,)), _ptr(Mq, (torch.uint8,)), _ptr(Ms, (torch.float32,)),
+                                  _ptr(Vq, (torch.uint8,)), _ptr(Vs, (torch.float32,)), _ptr(N, _BF16), R.numel(), step,
+                                  C.byref(hp), _stream()))
 
 
 # ---------------------------------------------------------------- INT8 linear layer

@@ -128,6 +128,18 @@ def test_int8_linear_argument_errors(L):
     assert L.qg_int8_linear_backward(FAKE + 8, FAKE, FAKE, FAKE, 16, 512, 512, 256, FAKE, FAKE, None) == 4
 
 
+def test_adam8_argument_errors(L):
+    hp = qg.hparams()
+    assert L.qg_state8_quant(None, 256, 1, FAKE, FAKE, None) == 1
+    assert L.qg_state8_quant(FAKE, 0, 1, FAKE, FAKE, None) == 2
+    assert L.qg_state8_quant(FAKE, 258, 1, FAKE, FAKE, None) == 2                            # not a multiple of 4
+    assert L.qg_state8_quant(FAKE, 256, 1, FAKE + 4, FAKE, None) == 4
+    assert L.qg_state8_dequant(FAKE, None, 256, 0, FAKE, None) == 1
+    assert L.qg_lowrank_adam8(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 256, 1, None, None) == 1
+    assert L.qg_lowrank_adam8(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 256, 0, C.byref(hp), None) == 2   # t >= 1
+    assert L.qg_lowrank_adam8(FAKE, FAKE, FAKE, FAKE + 8, FAKE, FAKE, 256, 1, C.byref(hp), None) == 4
+
+
 def test_plan_build_on_host(L):
     descs = (qg.MatrixDesc * 2)()
     for d, (m, n, r) in zip(descs, [(4096, 4096, 1024), (11008, 4096, 1024)]):
