@@ -131,6 +131,12 @@ int qg_state8_quant(const float* x, int64_t count, int is_signed, uint8_t* codes
 int qg_state8_dequant(const uint8_t* codes, const float* scales, int64_t count, int is_signed, float* x, void* stream);
 int qg_lowrank_adam8(const float* R, uint8_t* Mq, float* Ms, uint8_t* Vq, float* Vs, uint16_t* N_bf16,
                      int64_t count, int64_t step, const qg_hparams* hp, void* stream);
+/* qg_step8: one full step on one matrix with 8-bit Adam states, the paper's default configuration (Sec. 3.5): qg_project
+ * -> qg_lowrank_adam8 -> qg_backproject_update_sr on `stream`, with exactly their results.  R (fp32 r x n) and N are
+ * caller-provided scratch outputs and both required. */
+int qg_step8(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t* Wq, float* Ws,
+             uint8_t* Mq, float* Ms, uint8_t* Vq, float* Vs, float* R, uint16_t* N_bf16,
+             int64_t m, int64_t n, int64_t r, int group, const qg_hparams* hp, uint64_t seed, int64_t step, void* stream);
 
 /* ---- Projection and Adam fused (Sec. 3.5): the same arithmetic as qg_project followed by qg_lowrank_adam, with
  * Adam applied in the GEMM epilogue while R is still in registers.  M, V in/out, N out; R (nullable) receives the

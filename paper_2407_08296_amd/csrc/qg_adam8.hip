@@ -190,3 +190,12 @@ extern "C" int qg_lowrank_adam8(const float* R, uint8_t* Mq, float* Ms, uint8_t*
                        count, make_adam_coef(hp, step));
     return check_launch();
 }
+
+extern "C" int qg_step8(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t* Wq, float* Ws, uint8_t* Mq,
+                        float* Ms, uint8_t* Vq, float* Vs, float* R, uint16_t* N_bf16, int64_t m, int64_t n, int64_t r,
+                        int group, const qg_hparams* hp, uint64_t seed, int64_t step, void* stream) {
+    if (!R || !hp) return QG_ERR_NULL;
+    if (int e = qg_project(Pq, Ps, G_bf16, m, n, r, group, R, nullptr, 0, stream)) return e;
+    if (int e = qg_lowrank_adam8(R, Mq, Ms, Vq, Vs, N_bf16, r * n, step, hp, stream)) return e;
+    return qg_backproject_update_sr(Pq, Ps, N_bf16, Wq, Ws, m, n, r, group, hp->alpha, hp->lr, seed, step, nullptr, stream);
+}

@@ -26,7 +26,7 @@ EXPORTS = [
     "qg_project_adam", "qg_project_adam_many", "qg_diag_clock_probe", "qg_diag_mfma_loop",
     "qg_range_apply", "qg_orthonormalize_workspace_bytes", "qg_orthonormalize", "qg_refresh_workspace_bytes",
     "qg_subspace_refresh", "qg_subspace_refresh_many", "qg_int8_linear_forward", "qg_int8_linear_backward",
-    "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8",
+    "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8", "qg_step8",
 ]
 
 
@@ -107,6 +107,7 @@ def lib() -> C.CDLL:
         L.qg_state8_quant.argtypes = [vp, i64, i32, vp, vp, vp]
         L.qg_state8_dequant.argtypes = [vp, vp, i64, i32, vp, vp]
         L.qg_lowrank_adam8.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, C.POINTER(HParams), vp]
+        L.qg_step8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, C.POINTER(HParams), u64, i64, vp]
         L.qg_int8_linear_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
         L.qg_int8_linear_backward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp]
         L.qg_subspace_refresh_many.argtypes = [i32, C.POINTER(RefreshDesc), i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
@@ -309,6 +310,13 @@ def lowrank_adam8(R, Mq, Ms, Vq, Vs, N, step: int, hp: HParams) -> None:
     _check(lib().qg_lowrank_adam8(_ptr(R, (torch.float32,)), _ptr(Mq, (torch.uint8,)), _ptr(Ms, (torch.float32,)),
                                   _ptr(Vq, (torch.uint8,)), _ptr(Vs, (torch.float32,)), _ptr(N, _BF16), R.numel(), step,
                                   C.byref(hp), _stream()))
+
+
+def step8(Pq, Ps, G, Wq, Ws, Mq, Ms, Vq, Vs, R, N, m: int, n: int, r: int, hp: HParams, seed: int, step: int) -> None:
+    _check(lib().qg_step8(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(G, _BF16), _ptr(Wq, (torch.int8,)),
+                          _ptr(Ws, (torch.float32,)), _ptr(Mq, (torch.uint8,)), _ptr(Ms, (torch.float32,)),
+                          _ptr(Vq, (torch.uint8,)), _ptr(Vs, (torch.float32,)), _ptr(R, (torch.float32,)), _ptr(N, _BF16),
+                          m, n, r, GROUP, C.byref(hp), seed, step, _stream()))
 
 
 # ---------------------------------------------------------------- INT8 linear layer

@@ -11,6 +11,7 @@ import pytest
 import torch
 
 from oracle import qgalore as Q
+from paper_2407_08296_amd import inputs as I
 from paper_2407_08296_amd import qgalore as qg
 
 pytestmark = pytest.mark.gpu
@@ -70,3 +71,40 @@ def test_lowrank_adam8_steps(r, n):
             assert np.linalg.norm((gN - oNb)[far]) <= 1e-3 * np.linalg.norm(oNb[far])
         else:
             assert np.linalg.norm(gN - oNb) <= 1e-3 * np.linalg.norm(oNb)
+
+
+@pytest.mark.parametrize("m,n,r", [(512, 512, 128), (333, 264, 144)])
+def test_step8_is_project_adam8_backproject(m, n, r):
+    """The paper's default configuration in one call: against the three separate calls (bit for bit) and, for the
+    weight codes, against the oracle's chain (the bar of the fp32-state step)."""
+    W = I.weight_f32(m, n)
+    Wq, Ws = Q.quant_int8(W)
+    Pq, Ps = Q.quant_int4(I.projection_f32(m, r))
+    count = r * n
+    Mq, Ms = Q.state8_quant(np.zeros(count), True)
+    Vq, Vs = Q.state8_quant(np.zeros(count), False)
+    hp = qg.hparams()
+    seed = 5
+    for t in (1, 2):
+        Gb = I.gradient_bf16(m, n, t)
+        Gd = dev(Gb.view(np.int16))
+        a = [dev(x) for x in (Pq, Ps)] + [Gd] + [dev(x) for x in (Wq, Ws, Mq, Ms, Vq, Vs)]
+        R = torch.empty((r, n), dtype=torch.float32, device=DEV)
+        N = torch.empty((r, n), dtype=torch.bfloat16, device=DEV)
+        qg.step8(*a, R, N, m, n, r, hp, seed, t)
+        # the three separate calls on fresh copies
+        b = [dev(x) for x in (Pq, Ps)] + [Gd] + [dev(x) for x in (Wq, Ws, Mq, Ms, Vq, Vs)]
+        R2 = qg.project(b[0], b[1], Gd, m, n, r)
+        N2 = torch.empty_like(N)
+        qg.lowrank_adam8(R2, b[5], b[6], b[7], b[8], N2, t, hp)
+        qg.backproject_update_sr(b[0], b[1], N2, b[3], b[4], m, n, r, 0.25, 1e-3, seed, t)
+        for x, y in zip(a[3:], b[3:]):
+            assert torch.equal(x, y)
+        assert torch.equal(N.view(torch.int16), N2.view(torch.int16))
+        # the oracle's chain from the same (oracle) state
+        oR = Q.project(Pq, Ps, Gb, m, n, r)
+        Mq, Ms, Vq, Vs, oN, _, _ = Q.lowrank_adam8(oR, Mq, Ms, Vq, Vs, t, HP)
+        oU = Q.backproject(Pq, Ps, Q.bf16_rne(oN), m, r, HP.alpha)
+        Wq, Ws = Q.update_sr(Wq, Ws, oU, HP.lr, seed, t)
+        d = host(a[3]).astype(np.int32) - Wq.astype(np.int32)
+        assert np.abs(d).max() <= 1 and np.mean(d == 0) >= (0.995 if t == 1 else 0.9999)
