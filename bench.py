@@ -114,8 +114,9 @@ def cpu_baseline(config: int, shapes):
     except Exception:
         threads = len(os.sched_getaffinity(0))
     if config >= 2:
-        sample = shapes[:7]
-        note = "one decoder layer (7 matrices), scaled by sum(m*n*r) to the whole step"
+        layers = 3 if config == 4 else 6          # about 10-30 s of host time
+        sample = shapes[:7 * layers]
+        note = f"{layers} decoder layers ({7 * layers} matrices), scaled by sum(m*n*r) to the whole step"
     else:
         sample = shapes
         note = "the whole step"
