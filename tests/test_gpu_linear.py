@@ -117,3 +117,18 @@ def test_llama7b_attention_shape_by_sampled_outputs():
         want = np.array([f(a, b) for a, b in zip(ii, jj)])
         got = oh[ii, jj]
         assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 4 * k * 2.0 ** -24 * sc)
+
+
+def test_random_shapes():
+    """Twenty seeded random (tokens, m, n) below 400: tile edges, contraction tails and row alignments of every kind."""
+    rs = np.random.default_rng(11)
+    for _ in range(20):
+        tokens, m, n = (int(v) for v in rs.integers(1, 400, 3))
+        Wq, Ws, xb, dyb = case(tokens, m, n, seed=3)
+        xd, dyd = bits_t(xb, (tokens, n)), bits_t(dyb, (tokens, m))
+        y = qg.int8_linear_forward(xd, dev(Wq), dev(Ws))
+        dx, G = qg.int8_linear_backward(dyd, xd, dev(Wq), dev(Ws), m, n)
+        want_dx, want_G = Q.int8_linear_backward(dyb, xb, Wq, Ws)
+        check(host_f64(y), Q.int8_linear_forward(xb, Wq, Ws), n, 0.02)
+        check(host_f64(dx), want_dx, m, 0.05 * 0.02)
+        check(host_f64(G), want_G, tokens, 0.05)
