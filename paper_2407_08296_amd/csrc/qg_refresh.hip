@@ -629,7 +629,7 @@ extern "C" int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs,
     }
     if (!workspace) return QG_ERR_WORKSPACE;
     // as many matrices per batch as the workspace holds
-    int batch = count;
+    int batch = count < 32768 ? count : 32768;   // the batch index is a grid dimension
     while (batch > 1 && refresh_layout(m, n, r, batch).total > workspace_bytes) batch = (batch + 1) / 2;
     const RefreshLayout L = refresh_layout(m, n, r, batch);
     if (L.total > workspace_bytes) return QG_ERR_WORKSPACE;
