@@ -254,3 +254,55 @@ def test_refresh_at_llama7b_shapes_by_properties():
         e0 = float(qg.project(Pq, Ps, G, m, n, r).norm()) ** 2
         e1 = float(qg.project(Pq1, Ps1, G, m, n, r).norm()) ** 2
         assert e1 > 1.5 * e0
+
+
+def test_refresh_and_step_replay_from_a_graph():
+    """The library only launches kernels on the caller's stream (no allocation, no synchronisation, no memset
+    nodes), so its calls can be captured: a captured refresh and a captured step, replayed three times with eager
+    work in between, reproduce the eager results bit for bit."""
+    m, n, r = 512, 512, 128
+    Gb, Pq, Ps = start(m, n, r)
+    Gd, Pqd, Psd = bits_t(Gb), dev(Pq), dev(Ps)
+    Wq, Ws = qg.quant_int8(dev(I.weight_f32(m, n)))
+    M0 = torch.zeros((r, n), dtype=torch.float32, device=DEV)
+    hp = qg.hparams()
+    ws = torch.empty((qg.lib().qg_refresh_workspace_bytes(1, m, n, r),), dtype=torch.uint8, device=DEV)
+    out = qg.subspace_refresh(Pqd, Psd, Gd, m, n, r, 1, workspace=ws)
+    ref_P = (out[0].clone(), out[1].clone(), out[2].clone())
+    state = [Wq.clone(), Ws.clone(), M0.clone(), M0.clone()]
+    N = torch.empty((r, n), dtype=torch.bfloat16, device=DEV)
+    qg.step(Pqd, Psd, Gd, *state, None, N, m, n, r, hp, 7, 3)
+    torch.cuda.synchronize()
+    ref_S = [x.clone() for x in state] + [N.clone()]
+
+    gstate = [Wq.clone(), Ws.clone(), M0.clone(), M0.clone()]
+    gN = torch.empty_like(N)
+    Pq1, Ps1 = torch.empty_like(Pqd), torch.empty_like(Psd)
+    cos = torch.empty((1,), dtype=torch.float32, device=DEV)
+    info = torch.empty((1,), dtype=torch.int32, device=DEV)
+    L = qg.lib()
+
+    def calls():
+        st = torch.cuda.current_stream().cuda_stream
+        assert L.qg_subspace_refresh(Pqd.data_ptr(), Psd.data_ptr(), Gd.data_ptr(), m, n, r, 256, 1, Pq1.data_ptr(),
+                                     Ps1.data_ptr(), cos.data_ptr(), info.data_ptr(), ws.data_ptr(), ws.numel(), st) == 0
+        qg.step(Pqd, Psd, Gd, *gstate, None, gN, m, n, r, hp, 7, 3)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            calls()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for dst, src in zip(gstate, (Wq, Ws, M0, M0)):
+            dst.copy_(src)
+        Pq1.zero_(); Ps1.zero_(); cos.zero_(); gN.zero_()
+        _ = float((torch.randn((256, 256), device=DEV) @ torch.randn((256, 256), device=DEV)).sum())   # eager work between
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Pq1, ref_P[0]) and torch.equal(Ps1, ref_P[1]) and float(cos[0]) == float(ref_P[2][0])
+        assert int(info[0]) == 0
+        for got, want in zip(gstate + [gN], ref_S):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
