@@ -14,9 +14,8 @@ namespace qg {
 
 enum : int { kBf16KFast = 0, kBf16KSlow = 1, kInt8KFast = 2, kInt8KSlow = 3 };
 
-constexpr int kLinTM = 128;                // output tile: 128 (A's index) x TN (B's index, 256 or 128), 4 waves of 64 x TN/2
-constexpr int kLinK = 32;                  // contraction depth per step
-constexpr int kLinPF = kLinK + kPadX;      // pitch of an [x][k] tile
+constexpr int kLinTM = 128;                // output tile: 128 (A's index) x TN (B's index, 256 or 128), 4 waves of 64 x TN/2;
+                                           // BK (32 or 64) = contraction depth per step
 constexpr int kLinStrip = 8;               // row tiles per strip of the tile numbering
 
 // 16 consecutive INT8 codes starting at `src`, of which the first `valid` lie inside the matrix.
@@ -54,15 +53,15 @@ struct LinOperand {
 
 // Staging of one operand tile: global -> registers (fetch) -> LDS (commit; INT8 is dequantized here).  EXACT: the
 // tile lies inside the matrix, K is a whole number of steps and rows are 16-byte aligned - no checks.
-template <int LAYOUT, int XT, bool EXACT>
+template <int LAYOUT, int XT, int BK, bool EXACT>
 struct LinStage {
     static constexpr bool kFast = LAYOUT == kBf16KFast || LAYOUT == kInt8KFast;
     static constexpr bool kInt8 = LAYOUT == kInt8KFast || LAYOUT == kInt8KSlow;
     static constexpr int CH = kInt8 ? 16 : 8;                   // elements per 16-byte chunk (one block scale each)
-    static constexpr int CPR = (kFast ? kLinK : XT) / CH;       // chunks per tile row
-    static constexpr int PITCH = kFast ? kLinPF : XT + kPadK;   // LDS pitch: [x][k] or [k][x]
-    static constexpr int ELEMS = (kFast ? XT : kLinK) * PITCH;
-    static constexpr int PER = XT * kLinK / CH / 256;           // chunks per thread
+    static constexpr int CPR = (kFast ? BK : XT) / CH;          // chunks per tile row
+    static constexpr int PITCH = kFast ? BK + kPadX : XT + kPadK;   // LDS pitch: [x][k] or [k][x]
+    static constexpr int ELEMS = (kFast ? XT : BK) * PITCH;
+    static constexpr int PER = XT * BK / CH / 256;              // chunks per thread
     u32x4 v[PER];
     float s[kInt8 ? PER : 1];
 
@@ -112,11 +111,11 @@ struct LinStage {
 // columns.
 // Two LDS stages: while the MFMAs of step kt read stage kt & 1, the operands of step kt + 1 (fetched into registers
 // before those MFMAs) are written to the other stage; one barrier per step.
-template <int AL, int BL, bool EXACT, typename OUT, int TN>
+template <int AL, int BL, bool EXACT, typename OUT, int TN, int BK>
 __global__ __launch_bounds__(256, 2) void k_tile_gemm(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
                                                       OUT* __restrict__ C, int M, int N, int K, int tiles_m, int tiles_n) {
-    using SA = LinStage<AL, kLinTM, EXACT>;
-    using SB = LinStage<BL, TN, EXACT>;
+    using SA = LinStage<AL, kLinTM, BK, EXACT>;
+    using SB = LinStage<BL, TN, BK, EXACT>;
     __shared__ __attribute__((aligned(16))) uint16_t At[2][SA::ELEMS];
     __shared__ __attribute__((aligned(16))) uint16_t Bt[2][SB::ELEMS];
     const int lane = threadIdx.x & 63;
@@ -138,7 +137,7 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm(LinOperand A, LinOperand B
         for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-    const int KT = (K + kLinK - 1) / kLinK;
+    const int KT = (K + BK - 1) / BK;
     sa.fetch(A, i0, M, 0, K);
     sb.fetch(B, j0, N, 0, K);
     sa.commit(At[0]);
@@ -148,12 +147,12 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm(LinOperand A, LinOperand B
         const int cur = kt & 1;
         const bool more = kt + 1 < KT;
         if (more) {
-            sa.fetch(A, i0, M, (kt + 1) * kLinK, K);
-            sb.fetch(B, j0, N, (kt + 1) * kLinK, K);
+            sa.fetch(A, i0, M, (kt + 1) * BK, K);
+            sb.fetch(B, j0, N, (kt + 1) * BK, K);
         }
         __builtin_amdgcn_s_setprio(kMfmaPrio);     // the wave in its MFMA phase goes first (two workgroups per CU)
 #pragma unroll
-        for (int kk = 0; kk < kLinK / 16; ++kk) {
+        for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 af[MB], bf[NB];
 #pragma unroll
             for (int a = 0; a < MB; ++a) af[a] = SA::frag(At[cur], wm * 64 + a * 32, kk, lane);
@@ -193,29 +192,36 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm(LinOperand A, LinOperand B
         }
 }
 
-template <int AL, int BL, typename OUT, int TN>
-static void launch_tile_gemm_tn(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M, int64_t N,
-                                int64_t K, hipStream_t st) {
+template <int AL, int BL, typename OUT, int TN, int BK>
+static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M,
+                                   int64_t N, int64_t K, hipStream_t st) {
     const int64_t tiles_m = (M + kLinTM - 1) / kLinTM, tiles_n = (N + TN - 1) / TN;
     const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);   // a multiple of the 8 XCDs
     // no checks at all when every tile and every step is whole and rows start 16-byte aligned
-    const bool exact = M % kLinTM == 0 && N % TN == 0 && K % kLinK == 0 && A.ld % 8 == 0 && B.ld % 16 == 0;
+    const bool exact = M % kLinTM == 0 && N % TN == 0 && K % BK == 0 && A.ld % 8 == 0 && B.ld % 16 == 0;
     if (exact)
-        hipLaunchKernelGGL((k_tile_gemm<AL, BL, true, OUT, TN>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M, (int)N,
-                           (int)K, (int)tiles_m, (int)tiles_n);
+        hipLaunchKernelGGL((k_tile_gemm<AL, BL, true, OUT, TN, BK>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M,
+                           (int)N, (int)K, (int)tiles_m, (int)tiles_n);
     else
-        hipLaunchKernelGGL((k_tile_gemm<AL, BL, false, OUT, TN>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M, (int)N,
-                           (int)K, (int)tiles_m, (int)tiles_n);
+        hipLaunchKernelGGL((k_tile_gemm<AL, BL, false, OUT, TN, BK>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M,
+                           (int)N, (int)K, (int)tiles_m, (int)tiles_n);
 }
 
-// 128 x 256 tiles when they give every CU two workgroups, 128 x 128 tiles for smaller outputs.
+// Tile shape.  Operands whose contraction index is slow want the wide tile: 128 x 256 with 32-deep steps when that
+// gives every CU two workgroups, 128 x 128 for smaller outputs.  When both operands have the contraction index as
+// their fast index a load instruction touches one cache line per tile row, and what pays is whole lines: 128 x 128
+// with 64-deep steps (measured on the forward pass of the linear layer: 2.28 ms against 2.37 ms for the wide tile
+// and 2.80 ms for 128 x 128 with 32-deep steps).
 template <int AL, int BL, typename OUT>
 static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M, int64_t N,
                             int64_t K, hipStream_t st) {
-    if (((M + kLinTM - 1) / kLinTM) * ((N + 255) / 256) >= 512)
-        launch_tile_gemm_tn<AL, BL, OUT, 256>(A, B, bias, C, M, N, K, st);
+    constexpr bool both_fast = (AL == kBf16KFast || AL == kInt8KFast) && (BL == kBf16KFast || BL == kInt8KFast);
+    if constexpr (both_fast)
+        launch_tile_gemm_shape<AL, BL, OUT, 128, 64>(A, B, bias, C, M, N, K, st);
+    else if (((M + kLinTM - 1) / kLinTM) * ((N + 255) / 256) >= 512)
+        launch_tile_gemm_shape<AL, BL, OUT, 256, 32>(A, B, bias, C, M, N, K, st);
     else
-        launch_tile_gemm_tn<AL, BL, OUT, 128>(A, B, bias, C, M, N, K, st);
+        launch_tile_gemm_shape<AL, BL, OUT, 128, 32>(A, B, bias, C, M, N, K, st);
     return check_launch();
 }
 
