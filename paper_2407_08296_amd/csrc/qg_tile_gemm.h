@@ -192,6 +192,101 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm(LinOperand A, LinOperand B
         }
 }
 
+// Both operands bf16 with the contraction index as their slow index, whole tiles and aligned rows (grad_W at the
+// LLaMA shapes): the staging of the optimizer step's projection kernel for its gradient operand, applied to both -
+// direct global -> LDS loads into unpadded swizzled [k][x] tiles (no staging registers, no LDS write instructions),
+// two stages, the loads of step k+1 issued ahead of the MFMAs of step k, three workgroups per CU.
+template <typename OUT>
+__global__ __launch_bounds__(256, 3) void k_gemm_kslow_direct(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                                              OUT* __restrict__ C, int M, int N, int K, int tiles_m,
+                                                              int tiles_n) {
+    constexpr int TN = 256, BK = 32;
+    using AD = KMajorSwizzled<kLinTM, BK, 256>;
+    using BD = KMajorSwizzled<TN, BK, 256>;
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][AD::STAGE];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BD::STAGE];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= (uint32_t)(tiles_m * tiles_n)) return;
+    const int strip = (int)(tile / (uint32_t)(kLinStrip * tiles_n)), in_strip = (int)(tile % (uint32_t)(kLinStrip * tiles_n));
+    const int strip_rows = min(kLinStrip, tiles_m - strip * kLinStrip);
+    const int i0 = (strip * kLinStrip + in_strip % strip_rows) * kLinTM, j0 = (in_strip / strip_rows) * TN;
+    static_assert(AD::VARIANTS == 1 && BD::VARIANTS == 2, "per-lane source offsets below");
+    const uint32_t a_byte = AD::lane_src_bytes(lane, M, 0);
+    const uint32_t b_byte[2] = {BD::lane_src_bytes(lane, N, 0), BD::lane_src_bytes(lane, N, 1)};
+    auto gload = [&](int kt, int stage) {
+        const __amdgpu_buffer_rsrc_t ra = make_rsrc(A + (int64_t)kt * BK * M + i0);
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(B + (int64_t)kt * BK * N + j0);
+#pragma unroll
+        for (int p = 0; p < AD::PER; ++p)
+            buffer_load_lds16(ra, As[stage] + AD::load_row0(wave, p) * kLinTM, a_byte, 2u * (uint32_t)(AD::load_row0(wave, p) * M));
+#pragma unroll
+        for (int p = 0; p < BD::PER; ++p)
+            buffer_load_lds16(rb, Bs[stage] + BD::load_row0(wave, p) * TN, b_byte[p % 2], 2u * (uint32_t)(BD::load_row0(wave, p) * N));
+    };
+    constexpr int MB = 2, NB = 4;
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    int a_lane[MB], b_lane[NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a) a_lane[a] = AD::lane_offset(lane) + ((wm * 64 + a * 32) ^ AD::lane_swizzle(lane));
+#pragma unroll
+    for (int b = 0; b < NB; ++b) b_lane[b] = BD::lane_offset(lane) + ((wn * 128 + b * 32) ^ BD::lane_swizzle(lane));
+    auto mfma_step = [&](int stage) {
+        __builtin_amdgcn_s_setprio(kMfmaPrio);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[MB], bf[NB];
+#pragma unroll
+            for (int a = 0; a < MB; ++a) af[a] = read_kmajor_frag(As[stage] + kk * 16 * kLinTM + a_lane[a], kLinTM);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) bf[b] = read_kmajor_frag(Bs[stage] + kk * 16 * TN + b_lane[b], TN);
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_setprio(0);
+    };
+    auto landed = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };   // direct loads count like any other load
+    const int KT = K / BK;
+    // unrolled by two: constant LDS stages; loads past the end re-read the last K slab (in bounds, never consumed)
+    gload(0, 0);
+    landed();
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {
+        gload(min(kt + 1, KT - 1), 1);
+        mfma_step(0);
+        landed();
+        __syncthreads();
+        gload(min(kt + 2, KT - 1), 0);
+        if (kt + 1 < KT) mfma_step(1);
+        landed();
+        __syncthreads();
+    }
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int col = j0 + wn * 128 + b * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const float x = acc[a][b][v];
+                if constexpr (sizeof(OUT) == 4) C[(int64_t)row * N + col] = x;
+                else C[(int64_t)row * N + col] = to_bf16(x);
+            }
+        }
+}
+
 template <int AL, int BL, typename OUT, int TN, int BK>
 static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M,
                                    int64_t N, int64_t K, hipStream_t st) {
@@ -216,6 +311,15 @@ template <int AL, int BL, typename OUT>
 static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M, int64_t N,
                             int64_t K, hipStream_t st) {
     constexpr bool both_fast = (AL == kBf16KFast || AL == kInt8KFast) && (BL == kBf16KFast || BL == kInt8KFast);
+    if constexpr (AL == kBf16KSlow && BL == kBf16KSlow) {
+        const int64_t tiles_m = M / kLinTM, tiles_n = N / 256;
+        if (M % kLinTM == 0 && N % 256 == 0 && K % 32 == 0 && bias == nullptr && tiles_m * tiles_n >= 512 && K >= 32) {
+            const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);
+            hipLaunchKernelGGL((k_gemm_kslow_direct<OUT>), dim3(grid), dim3(256), 0, st, static_cast<const uint16_t*>(A.base),
+                               static_cast<const uint16_t*>(B.base), C, (int)M, (int)N, (int)K, (int)tiles_m, (int)tiles_n);
+            return check_launch();
+        }
+    }
     if constexpr (both_fast)
         launch_tile_gemm_shape<AL, BL, OUT, 128, 64>(A, B, bias, C, M, N, K, st);
     else if (((M + kLinTM - 1) / kLinTM) * ((N + 255) / 256) >= 512)
