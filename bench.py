@@ -61,7 +61,15 @@ def algorithmic_work(shapes):
     return flops, proj, adam, bp
 
 
-def build_state(config: int, device):
+def pitched(t, ld):
+    """Copy of the 2-D tensor t with rows ld elements apart (padding zero-filled)."""
+    import torch
+    out = torch.zeros((t.shape[0], ld), dtype=t.dtype, device=t.device)
+    out[:, :t.shape[1]].copy_(t)
+    return out
+
+
+def build_state(config: int, device, pad_rows: bool = False):
     """Device-resident synthetic state of every matrix of the workload.
 
     W ~ N(0, 0.02) quantized by qg_quant_int8; G = A B^T + E (rank 16 plus noise) in bf16; one orthonormal P per
@@ -92,11 +100,15 @@ def build_state(config: int, device):
         G.addmm_(A, B.t())
         Gb = G.to(torch.bfloat16)
         del G
+        ld = (n + 15) // 16 * 16 if pad_rows and n % 16 else 0   # rows 16-byte aligned in every array
+        if ld:
+            Gb, Wq = pitched(Gb, ld), pitched(Wq.view(m, n), ld)
+        w = ld or n
         mats.append(qg.MatrixState(m, n, r, Pq, Ps, Gb, Wq, Ws,
-                                   torch.zeros((r, n), dtype=torch.float32, device=device),
-                                   torch.zeros((r, n), dtype=torch.float32, device=device),
-                                   torch.empty((r, n), dtype=torch.float32, device=device),
-                                   torch.empty((r, n), dtype=torch.bfloat16, device=device)))
+                                   torch.zeros((r, w), dtype=torch.float32, device=device),
+                                   torch.zeros((r, w), dtype=torch.float32, device=device),
+                                   torch.empty((r, w), dtype=torch.float32, device=device),
+                                   torch.empty((r, w), dtype=torch.bfloat16, device=device), ld=ld))
     torch.cuda.synchronize()
     return mats
 
@@ -311,6 +323,9 @@ def main():
     ap.add_argument("--rsweep", action="store_true",
                     help="time qg_project / qg_lowrank_adam / qg_backproject_update_sr on one 2048x5461 matrix for "
                          "r in {128, 256, 512, 1024} (the roofline crossover of the LLaMA-1B shape) and exit")
+    ap.add_argument("--pad-rows", action="store_true",
+                    help="store matrices whose n is not a multiple of 16 with a row pitch of n rounded up to 16 "
+                         "(the descriptor's ld): aligned rows for the direct loads")
     ap.add_argument("--refresh", action="store_true",
                     help="time the subspace refresh (qg_subspace_refresh, one pass) over every matrix of the workload "
                          "instead of the optimizer step, print its own JSON line and exit")
@@ -380,7 +395,24 @@ def main():
             ga = run(lambda: qg.lowrank_adam_many(gplan, hp, 2), 10) / copies
             gb = run(lambda: qg.backproject_update_sr_many(gplan, hp, 0, 2), 10) / copies
             del gm, gplan
-            rows.append({"r": r, "grouped_project_us": gp * 1e3, "grouped_project_TFLOP/s": flops / gp / 1e9,
+            # the same 24 matrices stored with a row pitch of 5472: 16-byte aligned rows, the direct-load kernels
+            ld = (n + 15) // 16 * 16
+            gm = []
+            for _ in range(copies):
+                gm.append(qg.MatrixState(m, n, r, Pq, Ps, pitched(G, ld), pitched(Wq.view(m, n), ld), Ws.clone(),
+                                         torch.zeros((r, ld), device=device), torch.zeros((r, ld), device=device),
+                                         torch.empty((r, ld), device=device),
+                                         torch.empty((r, ld), dtype=torch.bfloat16, device=device), ld=ld))
+            gplan = qg.StepPlan(gm)
+            pp = run(lambda: qg.project_many(gplan), 10) / copies
+            pa = run(lambda: qg.lowrank_adam_many(gplan, hp, 2), 10) / copies
+            pb = run(lambda: qg.backproject_update_sr_many(gplan, hp, 0, 2), 10) / copies
+            pf = run(lambda: qg.project_adam_many(gplan, hp, 2, False), 10) / copies
+            del gm, gplan
+            rows.append({"r": r, "pitched_project_us": pp * 1e3, "pitched_project_TFLOP/s": flops / pp / 1e9,
+                         "pitched_adam_us": pa * 1e3, "pitched_backproject_us": pb * 1e3,
+                         "pitched_backproject_TFLOP/s": flops / pb / 1e9, "pitched_project_adam_us": pf * 1e3,
+                         "grouped_project_us": gp * 1e3, "grouped_project_TFLOP/s": flops / gp / 1e9,
                          "grouped_project_GB/s": b_proj / gp / 1e6, "grouped_adam_us": ga * 1e3,
                          "grouped_adam_GB/s": b_adam / ga / 1e6, "grouped_backproject_us": gb * 1e3,
                          "grouped_backproject_TFLOP/s": flops / gb / 1e9, "grouped_backproject_GB/s": b_bp / gb / 1e6,
@@ -398,9 +430,11 @@ def main():
         return
 
     shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(args.config)]
-    mats = build_state(args.config, device)
+    mats = build_state(args.config, device, args.pad_rows)
 
     if args.refresh:
+        if args.pad_rows:
+            sys.exit("bench.py: the subspace refresh takes dense gradients only (--pad-rows is for the step)")
         print(json.dumps(refresh_bench(args, shapes, mats)))
         return
     import dataclasses
@@ -487,7 +521,7 @@ def main():
     # matrix holds a whole number of blocks) serves the whole model between the two grouped GEMM launches.
     adam8 = step8 = None
     count8 = sum(r * n for m, n, r in shapes)
-    if all((r * n) % 256 == 0 for m, n, r in shapes):
+    if all((r * n) % 256 == 0 for m, n, r in shapes) and not args.pad_rows:
         R8 = torch.empty((count8,), dtype=torch.float32, device=device)
         N8 = torch.empty((count8,), dtype=torch.bfloat16, device=device)
         Mq8, Ms8 = qg.state8_quant(torch.zeros((count8,), dtype=torch.float32, device=device), True)
@@ -545,7 +579,8 @@ def main():
         "metric": "qgalore_step_ms_all_linear_weights", "value": ms_per_step, "unit": "ms", "n_gpus": 1,
         "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "launches_per_step": 2},
+        "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "launches_per_step": 2,
+                   "row_layout": "pitch of n rounded up to 16" if args.pad_rows else "dense"},
         "roofline": roofline, "kernels": kernels, "ceilings": ceilings, "step_stats": step_stats,
     }
     if step8 is not None:

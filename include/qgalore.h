@@ -65,7 +65,7 @@ typedef struct {
 } qg_policy;
 
 /* One matrix of a grouped step (qg_step_many).  All pointers are device
- * pointers with the layouts of the single-matrix calls. */
+ * pointers with the layouts of the single-matrix calls, except for the optional row pitch `ld`. */
 typedef struct {
     int64_t m, n, r;
     const uint8_t*  Pq;   /* INT4 P, packed            */
@@ -77,6 +77,13 @@ typedef struct {
     float*          V;    /* second moment r x n, in/out*/
     float*          R;    /* projected gradient r x n, out; may be NULL (not written then) */
     uint16_t*       N;    /* bf16 Adam direction r x n, out */
+    int64_t         ld;   /* row pitch, in elements, of EVERY n-wide array above (G, Wq: m rows; M, V, R, N: r rows).
+                             0 or n: dense rows.  Otherwise >= n and a multiple of 16: rows then start 16-byte aligned
+                             whatever n is, which takes a matrix with n % 8 != 0 (n = 5461 in the LLaMA-1B shapes) off
+                             the slow under-aligned path.  Every array holds rows * ld elements.  Padding columns are never read for a
+                             result; they are not written either, with two exceptions: N goes out as pairs of columns (an
+                             odd n overwrites the first padding column of N), and the unfused qg_lowrank_adam_many runs
+                             over the padding of M, V, N as well. */
 } qg_matrix_desc;
 
 const char* qg_status_string(int status);

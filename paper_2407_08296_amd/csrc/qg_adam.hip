@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void k_lowrank_adam_many(const PlanHeader* __r
         if (mats[mid].adam_chunk0 <= b) lo = mid; else hi = mid - 1;
     }
     const PlanMatrix& d = mats[lo];
-    adam_chunk(d.R, d.M, d.V, d.N, d.r * d.n, (int64_t)(b - d.adam_chunk0) * kAdamChunk, c);
+    adam_chunk(d.R, d.M, d.V, d.N, d.r * d.ld, (int64_t)(b - d.adam_chunk0) * kAdamChunk, c);   // padding included
 }
 
 AdamCoef make_adam_coef(const qg_hparams* hp, int64_t step) {

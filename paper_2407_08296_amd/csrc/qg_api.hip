@@ -32,8 +32,8 @@ int launch_adam_many(const PlanHeader*, const PlanHeader*, int64_t, const qg_hpa
 int launch_project_adam(const uint8_t*, const float*, const uint16_t*, float*, float*, float*, uint16_t*, int64_t, int64_t,
                         int64_t, int64_t, const qg_hparams*, hipStream_t);
 int launch_project_adam_many(const PlanHeader*, const PlanHeader*, int, int64_t, const qg_hparams*, hipStream_t);
-int project_mode(int64_t m, int64_t n, int64_t r);       // edge class the grouped projection needs for a matrix
-int backproject_mode(int64_t m, int64_t n, int64_t r);   // ... and the grouped back-projection
+int project_mode(int64_t m, int64_t n, int64_t ld, int64_t r);       // edge class the grouped projection needs for a matrix
+int backproject_mode(int64_t m, int64_t n, int64_t ld, int64_t r);   // ... and the grouped back-projection
 constexpr int kAdamChunkElems = 256 * 4 * 4;  // must equal kAdamChunk of qg_adam.hip
 
 static int check_mnr(int64_t m, int64_t n, int64_t r, int group) {
@@ -137,12 +137,15 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
         if (!d.Pq || !d.Ps || !d.G || !d.Wq || !d.Ws || !d.M || !d.V || !d.N) return QG_ERR_NULL;
         if (!d.R) h.no_R = 1;   // the unfused phases cannot run on this plan
         if (int e = check_mnr(d.m, d.n, d.r, kGroup)) return e;
+        // a row pitch other than n: at least n, rows 16-byte aligned in every array, m * ld inside the 32-bit range
+        if (d.ld != 0 && d.ld != d.n && (d.ld < d.n || (d.ld & 15) || d.m * d.ld >= (int64_t(1) << 32))) return QG_ERR_SHAPE;
         if (!aligned16(d.Pq) || !aligned16(d.Ps) || !aligned16(d.G) || !aligned16(d.Wq) || !aligned16(d.Ws) ||
             !aligned16(d.M) || !aligned16(d.V) || (d.R && !aligned16(d.R)) || !aligned16(d.N))
             return QG_ERR_ALIGN;
     }
     auto matrix_class = [](const qg_matrix_desc& d) {
-        const int a = project_mode(d.m, d.n, d.r), b = backproject_mode(d.m, d.n, d.r);
+        const int64_t ld = d.ld ? d.ld : d.n;
+        const int a = project_mode(d.m, d.n, ld, d.r), b = backproject_mode(d.m, d.n, ld, d.r);
         return a > b ? a : b;
     };
     uint64_t adam = 0, proj[kPlanClasses] = {0, 0, 0}, bp[kPlanClasses] = {0, 0, 0};
@@ -154,6 +157,7 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
             PlanMatrix pm;
             std::memset(&pm, 0, sizeof pm);
             pm.m = d.m; pm.n = d.n; pm.r = d.r;
+            pm.ld = d.ld ? d.ld : d.n;
             pm.Pq = d.Pq; pm.Ps = d.Ps; pm.G = d.G; pm.Wq = d.Wq; pm.Ws = d.Ws;
             pm.M = d.M; pm.V = d.V; pm.R = d.R; pm.N = d.N;
             pm.index = (uint32_t)i;
@@ -162,7 +166,7 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
             pm.bp_tile0 = (uint32_t)bp[cls];
             pm.proj_tiles_r = (uint32_t)((d.r + kManyProjBM - 1) / kManyProjBM);
             pm.bp_tiles_m = (uint32_t)((d.m + kManyBpBM - 1) / kManyBpBM);
-            adam += (uint64_t)((d.r * d.n + kAdamChunkElems - 1) / kAdamChunkElems);
+            adam += (uint64_t)((d.r * pm.ld + kAdamChunkElems - 1) / kAdamChunkElems);
             proj[cls] += (uint64_t)pm.proj_tiles_r * (uint64_t)((d.n + kManyProjBN - 1) / kManyProjBN);
             bp[cls] += (uint64_t)pm.bp_tiles_m * (uint64_t)((d.n + kManyBpBN - 1) / kManyBpBN);
             mats[out++] = pm;

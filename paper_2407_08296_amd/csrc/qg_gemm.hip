@@ -9,15 +9,17 @@ namespace qg {
 static inline unsigned grid8(uint32_t tiles) { return ((tiles + 7u) / 8u) * 8u; }
 
 // Edge mode of a matrix for tiles of TM (along r for the projection, along m for the back-projection) x TN and K
-// steps of BK over `kdim`.  The direct loads need 16-byte aligned rows (n % 8, and r % 16 for the 8-byte P fetches)
-// and 32-bit per-lane offsets.
-static inline int edge_mode(int64_t tiled, int TM, int64_t n, int TN, int64_t kdim, int BK, int64_t r) {
-    if (n > (int64_t(1) << 24) || (n % 8) != 0 || (r % 16) != 0) return kUnaligned;
+// steps of BK over `kdim`; ld is the row pitch of the n-wide arrays.  The direct loads need 16-byte aligned rows
+// (ld % 8, and r % 16 for the 8-byte P fetches) and 32-bit per-lane offsets.
+static inline int edge_mode(int64_t tiled, int TM, int64_t n, int64_t ld, int TN, int64_t kdim, int BK, int64_t r) {
+    if (ld > (int64_t(1) << 24) || (ld % 8) != 0 || (r % 16) != 0) return kUnaligned;
     if ((tiled % TM) == 0 && (n % TN) == 0 && (kdim % BK) == 0) return kExact;
     return kMasked;
 }
-int project_mode(int64_t m, int64_t n, int64_t r) { return edge_mode(r, kManyProjBM, n, kManyProjBN, m, 32, r); }
-int backproject_mode(int64_t m, int64_t n, int64_t r) { return edge_mode(m, kManyBpBM, n, kManyBpBN, r, 32, r); }
+int project_mode(int64_t m, int64_t n, int64_t ld, int64_t r) { return edge_mode(r, kManyProjBM, n, ld, kManyProjBN, m, 32, r); }
+int backproject_mode(int64_t m, int64_t n, int64_t ld, int64_t r) {
+    return edge_mode(m, kManyBpBM, n, ld, kManyBpBN, r, 32, r);
+}
 
 template <int BM, int BN, int BK, int WGM, int WGN, int MINWG>
 static int launch_project_cfg(const uint8_t* Pq, const float* Ps, const uint16_t* G, float* R, int m, int n, int r,
@@ -25,7 +27,7 @@ static int launch_project_cfg(const uint8_t* Pq, const float* Ps, const uint16_t
     const uint32_t tiles_r = (uint32_t)((r + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
     const uint32_t tiles = tiles_r * tiles_n;
     const dim3 grid(grid8(tiles)), block(WGM * WGN * 64);
-    switch (edge_mode(r, BM, n, BN, m, BK, r)) {
+    switch (edge_mode(r, BM, n, n, BN, m, BK, r)) {
         case kExact:
             hipLaunchKernelGGL((k_project<BM, BN, BK, WGM, WGN, kExact, MINWG>), grid, block, 0, stream, Pq, Ps, G, R, m,
                                n, r, tiles_r, tiles);
@@ -47,7 +49,7 @@ static int launch_project_adam_cfg(const uint8_t* Pq, const float* Ps, const uin
     const uint32_t tiles_r = (uint32_t)((r + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
     const uint32_t tiles = tiles_r * tiles_n;
     const dim3 grid(grid8(tiles)), block(WGM * WGN * 64);
-    switch (edge_mode(r, BM, n, BN, m, BK, r)) {
+    switch (edge_mode(r, BM, n, n, BN, m, BK, r)) {
         case kExact:
             hipLaunchKernelGGL((k_project_adam<BM, BN, BK, WGM, WGN, kExact, MINWG>), grid, block, 0, stream, Pq, Ps, G,
                                R, M, V, N, m, n, r, tiles_r, tiles, coef);
@@ -127,7 +129,7 @@ static int launch_backproject_cfg(const uint8_t* Pq, const float* Ps, const uint
 #define QG_LAUNCH_BP(MODE, DUMP)                                                                                    \
     hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, MODE, DUMP, PREF, kBpWgPerCu[MODE]>), grid, block, 0, stream, \
                        Pq, Ps, N, Wq, Ws, Udbg, m, n, r, alpha, lr, key, tiles_m, tiles)
-    switch (edge_mode(m, BMm, n, kGroup, r, BK, r)) {
+    switch (edge_mode(m, BMm, n, n, kGroup, r, BK, r)) {
         case kExact:
             if (Udbg) QG_LAUNCH_BP(kExact, true); else QG_LAUNCH_BP(kExact, false);
             break;

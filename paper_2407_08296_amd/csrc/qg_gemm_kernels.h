@@ -215,7 +215,7 @@ struct ProjShape {
 template <int BM, int BN, int BK, int WGM, int WGN, int MODE, bool FUSE_ADAM = false>
 __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
                                              const uint16_t* __restrict__ G, float* __restrict__ R, int m, int n,
-                                             int r, int r0, int n0, uint16_t* smem, float* __restrict__ Mo = nullptr,
+                                             int ld, int r, int r0, int n0, uint16_t* smem, float* __restrict__ Mo = nullptr,
                                              float* __restrict__ Vo = nullptr, uint16_t* __restrict__ No = nullptr,
                                              const AdamCoef* coef = nullptr) {
     constexpr bool RAGGED = MODE != kExact;      // masked epilogue
@@ -257,10 +257,10 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
     for (int p = 0; p < B_OFFS; ++p) {
         if constexpr (DIRECT) {
-            b_byte[p] = BD::lane_src_bytes(lane, n, p);
+            b_byte[p] = BD::lane_src_bytes(lane, ld, p);
         } else {
             const int ci = t + p * NT;
-            b_byte[p] = 2u * (uint32_t)((ci / BD::CPR) * n + (ci % BD::CPR) * 8);
+            b_byte[p] = 2u * (uint32_t)((ci / BD::CPR) * ld + (ci % BD::CPR) * 8);
         }
     }
 
@@ -271,7 +271,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
         const int64_t e0 = (int64_t)i0 * r;
         const uint8_t* pq = Pq + (e0 >> 1);
         const float* ps = Ps + (e0 >> 8);
-        const uint8_t* g = reinterpret_cast<const uint8_t*>(G + (int64_t)i0 * n + n0);
+        const uint8_t* g = reinterpret_cast<const uint8_t*>(G + (int64_t)i0 * ld + n0);
         if constexpr (DIRECT) {
             __amdgpu_buffer_rsrc_t rq, rs, rg;
             if constexpr (MODE == kExact) {
@@ -280,12 +280,12 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
                 const int64_t mr = (int64_t)m * r;
                 rq = make_rsrc(pq, bound_bytes((mr - e0) >> 1));
                 rs = make_rsrc(ps, bound_bytes((((mr + kGroup - 1) >> 8) - (e0 >> 8)) * 4));
-                rg = make_rsrc(g, bound_bytes(((int64_t)(m - i0) * n - n0) * 2));
+                rg = make_rsrc(g, bound_bytes(((int64_t)(m - i0) * ld - n0) * 2));
             }
 #pragma unroll
             for (int p = 0; p < B_PER; ++p)
                 buffer_load_lds16(rg, Bs + stage * S::B_STAGE + BD::load_row0(wave, p) * BN, b_byte[p % BD::VARIANTS],
-                                  2u * (uint32_t)(BD::load_row0(wave, p) * n));
+                                  2u * (uint32_t)(BD::load_row0(wave, p) * ld));
 #pragma unroll
             for (int p = 0; p < A_PER; ++p) {
                 buffer_load_words<WPT>(rq, a_el[p] >> 1, aw[p]);
@@ -398,21 +398,21 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int col = wn * WN + b * 32 + lcol;   // inside the tile
-            voff[b] = (!RAGGED || n0 + col < n) ? 4u * (uint32_t)(4 * lhalf * n + col) : 0x80000000u;
+            voff[b] = (!RAGGED || n0 + col < n) ? 4u * (uint32_t)(4 * lhalf * ld + col) : 0x80000000u;
         }
 #pragma unroll
         for (int a = 0; a < MB; ++a) {
             const int row0 = r0 + wm * WM + a * 32;
-            float* base = R + (int64_t)row0 * n + n0;
+            float* base = R + (int64_t)row0 * ld + n0;
             const __amdgpu_buffer_rsrc_t rr =
-                RAGGED ? make_rsrc(base, row0 < r ? bound_bytes(((int64_t)(r - row0) * n - n0) * 4) : 0) : make_rsrc(base);
+                RAGGED ? make_rsrc(base, row0 < r ? bound_bytes(((int64_t)(r - row0) * ld - n0) * 4) : 0) : make_rsrc(base);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const float x = acc[a][b][v];   // (a copy: bit_cast of a vector element lvalue reads element 0)
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, x), rr, voff[b],
-                                                          4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n), kAuxStream);
+                                                          4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * ld), kAuxStream);
                 }
         }
     } else if constexpr (DIRECT) {
@@ -431,14 +431,17 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
         for (int b = 0; b < NB; ++b) {
             const int col = wn * WN + b * 32 + lcol;   // inside the tile
             const bool ok = !RAGGED || n0 + col < n;
-            voff[b] = ok ? 4u * (uint32_t)(4 * lhalf * n + col) : 0x80000000u;
-            voffn[b] = ok ? 2u * (uint32_t)(4 * lhalf * n + col + (odd ? n - 1 : 0)) : 0x80000000u;
+            voff[b] = ok ? 4u * (uint32_t)(4 * lhalf * ld + col) : 0x80000000u;
+            // a pair is stored if its first (even) column is a real one: with an odd n (possible only with a row pitch
+            // ld > n) the pair of column n - 1 also covers the first padding column
+            const bool okn = !RAGGED || n0 + (col & ~1) < n;
+            voffn[b] = okn ? 2u * (uint32_t)(4 * lhalf * ld + col + (odd ? ld - 1 : 0)) : 0x80000000u;
         }
 #pragma unroll
         for (int a = 0; a < MB; ++a) {
             const int row0 = r0 + wm * WM + a * 32;
-            const int64_t e0 = (int64_t)row0 * n + n0;
-            const int left4 = RAGGED ? (row0 < r ? bound_bytes(((int64_t)(r - row0) * n - n0) * 4) : 0) : 0x7FFFFFFF;
+            const int64_t e0 = (int64_t)row0 * ld + n0;
+            const int left4 = RAGGED ? (row0 < r ? bound_bytes(((int64_t)(r - row0) * ld - n0) * 4) : 0) : 0x7FFFFFFF;
             const __amdgpu_buffer_rsrc_t rm = make_rsrc(Mo + e0, left4), rv = make_rsrc(Vo + e0, left4);
             const bool write_R = R != nullptr;
             const __amdgpu_buffer_rsrc_t rr = make_rsrc(write_R ? R + e0 : Mo + e0, write_R ? left4 : 0);
@@ -451,7 +454,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
                     for (int q = 0; q < 8; ++q) {
                         const int v = 8 * h + q;
-                        const uint32_t so = 4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n);
+                        const uint32_t so = 4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * ld);
                         mm[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, voff[b], so, kAuxStream));
                         vv[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, voff[b], so, kAuxStream));
                     }
@@ -461,7 +464,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
                         for (int e = 0; e < 2; ++e) {
                             const int v = 8 * h + q + e;
-                            const uint32_t so = 4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n);
+                            const uint32_t so = 4u * (uint32_t)((8 * (v >> 2) + (v & 3)) * ld);
                             const float rr_ = acc[a][b][v];
                             nn[e] = adam_one(rr_, mm[q + e], vv[q + e], c);
                             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, mm[q + e]), rm, voff[b], so, kAuxStream);
@@ -477,7 +480,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
                         const uint32_t nbr = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1, 0xF, 0xF, true);
                         const uint32_t pk = __builtin_amdgcn_perm(nbr, own, pair_sel);
                         __builtin_amdgcn_raw_buffer_store_b32(pk, rn, voffn[b],
-                                                              2u * (uint32_t)((8 * (v >> 2) + (v & 3)) * n), kAuxStream);
+                                                              2u * (uint32_t)((8 * (v >> 2) + (v & 3)) * ld), kAuxStream);
                     }
                 }
         }
@@ -491,7 +494,7 @@ __device__ __forceinline__ void project_tile(const uint8_t* __restrict__ Pq, con
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = r0 + wm * WM + a * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                    const int64_t off = (int64_t)row * n + col;
+                    const int64_t off = (int64_t)row * ld + col;
                     if (row < r && col < n) {
                         const float rr_ = acc[a][b][v];
                         float mm = Mo[off], vv = Vo[off];
@@ -514,7 +517,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project(const 
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    project_tile<BM, BN, BK, WGM, WGN, MODE>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
+    project_tile<BM, BN, BK, WGM, WGN, MODE>(Pq, Ps, G, R, m, n, n, r, (int)(tile % tiles_r) * BM,
                                                (int)(tile / tiles_r) * BN, smem);
 }
 
@@ -526,7 +529,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam(
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    project_tile<BM, BN, BK, WGM, WGN, MODE, true>(Pq, Ps, G, R, m, n, r, (int)(tile % tiles_r) * BM,
+    project_tile<BM, BN, BK, WGM, WGN, MODE, true>(Pq, Ps, G, R, m, n, n, r, (int)(tile % tiles_r) * BM,
                                                      (int)(tile / tiles_r) * BN, smem, M, V, N, &coef);
 }
 
@@ -549,7 +552,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(c
     const PlanMatrix* mats = plan_matrices(plan) + first;
     const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
     const uint32_t local = tile - d.proj_tile0;
-    project_tile<BM, BN, BK, WGM, WGN, MODE>(d.Pq, d.Ps, d.G, d.R, (int)d.m, (int)d.n, (int)d.r,
+    project_tile<BM, BN, BK, WGM, WGN, MODE>(d.Pq, d.Ps, d.G, d.R, (int)d.m, (int)d.n, (int)d.ld, (int)d.r,
                                                (int)(local % d.proj_tiles_r) * BM,
                                                (int)(local / d.proj_tiles_r) * BN, smem);
 }
@@ -566,7 +569,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam_m
     const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.proj_tile0; })];
     const uint32_t local = tile - d.proj_tile0;
     project_tile<BM, BN, BK, WGM, WGN, MODE, true>(d.Pq, d.Ps, d.G, write_R ? d.R : nullptr, (int)d.m, (int)d.n,
-                                                     (int)d.r, (int)(local % d.proj_tiles_r) * BM,
+                                                     (int)d.ld, (int)d.r, (int)(local % d.proj_tiles_r) * BM,
                                                      (int)(local / d.proj_tiles_r) * BN, smem, d.M, d.V, d.N, &coef);
 }
 
@@ -613,8 +616,8 @@ __device__ __forceinline__ constexpr int wtile_run_bits(int a, int v4) {
 template <int BMm, int BK, int WGn, int WGm, int MODE, bool DUMP_U, bool W_PREFETCH = true>
 __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
                                                  const uint16_t* __restrict__ N, int8_t* __restrict__ Wq,
-                                                 float* __restrict__ Ws, float* __restrict__ Udbg, int m, int n, int r,
-                                                 int m0, int tile_n, float alpha, float lr, uint32_t key,
+                                                 float* __restrict__ Ws, float* __restrict__ Udbg, int m, int n, int ld,
+                                                 int r, int m0, int tile_n, float alpha, float lr, uint32_t key,
                                                  uint16_t* smem) {
     constexpr bool RAGGED = MODE != kExact;      // masked epilogue
     constexpr bool DIRECT = MODE != kUnaligned;  // buffer / direct-to-LDS loads; a P fetch (8*WPT codes) starts at a
@@ -645,14 +648,14 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
 
     // ---- weight tile -> LDS (asynchronous direct loads where shapes allow) ----
     // whole tile inside the matrix and rows 16-byte aligned: the direct loads work in the edge-checking kernels too
-    const bool w_fast = !RAGGED || (m0 + BMm <= m && n0 + BNn <= n && (n & 15) == 0);
+    const bool w_fast = !RAGGED || (m0 + BMm <= m && n0 + BNn <= n && (ld & 15) == 0);
     auto load_wtile = [&]() {
     if (w_fast) {
 #pragma unroll
         for (int i = 0; i < W_ROUNDS; ++i) {
             const int rb = (wave * W_ROUNDS + i) * 4;             // first of the 4 rows this wave access covers
             const int row = rb + (lane >> 4), chunk = (lane ^ row) & 15;
-            const int8_t* src = Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16;
+            const int8_t* src = Wq + (int64_t)(m0 + row) * ld + n0 + chunk * 16;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(wt + rb * kGroup), 16, 0, 0);
         }
@@ -663,7 +666,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         for (int i = 0; i < W_ROUNDS; ++i) {
             const int rb = (wave * W_ROUNDS + i) * 4;
             const int row = rb + (lane >> 4), chunk = (lane ^ row) & 15;
-            const int8_t* src = Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16;
+            const int8_t* src = Wq + (int64_t)(m0 + row) * ld + n0 + chunk * 16;
             const int valid = m0 + row < m ? n - (n0 + chunk * 16) : 0;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (valid >= 16) {
@@ -693,10 +696,10 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
 #pragma unroll
     for (int p = 0; p < A_OFFS; ++p) {
         if constexpr (DIRECT) {
-            a_byte[p] = AD::lane_src_bytes(lane, n, p);
+            a_byte[p] = AD::lane_src_bytes(lane, ld, p);
         } else {
             const int ci = t + p * NT;
-            a_byte[p] = 2u * (uint32_t)((ci / AD::CPR) * n + (ci % AD::CPR) * 8);
+            a_byte[p] = 2u * (uint32_t)((ci / AD::CPR) * ld + (ci % AD::CPR) * 8);
         }
     }
 #pragma unroll
@@ -710,7 +713,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     // into registers.
     auto gload = [&](int kt, int stage) {
         const int k0 = kt * BK;
-        const uint8_t* nb = reinterpret_cast<const uint8_t*>(N + (int64_t)k0 * n + n0);
+        const uint8_t* nb = reinterpret_cast<const uint8_t*>(N + (int64_t)k0 * ld + n0);
         const uint8_t* pq = Pq + ((e_tile + k0) >> 1);
         const float* ps = Ps + (e_tile >> 8);
         if constexpr (DIRECT) {
@@ -719,14 +722,14 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
                 rn = make_rsrc(nb); rq = make_rsrc(pq); rs = make_rsrc(ps);
             } else {   // bounded by the end of each array: rows of N at or past r read as zero (the K tail)
                 const int64_t mr = (int64_t)m * r;
-                rn = make_rsrc(nb, bound_bytes(((int64_t)(r - k0) * n - n0) * 2));
+                rn = make_rsrc(nb, bound_bytes(((int64_t)(r - k0) * ld - n0) * 2));
                 rq = make_rsrc(pq, bound_bytes((mr - e_tile - k0) >> 1));
                 rs = make_rsrc(ps, bound_bytes((((mr + kGroup - 1) >> 8) - (e_tile >> 8)) * 4));
             }
 #pragma unroll
             for (int p = 0; p < A_PER; ++p)
                 buffer_load_lds16(rn, As + stage * S::A_STAGE + AD::load_row0(wave, p) * BNn, a_byte[p % AD::VARIANTS],
-                                  2u * (uint32_t)(AD::load_row0(wave, p) * n));
+                                  2u * (uint32_t)(AD::load_row0(wave, p) * ld));
 #pragma unroll
             for (int p = 0; p < B_PER; ++p) {
                 buffer_load_words<WPT>(rq, b_el[p] >> 1, bw[p]);
@@ -880,6 +883,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         const float inv = amax > 0.f ? 127.0f / amax : 0.f;
         if (wn == 0 && lhalf == 0 && row_ok) Ws[(int64_t)mrow * ng + tile_n] = s_new;
         const uint32_t idx_row = (uint32_t)mrow * (uint32_t)n + (uint32_t)n0;   // m*n < 2^32
+        const bool xor_ok = MODE == kExact || (DIRECT && (n & 3) == 0);   // wave-uniform
         const int wt_lane = wtile_offset(rl, wn * SN + 4 * lhalf);
 #pragma unroll
         for (int a = 0; a < IB; ++a)
@@ -887,14 +891,14 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
             for (int v4 = 0; v4 < 4; ++v4) {
                 const int col = wn * SN + a * 32 + 8 * v4 + 4 * lhalf;
                 uint32_t pk = 0;
-                // with aligned rows the run's first element index is a multiple of 4: index + e == index | e, and
+                // when n is a multiple of 4 the run's first element index is one too: index + e == index | e, and
                 // key ^ (index | e) == (key ^ index) ^ e, one xor per element instead of an add and an xor
-                const uint32_t run_key = key ^ (idx_row + (uint32_t)col);
+                const uint32_t run_idx = idx_row + (uint32_t)col;
+                const uint32_t run_key = key ^ run_idx;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float tq = acc[a][b][4 * v4 + e] * inv;
-                    const uint32_t h = DIRECT ? mix32(run_key ^ (uint32_t)e)
-                                              : mix32(key ^ (idx_row + (uint32_t)(col + e)));
+                    const uint32_t h = mix32(xor_ok ? run_key ^ (uint32_t)e : key ^ (run_idx + (uint32_t)e));
                     // fl32(tq + u) with u = (h >> 8) * 2^-24: the product is exact, so one fma rounds the same sum
                     const float v = __builtin_fmaf((float)(h >> 8), 0x1p-24f, tq);
                     // clamp(floor(v), -128, 127) as a byte: the saturating float -> u8 conversion of floor(v) + 128
@@ -913,14 +917,14 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         for (int i = 0; i < W_ROUNDS; ++i) {
             const int row = (wave * W_ROUNDS + i) * 4 + (lane >> 4), chunk = (lane ^ row) & 15;
             const u32x4 v = *reinterpret_cast<const u32x4*>(wt + row * kGroup + (lane & 15) * 16);
-            *reinterpret_cast<u32x4*>(Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16) = v;
+            *reinterpret_cast<u32x4*>(Wq + (int64_t)(m0 + row) * ld + n0 + chunk * 16) = v;
         }
     } else {
 #pragma unroll
         for (int i = 0; i < W_ROUNDS; ++i) {
             const int row = (wave * W_ROUNDS + i) * 4 + (lane >> 4), chunk = (lane ^ row) & 15;
             const u32x4 v = *reinterpret_cast<const u32x4*>(wt + row * kGroup + (lane & 15) * 16);
-            int8_t* dst = Wq + (int64_t)(m0 + row) * n + n0 + chunk * 16;
+            int8_t* dst = Wq + (int64_t)(m0 + row) * ld + n0 + chunk * 16;
             const int valid = m0 + row < m ? n - (n0 + chunk * 16) : 0;
             if (valid >= 16) {
                 *reinterpret_cast<u32x4_align1*>(dst) = v;
@@ -944,7 +948,7 @@ __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject(co
     __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    backproject_tile<BMm, BK, WGn, WGm, MODE, DUMP_U, W_PREFETCH>(Pq, Ps, N, Wq, Ws, Udbg, m, n, r, (int)(tile % tiles_m) * BMm,
+    backproject_tile<BMm, BK, WGn, WGm, MODE, DUMP_U, W_PREFETCH>(Pq, Ps, N, Wq, Ws, Udbg, m, n, n, r, (int)(tile % tiles_m) * BMm,
                                                 (int)(tile / tiles_m), alpha, lr, key, smem);
 }
 
@@ -960,7 +964,7 @@ __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_ma
     const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.bp_tile0; })];
     const uint32_t local = tile - d.bp_tile0;
     const uint32_t key = sr_key(seed + (uint64_t)d.index * 0x9E3779B97F4A7C15ull, step, 0u);
-    backproject_tile<BMm, BK, WGn, WGm, MODE, false, W_PREFETCH>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.r,
+    backproject_tile<BMm, BK, WGn, WGm, MODE, false, W_PREFETCH>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.ld, (int)d.r,
                                                 (int)(local % d.bp_tiles_m) * BMm, (int)(local / d.bp_tiles_m),
                                                 alpha, lr, key, smem);
 }

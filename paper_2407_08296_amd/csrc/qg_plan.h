@@ -18,6 +18,7 @@ constexpr int kManyBpBN = 256;    // columns of W (n) per tile = one quantizatio
 
 struct PlanMatrix {
     int64_t m, n, r;
+    int64_t ld;             // row pitch in elements of W, G, R, M, V, N (>= n)
     const uint8_t* Pq;
     const float* Ps;
     const uint16_t* G;

@@ -47,7 +47,7 @@ class Policy(C.Structure):
 class MatrixDesc(C.Structure):
     _fields_ = [("m", C.c_int64), ("n", C.c_int64), ("r", C.c_int64),
                 ("Pq", C.c_void_p), ("Ps", C.c_void_p), ("G", C.c_void_p), ("Wq", C.c_void_p), ("Ws", C.c_void_p),
-                ("M", C.c_void_p), ("V", C.c_void_p), ("R", C.c_void_p), ("N", C.c_void_p)]
+                ("M", C.c_void_p), ("V", C.c_void_p), ("R", C.c_void_p), ("N", C.c_void_p), ("ld", C.c_int64)]
 
 
 class RefreshDesc(C.Structure):
@@ -245,6 +245,7 @@ class MatrixState:
     V: torch.Tensor
     R: torch.Tensor | None
     N: torch.Tensor
+    ld: int = 0   # row pitch in elements of G, Wq, M, V, R, N; 0 = n
 
 
 class StepPlan:
@@ -260,6 +261,7 @@ class StepPlan:
             d.Wq, d.Ws = _ptr(s.Wq, (torch.int8,)), _ptr(s.Ws, (torch.float32,))
             d.M, d.V, d.R = _ptr(s.M, (torch.float32,)), _ptr(s.V, (torch.float32,)), _ptr(s.R, (torch.float32,))
             d.N = _ptr(s.N, _BF16)
+            d.ld = s.ld
         self.nbytes = lib().qg_plan_bytes(self.count, descs)
         self.host = torch.empty((self.nbytes,), dtype=torch.uint8).pin_memory()
         _check(lib().qg_plan_build(self.count, descs, self.host.data_ptr(), self.nbytes))

@@ -170,6 +170,18 @@ def test_plan_build_on_host(L):
     hdr = (C.c_uint32 * 16).from_buffer(buf)
     assert list(hdr[4:7]) == [1, 1, 0]
     assert list(hdr[7:10]) == [8 * 16, 8 * 11, 0] and list(hdr[10:13]) == [32 * 16, 86 * 11, 0]
+    descs[1].n, descs[1].ld = 5461, 5472                     # the same odd n with a row pitch: aligned rows, masked class
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 0
+    hdr = (C.c_uint32 * 16).from_buffer(buf)
+    assert list(hdr[4:7]) == [1, 1, 0]
+    assert hdr[2] == (1024 * 4096 + 1024 * 5472) // 4096     # the unfused Adam runs over the padding too
+    assert list(hdr[7:10]) == [8 * 16, 8 * 22, 0] and list(hdr[10:13]) == [32 * 16, 86 * 22, 0]
+    for bad in (5460, 5464, 5461 + 7):                       # below n; not a multiple of 16 (twice)
+        descs[1].ld = bad
+        assert L.qg_plan_build(2, descs, buf, nbytes) == 2
+    descs[1].ld = 5461                                       # ld == n is the dense layout
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 0
+    descs[1].ld = 0
     descs[1].n = 5461
     descs[1].r = 12
     assert L.qg_plan_build(2, descs, buf, nbytes) == 2

@@ -492,3 +492,85 @@ def test_diag_clock_probe_and_mfma_loop():
         torch.cuda.synchronize()
         assert flop == qg.DIAG_MFMA_WORKGROUPS * 8 * 8 * 16 * 32768.0
         assert bool(torch.isfinite(sink).all())
+
+
+# ------------------------------------------------------------------ padded rows (row pitch ld > n)
+def _pitched(a, ld, fill):
+    """(rows, n) host array -> (rows, ld) device tensor whose padding columns hold `fill`."""
+    a = np.asarray(a)
+    out = np.full((a.shape[0], ld), fill, dtype=a.dtype)
+    out[:, :a.shape[1]] = a
+    return dev(out)
+
+
+_NAN_BF16 = np.int16(0x7FC0)
+
+
+def _pitched_state(shapes_ld):
+    mats, data = [], []
+    for li, (m, n, r, ld) in enumerate(shapes_ld):
+        d = make_inputs(m, n, r, layer=li)
+        data.append(d)
+        G = _pitched(np.asarray(d["Gb"]).view(np.int16).reshape(m, n), ld, _NAN_BF16)
+        mats.append(qg.MatrixState(m, n, r, dev(d["Pq"]), dev(d["Ps"]), G, _pitched(d["Wq"].reshape(m, n), ld, 85),
+                                   dev(d["Ws"]),
+                                   _pitched(np.zeros((r, n), np.float32), ld, 777.0),
+                                   _pitched(np.zeros((r, n), np.float32), ld, 777.0),
+                                   _pitched(np.zeros((r, n), np.float32), ld, np.nan),
+                                   _pitched(np.zeros((r, n), np.int16), ld, 0x1234), ld=ld))
+    return mats, data
+
+
+@pytest.mark.parametrize("shapes_ld", [
+    [(333, 261, 144, 272), (512, 1365, 128, 1376)],      # odd n: the pitch moves them to the aligned, masked class
+    [(768, 768, 256, 800), (333, 264, 144, 288)],        # whole tiles with a pitch; aligned rows, a wider pitch
+    [(300, 700, 40, 704), (200, 517, 48, 528)],          # r % 16 != 0 keeps the general path; edges everywhere
+])
+def test_step_many_with_row_pitch(shapes_ld):
+    """A row pitch ld > n (the descriptor's `ld`): results equal the oracle's on the n real columns, the padding of the
+    weight, the moments and the outputs keeps its fill (whatever the gradient's padding holds: NaN here), and where the
+    dense layout runs in the same kernel class the two are bit-identical.  (N is stored as pairs of columns: with an
+    odd n the first padding column of N is overwritten.)"""
+    mats, data = _pitched_state(shapes_ld)
+    dense, _ = _state_for([(m, n, r) for m, n, r, _ in shapes_ld])
+    seed = 33
+    qg.step_many(qg.StepPlan(mats), qg.hparams(), seed, 1)
+    qg.step_many(qg.StepPlan(dense), qg.hparams(), seed, 1)
+    torch.cuda.synchronize()
+    for i, (s, dn, d) in enumerate(zip(mats, dense, data)):
+        n = s.n
+        o = Q.step(d["Wq"], d["Ws"], d["Gb"], d["Pq"], d["Ps"], np.zeros((s.r, n)), np.zeros((s.r, n)), 1, HP,
+                   seed=(seed + i * 0x9E3779B97F4A7C15) % 2 ** 64, r=s.r)
+        assert rel_fro(host(s.R[:, :n]), o["R"]) <= 2e-5
+        assert rel_fro(bf16_t_to_f64(s.N.view(torch.bfloat16)[:, :n].contiguous()), o["Nb"]) <= 1e-3
+        assert rel_fro(host(s.M[:, :n]), o["M"]) <= 2e-5 and rel_fro(host(s.V[:, :n]), o["V"]) <= 4e-5
+        check_codes(host(s.Wq[:, :n]), o["Wq"].reshape(s.m, n))
+        check_scales_step(host(s.Ws), o["Ws"], rel=5e-4)     # a first step from zero moments
+        # padding untouched
+        assert torch.all(s.Wq[:, n:] == 85) and torch.all(s.M[:, n:] == 777.0) and torch.all(s.V[:, n:] == 777.0)
+        assert torch.all(s.N[:, n + n % 2:] == 0x1234) and torch.all(torch.isnan(s.R[:, n:]))   # N goes out in pairs
+        if n % 8 == 0:   # same edge class with and without the pitch: same kernels, same arithmetic
+            assert torch.equal(s.Wq[:, :n], dn.Wq.view(s.m, n)) and torch.equal(s.Ws, dn.Ws)
+            assert torch.equal(s.M[:, :n], dn.M) and torch.equal(s.R[:, :n], dn.R)
+        else:
+            check_codes(host(s.Wq[:, :n]), host(dn.Wq).reshape(s.m, n))
+
+
+def test_unfused_phases_with_row_pitch():
+    """project_many -> lowrank_adam_many -> backproject_update_sr_many on pitched arrays give the fused step's state on
+    the real columns (the unfused Adam also runs over the padding, which nothing reads)."""
+    shapes_ld = [(333, 261, 144, 272), (768, 768, 256, 800), (300, 700, 40, 704)]
+    a, _ = _pitched_state(shapes_ld)
+    b, _ = _pitched_state(shapes_ld)
+    hp = qg.hparams()
+    qg.step_many(qg.StepPlan(a), hp, 5, 2)
+    pb = qg.StepPlan(b)
+    qg.project_many(pb)
+    qg.lowrank_adam_many(pb, hp, 2)
+    qg.backproject_update_sr_many(pb, hp, 5, 2)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        n = x.n
+        assert torch.equal(x.R[:, :n], y.R[:, :n]) and torch.equal(x.M[:, :n], y.M[:, :n])
+        assert torch.equal(x.V[:, :n], y.V[:, :n]) and torch.equal(x.N[:, :n], y.N[:, :n])
+        assert torch.equal(x.Wq, y.Wq) and torch.equal(x.Ws, y.Ws)
