@@ -472,6 +472,71 @@ def int8_linear_backward(dy_bits, x_bits, Wq, Ws):
 
 
 # --------------------------------------------------------------------------
+# Right-side projection.  The paper takes its projection from GaLore (Sec. 2,
+# Sec. 3.5), which projects a gradient from the left (R = P^T G, the form of
+# `step`) or from the right (R = G Q with Q the first r RIGHT singular
+# vectors, n x r; moments m x r; update alpha N Q^T).  Neither paper fixes the
+# memory layout of a weight.  The reading taken here: a matrix that is
+# projected from the right keeps its weight TRANSPOSED, S = W^T (n x m, INT8,
+# blocks of 256 along each row of S, i.e. along a column of W), so that its
+# blocks, its stochastic-rounding stream (element index j*m + i of S) and its
+# kernels are those of a left-projected n x m matrix.  The functions below
+# are written in the right-side form on the logical m x n matrix; that they
+# agree with `step` on the transposed arrays is a test, not an assumption.
+# Parity unpinned against the paper (it prints no right-side formula).
+# --------------------------------------------------------------------------
+def project_right(Qq, Qs, G_bits, m: int, n: int, r: int) -> np.ndarray:
+    """R = G Q (m x r): Q the INT4 n x r projection matrix, dequantized like P."""
+    Qd = dequant_p_bf16(Qq, Qs, n, r)
+    G = bf16_bits_to_f64(np.asarray(G_bits).reshape(m, n))
+    return G @ Qd
+
+
+def backproject_right(Qq, Qs, Nb, n: int, r: int, alpha: float) -> np.ndarray:
+    """U = alpha * N Q^T (m x n), Nb (m x r) being N already rounded to bf16."""
+    Qd = dequant_p_bf16(Qq, Qs, n, r)
+    return float(np.float32(alpha)) * (np.asarray(Nb, dtype=np.float64) @ Qd.T)
+
+
+def step_right(Sq, Ss, G_bits, Qq, Qs, M, V, t: int, hp: HParams, seed: int, r: int) -> dict:
+    """One step on a matrix projected from the right.  Sq, Ss: the weight as
+    stored, S = W^T (n x m codes, n x ceil(m/256) scales); G_bits: the gradient
+    of the logical weight W (m x n); M, V: moments m x r.  Returns R, M, V, N
+    (m x r), U (m x n) and the new stored codes and scales (of S)."""
+    Sq = np.asarray(Sq)
+    n, m = Sq.shape
+    R = project_right(Qq, Qs, G_bits, m, n, r)
+    M1, V1, N = lowrank_adam(R, M, V, t, hp)
+    Nb = bf16_rne(N)
+    U = backproject_right(Qq, Qs, Nb, n, r, hp.alpha)
+    newq, news = update_sr(Sq, Ss, U.T, hp.lr, seed, t)
+    return dict(R=R, M=M1, V=V1, N=N, Nb=Nb, U=U, Sq=newq, Ss=news)
+
+
+def int8_linear_t_forward(x_bits, Sq, Ss, bias_bits=None) -> np.ndarray:
+    """y = x W^T (+ bias) with the weight stored transposed, S = W^T (n x m):
+    y[t][o] = sum_i x[t][i] S[i][o]  (Appendix A, forward)."""
+    Sq = np.asarray(Sq)
+    n, m = Sq.shape
+    x = bf16_bits_to_f64(np.asarray(x_bits)).reshape(-1, n)
+    y = x @ dequant_w_bf16(Sq, Ss)
+    if bias_bits is not None:
+        y = y + bf16_bits_to_f64(np.asarray(bias_bits)).reshape(1, m)
+    return y
+
+
+def int8_linear_t_backward(dy_bits, x_bits, Sq, Ss):
+    """(grad_input, grad_S) for the weight stored transposed (Appendix A,
+    backward): grad_input = dy W = dy S^T (tokens x n); grad_S = (dy^T x)^T =
+    x^T dy (n x m), the gradient in the layout of S."""
+    Sq = np.asarray(Sq)
+    n, m = Sq.shape
+    dy = bf16_bits_to_f64(np.asarray(dy_bits)).reshape(-1, m)
+    x = bf16_bits_to_f64(np.asarray(x_bits)).reshape(-1, n)
+    return dy @ dequant_w_bf16(Sq, Ss).T, x.T @ dy
+
+
+# --------------------------------------------------------------------------
 # 8-bit Adam states (Sec. 3.5: "an 8-bit version of the Adam optimizer" is the
 # inner optimizer).  The paper takes the format from a third-party library
 # and does not define it; the format below is designed here after the
