@@ -192,6 +192,17 @@ def linear_bench(args, device):
         out["kernels"][name] = {"ms": ms, "TFLOP/s": flop / ms / 1e9, "frac_mfma": flop / ms / 1e9 / PEAK_BF16_TFLOPS}
     out["value"] = total
     out["mfma_bound_ms"] = 3 * flop / PEAK_BF16_TFLOPS / 1e9
+    # the same layer with every weight stored transposed (the storage of right-projected matrices): same flops, the
+    # forward pass then has the operand layout of grad_input and vice versa
+    tops = [(m, n, *qg.quant_int8(torch.randn((n, m), generator=g, device=device) * 0.02), x, dy)
+            for (m, n, _, _, x, dy) in ops]
+    tlegs = {
+        "forward": lambda: [qg.int8_linear_t_forward(x, Sq, Ss) for (m, n, Sq, Ss, x, dy) in tops],
+        "grad_input": lambda: [qg.int8_linear_t_backward(dy, None, Sq, Ss, m, n, want_G=False) for (m, n, Sq, Ss, x, dy) in tops],
+        "grad_W": lambda: [qg.int8_linear_t_backward(dy, x, None, None, m, n, want_dx=False) for (m, n, Sq, Ss, x, dy) in tops],
+    }
+    out["transposed_storage_ms"] = {name: timed(f, reps) for name, f in tlegs.items()}
+    del tops
     # the vendor GEMM (torch.mm -> hipBLASLt) on the same shapes with a bf16 weight, no dequantization: for scale
     if not args.no_cpu_baseline:                # the oracle as it stands on one small layer, next to the library on the same
         import numpy as np

@@ -237,6 +237,24 @@ int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, con
                             int64_t tokens, int64_t m, int64_t n, int group,
                             uint16_t* dx_bf16, uint16_t* G_bf16, void* stream);
 
+/* ---- Right-side projection (GaLore's second form, which Sec. 3.5 inherits: R = G Q with Q the n x r matrix of right
+ * singular vectors, moments m x r, update alpha N Q^T; used where a weight has more rows than columns).  A weight
+ * that is projected from the right is kept TRANSPOSED, S = W^T: n x m INT8 codes, blocks of 256 along each row of S,
+ * scales [n][ceil(m/256)].  Its optimizer step, subspace refresh and cosine check are then the left-side calls above
+ * on the n x m matrix S with P = Q (n x r) and the gradient in S's layout: qg_step(Qq, Qs, G_S, Sq, Ss, M, V, R, N,
+ * n, m, r, ...) with moments r x m (the transposes of GaLore's m x r; Adam is element-wise).  The two calls below are
+ * the linear layer on that storage; its backward pass writes the gradient directly in S's layout, so nothing is ever
+ * transposed in memory.
+ * qg_int8_linear_t_forward:  y [tokens][m] = x [tokens][n] * S (+ bias [m], bf16, nullable)      (= x W^T)
+ * qg_int8_linear_t_backward: dx [tokens][n] = dy [tokens][m] * S^T                                (= dy W)
+ *                            G_S [n][m] = x^T * dy                                               (= (dy^T x)^T)
+ * Arguments, limits, NULL outputs and alignment as for the two calls above. */
+int qg_int8_linear_t_forward(const uint16_t* x_bf16, const int8_t* Sq, const float* Ss, const uint16_t* bias_bf16,
+                             int64_t tokens, int64_t m, int64_t n, int group, uint16_t* y_bf16, void* stream);
+int qg_int8_linear_t_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Sq, const float* Ss,
+                              int64_t tokens, int64_t m, int64_t n, int group,
+                              uint16_t* dx_bf16, uint16_t* GS_bf16, void* stream);
+
 /* ---- Adaptive lazy update policy (Sec. 3.2), HOST ONLY (p is a host pointer):
  * streak counts consecutive checks with cos >= threshold; at k in a row the
  * interval doubles and the streak restarts; next_refresh advances by the

@@ -55,3 +55,41 @@ extern "C" int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* 
     }
     return QG_OK;
 }
+
+// The same layer on a weight stored transposed, S = W^T (n x m, blocks along m): the storage of a matrix whose
+// gradient is projected from the right.  The three products are the ones above with the operand roles exchanged: the
+// forward pass has the layout of grad_input, grad_input that of the forward pass, and the weight gradient comes out
+// in S's layout.
+extern "C" int qg_int8_linear_t_forward(const uint16_t* x_bf16, const int8_t* Sq, const float* Ss,
+                                        const uint16_t* bias_bf16, int64_t tokens, int64_t m, int64_t n, int group,
+                                        uint16_t* y_bf16, void* stream) {
+    if (!x_bf16 || !Sq || !Ss || !y_bf16) return QG_ERR_NULL;
+    if (int e = check_linear(tokens, m, n, group)) return e;
+    if (!aligned16(x_bf16) || !aligned16(Sq) || !aligned16(Ss) || !aligned16(y_bf16) || (bias_bf16 && !aligned16(bias_bf16)))
+        return QG_ERR_ALIGN;
+    const int sg = (int)((m + kGroup - 1) / kGroup);
+    // y[t][o] = sum_i x[t][i] S[i][o]
+    const LinOperand A = {x_bf16, nullptr, n, 0}, B = {Sq, Ss, m, sg};
+    return launch_tile_gemm<kBf16KFast, kInt8KSlow, uint16_t>(A, B, bias_bf16, y_bf16, tokens, m, n, (hipStream_t)stream);
+}
+
+extern "C" int qg_int8_linear_t_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Sq, const float* Ss,
+                                         int64_t tokens, int64_t m, int64_t n, int group, uint16_t* dx_bf16,
+                                         uint16_t* GS_bf16, void* stream) {
+    if (!dy_bf16 || (!dx_bf16 && !GS_bf16)) return QG_ERR_NULL;
+    if ((dx_bf16 && (!Sq || !Ss)) || (GS_bf16 && !x_bf16)) return QG_ERR_NULL;
+    if (int e = check_linear(tokens, m, n, group)) return e;
+    if (!aligned16(dy_bf16) || (x_bf16 && !aligned16(x_bf16)) || (Sq && !aligned16(Sq)) || (Ss && !aligned16(Ss)) ||
+        (dx_bf16 && !aligned16(dx_bf16)) || (GS_bf16 && !aligned16(GS_bf16)))
+        return QG_ERR_ALIGN;
+    const int sg = (int)((m + kGroup - 1) / kGroup);
+    if (dx_bf16) {   // dx[t][i] = sum_o dy[t][o] S[i][o]
+        const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {Sq, Ss, m, sg};
+        if (int e = launch_tile_gemm<kBf16KFast, kInt8KFast, uint16_t>(A, B, nullptr, dx_bf16, tokens, n, m, (hipStream_t)stream)) return e;
+    }
+    if (GS_bf16) {   // G_S[i][o] = sum_t x[t][i] dy[t][o]
+        const LinOperand A = {x_bf16, nullptr, n, 0}, B = {dy_bf16, nullptr, m, 0};
+        if (int e = launch_tile_gemm<kBf16KSlow, kBf16KSlow, uint16_t>(A, B, nullptr, GS_bf16, n, m, tokens, (hipStream_t)stream)) return e;
+    }
+    return QG_OK;
+}

@@ -26,6 +26,7 @@ EXPORTS = [
     "qg_project_adam", "qg_project_adam_many", "qg_diag_clock_probe", "qg_diag_mfma_loop",
     "qg_range_apply", "qg_orthonormalize_workspace_bytes", "qg_orthonormalize", "qg_refresh_workspace_bytes",
     "qg_subspace_refresh", "qg_subspace_refresh_many", "qg_int8_linear_forward", "qg_int8_linear_backward",
+    "qg_int8_linear_t_forward", "qg_int8_linear_t_backward",
     "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8", "qg_step8",
 ]
 
@@ -110,6 +111,8 @@ def lib() -> C.CDLL:
         L.qg_step8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, C.POINTER(HParams), u64, i64, vp]
         L.qg_int8_linear_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
         L.qg_int8_linear_backward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp]
+        L.qg_int8_linear_t_forward.argtypes = L.qg_int8_linear_forward.argtypes
+        L.qg_int8_linear_t_backward.argtypes = L.qg_int8_linear_backward.argtypes
         L.qg_subspace_refresh_many.argtypes = [i32, C.POINTER(RefreshDesc), i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
@@ -338,6 +341,27 @@ def int8_linear_backward(dy: torch.Tensor, x: torch.Tensor | None, Wq: torch.Ten
     G = torch.empty((m, n), dtype=torch.bfloat16, device=dy.device) if want_G else None
     _check(lib().qg_int8_linear_backward(_ptr(dy, _BF16), _ptr(x, _BF16), _ptr(Wq, (torch.int8,)),
                                          _ptr(Ws, (torch.float32,)), tokens, m, n, GROUP, _ptr(dx), _ptr(G), _stream()))
+    return dx, G
+
+
+def int8_linear_t_forward(x: torch.Tensor, Sq: torch.Tensor, Ss: torch.Tensor, bias: torch.Tensor | None = None):
+    """The layer on a weight stored transposed (Sq: [n][m])."""
+    tokens, n = x.shape
+    m = Sq.shape[1]
+    y = torch.empty((tokens, m), dtype=torch.bfloat16, device=x.device)
+    _check(lib().qg_int8_linear_t_forward(_ptr(x, _BF16), _ptr(Sq, (torch.int8,)), _ptr(Ss, (torch.float32,)),
+                                          _ptr(bias, _BF16), tokens, m, n, GROUP, _ptr(y), _stream()))
+    return y
+
+
+def int8_linear_t_backward(dy: torch.Tensor, x: torch.Tensor | None, Sq: torch.Tensor | None, Ss: torch.Tensor | None,
+                           m: int, n: int, want_dx: bool = True, want_G: bool = True):
+    """Returns (dx [tokens][n], G_S [n][m]) for a weight stored transposed."""
+    tokens = dy.shape[0]
+    dx = torch.empty((tokens, n), dtype=torch.bfloat16, device=dy.device) if want_dx else None
+    G = torch.empty((n, m), dtype=torch.bfloat16, device=dy.device) if want_G else None
+    _check(lib().qg_int8_linear_t_backward(_ptr(dy, _BF16), _ptr(x, _BF16), _ptr(Sq, (torch.int8,)),
+                                           _ptr(Ss, (torch.float32,)), tokens, m, n, GROUP, _ptr(dx), _ptr(G), _stream()))
     return dx, G
 
 

@@ -126,6 +126,16 @@ def test_int8_linear_argument_errors(L):
     assert L.qg_int8_linear_backward(FAKE, FAKE, None, FAKE, 16, 512, 512, 256, FAKE, None, None) == 1     # dx needs W
     assert L.qg_int8_linear_backward(FAKE, FAKE, FAKE, FAKE, 16, 512, 0, 256, FAKE, FAKE, None) == 2
     assert L.qg_int8_linear_backward(FAKE + 8, FAKE, FAKE, FAKE, 16, 512, 512, 256, FAKE, FAKE, None) == 4
+    # the same layer on a weight stored transposed
+    assert L.qg_int8_linear_t_forward(FAKE, None, FAKE, None, 16, 512, 512, 256, FAKE, None) == 1
+    assert L.qg_int8_linear_t_forward(FAKE, FAKE, FAKE, None, 16, 0, 512, 256, FAKE, None) == 2
+    assert L.qg_int8_linear_t_forward(FAKE, FAKE, FAKE, None, 16, 512, 512, 64, FAKE, None) == 3
+    assert L.qg_int8_linear_t_forward(FAKE, FAKE + 4, FAKE, None, 16, 512, 512, 256, FAKE, None) == 4
+    assert L.qg_int8_linear_t_backward(FAKE, FAKE, FAKE, FAKE, 16, 512, 512, 256, None, None, None) == 1
+    assert L.qg_int8_linear_t_backward(FAKE, None, FAKE, FAKE, 16, 512, 512, 256, None, FAKE, None) == 1
+    assert L.qg_int8_linear_t_backward(FAKE, FAKE, FAKE, None, 16, 512, 512, 256, FAKE, None, None) == 1
+    assert L.qg_int8_linear_t_backward(FAKE, FAKE, FAKE, FAKE, 1 << 20, 512, 1 << 12, 256, FAKE, FAKE, None) == 2
+    assert L.qg_int8_linear_t_backward(FAKE, FAKE, FAKE, FAKE, 16, 512, 512, 256, FAKE, FAKE + 2, None) == 4
 
 
 def test_adam8_argument_errors(L):
