@@ -18,7 +18,9 @@ readings are "parity unpinned" (no value printed in the paper can confirm
 them): the symmetric absmax scale with z = 0, the reciprocal-multiply form of
 W/s, the flat/row block rules, the nibble packing, the hash constants of the
 stochastic-rounding generator, the textbook Adam form and the column-mean
-cosine.
+cosine.  Later sections add the subspace refresh, the INT8 linear layer, 8-bit
+Adam states, right-side projection and the zero-point (asymmetric) weight
+format, each with its own readings.
 """
 from __future__ import annotations
 
@@ -615,3 +617,125 @@ def lowrank_adam8(R, Mq, Ms, Vq, Vs, t: int, hp: HParams):
     Mq1, Ms1 = state8_quant(M1, True)
     Vq1, Vs1 = state8_quant(V1, False)
     return Mq1, Ms1, Vq1, Vs1, N, M1, V1
+
+
+# --------------------------------------------------------------------------
+# Asymmetric (zero-point) INT8 weights.  Sec. 3.1 writes the quantizer with a
+# zero point, W_q = clamp(round(W/s) + z, -2^(n-1), 2^(n-1)-1), s and z per
+# block; Appendix A dequantizes W = (W_q - zeros) * scales.  Neither says how
+# s and z follow from the block.  The reading taken here (parity unpinned):
+# the usual min/max rule over a range that contains zero,
+#     lo = min(0, min x), hi = max(0, max x), s = (hi - lo)/255,
+#     z = clamp(-128 - round(lo/s), -128, 127),
+# so that lo maps to -128, hi to about 127 and 0 to the code z exactly.  As in
+# the symmetric quantizer W/s is the fp32 product with the fp32 reciprocal
+# 255/(hi - lo), and every decision step (min, max, difference, the two
+# quotients, the products) is taken in fp32.  A block that is all zero gets
+# s = 0, z = 0 and codes 0.  Zero points are whole numbers in [-128, 127]
+# (kept as fp32 next to the scales).
+# --------------------------------------------------------------------------
+def _zp_params(lo32: np.ndarray, hi32: np.ndarray):
+    """(s, 1/s, z) of each block from its fp32 minimum and maximum (zero already included)."""
+    rng = (hi32.astype(np.float32) - lo32.astype(np.float32)).astype(np.float32)
+    r64 = rng.astype(np.float64)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        s = np.where(r64 > 0, r64 / 255.0, 0.0).astype(np.float32)
+        inv = np.where(r64 > 0, 255.0 / r64, 0.0).astype(np.float32)
+    tz = (lo32.astype(np.float32) * inv).astype(np.float32)
+    z = np.where(r64 > 0, np.clip(-128.0 - np.rint(tz.astype(np.float64)), -128, 127), 0.0)
+    return s, inv, z.astype(np.float32)
+
+
+def quant_int8_zp(x):
+    """Quant_8 with a zero point (Sec. 3.1 eq.), blocks of 256 along each row.
+    Returns int8 codes [rows][cols], fp32 scales and fp32 zero points
+    [rows][ceil(cols/256)]."""
+    x = np.asarray(x, dtype=np.float32)
+    rows, cols = x.shape
+    ng = (cols + GROUP - 1) // GROUP
+    q = np.zeros((rows, cols), dtype=np.int8)
+    scales = np.zeros((rows, ng), dtype=np.float32)
+    zeros = np.zeros((rows, ng), dtype=np.float32)
+    for g in range(ng):
+        blk = x[:, g * GROUP:(g + 1) * GROUP]
+        lo = np.minimum(np.min(blk, axis=1), 0).astype(np.float32)
+        hi = np.maximum(np.max(blk, axis=1), 0).astype(np.float32)
+        s, inv, z = _zp_params(lo, hi)
+        scales[:, g], zeros[:, g] = s, z
+        t = (blk * inv[:, None]).astype(np.float32)
+        q[:, g * GROUP:(g + 1) * GROUP] = np.clip(np.rint(t.astype(np.float64)) + z[:, None], -128, 127).astype(np.int8)
+    return q, scales, zeros
+
+
+def dequant_int8_zp(q, scales, zeros) -> np.ndarray:
+    """W = (W_q - zeros) * scales (Appendix A), exact in fp64."""
+    q = np.asarray(q)
+    rows, cols = q.shape
+    s = np.repeat(np.asarray(scales, dtype=np.float64), GROUP, axis=1)[:, :cols]
+    z = np.repeat(np.asarray(zeros, dtype=np.float64), GROUP, axis=1)[:, :cols]
+    return (q.astype(np.float64) - z) * s
+
+
+def dequant_w_zp_bf16(Wq, Ws, Wz) -> np.ndarray:
+    """The zero-point weight as a GEMM operand: (code - zero) * scale rounded to fp32, then to bf16."""
+    return bf16_rne(dequant_int8_zp(Wq, Ws, Wz).astype(np.float32).astype(np.float64))
+
+
+def update_sr_zp(Wq, Ws, Wz, U, lr: float, seed: int, t: int):
+    """The INT8 update of Sec. 3.4/3.5 on a zero-point weight: x = (W_q - z) s -
+    lr U; per block new (s', z') from min/max as in quant_int8_zp; code =
+    clamp(F_SR(x/s') + z', -128, 127) with the draw u(seed, t, i*n + j).
+    Returns (codes, scales, zeros)."""
+    Wq = np.asarray(Wq)
+    m, n = Wq.shape
+    x = dequant_int8_zp(Wq, Ws, Wz) - float(np.float32(lr)) * np.asarray(U, dtype=np.float64)
+    x32 = x.astype(np.float32)
+    ng = (n + GROUP - 1) // GROUP
+    newq = np.zeros((m, n), dtype=np.int8)
+    news = np.zeros((m, ng), dtype=np.float32)
+    newz = np.zeros((m, ng), dtype=np.float32)
+    ii = np.arange(m, dtype=np.uint64)[:, None]
+    for g in range(ng):
+        c0, c1 = g * GROUP, min((g + 1) * GROUP, n)
+        blk = x32[:, c0:c1]
+        lo = np.minimum(np.min(blk, axis=1), 0).astype(np.float32)
+        hi = np.maximum(np.max(blk, axis=1), 0).astype(np.float32)
+        s, inv, z = _zp_params(lo, hi)
+        news[:, g], newz[:, g] = s, z
+        tq = (blk * inv[:, None]).astype(np.float32)
+        idx = ii * np.uint64(n) + np.arange(c0, c1, dtype=np.uint64)[None, :]
+        u = sr_uniform(seed, t, idx)
+        newq[:, c0:c1] = np.clip(sr_round(tq, u) + z[:, None].astype(np.float64), -128, 127).astype(np.int8)
+    return newq, news, newz
+
+
+def step_zp(Wq, Ws, Wz, G_bits, Pq, Ps, M, V, t: int, hp: HParams, seed: int, r: int) -> dict:
+    """`step` on a zero-point weight: only the weight's format differs."""
+    Wq = np.asarray(Wq)
+    m, n = Wq.shape
+    R = project(Pq, Ps, G_bits, m, n, r)
+    M1, V1, N = lowrank_adam(R, M, V, t, hp)
+    Nb = bf16_rne(N)
+    U = backproject(Pq, Ps, Nb, m, r, hp.alpha)
+    newq, news, newz = update_sr_zp(Wq, Ws, Wz, U, hp.lr, seed, t)
+    return dict(R=R, M=M1, V=V1, N=N, Nb=Nb, U=U, Wq=newq, Ws=news, Wz=newz)
+
+
+def int8_linear_zp_forward(x_bits, Wq, Ws, Wz, bias_bits=None) -> np.ndarray:
+    """Appendix A forward with zeros: y = x ((W_q - zeros) * scales)^T (+ bias)."""
+    Wq = np.asarray(Wq)
+    m, n = Wq.shape
+    x = bf16_bits_to_f64(np.asarray(x_bits)).reshape(-1, n)
+    y = x @ dequant_w_zp_bf16(Wq, Ws, Wz).T
+    if bias_bits is not None:
+        y = y + bf16_bits_to_f64(np.asarray(bias_bits)).reshape(1, m)
+    return y
+
+
+def int8_linear_zp_backward(dy_bits, x_bits, Wq, Ws, Wz):
+    """Appendix A backward with zeros: (dy W, dy^T x)."""
+    Wq = np.asarray(Wq)
+    m, n = Wq.shape
+    dy = bf16_bits_to_f64(np.asarray(dy_bits)).reshape(-1, m)
+    x = bf16_bits_to_f64(np.asarray(x_bits)).reshape(-1, n)
+    return dy @ dequant_w_zp_bf16(Wq, Ws, Wz), dy.T @ x
