@@ -69,7 +69,7 @@ def pitched(t, ld):
     return out
 
 
-def build_state(config: int, device, pad_rows: bool = False):
+def build_state(config: int, device, pad_rows: bool = False, zero_points: bool = False):
     """Device-resident synthetic state of every matrix of the workload.
 
     W ~ N(0, 0.02) quantized by qg_quant_int8; G = A B^T + E (rank 16 plus noise) in bf16; one orthonormal P per
@@ -92,7 +92,11 @@ def build_state(config: int, device, pad_rows: bool = False):
             pcache[(m, r)] = qg.quant_int4(P)
         Pq, Ps = pcache[(m, r)]
         W = torch.randn((m, n), generator=gen, device=device, dtype=torch.float32) * 0.02
-        Wq, Ws = qg.quant_int8(W)
+        Wz = None
+        if zero_points:
+            Wq, Ws, Wz = qg.quant_int8_zp(W)
+        else:
+            Wq, Ws = qg.quant_int8(W)
         del W
         A = torch.randn((m, 16), generator=gen, device=device) * 0.01
         B = torch.randn((n, 16), generator=gen, device=device) * 0.01
@@ -108,7 +112,7 @@ def build_state(config: int, device, pad_rows: bool = False):
                                    torch.zeros((r, w), dtype=torch.float32, device=device),
                                    torch.zeros((r, w), dtype=torch.float32, device=device),
                                    torch.empty((r, w), dtype=torch.float32, device=device),
-                                   torch.empty((r, w), dtype=torch.bfloat16, device=device), ld=ld))
+                                   torch.empty((r, w), dtype=torch.bfloat16, device=device), ld=ld, Wz=Wz))
     torch.cuda.synchronize()
     return mats
 
@@ -337,6 +341,8 @@ def main():
     ap.add_argument("--pad-rows", action="store_true",
                     help="store matrices whose n is not a multiple of 16 with a row pitch of n rounded up to 16 "
                          "(the descriptor's ld): aligned rows for the direct loads")
+    ap.add_argument("--zero-points", action="store_true",
+                    help="weights in the zero-point (asymmetric) INT8 format instead of the symmetric one")
     ap.add_argument("--refresh", action="store_true",
                     help="time the subspace refresh (qg_subspace_refresh, one pass) over every matrix of the workload "
                          "instead of the optimizer step, print its own JSON line and exit")
@@ -441,7 +447,7 @@ def main():
         return
 
     shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(args.config)]
-    mats = build_state(args.config, device, args.pad_rows)
+    mats = build_state(args.config, device, args.pad_rows, args.zero_points)
 
     if args.refresh:
         if args.pad_rows:
@@ -591,7 +597,8 @@ def main():
         "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOADS[args.config], "matrices": len(shapes), "launches_per_step": 2,
-                   "row_layout": "pitch of n rounded up to 16" if args.pad_rows else "dense"},
+                   "row_layout": "pitch of n rounded up to 16" if args.pad_rows else "dense",
+                   "weight_format": "INT8 with zero points" if args.zero_points else "INT8 symmetric"},
         "roofline": roofline, "kernels": kernels, "ceilings": ceilings, "step_stats": step_stats,
     }
     if step8 is not None:

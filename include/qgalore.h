@@ -84,6 +84,8 @@ typedef struct {
                              result; they are not written either, with two exceptions: N goes out as pairs of columns (an
                              odd n overwrites the first padding column of N), and the unfused qg_lowrank_adam_many runs
                              over the padding of M, V, N as well. */
+    float*          Wz;   /* zero points of W, [m][ceil(n/256)], in/out, or NULL: the symmetric format.  Either every
+                             matrix of a plan has them or none (QG_ERR_NULL otherwise). */
 } qg_matrix_desc;
 
 const char* qg_status_string(int status);
@@ -254,6 +256,38 @@ int qg_int8_linear_t_forward(const uint16_t* x_bf16, const int8_t* Sq, const flo
 int qg_int8_linear_t_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Sq, const float* Ss,
                               int64_t tokens, int64_t m, int64_t n, int group,
                               uint16_t* dx_bf16, uint16_t* GS_bf16, void* stream);
+
+/* ---- Zero-point (asymmetric) INT8 weights: the quantizer as Sec. 3.1 writes it, W_q = clamp(round(W/s) + z), and
+ * Appendix A's dequantization W = (W_q - zeros) * scales.  Per block of 256 elements of a row: lo = min(0, min x),
+ * hi = max(0, max x), s = (hi - lo)/255, z = clamp(-128 - round(lo * (255/(hi - lo))), -128, 127), code =
+ * clamp(round(x * (255/(hi - lo))) + z, -128, 127), all in fp32; an all-zero block has s = 0, z = 0.  Zero points are
+ * whole numbers kept as fp32 [rows][ceil(cols/256)], next to the scales.  Zero itself is always a code (z).
+ * qg_quant_int8_zp / qg_dequant_int8_zp: as qg_quant_int8 / qg_dequant_int8, with the zero points.
+ * qg_backproject_update_sr_zp: as qg_backproject_update_sr on such a weight: x = (W_q - z)*s - lr*U, new (s', z')
+ *   from the block's min and max as above, code' = clamp(floor(x*(255/(hi - lo)) + u) + z', -128, 127) with the same
+ *   uniform draw u; Wq, Ws, Wz updated in place.
+ * qg_step_zp: qg_step on such a weight (qg_project_adam, then qg_backproject_update_sr_zp); in a grouped plan give
+ *   every descriptor its Wz.
+ * qg_int8_linear_zp_forward / _backward: the linear layer on such a weight (W dequantized inside the GEMMs as
+ *   bf16(fl32((code - zero) * scale))).
+ * Shapes, limits, alignment and NULL rules as for the calls they mirror; Wz may never be NULL. */
+int qg_quant_int8_zp(const float* x, int64_t rows, int64_t cols, int group, int8_t* q, float* scales, float* zeros,
+                     void* stream);
+int qg_dequant_int8_zp(const int8_t* q, const float* scales, const float* zeros, int64_t rows, int64_t cols, int group,
+                       float* x, void* stream);
+int qg_backproject_update_sr_zp(const uint8_t* Pq, const float* Ps, const uint16_t* N_bf16,
+                                int8_t* Wq, float* Ws, float* Wz, int64_t m, int64_t n, int64_t r, int group,
+                                float alpha, float lr, uint64_t seed, int64_t step, void* stream);
+int qg_step_zp(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
+               int8_t* Wq, float* Ws, float* Wz, float* M, float* V, float* R, uint16_t* N_bf16,
+               int64_t m, int64_t n, int64_t r, int group,
+               const qg_hparams* hp, uint64_t seed, int64_t step, void* stream);
+int qg_int8_linear_zp_forward(const uint16_t* x_bf16, const int8_t* Wq, const float* Ws, const float* Wz,
+                              const uint16_t* bias_bf16, int64_t tokens, int64_t m, int64_t n, int group,
+                              uint16_t* y_bf16, void* stream);
+int qg_int8_linear_zp_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
+                               const float* Wz, int64_t tokens, int64_t m, int64_t n, int group,
+                               uint16_t* dx_bf16, uint16_t* G_bf16, void* stream);
 
 /* ---- Adaptive lazy update policy (Sec. 3.2), HOST ONLY (p is a host pointer):
  * streak counts consecutive checks with cos >= threshold; at k in a row the

@@ -23,8 +23,8 @@ int check_launch() {
 
 // defined in qg_gemm.hip / qg_adam.hip
 int launch_project(const uint8_t*, const float*, const uint16_t*, float*, int64_t, int64_t, int64_t, hipStream_t);
-int launch_backproject(const uint8_t*, const float*, const uint16_t*, int8_t*, float*, float*, int64_t, int64_t, int64_t,
-                       float, float, uint64_t, int64_t, hipStream_t);
+int launch_backproject(const uint8_t*, const float*, const uint16_t*, int8_t*, float*, float*, float*, int64_t, int64_t,
+                       int64_t, float, float, uint64_t, int64_t, hipStream_t);   // ..., Ws, Wz (or null), U dump (or null)
 int launch_adam(const float*, float*, float*, uint16_t*, int64_t, int64_t, const qg_hparams*, hipStream_t);
 int launch_project_many(const PlanHeader*, const PlanHeader*, hipStream_t);
 int launch_backproject_many(const PlanHeader*, const PlanHeader*, float, float, uint64_t, int64_t, hipStream_t);
@@ -83,7 +83,32 @@ extern "C" int qg_backproject_update_sr(const uint8_t* Pq, const float* Ps, cons
     if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(N_bf16) || !aligned16(Wq) || !aligned16(Ws) ||
         (U_debug && !aligned16(U_debug)))
         return QG_ERR_ALIGN;
-    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, U_debug, m, n, r, alpha, lr, seed, step, (hipStream_t)stream);
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, U_debug, m, n, r, alpha, lr, seed, step, (hipStream_t)stream);
+}
+
+extern "C" int qg_backproject_update_sr_zp(const uint8_t* Pq, const float* Ps, const uint16_t* N_bf16, int8_t* Wq,
+                                           float* Ws, float* Wz, int64_t m, int64_t n, int64_t r, int group, float alpha,
+                                           float lr, uint64_t seed, int64_t step, void* stream) {
+    if (!Pq || !Ps || !N_bf16 || !Wq || !Ws || !Wz) return QG_ERR_NULL;
+    if (int e = check_mnr(m, n, r, group)) return e;
+    if (step < 1) return QG_ERR_SHAPE;
+    if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(N_bf16) || !aligned16(Wq) || !aligned16(Ws) || !aligned16(Wz))
+        return QG_ERR_ALIGN;
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, Wz, nullptr, m, n, r, alpha, lr, seed, step, (hipStream_t)stream);
+}
+
+extern "C" int qg_step_zp(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t* Wq, float* Ws, float* Wz,
+                          float* M, float* V, float* R, uint16_t* N_bf16, int64_t m, int64_t n, int64_t r, int group,
+                          const qg_hparams* hp, uint64_t seed, int64_t step, void* stream) {
+    if (!Pq || !Ps || !G_bf16 || !Wq || !Ws || !Wz || !M || !V || !N_bf16 || !hp) return QG_ERR_NULL;
+    if (int e = check_mnr(m, n, r, group)) return e;
+    if (step < 1) return QG_ERR_SHAPE;
+    if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(G_bf16) || !aligned16(Wq) || !aligned16(Ws) || !aligned16(Wz) ||
+        !aligned16(M) || !aligned16(V) || (R && !aligned16(R)) || !aligned16(N_bf16))
+        return QG_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (int e = launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, r, step, hp, s)) return e;
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, Wz, nullptr, m, n, r, hp->alpha, hp->lr, seed, step, s);
 }
 
 extern "C" int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t* Wq, float* Ws, float* M,
@@ -100,7 +125,7 @@ extern "C" int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf1
         return QG_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     if (int e = launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, r, step, hp, s)) return e;
-    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, m, n, r, hp->alpha, hp->lr, seed, step, s);
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, nullptr, m, n, r, hp->alpha, hp->lr, seed, step, s);
 }
 
 extern "C" int qg_policy_update(qg_policy* p, float cos) {
@@ -140,9 +165,12 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
         // a row pitch other than n: at least n, rows 16-byte aligned in every array, m * ld inside the 32-bit range
         if (d.ld != 0 && d.ld != d.n && (d.ld < d.n || (d.ld & 15) || d.m * d.ld >= (int64_t(1) << 32))) return QG_ERR_SHAPE;
         if (!aligned16(d.Pq) || !aligned16(d.Ps) || !aligned16(d.G) || !aligned16(d.Wq) || !aligned16(d.Ws) ||
-            !aligned16(d.M) || !aligned16(d.V) || (d.R && !aligned16(d.R)) || !aligned16(d.N))
+            !aligned16(d.M) || !aligned16(d.V) || (d.R && !aligned16(d.R)) || !aligned16(d.N) ||
+            (d.Wz && !aligned16(d.Wz)))
             return QG_ERR_ALIGN;
+        if ((d.Wz != nullptr) != (descs[0].Wz != nullptr)) return QG_ERR_NULL;   // zero points: all matrices or none
     }
+    h.zero_points = descs[0].Wz != nullptr ? 1u : 0u;
     auto matrix_class = [](const qg_matrix_desc& d) {
         const int64_t ld = d.ld ? d.ld : d.n;
         const int a = project_mode(d.m, d.n, ld, d.r), b = backproject_mode(d.m, d.n, ld, d.r);
@@ -159,7 +187,7 @@ extern "C" int qg_plan_build(int count, const qg_matrix_desc* descs, void* plan_
             pm.m = d.m; pm.n = d.n; pm.r = d.r;
             pm.ld = d.ld ? d.ld : d.n;
             pm.Pq = d.Pq; pm.Ps = d.Ps; pm.G = d.G; pm.Wq = d.Wq; pm.Ws = d.Ws;
-            pm.M = d.M; pm.V = d.V; pm.R = d.R; pm.N = d.N;
+            pm.M = d.M; pm.V = d.V; pm.R = d.R; pm.N = d.N; pm.Wz = d.Wz;
             pm.index = (uint32_t)i;
             pm.adam_chunk0 = (uint32_t)adam;
             pm.proj_tile0 = (uint32_t)proj[cls];

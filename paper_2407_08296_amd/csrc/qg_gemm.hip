@@ -121,15 +121,25 @@ static constexpr int kBpWgPerCu[3] = {3, 3, 2};
 
 template <int BMm, int BK, int WGn, int WGm, bool PREF>
 static int launch_backproject_cfg(const uint8_t* Pq, const float* Ps, const uint16_t* N, int8_t* Wq, float* Ws,
-                                  float* Udbg, int m, int n, int r, float alpha, float lr, uint32_t key,
+                                  float* Wz, float* Udbg, int m, int n, int r, float alpha, float lr, uint32_t key,
                                   hipStream_t stream) {
     const uint32_t tiles_m = (uint32_t)((m + BMm - 1) / BMm), tiles_n = (uint32_t)((n + kGroup - 1) / kGroup);
     const uint32_t tiles = tiles_m * tiles_n;
     const dim3 grid(grid8(tiles)), block(WGn * WGm * 64);
 #define QG_LAUNCH_BP(MODE, DUMP)                                                                                    \
     hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, MODE, DUMP, PREF, kBpWgPerCu[MODE]>), grid, block, 0, stream, \
-                       Pq, Ps, N, Wq, Ws, Udbg, m, n, r, alpha, lr, key, tiles_m, tiles)
-    switch (edge_mode(m, BMm, n, n, kGroup, r, BK, r)) {
+                       Pq, Ps, N, Wq, Ws, nullptr, Udbg, m, n, r, alpha, lr, key, tiles_m, tiles)
+#define QG_LAUNCH_BP_ZP(MODE)                                                                                        \
+    hipLaunchKernelGGL((k_backproject<BMm, BK, WGn, WGm, MODE, false, PREF, kBpWgPerCu[MODE], true>), grid, block, 0, \
+                       stream, Pq, Ps, N, Wq, Ws, Wz, nullptr, m, n, r, alpha, lr, key, tiles_m, tiles)
+    const int mode = edge_mode(m, BMm, n, n, kGroup, r, BK, r);
+    if (Wz != nullptr) {   // zero-point weights (no U dump)
+        if (mode == kExact) QG_LAUNCH_BP_ZP(kExact);
+        else if (mode == kMasked) QG_LAUNCH_BP_ZP(kMasked);
+        else QG_LAUNCH_BP_ZP(kUnaligned);
+        return check_launch();
+    }
+    switch (mode) {
         case kExact:
             if (Udbg) QG_LAUNCH_BP(kExact, true); else QG_LAUNCH_BP(kExact, false);
             break;
@@ -140,16 +150,17 @@ static int launch_backproject_cfg(const uint8_t* Pq, const float* Ps, const uint
             if (Udbg) QG_LAUNCH_BP(kUnaligned, true); else QG_LAUNCH_BP(kUnaligned, false);
     }
 #undef QG_LAUNCH_BP
+#undef QG_LAUNCH_BP_ZP
     return check_launch();
 }
 
-int launch_backproject(const uint8_t* Pq, const float* Ps, const uint16_t* N, int8_t* Wq, float* Ws, float* Udbg,
-                       int64_t m, int64_t n, int64_t r, float alpha, float lr, uint64_t seed, int64_t step,
+int launch_backproject(const uint8_t* Pq, const float* Ps, const uint16_t* N, int8_t* Wq, float* Ws, float* Wz,
+                       float* Udbg, int64_t m, int64_t n, int64_t r, float alpha, float lr, uint64_t seed, int64_t step,
                        hipStream_t stream) {
     const uint32_t key = sr_key(seed, (uint64_t)step, 0u);
     // 128-row tiles, weight tile sharing the staging LDS, several workgroups per CU: the VALU-heavy update epilogue
     // of one workgroup overlaps the MFMA main loops of the others.
-    return launch_backproject_cfg<128, 32, 2, 2, false>(Pq, Ps, N, Wq, Ws, Udbg, (int)m, (int)n, (int)r, alpha, lr,
+    return launch_backproject_cfg<128, 32, 2, 2, false>(Pq, Ps, N, Wq, Ws, Wz, Udbg, (int)m, (int)n, (int)r, alpha, lr,
                                                            key, stream);
 }
 
@@ -180,7 +191,17 @@ int launch_backproject_many(const PlanHeader* plan_host, const PlanHeader* plan_
         const uint32_t tiles = plan_host->bp_tiles[cls];
         if (cnt == 0 || tiles == 0) continue;
         const dim3 grid(grid8(tiles)), block(256);
-        if (cls == kExact)
+        if (plan_host->zero_points) {
+            if (cls == kExact)
+                hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, kExact, false, kBpWgPerCu[kExact], true>), grid,
+                                   block, 0, stream, plan_dev, first, cnt, tiles, alpha, lr, seed, (uint64_t)step);
+            else if (cls == kMasked)
+                hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, kMasked, false, kBpWgPerCu[kMasked], true>), grid,
+                                   block, 0, stream, plan_dev, first, cnt, tiles, alpha, lr, seed, (uint64_t)step);
+            else
+                hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, kUnaligned, false, kBpWgPerCu[kUnaligned], true>),
+                                   grid, block, 0, stream, plan_dev, first, cnt, tiles, alpha, lr, seed, (uint64_t)step);
+        } else if (cls == kExact)
             hipLaunchKernelGGL((k_backproject_many<kManyBpBM, 32, 2, 2, kExact, false, kBpWgPerCu[kExact]>), grid, block,
                                0, stream, plan_dev, first, cnt, tiles, alpha, lr, seed, (uint64_t)step);
         else if (cls == kMasked)

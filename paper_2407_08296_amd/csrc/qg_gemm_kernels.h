@@ -584,7 +584,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam_m
 // W_PREFETCH: the weight tile has LDS of its own and is fetched before the main loop (one workgroup per CU);
 // otherwise it reuses the staging buffers after the main loop (smaller footprint, two workgroups per CU, whose
 // epilogue and main loop then overlap).
-template <int BMm, int BK, int WGn, int WGm, bool W_PREFETCH = true>
+template <int BMm, int BK, int WGn, int WGm, bool W_PREFETCH = true, bool ZP = false>
 struct BpShape {
     static constexpr int BNn = kGroup;
     static constexpr int NT = WGn * WGm * 64;
@@ -593,7 +593,8 @@ struct BpShape {
     static constexpr int A_STAGE = BK * PA, B_STAGE = BMm * PB;
     static constexpr int STAGING = 2 * (A_STAGE + B_STAGE);   // uint16 elements
     static constexpr int WTILE = BMm * BNn / 2;                // INT8 weight tile, in uint16 elements
-    static constexpr int WOFF = W_PREFETCH ? STAGING : WGn * BMm * 2;   // after the row-max exchange area if aliased
+    static constexpr int EXCH = (ZP ? 2 : 1) * WGn * BMm * 2;   // row-max (and, with zero points, row-min) exchange
+    static constexpr int WOFF = W_PREFETCH ? STAGING : EXCH;    // after the exchange area if aliased
     static constexpr int SMEM = W_PREFETCH ? STAGING + WTILE : (STAGING > WOFF + WTILE ? STAGING : WOFF + WTILE);
 };
 
@@ -613,16 +614,20 @@ __device__ __forceinline__ constexpr int wtile_run_bits(int a, int v4) {
     return ((2 * a + (v4 >> 1)) << 4) | ((v4 & 1) << 3);
 }
 
-template <int BMm, int BK, int WGn, int WGm, int MODE, bool DUMP_U, bool W_PREFETCH = true>
+// ZP: the weight carries a zero point per block (Sec. 3.1 eq.; Appendix A's `W_q - zeros`): x = (code - z)*s - lr*U,
+// the new block takes s' = (hi - lo)/255 over [min(0, min x), max(0, max x)], z' = -128 - round(lo/s'), and the
+// stochastically rounded code is floor(x/s' + u) + z'.
+template <int BMm, int BK, int WGn, int WGm, int MODE, bool DUMP_U, bool W_PREFETCH = true, bool ZP = false>
 __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq, const float* __restrict__ Ps,
                                                  const uint16_t* __restrict__ N, int8_t* __restrict__ Wq,
-                                                 float* __restrict__ Ws, float* __restrict__ Udbg, int m, int n, int ld,
+                                                 float* __restrict__ Ws, float* __restrict__ Wz,
+                                                 float* __restrict__ Udbg, int m, int n, int ld,
                                                  int r, int m0, int tile_n, float alpha, float lr, uint32_t key,
                                                  uint16_t* smem) {
     constexpr bool RAGGED = MODE != kExact;      // masked epilogue
     constexpr bool DIRECT = MODE != kUnaligned;  // buffer / direct-to-LDS loads; a P fetch (8*WPT codes) starts at a
                                                  // multiple of 8*WPT codes, so it lies in one block of 256
-    using S = BpShape<BMm, BK, WGn, WGm, W_PREFETCH>;
+    using S = BpShape<BMm, BK, WGn, WGm, W_PREFETCH, ZP>;
     constexpr int BNn = S::BNn, NT = S::NT, NW = WGn * WGm;
     constexpr int SN = BNn / WGn, SM = BMm / WGm, IB = SN / 32, JB = SM / 32;
     constexpr int PA = S::PA, PB = S::PB;
@@ -634,7 +639,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     static_assert(BK % (8 * WPT) == 0, "tile shape");
     constexpr int W_ROUNDS = BMm / 4 / NW;   // each wave-wide 16-byte access covers 4 tile rows
     static_assert(A_PER * NT * 8 == BK * BNn, "staging must divide evenly");
-    static_assert(WGn * BMm * 4 <= S::STAGING * 2, "row-max exchange must fit in the staging buffers");
+    static_assert(S::EXCH <= S::STAGING, "row-max exchange must fit in the staging buffers");
     static_assert((BMm / 4) % NW == 0, "weight tile rows must divide evenly over the waves");
     static_assert(SN % 32 == 0 && (SN & (SN - 1)) == 0, "a wave's column span must be a power of two (wtile_run_bits)");
     uint16_t* As = smem;
@@ -834,15 +839,19 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
 
     // ---- epilogue: x = Wq*s - lr*U in place of the accumulators, per-row block absmax ----
     float* smax = reinterpret_cast<float*>(smem);  // [WGn][BMm]; staging buffers are free after the last barrier
+    float* smin = smax + WGn * BMm;                // the same for the row minima of the zero-point format
     const float nlra = -(lr * alpha);
     float rowmax[JB];
+    float rowmin[ZP ? JB : 1];
 #pragma unroll
     for (int b = 0; b < JB; ++b) {
         const int rl = wm * SM + b * 32 + lrow;       // row inside the tile
         const int mrow = m0 + rl;
         const bool row_ok = !RAGGED || mrow < m;
         const float s_old = row_ok ? Ws[(int64_t)mrow * ng + tile_n] : 0.f;
-        float mx = 0.f;
+        float z_old = 0.f;
+        if constexpr (ZP) z_old = row_ok ? Wz[(int64_t)mrow * ng + tile_n] : 0.f;
+        float mx = 0.f, mn = 0.f;   // the zero-point range contains zero
         const int wt_lane = wtile_offset(rl, wn * SN + 4 * lhalf);
 #pragma unroll
         for (int a = 0; a < IB; ++a)
@@ -852,19 +861,30 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
                 const uint32_t w = *reinterpret_cast<const uint32_t*>(wt + (wt_lane ^ wtile_run_bits(a, v4)));
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float cw = (float)(int)(int8_t)(w >> (8 * e)) * s_old;
+                    const float code = (float)(int)(int8_t)(w >> (8 * e));
+                    const float cw = ZP ? (code - z_old) * s_old : code * s_old;
                     const bool ok = !RAGGED || (row_ok && n0 + col + e < n);
                     if (DUMP_U) {
                         if (ok) Udbg[(int64_t)mrow * n + n0 + col + e] = alpha * acc[a][b][4 * v4 + e];
                     }
                     const float x = ok ? __builtin_fmaf(nlra, acc[a][b][4 * v4 + e], cw) : 0.f;
                     acc[a][b][4 * v4 + e] = x;
-                    mx = fmaxf(mx, fabsf(x));
+                    if constexpr (ZP) {
+                        mx = fmaxf(mx, x);
+                        mn = fminf(mn, x);
+                    } else {
+                        mx = fmaxf(mx, fabsf(x));
+                    }
                 }
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         rowmax[b] = mx;
         if (WGn > 1 && lhalf == 0) smax[wn * BMm + rl] = mx;
+        if constexpr (ZP) {
+            mn = fminf(mn, __shfl_xor(mn, 32, 64));
+            rowmin[b] = mn;
+            if (WGn > 1 && lhalf == 0) smin[wn * BMm + rl] = mn;
+        }
     }
     if (WGn > 1) __syncthreads();
 
@@ -879,8 +899,23 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
 #pragma unroll
             for (int w = 0; w < WGn; ++w) amax = fmaxf(amax, smax[w * BMm + rl]);
         }
-        const float s_new = amax > 0.f ? amax / 127.0f : 0.f;
-        const float inv = amax > 0.f ? 127.0f / amax : 0.f;
+        float s_new, inv, code_bias = 128.0f;   // added to floor(v) before the saturating conversion: 128 (+ z')
+        if constexpr (ZP) {
+            float amin = rowmin[b];
+            if (WGn > 1) {
+#pragma unroll
+                for (int w = 0; w < WGn; ++w) amin = fminf(amin, smin[w * BMm + rl]);
+            }
+            const float rng = amax - amin;
+            s_new = rng > 0.f ? rng / 255.0f : 0.f;
+            inv = rng > 0.f ? 255.0f / rng : 0.f;
+            const float z_new = rng > 0.f ? fminf(fmaxf(-128.f - rintf(amin * inv), -128.f), 127.f) : 0.f;
+            if (wn == 0 && lhalf == 0 && row_ok) Wz[(int64_t)mrow * ng + tile_n] = z_new;
+            code_bias = 128.0f + z_new;
+        } else {
+            s_new = amax > 0.f ? amax / 127.0f : 0.f;
+            inv = amax > 0.f ? 127.0f / amax : 0.f;
+        }
         if (wn == 0 && lhalf == 0 && row_ok) Ws[(int64_t)mrow * ng + tile_n] = s_new;
         const uint32_t idx_row = (uint32_t)mrow * (uint32_t)n + (uint32_t)n0;   // m*n < 2^32
         const bool xor_ok = MODE == kExact || (DIRECT && (n & 3) == 0);   // wave-uniform
@@ -903,7 +938,7 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
                     const float v = __builtin_fmaf((float)(h >> 8), 0x1p-24f, tq);
                     // clamp(floor(v), -128, 127) as a byte: the saturating float -> u8 conversion of floor(v) + 128
                     // (exact: |v| stays far below 2^23) packs straight into byte e; the bias comes off below
-                    pk = __builtin_amdgcn_cvt_pk_u8_f32(floorf(v) + 128.0f, e, pk);
+                    pk = __builtin_amdgcn_cvt_pk_u8_f32(floorf(v) + code_bias, e, pk);
                 }
                 pk ^= 0x80808080u;
                 *reinterpret_cast<uint32_t*>(wt + (wt_lane ^ wtile_run_bits(a, v4))) = pk;
@@ -937,34 +972,36 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     }
 }
 
-template <int BMm, int BK, int WGn, int WGm, int MODE, bool DUMP_U, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
+template <int BMm, int BK, int WGn, int WGm, int MODE, bool DUMP_U, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1,
+          bool ZP = false>
 __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject(const uint8_t* __restrict__ Pq,
                                                                const float* __restrict__ Ps,
                                                                const uint16_t* __restrict__ N,
                                                                int8_t* __restrict__ Wq, float* __restrict__ Ws,
+                                                               float* __restrict__ Wz,
                                                                float* __restrict__ Udbg, int m, int n, int r,
                                                                float alpha, float lr, uint32_t key, uint32_t tiles_m,
                                                                uint32_t tiles) {
-    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH>::SMEM];
+    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH, ZP>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    backproject_tile<BMm, BK, WGn, WGm, MODE, DUMP_U, W_PREFETCH>(Pq, Ps, N, Wq, Ws, Udbg, m, n, n, r, (int)(tile % tiles_m) * BMm,
+    backproject_tile<BMm, BK, WGn, WGm, MODE, DUMP_U, W_PREFETCH, ZP>(Pq, Ps, N, Wq, Ws, Wz, Udbg, m, n, n, r, (int)(tile % tiles_m) * BMm,
                                                 (int)(tile / tiles_m), alpha, lr, key, smem);
 }
 
-template <int BMm, int BK, int WGn, int WGm, int MODE, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1>
+template <int BMm, int BK, int WGn, int WGm, int MODE, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1, bool ZP = false>
 __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_many(const PlanHeader* __restrict__ plan, int first,
                                                                                    int count, uint32_t tiles,
                                                                                    float alpha, float lr,
                                                                                    uint64_t seed, uint64_t step) {
-    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH>::SMEM];
+    __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH, ZP>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
     const PlanMatrix* mats = plan_matrices(plan) + first;
     const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.bp_tile0; })];
     const uint32_t local = tile - d.bp_tile0;
     const uint32_t key = sr_key(seed + (uint64_t)d.index * 0x9E3779B97F4A7C15ull, step, 0u);
-    backproject_tile<BMm, BK, WGn, WGm, MODE, false, W_PREFETCH>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, nullptr, (int)d.m, (int)d.n, (int)d.ld, (int)d.r,
+    backproject_tile<BMm, BK, WGn, WGm, MODE, false, W_PREFETCH, ZP>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, d.Wz, nullptr, (int)d.m, (int)d.n, (int)d.ld, (int)d.r,
                                                 (int)(local % d.bp_tiles_m) * BMm, (int)(local / d.bp_tiles_m),
                                                 alpha, lr, key, smem);
 }

@@ -93,3 +93,39 @@ extern "C" int qg_int8_linear_t_backward(const uint16_t* dy_bf16, const uint16_t
     }
     return QG_OK;
 }
+
+// The layer on a zero-point weight (Sec. 3.1 eq. with z; Appendix A: W = (W_q - zeros) * scales): the same products,
+// the weight operand dequantized as bf16(fl32((code - zero) * scale)).  grad_W does not read the weight.
+extern "C" int qg_int8_linear_zp_forward(const uint16_t* x_bf16, const int8_t* Wq, const float* Ws, const float* Wz,
+                                         const uint16_t* bias_bf16, int64_t tokens, int64_t m, int64_t n, int group,
+                                         uint16_t* y_bf16, void* stream) {
+    if (!x_bf16 || !Wq || !Ws || !Wz || !y_bf16) return QG_ERR_NULL;
+    if (int e = check_linear(tokens, m, n, group)) return e;
+    if (!aligned16(x_bf16) || !aligned16(Wq) || !aligned16(Ws) || !aligned16(Wz) || !aligned16(y_bf16) ||
+        (bias_bf16 && !aligned16(bias_bf16)))
+        return QG_ERR_ALIGN;
+    const int sg = (int)((n + kGroup - 1) / kGroup);
+    const LinOperand A = {x_bf16, nullptr, n, 0}, B = {Wq, Ws, n, sg, Wz};
+    return launch_tile_gemm<kBf16KFast, kInt8ZKFast, uint16_t>(A, B, bias_bf16, y_bf16, tokens, m, n, (hipStream_t)stream);
+}
+
+extern "C" int qg_int8_linear_zp_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq,
+                                          const float* Ws, const float* Wz, int64_t tokens, int64_t m, int64_t n,
+                                          int group, uint16_t* dx_bf16, uint16_t* G_bf16, void* stream) {
+    if (!dy_bf16 || (!dx_bf16 && !G_bf16)) return QG_ERR_NULL;
+    if ((dx_bf16 && (!Wq || !Ws || !Wz)) || (G_bf16 && !x_bf16)) return QG_ERR_NULL;
+    if (int e = check_linear(tokens, m, n, group)) return e;
+    if (!aligned16(dy_bf16) || (x_bf16 && !aligned16(x_bf16)) || (Wq && !aligned16(Wq)) || (Ws && !aligned16(Ws)) ||
+        (Wz && !aligned16(Wz)) || (dx_bf16 && !aligned16(dx_bf16)) || (G_bf16 && !aligned16(G_bf16)))
+        return QG_ERR_ALIGN;
+    const int sg = (int)((n + kGroup - 1) / kGroup);
+    if (dx_bf16) {
+        const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {Wq, Ws, n, sg, Wz};
+        if (int e = launch_tile_gemm<kBf16KFast, kInt8ZKSlow, uint16_t>(A, B, nullptr, dx_bf16, tokens, n, m, (hipStream_t)stream)) return e;
+    }
+    if (G_bf16) {
+        const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {x_bf16, nullptr, n, 0};
+        if (int e = launch_tile_gemm<kBf16KSlow, kBf16KSlow, uint16_t>(A, B, nullptr, G_bf16, m, n, tokens, (hipStream_t)stream)) return e;
+    }
+    return QG_OK;
+}

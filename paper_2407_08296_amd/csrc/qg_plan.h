@@ -24,6 +24,7 @@ struct PlanMatrix {
     const uint16_t* G;
     int8_t* Wq;
     float* Ws;
+    float* Wz;              // zero points of W (zero-point format) or null
     float* M;
     float* V;
     float* R;
@@ -49,7 +50,8 @@ struct PlanHeader {
     int32_t class_count[kPlanClasses];    // matrices per class, in storage order
     uint32_t proj_tiles[kPlanClasses];
     uint32_t bp_tiles[kPlanClasses];
-    uint32_t pad_[3];
+    uint32_t zero_points;                 // 1 if the weights carry zero points (all of them or none)
+    uint32_t pad_[2];
 };
 static_assert(sizeof(PlanHeader) % 16 == 0, "records must stay 16-byte aligned");
 

@@ -6,9 +6,12 @@ namespace qg {
 
 // One wave per block of 256 elements; each lane owns 4 consecutive elements.
 // INT8: blocks live inside a row (row-major [rows][cols], short last block).
+// ZP: the quantizer with a zero point (Sec. 3.1 eq.): range [min(0, min x), max(0, max x)] over 255 steps,
+// z = -128 - round(lo / s), code = clamp(round(x / s) + z).
+template <bool ZP>
 __global__ __launch_bounds__(256) void k_quant_int8(const float* __restrict__ x, int64_t rows, int64_t cols,
                                                     int64_t ng, int8_t* __restrict__ q,
-                                                    float* __restrict__ scales) {
+                                                    float* __restrict__ scales, float* __restrict__ zeros) {
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (wave >= rows * ng) return;
     const int lane = threadIdx.x & 63;
@@ -27,14 +30,26 @@ __global__ __launch_bounds__(256) void k_quant_int8(const float* __restrict__ x,
         for (int j = 0; j < 4; ++j)
             if (c0 + j < cols) v[j] = xr[c0 + j];
     }
-    float a = fmaxf(fmaxf(fabsf(v[0]), fabsf(v[1])), fmaxf(fabsf(v[2]), fabsf(v[3])));
-    a = wave_max(a);
-    const float s = a > 0.f ? a / 127.0f : 0.f;
-    const float inv = a > 0.f ? 127.0f / a : 0.f;
+    float s, inv, z = 0.f;
+    if constexpr (ZP) {
+        // elements past the row's end hold 0, which the range contains anyway
+        const float hi = wave_max(fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), 0.f));
+        const float lo = -wave_max(fmaxf(fmaxf(fmaxf(-v[0], -v[1]), fmaxf(-v[2], -v[3])), 0.f));
+        const float rng = hi - lo;
+        s = rng > 0.f ? rng / 255.0f : 0.f;
+        inv = rng > 0.f ? 255.0f / rng : 0.f;
+        z = rng > 0.f ? fminf(fmaxf(-128.f - rintf(lo * inv), -128.f), 127.f) : 0.f;
+        if (lane == 0) zeros[row * ng + g] = z;
+    } else {
+        float a = fmaxf(fmaxf(fabsf(v[0]), fabsf(v[1])), fmaxf(fabsf(v[2]), fabsf(v[3])));
+        a = wave_max(a);
+        s = a > 0.f ? a / 127.0f : 0.f;
+        inv = a > 0.f ? 127.0f / a : 0.f;
+    }
     if (lane == 0) scales[row * ng + g] = s;
     int c[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) c[j] = (int)fminf(fmaxf(rintf(v[j] * inv), -128.f), 127.f);
+    for (int j = 0; j < 4; ++j) c[j] = (int)fminf(fmaxf(rintf(v[j] * inv) + z, -128.f), 127.f);
     int8_t* qr = q + row * cols;
     if (vec) {
         if (c0 < cols) {
@@ -83,11 +98,13 @@ __global__ __launch_bounds__(256) void k_quant_int4(const float* __restrict__ x,
 }
 
 __global__ __launch_bounds__(256) void k_dequant_int8(const int8_t* __restrict__ q, const float* __restrict__ scales,
-                                                      int64_t rows, int64_t cols, int64_t ng, float* __restrict__ x) {
+                                                      const float* __restrict__ zeros, int64_t rows, int64_t cols,
+                                                      int64_t ng, float* __restrict__ x) {
     const int64_t total = rows * cols;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
         const int64_t row = e / cols, c = e % cols;
-        x[e] = (float)q[e] * scales[row * ng + c / kGroup];
+        const float z = zeros != nullptr ? zeros[row * ng + c / kGroup] : 0.f;
+        x[e] = ((float)q[e] - z) * scales[row * ng + c / kGroup];
     }
 }
 
@@ -135,8 +152,32 @@ extern "C" int qg_quant_int8(const float* x, int64_t rows, int64_t cols, int gro
     const int64_t ng = (cols + kGroup - 1) / kGroup;
     const int64_t waves = rows * ng;
     if ((waves + 3) / 4 > 0x7FFFFFFF) return QG_ERR_SHAPE;
-    hipLaunchKernelGGL(k_quant_int8, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, (hipStream_t)stream, x, rows,
-                       cols, ng, q, scales);
+    hipLaunchKernelGGL(k_quant_int8<false>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, (hipStream_t)stream, x, rows,
+                       cols, ng, q, scales, (float*)nullptr);
+    return check_launch();
+}
+
+extern "C" int qg_quant_int8_zp(const float* x, int64_t rows, int64_t cols, int group, int8_t* q, float* scales,
+                                float* zeros, void* stream) {
+    if (!zeros) return QG_ERR_NULL;
+    if (int e = check_quant_args(x, q, scales, rows, cols, group)) return e;
+    if (!aligned16(zeros)) return QG_ERR_ALIGN;
+    const int64_t ng = (cols + kGroup - 1) / kGroup;
+    const int64_t waves = rows * ng;
+    if ((waves + 3) / 4 > 0x7FFFFFFF) return QG_ERR_SHAPE;
+    hipLaunchKernelGGL(k_quant_int8<true>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, (hipStream_t)stream, x, rows,
+                       cols, ng, q, scales, zeros);
+    return check_launch();
+}
+
+extern "C" int qg_dequant_int8_zp(const int8_t* q, const float* scales, const float* zeros, int64_t rows, int64_t cols,
+                                  int group, float* x, void* stream) {
+    if (!zeros) return QG_ERR_NULL;
+    if (int e = check_quant_args(q, scales, x, rows, cols, group)) return e;
+    if (!aligned16(zeros)) return QG_ERR_ALIGN;
+    const int64_t ng = (cols + kGroup - 1) / kGroup;
+    hipLaunchKernelGGL(k_dequant_int8, dim3(grid_for(rows * cols, 256, 65536)), dim3(256), 0, (hipStream_t)stream, q,
+                       scales, zeros, rows, cols, ng, x);
     return check_launch();
 }
 
@@ -156,7 +197,7 @@ extern "C" int qg_dequant_int8(const int8_t* q, const float* scales, int64_t row
     if (int e = check_quant_args(q, scales, x, rows, cols, group)) return e;
     const int64_t ng = (cols + kGroup - 1) / kGroup;
     hipLaunchKernelGGL(k_dequant_int8, dim3(grid_for(rows * cols, 256, 65536)), dim3(256), 0, (hipStream_t)stream, q,
-                       scales, rows, cols, ng, x);
+                       scales, (const float*)nullptr, rows, cols, ng, x);
     return check_launch();
 }
 

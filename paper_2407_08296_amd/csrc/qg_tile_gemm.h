@@ -12,7 +12,8 @@
 
 namespace qg {
 
-enum : int { kBf16KFast = 0, kBf16KSlow = 1, kInt8KFast = 2, kInt8KSlow = 3 };
+// (the Z layouts: INT8 with a zero point per block, dequantized as (code - zero) * scale)
+enum : int { kBf16KFast = 0, kBf16KSlow = 1, kInt8KFast = 2, kInt8KSlow = 3, kInt8ZKFast = 4, kInt8ZKSlow = 5 };
 
 constexpr int kLinTM = 128;                // output tile: 128 (A's index) x TN (B's index, 256 or 128), 4 waves of 64 x TN/2;
                                            // BK (32 or 64) = contraction depth per step
@@ -29,13 +30,15 @@ __device__ __forceinline__ u32x4 load16_i8_guarded(const int8_t* src, int valid)
     return o;
 }
 
-// bf16(fl32(code * s)) of the 8 codes in two words
-__device__ __forceinline__ u32x4 dequant8_i8_bf16(uint32_t c0, uint32_t c1, float s) {
+// bf16(fl32(code * s)) of the 8 codes in two words; ZP: bf16(fl32((code - z) * s)), the difference being exact
+template <bool ZP = false>
+__device__ __forceinline__ u32x4 dequant8_i8_bf16(uint32_t c0, uint32_t c1, float s, float z = 0.f) {
     float e[8];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        e[j] = (float)(int)(int8_t)(c0 >> (8 * j)) * s;
-        e[4 + j] = (float)(int)(int8_t)(c1 >> (8 * j)) * s;
+        const float a = (float)(int)(int8_t)(c0 >> (8 * j)), b = (float)(int)(int8_t)(c1 >> (8 * j));
+        e[j] = ZP ? (a - z) * s : a * s;
+        e[4 + j] = ZP ? (b - z) * s : b * s;
     }
     const u32x4 o = {pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]), pack_bf16x2(e[4], e[5]), pack_bf16x2(e[6], e[7])};
     return o;
@@ -49,14 +52,16 @@ struct LinOperand {
     const float* scales;   // INT8 only: [rows][sgroups]
     int64_t ld;            // row length in elements
     int sgroups;
+    const float* zeros = nullptr;   // INT8 with zero points only: [rows][sgroups]
 };
 
 // Staging of one operand tile: global -> registers (fetch) -> LDS (commit; INT8 is dequantized here).  EXACT: the
 // tile lies inside the matrix, K is a whole number of steps and rows are 16-byte aligned - no checks.
 template <int LAYOUT, int XT, int BK, bool EXACT>
 struct LinStage {
-    static constexpr bool kFast = LAYOUT == kBf16KFast || LAYOUT == kInt8KFast;
-    static constexpr bool kInt8 = LAYOUT == kInt8KFast || LAYOUT == kInt8KSlow;
+    static constexpr bool kFast = LAYOUT == kBf16KFast || LAYOUT == kInt8KFast || LAYOUT == kInt8ZKFast;
+    static constexpr bool kZero = LAYOUT == kInt8ZKFast || LAYOUT == kInt8ZKSlow;
+    static constexpr bool kInt8 = LAYOUT == kInt8KFast || LAYOUT == kInt8KSlow || kZero;
     static constexpr int CH = kInt8 ? 16 : 8;                   // elements per 16-byte chunk (one block scale each)
     static constexpr int CPR = (kFast ? BK : XT) / CH;          // chunks per tile row
     static constexpr int PITCH = kFast ? BK + kPadX : XT + kPadK;   // LDS pitch: [x][k] or [k][x]
@@ -64,6 +69,7 @@ struct LinStage {
     static constexpr int PER = XT * BK / CH / 256;              // chunks per thread
     u32x4 v[PER];
     float s[kInt8 ? PER : 1];
+    float z[kZero ? PER : 1];
 
     __device__ __forceinline__ void fetch(const LinOperand& op, int x0, int X, int k0, int K) {
 #pragma unroll
@@ -79,6 +85,7 @@ struct LinStage {
                 const int8_t* src = static_cast<const int8_t*>(op.base) + off;
                 if constexpr (EXACT) v[q] = *reinterpret_cast<const u32x4*>(src); else v[q] = load16_i8_guarded(src, valid);
                 s[q] = valid > 0 ? op.scales[(int64_t)row * op.sgroups + (col >> 8)] : 0.f;
+                if constexpr (kZero) z[q] = valid > 0 ? op.zeros[(int64_t)row * op.sgroups + (col >> 8)] : 0.f;
             } else {
                 const uint16_t* src = static_cast<const uint16_t*>(op.base) + off;
                 if constexpr (EXACT) v[q] = *reinterpret_cast<const u32x4*>(src); else v[q] = load8_bf16_guarded(src, valid);
@@ -91,8 +98,8 @@ struct LinStage {
             const int idx = threadIdx.x + 256 * q;
             uint16_t* dst = tile + (idx / CPR) * PITCH + (idx % CPR) * CH;
             if constexpr (kInt8) {
-                *reinterpret_cast<u32x4*>(dst) = dequant8_i8_bf16(v[q][0], v[q][1], s[q]);
-                *reinterpret_cast<u32x4*>(dst + 8) = dequant8_i8_bf16(v[q][2], v[q][3], s[q]);
+                *reinterpret_cast<u32x4*>(dst) = dequant8_i8_bf16<kZero>(v[q][0], v[q][1], s[q], kZero ? z[q] : 0.f);
+                *reinterpret_cast<u32x4*>(dst + 8) = dequant8_i8_bf16<kZero>(v[q][2], v[q][3], s[q], kZero ? z[q] : 0.f);
             } else {
                 *reinterpret_cast<u32x4*>(dst) = v[q];
             }
@@ -310,7 +317,8 @@ static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, con
 template <int AL, int BL, typename OUT>
 static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M, int64_t N,
                             int64_t K, hipStream_t st) {
-    constexpr bool both_fast = (AL == kBf16KFast || AL == kInt8KFast) && (BL == kBf16KFast || BL == kInt8KFast);
+    constexpr bool both_fast = (AL == kBf16KFast || AL == kInt8KFast || AL == kInt8ZKFast) &&
+                               (BL == kBf16KFast || BL == kInt8KFast || BL == kInt8ZKFast);
     if constexpr (AL == kBf16KSlow && BL == kBf16KSlow) {
         const int64_t tiles_m = M / kLinTM, tiles_n = N / 256;
         if (M % kLinTM == 0 && N % 256 == 0 && K % 32 == 0 && bias == nullptr && tiles_m * tiles_n >= 512 && K >= 32) {

@@ -27,6 +27,8 @@ EXPORTS = [
     "qg_range_apply", "qg_orthonormalize_workspace_bytes", "qg_orthonormalize", "qg_refresh_workspace_bytes",
     "qg_subspace_refresh", "qg_subspace_refresh_many", "qg_int8_linear_forward", "qg_int8_linear_backward",
     "qg_int8_linear_t_forward", "qg_int8_linear_t_backward",
+    "qg_quant_int8_zp", "qg_dequant_int8_zp", "qg_backproject_update_sr_zp", "qg_step_zp",
+    "qg_int8_linear_zp_forward", "qg_int8_linear_zp_backward",
     "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8", "qg_step8",
 ]
 
@@ -48,7 +50,8 @@ class Policy(C.Structure):
 class MatrixDesc(C.Structure):
     _fields_ = [("m", C.c_int64), ("n", C.c_int64), ("r", C.c_int64),
                 ("Pq", C.c_void_p), ("Ps", C.c_void_p), ("G", C.c_void_p), ("Wq", C.c_void_p), ("Ws", C.c_void_p),
-                ("M", C.c_void_p), ("V", C.c_void_p), ("R", C.c_void_p), ("N", C.c_void_p), ("ld", C.c_int64)]
+                ("M", C.c_void_p), ("V", C.c_void_p), ("R", C.c_void_p), ("N", C.c_void_p), ("ld", C.c_int64),
+                ("Wz", C.c_void_p)]
 
 
 class RefreshDesc(C.Structure):
@@ -78,6 +81,13 @@ def lib() -> C.CDLL:
         L.qg_project.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, sz, vp]
         L.qg_lowrank_adam.argtypes = [vp, vp, vp, vp, i64, i64, C.POINTER(HParams), vp]
         L.qg_backproject_update_sr.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, f32, f32, u64, i64, vp, vp]
+        L.qg_quant_int8_zp.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
+        L.qg_dequant_int8_zp.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp]
+        L.qg_backproject_update_sr_zp.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, f32, f32, u64, i64, vp]
+        L.qg_step_zp.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, C.POINTER(HParams), u64,
+                                 i64, vp]
+        L.qg_int8_linear_zp_forward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
+        L.qg_int8_linear_zp_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp]
         L.qg_cossim_workspace_bytes.restype = sz
         L.qg_cossim_workspace_bytes.argtypes = [i64, i64]
         L.qg_subspace_cossim.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, sz, vp]
@@ -249,6 +259,7 @@ class MatrixState:
     R: torch.Tensor | None
     N: torch.Tensor
     ld: int = 0   # row pitch in elements of G, Wq, M, V, R, N; 0 = n
+    Wz: torch.Tensor | None = None   # zero points of W (all matrices of a plan, or none)
 
 
 class StepPlan:
@@ -265,6 +276,7 @@ class StepPlan:
             d.M, d.V, d.R = _ptr(s.M, (torch.float32,)), _ptr(s.V, (torch.float32,)), _ptr(s.R, (torch.float32,))
             d.N = _ptr(s.N, _BF16)
             d.ld = s.ld
+            d.Wz = _ptr(s.Wz, (torch.float32,))
         self.nbytes = lib().qg_plan_bytes(self.count, descs)
         self.host = torch.empty((self.nbytes,), dtype=torch.uint8).pin_memory()
         _check(lib().qg_plan_build(self.count, descs, self.host.data_ptr(), self.nbytes))
@@ -293,6 +305,60 @@ def project_adam_many(plan: StepPlan, hp: HParams, step: int, write_R: bool = Fa
 def backproject_update_sr_many(plan: StepPlan, hp: HParams, seed: int, step: int) -> None:
     _check(lib().qg_backproject_update_sr_many(plan.count, plan.host.data_ptr(), plan.dev.data_ptr(), plan.nbytes,
                                                C.byref(hp), seed, step, _stream()))
+
+
+# ---------------------------------------------------------------- zero-point (asymmetric) INT8 weights
+def quant_int8_zp(x: torch.Tensor):
+    rows, cols = x.shape
+    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device)
+    s = torch.empty((rows, (cols + GROUP - 1) // GROUP), dtype=torch.float32, device=x.device)
+    z = torch.empty_like(s)
+    _check(lib().qg_quant_int8_zp(_ptr(x, (torch.float32,)), rows, cols, GROUP, _ptr(q), _ptr(s), _ptr(z), _stream()))
+    return q, s, z
+
+
+def dequant_int8_zp(q: torch.Tensor, s: torch.Tensor, z: torch.Tensor) -> torch.Tensor:
+    rows, cols = q.shape
+    x = torch.empty((rows, cols), dtype=torch.float32, device=q.device)
+    _check(lib().qg_dequant_int8_zp(_ptr(q, (torch.int8,)), _ptr(s, (torch.float32,)), _ptr(z, (torch.float32,)), rows,
+                                    cols, GROUP, _ptr(x), _stream()))
+    return x
+
+
+def backproject_update_sr_zp(Pq, Ps, N, Wq, Ws, Wz, m: int, n: int, r: int, alpha: float, lr: float, seed: int,
+                             step: int) -> None:
+    _check(lib().qg_backproject_update_sr_zp(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(N, _BF16),
+                                             _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)),
+                                             _ptr(Wz, (torch.float32,)), m, n, r, GROUP, alpha, lr, seed, step, _stream()))
+
+
+def step_zp(Pq, Ps, G, Wq, Ws, Wz, M, V, R, N, m: int, n: int, r: int, hp: HParams, seed: int, step: int) -> None:
+    _check(lib().qg_step_zp(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(G, _BF16),
+                            _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)), _ptr(Wz, (torch.float32,)),
+                            _ptr(M, (torch.float32,)), _ptr(V, (torch.float32,)), _ptr(R, (torch.float32,)),
+                            _ptr(N, _BF16), m, n, r, GROUP, C.byref(hp), seed, step, _stream()))
+
+
+def int8_linear_zp_forward(x: torch.Tensor, Wq: torch.Tensor, Ws: torch.Tensor, Wz: torch.Tensor,
+                           bias: torch.Tensor | None = None):
+    tokens, n = x.shape
+    m = Wq.shape[0]
+    y = torch.empty((tokens, m), dtype=torch.bfloat16, device=x.device)
+    _check(lib().qg_int8_linear_zp_forward(_ptr(x, _BF16), _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)),
+                                           _ptr(Wz, (torch.float32,)), _ptr(bias, _BF16), tokens, m, n, GROUP,
+                                           _ptr(y), _stream()))
+    return y
+
+
+def int8_linear_zp_backward(dy: torch.Tensor, x: torch.Tensor | None, Wq, Ws, Wz, m: int, n: int,
+                            want_dx: bool = True, want_G: bool = True):
+    tokens = dy.shape[0]
+    dx = torch.empty((tokens, n), dtype=torch.bfloat16, device=dy.device) if want_dx else None
+    G = torch.empty((m, n), dtype=torch.bfloat16, device=dy.device) if want_G else None
+    _check(lib().qg_int8_linear_zp_backward(_ptr(dy, _BF16), _ptr(x, _BF16), _ptr(Wq, (torch.int8,)),
+                                            _ptr(Ws, (torch.float32,)), _ptr(Wz, (torch.float32,)), tokens, m, n, GROUP,
+                                            _ptr(dx), _ptr(G), _stream()))
+    return dx, G
 
 
 # ---------------------------------------------------------------- 8-bit Adam states

@@ -138,6 +138,38 @@ def test_int8_linear_argument_errors(L):
     assert L.qg_int8_linear_t_backward(FAKE, FAKE, FAKE, FAKE, 16, 512, 512, 256, FAKE, FAKE + 2, None) == 4
 
 
+def test_zero_point_argument_errors(L):
+    hp = qg.hparams()
+    assert L.qg_quant_int8_zp(FAKE, 4, 256, 256, FAKE, FAKE, None, None) == 1
+    assert L.qg_quant_int8_zp(FAKE, 0, 256, 256, FAKE, FAKE, FAKE, None) == 2
+    assert L.qg_quant_int8_zp(FAKE, 4, 256, 128, FAKE, FAKE, FAKE, None) == 3
+    assert L.qg_quant_int8_zp(FAKE, 4, 256, 256, FAKE, FAKE, FAKE + 4, None) == 4
+    assert L.qg_dequant_int8_zp(FAKE, FAKE, None, 4, 256, 256, FAKE, None) == 1
+    assert L.qg_backproject_update_sr_zp(FAKE, FAKE, FAKE, FAKE, FAKE, None, 512, 512, 128, 256, 0.25, 1e-3, 0, 1, None) == 1
+    assert L.qg_backproject_update_sr_zp(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 12, 256, 0.25, 1e-3, 0, 1, None) == 2
+    assert L.qg_backproject_update_sr_zp(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 128, 256, 0.25, 1e-3, 0, 0, None) == 2
+    assert L.qg_backproject_update_sr_zp(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 8, 512, 512, 128, 256, 0.25, 1e-3, 0, 1, None) == 4
+    assert L.qg_step_zp(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, None, FAKE, 512, 512, 128, 256, C.byref(hp), 0, 1, None) == 1
+    assert L.qg_step_zp(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 512, 512, 128, 64, C.byref(hp), 0, 1, None) == 3
+    assert L.qg_int8_linear_zp_forward(FAKE, FAKE, FAKE, None, None, 16, 512, 512, 256, FAKE, None) == 1
+    assert L.qg_int8_linear_zp_forward(FAKE, FAKE, FAKE, FAKE, None, 16, 512, 0, 256, FAKE, None) == 2
+    assert L.qg_int8_linear_zp_backward(FAKE, FAKE, FAKE, FAKE, None, 16, 512, 512, 256, FAKE, FAKE, None) == 1   # dx needs Wz
+    assert L.qg_int8_linear_zp_backward(FAKE, FAKE, None, None, None, 16, 512, 512, 256, None, FAKE + 2, None) == 4
+    # a plan takes zero points for all matrices or for none
+    descs = (qg.MatrixDesc * 2)()
+    for d in descs:
+        d.m, d.n, d.r = 512, 512, 128
+        for f in ("Pq", "Ps", "G", "Wq", "Ws", "M", "V", "R", "N"):
+            setattr(d, f, FAKE)
+    nbytes = L.qg_plan_bytes(2, descs)
+    buf = C.create_string_buffer(nbytes)
+    descs[0].Wz = FAKE
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 1
+    descs[1].Wz = FAKE
+    assert L.qg_plan_build(2, descs, buf, nbytes) == 0
+    assert (C.c_uint32 * 16).from_buffer(buf)[13] == 1      # header word: zero-point plan
+
+
 def test_adam8_argument_errors(L):
     hp = qg.hparams()
     assert L.qg_state8_quant(None, 256, 1, FAKE, FAKE, None) == 1
