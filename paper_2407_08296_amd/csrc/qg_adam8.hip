@@ -9,8 +9,8 @@
 //           the negatives from -1 up, 127 zero, 128..254 the positives; index 255 is not used.
 // One step: states are dequantized (table[code] * scale), updated exactly like the fp32 states, and quantized again;
 // 10 bytes of HBM traffic per element instead of 22.  A wave owns a block: a lane holds four consecutive elements,
-// the block maximum is a wave reduction; the nearest entry is estimated arithmetically (the table is linear inside a
-// decade) and settled against the four midpoints around the estimate in LDS.
+// the block maximum is a wave reduction; the nearest entry comes from a bucket table indexed by the value's top
+// float bits plus one comparison with a midpoint.
 #include "qg_common.h"
 
 namespace qg {
@@ -20,13 +20,23 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int kS8Block = kGroup;      // elements per block
 constexpr int kS8SignedZero = 127;    // index of 0 in the signed table
 
+// Bucket table of the encoder: the positive floats up to 1 are cut into buckets by their top 15 bits (exponent and 7
+// mantissa bits); lut[bucket] = number of midpoints below the bucket's lower edge.  Buckets are narrower than the
+// spacing of the midpoints everywhere (at most one midpoint per bucket, which s8_build relies on and the bit-exact
+// tests of the quantizer cover), so the code of a value is lut[bucket] plus one comparison with the next midpoint.
+constexpr int kS8KeyShift = 16;
+constexpr int kS8KeyOne = 0x3F800000 >> kS8KeyShift;     // bucket of 1.0
+constexpr int kS8UKey0 = 0x33560000 >> kS8KeyShift;      // bucket of the first midpoint of the unsigned table, 5e-8
+constexpr int kS8SKey0 = 0x35060000 >> kS8KeyShift;      // ... of the positive half of the signed table, 5e-7
+constexpr int kS8ULut = kS8KeyOne - kS8UKey0 + 1, kS8SLut = kS8KeyOne - kS8SKey0 + 1;
+
 struct S8Tables {
     float uval[256];    // unsigned table
     float umid[256];    // midpoints of neighbouring entries, padded with +inf
     float sval[256];    // signed table (255 entries, the last one repeated)
     float smid[256];
-    float pw[8];        // 10^-j
-    float ipw[8];       // 10^j
+    uint8_t ulut[(kS8ULut + 15) / 16 * 16];
+    uint8_t slut[(kS8SLut + 15) / 16 * 16];   // over the midpoints of the positive half, smid[127 + j]
 };
 
 // Entry p >= 1 of the positive half of a table with levels 0..top.
@@ -34,6 +44,16 @@ __device__ inline double s8_positive(int p, int top) {
     const double pow10neg[8] = {1e0, 1e-1, 1e-2, 1e-3, 1e-4, 1e-5, 1e-6, 1e-7};
     const int L = 31 - __clz(p), k = p - (1 << L);
     return pow10neg[top - L] * (0.1 + 0.9 * (double)(k + 1) / (double)(1 << L));
+}
+
+// Number of the `count` ascending midpoints mid[0..count) that lie below x.
+__device__ inline int s8_count_below(const float* mid, int count, float x) {
+    int lo = 0, hi = count;   // answer in [lo, hi]
+    while (lo < hi) {
+        const int m = (lo + hi) >> 1;
+        if (mid[m] < x) lo = m + 1; else hi = m;
+    }
+    return lo;
 }
 
 // Every workgroup (256 threads) builds the tables from the definition; thread p makes entry p.
@@ -45,41 +65,27 @@ __device__ inline void s8_build(S8Tables& T) {
     else if (p == kS8SignedZero) s = 0.f;
     else s = (float)s8_positive((p < 255 ? p : 254) - kS8SignedZero, 6);
     T.sval[p] = s;
-    if (p < 8) {
-        const double pow10[8] = {1e0, 1e1, 1e2, 1e3, 1e4, 1e5, 1e6, 1e7};
-        T.pw[p] = (float)(1.0 / pow10[p]);
-        T.ipw[p] = (float)pow10[p];
-    }
     __syncthreads();
     T.umid[p] = p < 255 ? (float)(0.5 * ((double)T.uval[p] + (double)T.uval[p + 1])) : INFINITY;
     T.smid[p] = p < 254 ? (float)(0.5 * ((double)T.sval[p] + (double)T.sval[p + 1])) : INFINITY;
     __syncthreads();
+    for (int i = p; i < kS8ULut; i += 256)
+        T.ulut[i] = (uint8_t)s8_count_below(T.umid, 255, __builtin_bit_cast(float, (uint32_t)(kS8UKey0 + i) << kS8KeyShift));
+    for (int i = p; i < kS8SLut; i += 256)
+        T.slut[i] = (uint8_t)s8_count_below(T.smid + kS8SignedZero, 127,
+                                            __builtin_bit_cast(float, (uint32_t)(kS8SKey0 + i) << kS8KeyShift));
+    __syncthreads();
 }
 
-// Index, to within one entry, of the entry nearest to the magnitude ax >= 0 in the positive half of a table with
-// levels 0..TOP (index 0 = the zero entry).  The decade comes from the binary exponent (floor(e2 log10 2), one low at
-// most, put right by one comparison with the decade's top); inside a decade the entries are linear.  Checked on the
-// host against a sorted search for every entry and midpoint +- 4 ulps and 10^7 random values: never off by more
-// than one.
-template <int TOP>
-__device__ inline int s8_estimate(const S8Tables& T, float ax) {
-    const int e2 = (int)(__builtin_bit_cast(uint32_t, ax) >> 23) - 127;
-    int L = min(max(TOP + 1 + ((e2 * 1233) >> 12), 0), TOP);
-    if (L < TOP && ax > T.pw[TOP - L]) ++L;
-    const float t = ax * T.ipw[TOP - L];
-    const float c = (float)(1 << L) * (1.0f / 0.9f);
-    const int k = (int)rintf(t * c - 0.1f * c - 1.0f);
-    return (1 << L) + min(max(k, -1), 1 << L);
-}
-
-// Index of the nearest table entry, ties to the lower index = the number of midpoints below x: the estimate is
-// within one entry, so counting the four midpoints around it settles it exactly.
-__device__ inline uint32_t s8_nearest4(const float* mid, int est, float x) {
-    const float* m = mid + est - 2;
-    return (uint32_t)(est - 2 + (m[0] < x) + (m[1] < x) + (m[2] < x) + (m[3] < x));
+// Bucket of the magnitude ax >= 0 (values above 1 by a rounding error share the bucket of 1).
+template <int KEY0, int SIZE>
+__device__ inline int s8_bucket(float ax) {
+    const int key = (int)(__builtin_bit_cast(uint32_t, ax) >> kS8KeyShift);
+    return min(max(key - KEY0, 0), SIZE - 1);
 }
 
 // Codes of the lane's four values of a block whose absolute maximum is amax; returns them packed, low byte first.
+// A code is the index of the nearest table entry, ties to the lower index = the number of midpoints below the value.
 template <bool SIGNED>
 __device__ inline uint32_t s8_encode4(const S8Tables& T, const float (&x)[4], float amax) {
     const float inv = amax > 0.f ? 1.0f / amax : 0.f;
@@ -89,11 +95,14 @@ __device__ inline uint32_t s8_encode4(const S8Tables& T, const float (&x)[4], fl
         const float xn = x[j] * inv;
         uint32_t code;
         if constexpr (SIGNED) {
-            const int pm = min(max(s8_estimate<6>(T, fabsf(xn)), 0), kS8SignedZero);
-            const int est = xn < 0.f ? kS8SignedZero - pm : kS8SignedZero + pm;
-            code = s8_nearest4(T.smid, min(max(est, 2), 252), xn);
+            // the table is symmetric: midpoints below a negative value -a = 127 - (positive midpoints <= a)
+            const float a = fabsf(xn);
+            const int c = T.slut[s8_bucket<kS8SKey0, kS8SLut>(a)];
+            const float mid = T.smid[kS8SignedZero + c];
+            code = xn < 0.f ? (uint32_t)(kS8SignedZero - c - (mid <= a)) : (uint32_t)(kS8SignedZero + c + (mid < a));
         } else {
-            code = s8_nearest4(T.umid, min(max(s8_estimate<7>(T, xn), 2), 253), xn);
+            const int c = T.ulut[s8_bucket<kS8UKey0, kS8ULut>(fmaxf(xn, 0.f))];   // nothing lies below a negative value
+            code = (uint32_t)(c + (T.umid[c] < xn));
         }
         pk |= code << (8 * j);
     }
@@ -182,6 +191,7 @@ __global__ __launch_bounds__(256) void k_lowrank_adam8(const float* __restrict__
 static unsigned s8_grid(int64_t count) {
     const int64_t blocks = (count + kS8Block - 1) / kS8Block, wgs = (blocks + 3) / 4;
     return (unsigned)(wgs < 8192 ? wgs : 8192);          // 32 waves per CU at most; the rest is a grid-stride loop
+                                                         // (2048 workgroups, one resident set, measured slower)
 }
 
 static int check_state8(int64_t count) {
