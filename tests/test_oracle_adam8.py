@@ -91,3 +91,21 @@ def test_adam_with_8bit_states_tracks_fp_adam_and_saturates():
     b1, b2 = float(np.float32(0.9)), float(np.float32(0.999))
     assert np.allclose(M2, b1 * Md + (1 - b1) * R, rtol=1e-15) and np.allclose(V2, b2 * Vd + (1 - b2) * R * R, rtol=1e-15)
     assert np.array_equal(Q.state8_quant(M2, True)[0], Mq2)
+
+
+def test_midpoints_are_wider_apart_than_float_buckets_of_15_bits():
+    """A property of the format the library's encoder builds on: cut the positive floats by their top 15 bits (8
+    exponent + 7 mantissa bits); between the first midpoint and 1 no such bucket holds more than one midpoint of the
+    unsigned table or of the positive half of the signed one, so a value's code is the count of midpoints below its
+    bucket's lower edge plus at most one."""
+    for signed in (False, True):
+        tab = Q.state8_table(signed).astype(np.float32)
+        mids = np.asarray(Q._state8_mids(tab), dtype=np.float32)
+        pm = mids[127:254] if signed else mids[:255]
+        assert np.all(np.diff(pm) > 0) and pm[0] > 0
+        k0 = int(np.float32(pm[0]).view(np.uint32)) >> 16
+        k1 = int(np.float32(1.0).view(np.uint32)) >> 16
+        edges = (np.arange(k0, k1 + 2, dtype=np.uint32) << np.uint32(16)).view(np.float32)
+        below = np.searchsorted(pm, edges, side="left")
+        assert np.diff(below).max() == 1
+        assert (k0, k1) == ((13574, 16256) if signed else (13142, 16256))
