@@ -2,16 +2,22 @@
 // cosine between corresponding columns of two INT4 projection matrices.
 // Deterministic: per-row-chunk partial sums, then per-column cosines and their mean, all in fixed orders.
 #include "qg_common.h"
+#include "qg_cossim.h"
 
 namespace qg {
 
 constexpr int kCosRows = 64;  // rows per partial-sum chunk
 
+// Up to kCosBatchMax pairs of one shape per launch (gridDim.y of them), pointers by value (CosBatch); pair z uses the
+// workspace slice at z * ws_stride floats and writes cos_out[z].
 // partial[chunk][3][r]: dot, |a|^2, |b|^2 of each column over the chunk's rows.
-__global__ __launch_bounds__(256) void k_cossim_partial(const uint8_t* __restrict__ PqA, const float* __restrict__ PsA,
-                                                        const uint8_t* __restrict__ PqB, const float* __restrict__ PsB,
-                                                        int m, int r, int wpr, int lanes_rows, int chunks,
-                                                        float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void k_cossim_partial(CosBatch batch, int m, int r, int wpr, int lanes_rows, int chunks,
+                                                        float* __restrict__ partial, int64_t ws_stride) {
+    const uint8_t* __restrict__ PqA = batch.PqA[blockIdx.y];
+    const float* __restrict__ PsA = batch.PsA[blockIdx.y];
+    const uint8_t* __restrict__ PqB = batch.PqB[blockIdx.y];
+    const float* __restrict__ PsB = batch.PsB[blockIdx.y];
+    partial += ws_stride * blockIdx.y;
     const int t = threadIdx.x;
     const int rl = t / wpr, wc0 = t % wpr;
     if (rl >= lanes_rows) return;
@@ -53,7 +59,9 @@ __global__ __launch_bounds__(256) void k_cossim_partial(const uint8_t* __restric
 constexpr int kCosGroup = 64;
 
 __global__ __launch_bounds__(256) void k_cossim_columns(const float* __restrict__ partial, int r, int chunks,
-                                                        float* __restrict__ group_sum) {
+                                                        float* __restrict__ group_sum, int64_t ws_stride) {
+    partial += ws_stride * blockIdx.y;
+    group_sum += ws_stride * blockIdx.y;
     __shared__ float sh[3][4][kCosGroup];
     __shared__ float cosv[kCosGroup];
     const int t = threadIdx.x, cl = t & 63, part = t >> 6;
@@ -86,11 +94,42 @@ __global__ __launch_bounds__(256) void k_cossim_columns(const float* __restrict_
     if (t == 0) group_sum[blockIdx.x] = cosv[0];
 }
 
-__global__ void k_cossim_mean(const float* __restrict__ group_sum, int groups, int r, float* __restrict__ cos_out) {
+__global__ void k_cossim_mean(const float* __restrict__ group_sum, int groups, int r, float* __restrict__ cos_out,
+                              int64_t ws_stride) {
+    group_sum += ws_stride * blockIdx.x;
     float acc = 0.f;
     for (int g = 0; g < groups; ++g) acc += group_sum[g];
-    cos_out[0] = acc / (float)r;
+    cos_out[blockIdx.x] = acc / (float)r;
 }
+
+static size_t cossim_ws_floats(int64_t m, int64_t r) {
+    const int64_t chunks = (m + kCosRows - 1) / kCosRows;
+    const int64_t groups = (r + kCosGroup - 1) / kCosGroup;
+    return (size_t)((chunks * 3 * r + groups + 63) / 64 * 64);   // partial sums, then one sum per column group; padded
+}
+
+// `count` <= kCosBatchMax pairs; workspace: count slices of cossim_ws_floats(m, r) floats.
+int launch_cossim_batch(const CosBatch& batch, int count, int64_t m, int64_t r, float* cos_out, float* ws,
+                        hipStream_t stream) {
+    const int W = (int)(r >> 3);
+    const int wpr = W < 256 ? W : 256;
+    const int lanes_rows = 256 / wpr;
+    const int chunks = (int)((m + kCosRows - 1) / kCosRows);
+    const int blocks = (chunks + lanes_rows - 1) / lanes_rows;
+    const int64_t stride = (int64_t)cossim_ws_floats(m, r);
+    hipLaunchKernelGGL(k_cossim_partial, dim3(blocks, count), dim3(256), 0, stream, batch, (int)m, (int)r, wpr, lanes_rows,
+                       chunks, ws, stride);
+    if (int e = check_launch()) return e;
+    const int groups = (int)((r + kCosGroup - 1) / kCosGroup);
+    float* group_sum = ws + (int64_t)chunks * 3 * r;
+    hipLaunchKernelGGL(k_cossim_columns, dim3(groups, count), dim3(256), 0, stream, (const float*)ws, (int)r, chunks,
+                       group_sum, stride);
+    hipLaunchKernelGGL(k_cossim_mean, dim3(count), dim3(1), 0, stream, (const float*)group_sum, groups, (int)r, cos_out,
+                       stride);
+    return check_launch();
+}
+
+size_t cossim_batch_workspace_bytes(int64_t m, int64_t r, int count) { return cossim_ws_floats(m, r) * 4 * (size_t)count; }
 
 }  // namespace qg
 
@@ -113,19 +152,9 @@ extern "C" int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const ui
     if ((reinterpret_cast<uintptr_t>(cos_out) & 3u) != 0) return QG_ERR_ALIGN;
     if (!workspace || workspace_bytes < qg_cossim_workspace_bytes(m, r) || !aligned16(workspace))
         return QG_ERR_WORKSPACE;
-    const int W = (int)(r >> 3);
-    const int wpr = W < 256 ? W : 256;
-    const int lanes_rows = 256 / wpr;
-    const int chunks = (int)((m + kCosRows - 1) / kCosRows);
-    const int blocks = (chunks + lanes_rows - 1) / lanes_rows;
-    hipLaunchKernelGGL(k_cossim_partial, dim3(blocks), dim3(256), 0, (hipStream_t)stream, PqA, PsA, PqB, PsB, (int)m,
-                       (int)r, wpr, lanes_rows, chunks, (float*)workspace);
-    if (int e = check_launch()) return e;
-    const int groups = (int)((r + kCosGroup - 1) / kCosGroup);
-    float* group_sum = (float*)workspace + (int64_t)chunks * 3 * r;
-    hipLaunchKernelGGL(k_cossim_columns, dim3(groups), dim3(256), 0, (hipStream_t)stream, (const float*)workspace, (int)r,
-                       chunks, group_sum);
-    hipLaunchKernelGGL(k_cossim_mean, dim3(1), dim3(1), 0, (hipStream_t)stream, (const float*)group_sum, groups, (int)r,
-                       cos_out);
-    return check_launch();
+    CosBatch batch;
+    for (int i = 0; i < kCosBatchMax; ++i) {
+        batch.PqA[i] = PqA; batch.PsA[i] = PsA; batch.PqB[i] = PqB; batch.PsB[i] = PsB;
+    }
+    return launch_cossim_batch(batch, 1, m, r, cos_out, (float*)workspace, (hipStream_t)stream);
 }

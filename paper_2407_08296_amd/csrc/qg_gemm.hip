@@ -116,6 +116,31 @@ int launch_project(const uint8_t* Pq, const float* Ps, const uint16_t* G, float*
     return launch_project_cfg<128, 128, 32, 2, 2, 2>(Pq, Ps, G, R, (int)m, (int)n, (int)r, stream);
 }
 
+// R_z = dequant(P_z)^T G_z for `count` (<= kProjBatchMax) matrices of one shape in one launch, with the tiles of the
+// grouped step (same arithmetic per element as launch_project: the order of the sum over m does not depend on the
+// tile shape).
+int launch_project_batch(const ProjBatch& batch, int count, float* R, int64_t strideR, int64_t m, int64_t n, int64_t r,
+                         hipStream_t stream) {
+    constexpr int BM = kManyProjBM, BN = kManyProjBN;
+    const uint32_t tiles_r = (uint32_t)((r + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
+    const uint32_t tiles_per = tiles_r * tiles_n, tiles = tiles_per * (uint32_t)count;
+    const dim3 grid(grid8(tiles)), block(256);
+    switch (edge_mode(r, BM, n, n, BN, m, 32, r)) {
+        case kExact:
+            hipLaunchKernelGGL((k_project_batch<BM, BN, 32, 2, 2, kExact, 2>), grid, block, 0, stream, batch, R, strideR,
+                               (int)m, (int)n, (int)r, tiles_r, tiles_per, tiles);
+            break;
+        case kMasked:
+            hipLaunchKernelGGL((k_project_batch<BM, BN, 32, 2, 2, kMasked, 2>), grid, block, 0, stream, batch, R, strideR,
+                               (int)m, (int)n, (int)r, tiles_r, tiles_per, tiles);
+            break;
+        default:
+            hipLaunchKernelGGL((k_project_batch<BM, BN, 32, 2, 2, kUnaligned, 2>), grid, block, 0, stream, batch, R,
+                               strideR, (int)m, (int)n, (int)r, tiles_r, tiles_per, tiles);
+    }
+    return check_launch();
+}
+
 // Workgroups per CU the back-projection instances are compiled for (the checked variants need more registers).
 static constexpr int kBpWgPerCu[3] = {3, 3, 2};
 

@@ -557,6 +557,29 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(c
                                                (int)(local / d.proj_tiles_r) * BN, smem);
 }
 
+// Up to kProjBatchMax matrices of one shape in one launch, their pointers passed by value (no plan in device memory:
+// what the subspace refresh needs, which owns no device buffer beyond its workspace and may run under graph capture).
+// R of matrix z goes to R + z * strideR.
+constexpr int kProjBatchMax = 16;
+struct ProjBatch {
+    const uint8_t* Pq[kProjBatchMax];
+    const float* Ps[kProjBatchMax];
+    const uint16_t* G[kProjBatchMax];
+};
+
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU = 1>
+__global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_batch(ProjBatch batch, float* __restrict__ R,
+                                                                                int64_t strideR, int m, int n, int r,
+                                                                                uint32_t tiles_r, uint32_t tiles_per,
+                                                                                uint32_t tiles) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    if (tile >= tiles) return;
+    const uint32_t z = tile / tiles_per, local = tile % tiles_per;
+    project_tile<BM, BN, BK, WGM, WGN, MODE>(batch.Pq[z], batch.Ps[z], batch.G[z], R + (int64_t)z * strideR, m, n, n, r,
+                                               (int)(local % tiles_r) * BM, (int)(local / tiles_r) * BN, smem);
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam_many(const PlanHeader* __restrict__ plan,
                                                                                      int first, int count,

@@ -17,9 +17,13 @@
 // the first round's pivots positive for cond(Y) well beyond 1e8 at no cost in the result.  A column that is
 // numerically dependent on its predecessors (a last-round pivot no larger than the shift) is reported through
 // `info`; every kernel runs to completion whatever the data.
+#include "qg_cossim.h"
 #include "qg_tile_gemm.h"
 
 namespace qg {
+
+int launch_project_batch(const ProjBatch& batch, int count, float* R, int64_t strideR, int64_t m, int64_t n, int64_t r,
+                         hipStream_t stream);   // qg_gemm.hip
 
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef double f64x2 __attribute__((ext_vector_type(2)));
@@ -498,19 +502,29 @@ static OrthLayout orth_layout(int64_t m, int64_t r, int64_t batch) {
 // Workspace of the refresh of `batch` matrices of one shape: R and Z of the matrix in flight (shared: the
 // per-matrix launches are ordered on the stream), per matrix Y (which also receives Q), then the orthonormalisation's
 // and the cosine check's.
+// The two GEMMs that precede the orthonormalisation (R = P^T G, Y = G Z^T) run over groups of up to kRefreshGroup
+// matrices per launch, so R and Z are held for that many matrices; Y, Q and the Cholesky QR for the whole batch.
+constexpr int kRefreshGroup = 16;
+static_assert(kRefreshGroup <= kProjBatchMax && kRefreshGroup <= kLinBatchMax && kRefreshGroup <= kCosBatchMax, "group size");
 struct RefreshLayout {
     size_t R, Z, Y, orth, cos, total;
     size_t y_bytes;   // per matrix
+    size_t r_bytes, z_bytes;
+    int group;        // matrices per GEMM launch
 };
 static RefreshLayout refresh_layout(int64_t m, int64_t n, int64_t r, int64_t batch) {
     RefreshLayout L;
+    L.group = (int)(batch < kRefreshGroup ? batch : kRefreshGroup);
     L.y_bytes = align256((size_t)m * r * 4);
+    const size_t slice = ((size_t)r * n + 127) / 128 * 128;   // elements per matrix of R and of Z: the same count, so
+    L.r_bytes = slice * 4;                                     // that one conversion launch maps R onto Z slice by slice
+    L.z_bytes = slice * 2;
     L.R = 0;
-    L.Z = L.R + align256((size_t)r * n * 4);
-    L.Y = L.Z + align256((size_t)r * n * 2);
+    L.Z = L.R + L.r_bytes * L.group;
+    L.Y = L.Z + L.z_bytes * L.group;
     L.orth = L.Y + 2 * L.y_bytes * batch;        // Y and Q of every matrix
     L.cos = L.orth + orth_layout(m, r, batch).total;
-    L.total = L.cos + align256(qg_cossim_workspace_bytes(m, r));
+    L.total = L.cos + align256(cossim_batch_workspace_bytes(m, r, L.group));
     return L;
 }
 
@@ -640,16 +654,41 @@ extern "C" int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs,
     float* Q = reinterpret_cast<float*>(ws + L.Y + L.y_bytes * batch);
     const int64_t sY = (int64_t)(L.y_bytes / 4);
     hipStream_t st = (hipStream_t)stream;
+    const int64_t sR = (int64_t)(L.r_bytes / 4);
     for (int first = 0; first < count; first += batch) {
         const int nb = count - first < batch ? count - first : batch;
         for (int pass = 0; pass < passes; ++pass) {
-            for (int b = 0; b < nb; ++b) {
-                const qg_refresh_desc& d = descs[first + b];
-                const uint8_t* pq = pass == 0 ? d.Pq : d.Pq_new;
-                const float* ps = pass == 0 ? d.Ps : d.Ps_new;
-                if (int e = qg_project(pq, ps, d.G, m, n, r, group, R, nullptr, 0, stream)) return e;
-                if (int e = launch_to_bf16(R, Z, r * n, st)) return e;
-                if (int e = launch_range(d.G, Z, Y + b * sY, m, n, r, st)) return e;
+            for (int g0 = 0; g0 < nb; g0 += L.group) {
+                const int ng = nb - g0 < L.group ? nb - g0 : L.group;
+                if (ng == 1) {   // one matrix: the single-matrix launches (smaller tiles, lower latency)
+                    const qg_refresh_desc& d = descs[first + g0];
+                    const uint8_t* pq = pass == 0 ? d.Pq : d.Pq_new;
+                    const float* ps = pass == 0 ? d.Ps : d.Ps_new;
+                    if (int e = qg_project(pq, ps, d.G, m, n, r, group, R, nullptr, 0, stream)) return e;
+                    if (int e = launch_to_bf16(R, Z, r * n, st)) return e;
+                    if (int e = launch_range(d.G, Z, Y + g0 * sY, m, n, r, st)) return e;
+                    continue;
+                }
+                ProjBatch pb;
+                LinBatch lb;
+                for (int b = 0; b < ng; ++b) {
+                    const qg_refresh_desc& d = descs[first + g0 + b];
+                    pb.Pq[b] = pass == 0 ? d.Pq : d.Pq_new;
+                    pb.Ps[b] = pass == 0 ? d.Ps : d.Ps_new;
+                    pb.G[b] = d.G;
+                    lb.a[b] = d.G;
+                }
+                for (int b = ng; b < kRefreshGroup; ++b) {   // unused slots: valid pointers, never dereferenced
+                    pb.Pq[b] = pb.Pq[0]; pb.Ps[b] = pb.Ps[0]; pb.G[b] = pb.G[0]; lb.a[b] = lb.a[0];
+                }
+                lb.strideB_bytes = (int64_t)L.z_bytes;
+                lb.strideC = sY;
+                if (int e = launch_project_batch(pb, ng, R, sR, m, n, r, st)) return e;
+                // the slices of R and of Z hold the same number of elements
+                if (int e = launch_to_bf16(R, Z, sR * (ng - 1) + r * n, st)) return e;
+                const LinOperand A = {pb.G[0], nullptr, n, 0}, B = {Z, nullptr, n, 0};
+                if (int e = launch_tile_gemm<kBf16KFast, kBf16KFast, float>(A, B, nullptr, Y + g0 * sY, m, r, n, st, &lb, ng))
+                    return e;
             }
             if (int e = launch_orth(Y, sY, Q, sY, m, r, nb, info + first, pass == 0, ws + L.orth, st)) return e;
             for (int b = 0; b < nb; ++b) {
@@ -657,10 +696,14 @@ extern "C" int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs,
                 if (int e = qg_quant_int4(Q + b * sY, m, r, group, d.Pq_new, d.Ps_new, stream)) return e;
             }
         }
-        for (int b = 0; b < nb; ++b) {
-            const qg_refresh_desc& d = descs[first + b];
-            if (int e = qg_subspace_cossim(d.Pq, d.Ps, d.Pq_new, d.Ps_new, m, r, group, cos_out + first + b, ws + L.cos,
-                                           workspace_bytes - L.cos, stream))
+        for (int g0 = 0; g0 < nb; g0 += L.group) {
+            const int ng = nb - g0 < L.group ? nb - g0 : L.group;
+            CosBatch cb;
+            for (int b = 0; b < kCosBatchMax; ++b) {   // unused slots repeat the first pair
+                const qg_refresh_desc& d = descs[first + g0 + (b < ng ? b : 0)];
+                cb.PqA[b] = d.Pq; cb.PsA[b] = d.Ps; cb.PqB[b] = d.Pq_new; cb.PsB[b] = d.Ps_new;
+            }
+            if (int e = launch_cossim_batch(cb, ng, m, r, cos_out + first + g0, reinterpret_cast<float*>(ws + L.cos), st))
                 return e;
         }
     }

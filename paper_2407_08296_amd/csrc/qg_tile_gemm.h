@@ -55,6 +55,15 @@ struct LinOperand {
     const float* zeros = nullptr;   // INT8 with zero points only: [rows][sgroups]
 };
 
+// Several GEMMs of one shape in one launch (gridDim.y of them): GEMM z takes its A operand from a[z], its B operand
+// strideB_bytes * z past B's base and writes C + strideC * z.  One GEMM: a[0] = A's base, strides 0.
+constexpr int kLinBatchMax = 16;
+struct LinBatch {
+    const void* a[kLinBatchMax];
+    int64_t strideB_bytes;
+    int64_t strideC;
+};
+
 // Staging of one operand tile: global -> registers (fetch) -> LDS (commit; INT8 is dequantized here).  EXACT: the
 // tile lies inside the matrix, K is a whole number of steps and rows are 16-byte aligned - no checks.
 template <int LAYOUT, int XT, int BK, bool EXACT>
@@ -120,9 +129,13 @@ struct LinStage {
 // before those MFMAs) are written to the other stage; one barrier per step.
 template <int AL, int BL, bool EXACT, typename OUT, int TN, int BK>
 __global__ __launch_bounds__(256, 2) void k_tile_gemm(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
-                                                      OUT* __restrict__ C, int M, int N, int K, int tiles_m, int tiles_n) {
+                                                      OUT* __restrict__ C, int M, int N, int K, int tiles_m, int tiles_n,
+                                                      LinBatch batch) {
     using SA = LinStage<AL, kLinTM, BK, EXACT>;
     using SB = LinStage<BL, TN, BK, EXACT>;
+    A.base = batch.a[blockIdx.y];
+    B.base = static_cast<const char*>(B.base) + batch.strideB_bytes * blockIdx.y;
+    C += batch.strideC * blockIdx.y;
     __shared__ __attribute__((aligned(16))) uint16_t At[2][SA::ELEMS];
     __shared__ __attribute__((aligned(16))) uint16_t Bt[2][SB::ELEMS];
     const int lane = threadIdx.x & 63;
@@ -296,17 +309,25 @@ __global__ __launch_bounds__(256, 3) void k_gemm_kslow_direct(const uint16_t* __
 
 template <int AL, int BL, typename OUT, int TN, int BK>
 static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M,
-                                   int64_t N, int64_t K, hipStream_t st) {
+                                   int64_t N, int64_t K, hipStream_t st, const LinBatch* many, int count) {
     const int64_t tiles_m = (M + kLinTM - 1) / kLinTM, tiles_n = (N + TN - 1) / TN;
-    const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);   // a multiple of the 8 XCDs
+    const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8), (unsigned)count);   // x: a multiple of the 8 XCDs
+    LinBatch batch;
+    if (many != nullptr) {
+        batch = *many;
+    } else {
+        batch.a[0] = A.base;
+        batch.strideB_bytes = 0;
+        batch.strideC = 0;
+    }
     // no checks at all when every tile and every step is whole and rows start 16-byte aligned
     const bool exact = M % kLinTM == 0 && N % TN == 0 && K % BK == 0 && A.ld % 8 == 0 && B.ld % 16 == 0;
     if (exact)
-        hipLaunchKernelGGL((k_tile_gemm<AL, BL, true, OUT, TN, BK>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M,
-                           (int)N, (int)K, (int)tiles_m, (int)tiles_n);
+        hipLaunchKernelGGL((k_tile_gemm<AL, BL, true, OUT, TN, BK>), grid, dim3(256), 0, st, A, B, bias, C, (int)M,
+                           (int)N, (int)K, (int)tiles_m, (int)tiles_n, batch);
     else
-        hipLaunchKernelGGL((k_tile_gemm<AL, BL, false, OUT, TN, BK>), dim3(grid), dim3(256), 0, st, A, B, bias, C, (int)M,
-                           (int)N, (int)K, (int)tiles_m, (int)tiles_n);
+        hipLaunchKernelGGL((k_tile_gemm<AL, BL, false, OUT, TN, BK>), grid, dim3(256), 0, st, A, B, bias, C, (int)M,
+                           (int)N, (int)K, (int)tiles_m, (int)tiles_n, batch);
 }
 
 // Tile shape.  Operands whose contraction index is slow want the wide tile: 128 x 256 with 32-deep steps when that
@@ -316,12 +337,13 @@ static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, con
 // and 2.80 ms for 128 x 128 with 32-deep steps).
 template <int AL, int BL, typename OUT>
 static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M, int64_t N,
-                            int64_t K, hipStream_t st) {
+                            int64_t K, hipStream_t st, const LinBatch* many = nullptr, int count = 1) {
     constexpr bool both_fast = (AL == kBf16KFast || AL == kInt8KFast || AL == kInt8ZKFast) &&
                                (BL == kBf16KFast || BL == kInt8KFast || BL == kInt8ZKFast);
     if constexpr (AL == kBf16KSlow && BL == kBf16KSlow) {
         const int64_t tiles_m = M / kLinTM, tiles_n = N / 256;
-        if (M % kLinTM == 0 && N % 256 == 0 && K % 32 == 0 && bias == nullptr && tiles_m * tiles_n >= 512 && K >= 32) {
+        if (many == nullptr && M % kLinTM == 0 && N % 256 == 0 && K % 32 == 0 && bias == nullptr &&
+            tiles_m * tiles_n >= 512 && K >= 32) {
             const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);
             hipLaunchKernelGGL((k_gemm_kslow_direct<OUT>), dim3(grid), dim3(256), 0, st, static_cast<const uint16_t*>(A.base),
                                static_cast<const uint16_t*>(B.base), C, (int)M, (int)N, (int)K, (int)tiles_m, (int)tiles_n);
@@ -329,11 +351,11 @@ static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint
         }
     }
     if constexpr (both_fast)
-        launch_tile_gemm_shape<AL, BL, OUT, 128, 64>(A, B, bias, C, M, N, K, st);
-    else if (((M + kLinTM - 1) / kLinTM) * ((N + 255) / 256) >= 512)
-        launch_tile_gemm_shape<AL, BL, OUT, 256, 32>(A, B, bias, C, M, N, K, st);
+        launch_tile_gemm_shape<AL, BL, OUT, 128, 64>(A, B, bias, C, M, N, K, st, many, count);
+    else if (((M + kLinTM - 1) / kLinTM) * ((N + 255) / 256) * count >= 512)
+        launch_tile_gemm_shape<AL, BL, OUT, 256, 32>(A, B, bias, C, M, N, K, st, many, count);
     else
-        launch_tile_gemm_shape<AL, BL, OUT, 128, 32>(A, B, bias, C, M, N, K, st);
+        launch_tile_gemm_shape<AL, BL, OUT, 128, 32>(A, B, bias, C, M, N, K, st, many, count);
     return check_launch();
 }
 

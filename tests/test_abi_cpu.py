@@ -93,7 +93,9 @@ def test_refresh_argument_errors(L):
     assert rb >= 128 * 512 * 6 + 2 * 512 * 128 * 4 + ob + L.qg_cossim_workspace_bytes(512, 128)
     assert L.qg_refresh_workspace_bytes(1, 512, 0, 128) == 0 and L.qg_refresh_workspace_bytes(0, 512, 512, 128) == 0
     rb4 = L.qg_refresh_workspace_bytes(4, 512, 512, 128)
-    assert rb < rb4 < 4 * rb                                                                 # R and Z are shared
+    assert rb < rb4 <= 4 * rb
+    rb64 = L.qg_refresh_workspace_bytes(64, 512, 512, 128)                                   # R and Z: 16 matrices at most
+    assert 16 * rb < rb64 <= 64 * rb - 48 * 128 * 512 * 6
     args = (FAKE, FAKE, FAKE, 512, 512, 128, 256, 1, FAKE + 4096, FAKE + 8192, FAKE, FAKE, FAKE, rb, None)
 
     def call(**kw):
