@@ -30,7 +30,8 @@ typedef double f64x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kNB = 64;               // block size of the fp64 kernels: one workgroup (4 waves) per 64 x 64 block
 constexpr int kKC = 32;               // K extent staged in LDS per barrier pair
-constexpr int kPitchKF = kKC + 4;     // LDS pitch of a [64][k] chunk (k fastest)
+constexpr int kPitchKF = kKC + 1;     // LDS pitch of a [64][k] chunk (k fastest): odd, so that the 16 rows a fragment
+                                      // read touches at one k fall on 16 different bank pairs (36 gave 4-way conflicts)
 constexpr int kPitchKS = kNB + 16;    // LDS pitch of a [k][64] chunk (k slowest)
 constexpr int kPitchT = kNB + 2;      // LDS pitch of a 64 x 64 intermediate
 
