@@ -288,6 +288,16 @@ def refresh_bench(args, shapes, mats):
         many = timed(lambda: qg.subspace_refresh_many([x.Pq for x in g], [x.Ps for x in g], [x.G for x in g], m, n, r, 1,
                                                       workspace=ws, out=outs[(m, n, r)]), 1)
         per_shape[f"{m}x{n} r{r}"] = {"count": len(g), "single_call_ms": one, "batched_ms_per_matrix": many / len(g)}
+    # what the fp64 matrix pipe sustains with nothing else to do: register-only loop, three 256-thread workgroups per
+    # CU (the residency of k_gram and k_apply) and eight (a full CU)
+    sink = torch.empty((256 * 8 * 256,), dtype=torch.float32, device=dev)
+    ceilings = {"note": "register-only v_mfma_f64_16x16x4 loop, 8 independent accumulators per wave, TFLOP/s"}
+    for per_cu in (3, 8):
+        it = 2000
+        fl = qg.diag_mfma_f64_loop(it, 256 * per_cu, sink)
+        t = timed(lambda: qg.diag_mfma_f64_loop(it, 256 * per_cu, sink), 3)
+        ceilings[f"mfma_f64_loop_{per_cu}_workgroups_per_cu"] = fl / t / 1e9
+    del sink
     bf16_flop = sum(4.0 * m * n * r for m, n, r in shapes)                 # R = P^T G and Y = G Z^T
     fp64_flop = sum(2 * (m * r * r + r ** 3 / 3 + r ** 3 / 3 + m * r * r) for m, n, r in shapes)   # two rounds
     out = {"metric": "Q-GaLore subspace refresh ms over all linear weights", "value": ms, "unit": "ms",
@@ -299,6 +309,7 @@ def refresh_bench(args, shapes, mats):
            "work": {"bf16_TFLOP": bf16_flop / 1e12, "fp64_TFLOP": fp64_flop / 1e12,
                     "bf16_bound_ms": bf16_flop / PEAK_BF16_TFLOPS / 1e9, "fp64_bound_ms": fp64_flop / PEAK_FP64_TFLOPS / 1e9},
            "amortized_ms_per_step_at_interval_200": ms / 200.0,
+           "ceilings": ceilings,
            "context": "the paper reports about 10 minutes per SVD refresh of LLaMA-7B on one RTX A6000 (Sec. 4.3)"}
     if not args.no_cpu_baseline:
         import numpy as np

@@ -345,10 +345,15 @@ int qg_backproject_update_sr_many(int count, const void* plan_host, const void* 
  * iters (1 .. 2^24) rounds of 16 independent bf16 32x32x16 MFMAs on register operands, i.e.
  * QG_DIAG_MFMA_WORKGROUPS * 8 * iters * 16 * 32768 flop per launch: the ceiling of the matrix pipe with nothing else
  * running.  random_operands != 0 fills the operands with varied finite bit patterns (the sustained clock depends on
- * the data), 0 with constants.  sink: device, QG_DIAG_MFMA_WORKGROUPS * 512 floats (written so the loop is live). */
+ * the data), 0 with constants.  sink: device, QG_DIAG_MFMA_WORKGROUPS * 512 floats (written so the loop is live).
+ *
+ * qg_diag_mfma_f64_loop: `workgroups` (1 .. 65536) workgroups of 256 threads; each wave issues iters rounds of 8
+ * independent v_mfma_f64_16x16x4 on register operands: workgroups * 4 * iters * 8 * 2048 flop per launch, the
+ * ceiling of the fp64 matrix pipe for the kernels of the subspace refresh.  sink: workgroups * 256 floats. */
 #define QG_DIAG_MFMA_WORKGROUPS 512
 int qg_diag_clock_probe(int64_t ticks_100mhz, int64_t* out2, void* stream);
 int qg_diag_mfma_loop(int64_t iters, int random_operands, float* sink, void* stream);
+int qg_diag_mfma_f64_loop(int64_t iters, int workgroups, float* sink, void* stream);
 
 /* ---- Test helper: out[i] = u(seed, step, idx0 + i) for i < count, the uniform
  * draws of the stochastic-rounding generator, as fp32. */

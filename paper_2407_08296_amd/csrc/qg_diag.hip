@@ -61,6 +61,24 @@ __global__ __launch_bounds__(512) void k_mfma_loop(long long iters, float* sink)
     sink[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// The same for the fp64 matrix cores: rounds of 8 independent v_mfma_f64_16x16x4 on register operands, 256-thread
+// workgroups (the shape of the refresh's fp64 kernels; three of them per CU are resident there).
+typedef double diag_f64x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void k_mfma_f64_loop(long long iters, float* sink) {
+    diag_f64x4 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = diag_f64x4{0.0, 0.0, 0.0, 0.0};
+    const double a = 1.0 + threadIdx.x * 0x1p-10, b = 2.0 - threadIdx.x * 0x1p-10;
+    for (long long it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[i], 0, 0, 0);
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += (acc[i][0] + acc[i][1]) + (acc[i][2] + acc[i][3]);
+    sink[blockIdx.x * blockDim.x + threadIdx.x] = (float)s;
+}
+
 }  // namespace qg
 
 using namespace qg;
@@ -82,5 +100,12 @@ extern "C" int qg_diag_mfma_loop(int64_t iters, int random_operands, float* sink
     else
         hipLaunchKernelGGL(k_mfma_loop<false>, dim3(QG_DIAG_MFMA_WORKGROUPS), dim3(512), 0, (hipStream_t)stream,
                            (long long)iters, sink);
+    return check_launch();
+}
+
+extern "C" int qg_diag_mfma_f64_loop(int64_t iters, int workgroups, float* sink, void* stream) {
+    if (!sink) return QG_ERR_NULL;
+    if (iters < 1 || iters > (int64_t(1) << 24) || workgroups < 1 || workgroups > 65536) return QG_ERR_SHAPE;
+    hipLaunchKernelGGL(k_mfma_f64_loop, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)stream, (long long)iters, sink);
     return check_launch();
 }

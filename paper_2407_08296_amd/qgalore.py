@@ -24,6 +24,7 @@ EXPORTS = [
     "qg_policy_update", "qg_workspace_bytes", "qg_step", "qg_plan_bytes", "qg_plan_build", "qg_step_many",
     "qg_sr_uniform", "qg_project_many", "qg_lowrank_adam_many", "qg_backproject_update_sr_many",
     "qg_project_adam", "qg_project_adam_many", "qg_diag_clock_probe", "qg_diag_mfma_loop",
+    "qg_diag_mfma_f64_loop",
     "qg_range_apply", "qg_orthonormalize_workspace_bytes", "qg_orthonormalize", "qg_refresh_workspace_bytes",
     "qg_subspace_refresh", "qg_subspace_refresh_many", "qg_int8_linear_forward", "qg_int8_linear_backward",
     "qg_int8_linear_t_forward", "qg_int8_linear_t_backward",
@@ -108,6 +109,7 @@ def lib() -> C.CDLL:
         L.qg_project_adam_many.argtypes = [i32, vp, vp, sz, C.POINTER(HParams), i64, i32, vp]
         L.qg_diag_clock_probe.argtypes = [i64, vp, vp]
         L.qg_diag_mfma_loop.argtypes = [i64, i32, vp, vp]
+        L.qg_diag_mfma_f64_loop.argtypes = [i64, i32, vp, vp]
         L.qg_range_apply.argtypes = [vp, vp, i64, i64, i64, vp, vp]
         L.qg_orthonormalize_workspace_bytes.restype = sz
         L.qg_orthonormalize_workspace_bytes.argtypes = [i64, i64]
@@ -505,6 +507,13 @@ def diag_mfma_loop(iters: int, random_operands: bool, sink: torch.Tensor) -> flo
     assert sink.numel() >= DIAG_MFMA_WORKGROUPS * 512
     _check(lib().qg_diag_mfma_loop(iters, int(random_operands), _ptr(sink, (torch.float32,)), _stream()))
     return DIAG_MFMA_WORKGROUPS * 8 * iters * 16 * 32768.0
+
+
+def diag_mfma_f64_loop(iters: int, workgroups: int, sink: torch.Tensor) -> float:
+    """Enqueue the register-only fp64 MFMA loop; returns the flop it performs."""
+    assert sink.numel() >= workgroups * 256
+    _check(lib().qg_diag_mfma_f64_loop(iters, workgroups, _ptr(sink, (torch.float32,)), _stream()))
+    return workgroups * 4 * iters * 8 * 2048.0
 
 
 def sr_uniform(seed: int, step: int, idx0: int, count: int, device="cuda") -> torch.Tensor:

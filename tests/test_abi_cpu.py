@@ -172,6 +172,13 @@ def test_zero_point_argument_errors(L):
     assert (C.c_uint32 * 16).from_buffer(buf)[13] == 1      # header word: zero-point plan
 
 
+def test_diag_argument_errors(L):
+    assert L.qg_diag_mfma_f64_loop(10, 4, None, None) == 1
+    assert L.qg_diag_mfma_f64_loop(0, 4, FAKE, None) == 2
+    assert L.qg_diag_mfma_f64_loop(10, 0, FAKE, None) == 2
+    assert L.qg_diag_mfma_f64_loop(10, 1 << 20, FAKE, None) == 2
+
+
 def test_adam8_argument_errors(L):
     hp = qg.hparams()
     assert L.qg_state8_quant(None, 256, 1, FAKE, FAKE, None) == 1

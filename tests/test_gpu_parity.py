@@ -492,6 +492,11 @@ def test_diag_clock_probe_and_mfma_loop():
         torch.cuda.synchronize()
         assert flop == qg.DIAG_MFMA_WORKGROUPS * 8 * 8 * 16 * 32768.0
         assert bool(torch.isfinite(sink).all())
+    sink64 = torch.zeros((16 * 256,), dtype=torch.float32, device="cuda")
+    assert qg.diag_mfma_f64_loop(3, 16, sink64) == 16 * 4 * 3 * 8 * 2048.0
+    torch.cuda.synchronize()
+    # every accumulator entry is a sum over k of a(lane) * b(lane) products of values near 1 and 2: positive, finite
+    assert bool(torch.isfinite(sink64).all()) and bool((sink64 > 0).all())
 
 
 # ------------------------------------------------------------------ padded rows (row pitch ld > n)
