@@ -29,7 +29,9 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef double f64x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kNB = 64;               // block size of the fp64 kernels: one workgroup (4 waves) per 64 x 64 block
-constexpr int kKC = 32;               // K extent staged in LDS per barrier pair
+constexpr int kKC = 16;               // K extent staged in LDS per barrier pair: 20 KB of LDS per workgroup, so that six
+                                      // or more are resident per CU (the fp64 matrix pipe sustains more with more waves
+                                      // per SIMD; 32 gave three workgroups and 9 % more time, 8 no further gain)
 constexpr int kPitchKF = kKC + 1;     // LDS pitch of a [64][k] chunk (k fastest): odd, so that the 16 rows a fragment
                                       // read touches at one k fall on 16 different bank pairs (36 gave 4-way conflicts)
 constexpr int kPitchKS = kNB + 16;    // LDS pitch of a [k][64] chunk (k slowest)
