@@ -8,7 +8,10 @@ are timed too, after the timed region, for their own roofline fractions.  The de
 headline metric is quoted on: LLaMA-7B shapes (224 matrices, r = 1024).
 Inputs are synthetic, generated on the device before the timed region, and stay resident in HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (ms per step), roofline (the slower of the two launches against the bf16 MFMA
+peak, with measured HBM traffic), kernels (every launch with its rate), ceilings (what the machine sustained in the
+same run), cpu_baseline (the oracle on a sample of the workload).  Other modes: --refresh, --linear, --rsweep,
+--config N, --pad-rows, --zero-points.
 """
 from __future__ import annotations
 
