@@ -66,7 +66,7 @@ struct LinBatch {
 
 // Staging of one operand tile: global -> registers (fetch) -> LDS (commit; INT8 is dequantized here).  EXACT: the
 // tile lies inside the matrix, K is a whole number of steps and rows are 16-byte aligned - no checks.
-template <int LAYOUT, int XT, int BK, bool EXACT>
+template <int LAYOUT, int XT, int BK, bool EXACT, int NT = 256>
 struct LinStage {
     static constexpr bool kFast = LAYOUT == kBf16KFast || LAYOUT == kInt8KFast || LAYOUT == kInt8ZKFast;
     static constexpr bool kZero = LAYOUT == kInt8ZKFast || LAYOUT == kInt8ZKSlow;
@@ -75,7 +75,8 @@ struct LinStage {
     static constexpr int CPR = (kFast ? BK : XT) / CH;          // chunks per tile row
     static constexpr int PITCH = kFast ? BK + kPadX : XT + kPadK;   // LDS pitch: [x][k] or [k][x]
     static constexpr int ELEMS = (kFast ? XT : BK) * PITCH;
-    static constexpr int PER = XT * BK / CH / 256;              // chunks per thread
+    static constexpr int PER = XT * BK / CH / NT;               // chunks per thread (NT threads in the workgroup)
+    static_assert(XT * BK % (CH * NT) == 0, "tile must divide evenly over the threads");
     u32x4 v[PER];
     float s[kInt8 ? PER : 1];
     float z[kZero ? PER : 1];
@@ -83,7 +84,7 @@ struct LinStage {
     __device__ __forceinline__ void fetch(const LinOperand& op, int x0, int X, int k0, int K) {
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
-            const int idx = threadIdx.x + 256 * q;
+            const int idx = threadIdx.x + NT * q;
             const int tr = idx / CPR, tc = (idx % CPR) * CH;         // row and first column inside the tile
             const int row = kFast ? x0 + tr : k0 + tr;               // ... and inside the matrix
             const int col = kFast ? k0 + tc : x0 + tc;
@@ -104,7 +105,7 @@ struct LinStage {
     __device__ __forceinline__ void commit(uint16_t* tile) const {
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
-            const int idx = threadIdx.x + 256 * q;
+            const int idx = threadIdx.x + NT * q;
             uint16_t* dst = tile + (idx / CPR) * PITCH + (idx % CPR) * CH;
             if constexpr (kInt8) {
                 *reinterpret_cast<u32x4*>(dst) = dequant8_i8_bf16<kZero>(v[q][0], v[q][1], s[q], kZero ? z[q] : 0.f);
@@ -127,12 +128,17 @@ struct LinStage {
 // columns.
 // Two LDS stages: while the MFMAs of step kt read stage kt & 1, the operands of step kt + 1 (fetched into registers
 // before those MFMAs) are written to the other stage; one barrier per step.
-template <int AL, int BL, bool EXACT, typename OUT, int TN, int BK>
-__global__ __launch_bounds__(256, 2) void k_tile_gemm(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
+// WM: wave rows of the workgroup (2: 128-row tile, 256 threads, two workgroups per CU; 4: 256-row tile, 512 threads,
+// one workgroup per CU - the B tile, and with it the dequantization of an INT8 B operand, is then shared by twice as
+// many MFMAs).
+template <int AL, int BL, bool EXACT, typename OUT, int TN, int BK, int WM = 2>
+__global__ __launch_bounds__(WM * 128, WM == 2 ? 2 : 1) void k_tile_gemm(LinOperand A, LinOperand B,
+                                                      const uint16_t* __restrict__ bias,
                                                       OUT* __restrict__ C, int M, int N, int K, int tiles_m, int tiles_n,
                                                       LinBatch batch) {
-    using SA = LinStage<AL, kLinTM, BK, EXACT>;
-    using SB = LinStage<BL, TN, BK, EXACT>;
+    constexpr int TM = 64 * WM, NT = 128 * WM;
+    using SA = LinStage<AL, TM, BK, EXACT, NT>;
+    using SB = LinStage<BL, TN, BK, EXACT, NT>;
     A.base = batch.a[blockIdx.y];
     B.base = static_cast<const char*>(B.base) + batch.strideB_bytes * blockIdx.y;
     C += batch.strideC * blockIdx.y;
@@ -146,7 +152,7 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm(LinOperand A, LinOperand B
     if (tile >= (uint32_t)(tiles_m * tiles_n)) return;
     const int strip = (int)(tile / (uint32_t)(kLinStrip * tiles_n)), in_strip = (int)(tile % (uint32_t)(kLinStrip * tiles_n));
     const int strip_rows = min(kLinStrip, tiles_m - strip * kLinStrip);
-    const int i0 = (strip * kLinStrip + in_strip % strip_rows) * kLinTM, j0 = (in_strip / strip_rows) * TN;
+    const int i0 = (strip * kLinStrip + in_strip % strip_rows) * TM, j0 = (in_strip / strip_rows) * TN;
     SA sa;
     SB sb;
     constexpr int MB = 2, NB = TN / 64;        // 32 x 32 blocks of the wave's 64 x TN/2
@@ -307,10 +313,11 @@ __global__ __launch_bounds__(256, 3) void k_gemm_kslow_direct(const uint16_t* __
         }
 }
 
-template <int AL, int BL, typename OUT, int TN, int BK>
+template <int AL, int BL, typename OUT, int TN, int BK, int WM = 2>
 static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M,
                                    int64_t N, int64_t K, hipStream_t st, const LinBatch* many, int count) {
-    const int64_t tiles_m = (M + kLinTM - 1) / kLinTM, tiles_n = (N + TN - 1) / TN;
+    constexpr int TM = 64 * WM;
+    const int64_t tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8), (unsigned)count);   // x: a multiple of the 8 XCDs
     LinBatch batch;
     if (many != nullptr) {
@@ -321,12 +328,12 @@ static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, con
         batch.strideC = 0;
     }
     // no checks at all when every tile and every step is whole and rows start 16-byte aligned
-    const bool exact = M % kLinTM == 0 && N % TN == 0 && K % BK == 0 && A.ld % 8 == 0 && B.ld % 16 == 0;
+    const bool exact = M % TM == 0 && N % TN == 0 && K % BK == 0 && A.ld % 8 == 0 && B.ld % 16 == 0;
     if (exact)
-        hipLaunchKernelGGL((k_tile_gemm<AL, BL, true, OUT, TN, BK>), grid, dim3(256), 0, st, A, B, bias, C, (int)M,
+        hipLaunchKernelGGL((k_tile_gemm<AL, BL, true, OUT, TN, BK, WM>), grid, dim3(128 * WM), 0, st, A, B, bias, C, (int)M,
                            (int)N, (int)K, (int)tiles_m, (int)tiles_n, batch);
     else
-        hipLaunchKernelGGL((k_tile_gemm<AL, BL, false, OUT, TN, BK>), grid, dim3(256), 0, st, A, B, bias, C, (int)M,
+        hipLaunchKernelGGL((k_tile_gemm<AL, BL, false, OUT, TN, BK, WM>), grid, dim3(128 * WM), 0, st, A, B, bias, C, (int)M,
                            (int)N, (int)K, (int)tiles_m, (int)tiles_n, batch);
 }
 
@@ -347,6 +354,15 @@ static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint
             const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);
             hipLaunchKernelGGL((k_gemm_kslow_direct<OUT>), dim3(grid), dim3(256), 0, st, static_cast<const uint16_t*>(A.base),
                                static_cast<const uint16_t*>(B.base), C, (int)M, (int)N, (int)K, (int)tiles_m, (int)tiles_n);
+            return check_launch();
+        }
+    }
+    if constexpr (BL == kInt8KSlow || BL == kInt8ZKSlow) {
+        // an INT8 B operand is dequantized by every workgroup that stages it: 256-row tiles halve that work per MFMA
+        // (grad_input of a 7B layer 1.82 -> 1.72 ms; with the contraction index fast in both operands the same change
+        // bought nothing, so that case keeps the 128-row tile)
+        if (M >= 1024 && ((M + 255) / 256) * ((N + 255) / 256) >= 256) {
+            launch_tile_gemm_shape<AL, BL, OUT, 256, 32, 4>(A, B, bias, C, M, N, K, st, many, count);
             return check_launch();
         }
     }
