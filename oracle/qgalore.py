@@ -681,13 +681,15 @@ def dequant_w_zp_bf16(Wq, Ws, Wz) -> np.ndarray:
     return bf16_rne(dequant_int8_zp(Wq, Ws, Wz).astype(np.float32).astype(np.float64))
 
 
-def update_sr_zp(Wq, Ws, Wz, U, lr: float, seed: int, t: int):
+def update_sr_zp(Wq, Ws, Wz, U, lr: float, seed: int, t: int, n_total: int | None = None, col0: int = 0):
     """The INT8 update of Sec. 3.4/3.5 on a zero-point weight: x = (W_q - z) s -
     lr U; per block new (s', z') from min/max as in quant_int8_zp; code =
-    clamp(F_SR(x/s') + z', -128, 127) with the draw u(seed, t, i*n + j).
+    clamp(F_SR(x/s') + z', -128, 127) with the draw u(seed, t, i*n_total + col0 + j)
+    (a slice of columns of a wider matrix, as in update_sr).
     Returns (codes, scales, zeros)."""
     Wq = np.asarray(Wq)
     m, n = Wq.shape
+    n_total = n if n_total is None else n_total
     x = dequant_int8_zp(Wq, Ws, Wz) - float(np.float32(lr)) * np.asarray(U, dtype=np.float64)
     x32 = x.astype(np.float32)
     ng = (n + GROUP - 1) // GROUP
@@ -703,21 +705,23 @@ def update_sr_zp(Wq, Ws, Wz, U, lr: float, seed: int, t: int):
         s, inv, z = _zp_params(lo, hi)
         news[:, g], newz[:, g] = s, z
         tq = (blk * inv[:, None]).astype(np.float32)
-        idx = ii * np.uint64(n) + np.arange(c0, c1, dtype=np.uint64)[None, :]
+        idx = ii * np.uint64(n_total) + np.arange(col0 + c0, col0 + c1, dtype=np.uint64)[None, :]
         u = sr_uniform(seed, t, idx)
         newq[:, c0:c1] = np.clip(sr_round(tq, u) + z[:, None].astype(np.float64), -128, 127).astype(np.int8)
     return newq, news, newz
 
 
-def step_zp(Wq, Ws, Wz, G_bits, Pq, Ps, M, V, t: int, hp: HParams, seed: int, r: int) -> dict:
-    """`step` on a zero-point weight: only the weight's format differs."""
+def step_zp(Wq, Ws, Wz, G_bits, Pq, Ps, M, V, t: int, hp: HParams, seed: int, r: int,
+            n_total: int | None = None, col0: int = 0) -> dict:
+    """`step` on a zero-point weight: only the weight's format differs (a slice of
+    columns of a wider matrix can be stepped alone, as in `step`)."""
     Wq = np.asarray(Wq)
     m, n = Wq.shape
     R = project(Pq, Ps, G_bits, m, n, r)
     M1, V1, N = lowrank_adam(R, M, V, t, hp)
     Nb = bf16_rne(N)
     U = backproject(Pq, Ps, Nb, m, r, hp.alpha)
-    newq, news, newz = update_sr_zp(Wq, Ws, Wz, U, hp.lr, seed, t)
+    newq, news, newz = update_sr_zp(Wq, Ws, Wz, U, hp.lr, seed, t, n_total, col0)
     return dict(R=R, M=M1, V=V1, N=N, Nb=Nb, U=U, Wq=newq, Ws=news, Wz=newz)
 
 

@@ -579,3 +579,34 @@ def test_unfused_phases_with_row_pitch():
         assert torch.equal(x.R[:, :n], y.R[:, :n]) and torch.equal(x.M[:, :n], y.M[:, :n])
         assert torch.equal(x.V[:, :n], y.V[:, :n]) and torch.equal(x.N[:, :n], y.N[:, :n])
         assert torch.equal(x.Wq, y.Wq) and torch.equal(x.Ws, y.Ws)
+
+
+def test_llama1b_down_shape_with_row_pitch_sampled_columns():
+    """The shape the row pitch exists for: 2048 x 5461 (the `down` weights of the LLaMA-1B shapes), r = 512, stored
+    with ld = 5472, through the grouped launch; the oracle recomputes column blocks across the matrix, the ragged
+    last one (85 columns) included."""
+    m, n, r, ld = 2048, 5461, 512, 5472
+    d = make_inputs(m, n, r, kind=6)
+    G = _pitched(np.asarray(d["Gb"]).view(np.int16).reshape(m, n), ld, _NAN_BF16)
+    s = qg.MatrixState(m, n, r, dev(d["Pq"]), dev(d["Ps"]), G, _pitched(d["Wq"].reshape(m, n), ld, 85), dev(d["Ws"]),
+                       torch.zeros((r, ld), dtype=torch.float32, device=DEV),
+                       torch.zeros((r, ld), dtype=torch.float32, device=DEV),
+                       torch.empty((r, ld), dtype=torch.float32, device=DEV),
+                       torch.empty((r, ld), dtype=torch.bfloat16, device=DEV), ld=ld)
+    qg.step_many(qg.StepPlan([s]), qg.hparams(), 0, 1)
+    torch.cuda.synchronize()
+    gR, gM, gV, gWq, gWs = host(s.R), host(s.M), host(s.V), host(s.Wq), host(s.Ws)
+    gN = bf16_t_to_f64(s.N[:, :n].contiguous())
+    Gb = np.asarray(d["Gb"]).reshape(m, n)
+    ng = (n + 255) // 256
+    for g in sorted({0, ng // 2, ng - 1}):
+        c0, c1 = g * 256, min((g + 1) * 256, n)
+        sl = slice(c0, c1)
+        o = Q.step(d["Wq"].reshape(m, n)[:, sl], d["Ws"][:, g:g + 1], Gb[:, sl], d["Pq"], d["Ps"],
+                   np.zeros((r, c1 - c0)), np.zeros((r, c1 - c0)), 1, HP, seed=0, r=r, n_total=n, col0=c0)
+        assert rel_fro(gR[:, sl], o["R"]) <= 2e-5
+        check_first_step_direction(gN[:, sl], gR[:, sl], o)
+        assert rel_fro(gM[:, sl], o["M"]) <= 2e-5 and rel_fro(gV[:, sl], o["V"]) <= 4e-5
+        check_codes(gWq[:, sl], o["Wq"])
+        check_scales_step(gWs[:, g:g + 1], o["Ws"], rel=5e-4)
+    assert np.all(gWq[:, n:] == 85)

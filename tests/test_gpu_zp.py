@@ -151,3 +151,28 @@ def test_linear_zp(tokens, m, n):
     dx, G = qg.int8_linear_zp_backward(dyd, xd, dq, ds, dz, m, n)
     check(host_f64(dx), want_dx, m, 0.05 * 0.04)
     check(host_f64(G), want_G, tokens, 0.05)
+
+
+def test_zero_point_step_at_a_llama7b_shape_sampled_columns():
+    """4096 x 4096, r = 1024 through the grouped launch with zero points in the descriptor; the step is
+    column-separable, so the oracle recomputes whole 256-column blocks (with their own zero points) across the matrix."""
+    m = n = 4096
+    r = 1024
+    W = shifted_weight(m, n, 6)
+    q, s_, z = Q.quant_int8_zp(W)
+    Pq, Ps = Q.quant_int4(I.projection_f32(m, r))
+    Gb = np.asarray(I.gradient_bf16(m, n, 1, 0)).reshape(m, n)
+    st = qg.MatrixState(m, n, r, dev(Pq), dev(Ps), dev(Gb), dev(q), dev(s_),
+                        torch.zeros((r, n), device=DEV), torch.zeros((r, n), device=DEV),
+                        torch.empty((r, n), device=DEV), torch.empty((r, n), dtype=torch.bfloat16, device=DEV), Wz=dev(z))
+    seed = 4
+    qg.step_many(qg.StepPlan([st]), qg.hparams(), seed, 1)
+    torch.cuda.synchronize()
+    gq, gs, gz = host(st.Wq), host(st.Ws), host(st.Wz)
+    for g in (0, 7, 15):
+        sl = slice(g * 256, (g + 1) * 256)
+        o = Q.step_zp(q[:, sl], s_[:, g:g + 1], z[:, g:g + 1], Gb[:, sl], Pq, Ps, np.zeros((r, 256)), np.zeros((r, 256)), 1,
+                      HP, seed=seed, r=r, n_total=n, col0=g * 256)
+        assert rel_fro(host(st.R)[:, sl], o["R"]) <= 2e-5
+        check_update(torch.from_numpy(gq[:, sl]), torch.from_numpy(gs[:, g:g + 1]), torch.from_numpy(gz[:, g:g + 1]),
+                     o, first_step=True)
