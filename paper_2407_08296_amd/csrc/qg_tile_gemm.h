@@ -337,11 +337,15 @@ static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, con
                            (int)N, (int)K, (int)tiles_m, (int)tiles_n, batch);
 }
 
-// Tile shape.  Operands whose contraction index is slow want the wide tile: 128 x 256 with 32-deep steps when that
-// gives every CU two workgroups, 128 x 128 for smaller outputs.  When both operands have the contraction index as
-// their fast index a load instruction touches one cache line per tile row, and what pays is whole lines: 128 x 128
-// with 64-deep steps (measured on the forward pass of the linear layer: 2.28 ms against 2.37 ms for the wide tile
-// and 2.80 ms for 128 x 128 with 32-deep steps).
+// Tile shape, from measurements on the linear layer of the LLaMA-7B shapes (ms per decoder layer at 4096 tokens):
+//  * large outputs with an INT8 B operand, or with the contraction index fast in both operands: 256 x 256 tiles with
+//    64-deep steps, eight waves, one workgroup per CU (144 KB of LDS).  The B tile - and the dequantization of an
+//    INT8 B - is shared by twice as many MFMAs as in a 128-row tile, global traffic per MFMA halves, and 64-deep
+//    steps fetch whole cache lines of operands whose rows run along k.  Forward pass 2.24 -> 1.87, grad_input
+//    1.82 -> 1.66 (256 x 256 x 32 with eight waves: 1.72; 256 x 128 x 64: forward unchanged at 2.24).
+//  * otherwise two workgroups of four waves per CU: 128 x 128 x 64 when both operands have k fast (2.28 against 2.37
+//    for 128 x 256 x 32 and 2.80 for 128 x 128 x 32 on the forward pass), 128 x 256 x 32 when that fills the chip,
+//    128 x 128 x 32 for small outputs.
 template <int AL, int BL, typename OUT>
 static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M, int64_t N,
                             int64_t K, hipStream_t st, const LinBatch* many = nullptr, int count = 1) {
@@ -357,12 +361,10 @@ static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint
             return check_launch();
         }
     }
-    if constexpr (BL == kInt8KSlow || BL == kInt8ZKSlow) {
-        // an INT8 B operand is dequantized by every workgroup that stages it: 256-row tiles halve that work per MFMA
-        // (grad_input of a 7B layer 1.82 -> 1.72 ms; with the contraction index fast in both operands the same change
-        // bought nothing, so that case keeps the 128-row tile)
-        if (M >= 1024 && ((M + 255) / 256) * ((N + 255) / 256) >= 256) {
-            launch_tile_gemm_shape<AL, BL, OUT, 256, 32, 4>(A, B, bias, C, M, N, K, st, many, count);
+    constexpr bool int8_b = BL == kInt8KFast || BL == kInt8KSlow || BL == kInt8ZKFast || BL == kInt8ZKSlow;
+    if constexpr (int8_b || both_fast) {
+        if (M >= 1024 && ((M + 255) / 256) * ((N + 255) / 256) * count >= 256) {   // at least one workgroup per CU
+            launch_tile_gemm_shape<AL, BL, OUT, 256, 64, 4>(A, B, bias, C, M, N, K, st, many, count);
             return check_launch();
         }
     }

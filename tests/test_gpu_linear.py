@@ -97,23 +97,27 @@ def test_gradient_feeds_the_optimizer_step():
     assert np.linalg.norm(got - want) <= 2e-5 * np.linalg.norm(want)
 
 
-def test_llama7b_attention_shape_by_sampled_outputs():
-    """4096 tokens through a 4096 x 4096 layer: sampled outputs against fp64 dot products of the same operands."""
-    tokens, m, n = 4096, 4096, 4096
-    g = torch.Generator(device=DEV).manual_seed(3)
-    Wq, Ws = qg.quant_int8(torch.randn((m, n), generator=g, device=DEV) * 0.02)
-    x = torch.randn((tokens, n), generator=g, device=DEV).to(torch.bfloat16)
-    dy = (torch.randn((tokens, m), generator=g, device=DEV) * 0.05).to(torch.bfloat16)
-    y = qg.int8_linear_forward(x, Wq, Ws)
-    dx, G = qg.int8_linear_backward(dy, x, Wq, Ws, m, n)
-    Wd = Q.dequant_w_bf16(Wq.cpu().numpy(), Ws.cpu().numpy())
-    xh, dyh = host_f64(x), host_f64(dy)
+@pytest.mark.parametrize("tokens,m,n", [(4096, 4096, 4096), (4100, 4099, 4102)])
+def test_large_layer_by_sampled_outputs(tokens, m, n):
+    """4096 tokens through a 4096 x 4096 layer (the LLaMA-7B attention shape, whole 256 x 256 x 64 tiles), and a
+    ragged neighbour of it (edge tiles, a contraction tail and unaligned rows in the same large-tile kernels):
+    sampled outputs, the last row and column among them, against fp64 dot products of the same operands."""
+    g = np.random.default_rng([3, tokens, m, n])
+    Wq, Ws = Q.quant_int8((g.standard_normal((m, n)) * 0.02).astype(np.float32))
+    xb = Q.f64_to_bf16_bits(g.standard_normal((tokens, n)))
+    dyb = Q.f64_to_bf16_bits(g.standard_normal((tokens, m)) * 0.05)
+    x, dy, dWq, dWs = bits_t(xb, (tokens, n)), bits_t(dyb, (tokens, m)), dev(Wq), dev(Ws)
+    y = qg.int8_linear_forward(x, dWq, dWs)
+    dx, G = qg.int8_linear_backward(dy, x, dWq, dWs, m, n)
+    Wd = Q.dequant_w_bf16(Wq, Ws)
+    xh = Q.bf16_bits_to_f64(xb).reshape(tokens, n)
+    dyh = Q.bf16_bits_to_f64(dyb).reshape(tokens, m)
     rs = np.random.default_rng(8)
     for out, f, k, sc in ((y, lambda a, b: xh[a] @ Wd[b], n, 0.02), (dx, lambda a, b: dyh[a] @ Wd[:, b], m, 1e-3),
                           (G, lambda a, b: dyh[:, a] @ xh[:, b], tokens, 0.05)):
         oh = host_f64(out)
-        ii = rs.integers(0, oh.shape[0], 200)
-        jj = rs.integers(0, oh.shape[1], 200)
+        ii = np.concatenate([rs.integers(0, oh.shape[0], 200), [oh.shape[0] - 1, 0, oh.shape[0] - 1]])
+        jj = np.concatenate([rs.integers(0, oh.shape[1], 200), [oh.shape[1] - 1, oh.shape[1] - 1, 0]])
         want = np.array([f(a, b) for a, b in zip(ii, jj)])
         got = oh[ii, jj]
         assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 4 * k * 2.0 ** -24 * sc)
