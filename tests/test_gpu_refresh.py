@@ -216,6 +216,23 @@ def test_batched_refresh_equals_the_single_matrix_calls(m, n, r, passes):
     assert not np.array_equal(host(pq[0]), host(pq[1]))
 
 
+@pytest.mark.parametrize("count", [17, 19])
+def test_batched_refresh_across_launch_groups(count):
+    """More matrices than one GEMM launch takes (groups of 16): a last group of one matrix (the single-matrix
+    launches) and of three, each matrix bit for bit what the single call gives."""
+    m, n, r = 256, 320, 64
+    ins = [start(m, n, r, seed=s) for s in range(count)]
+    Gs = [bits_t(Gb) for Gb, _, _ in ins]
+    Pqs = [dev(Pq) for _, Pq, _ in ins]
+    Pss = [dev(Ps) for _, _, Ps in ins]
+    pq, ps, cos, info, _ = qg.subspace_refresh_many(Pqs, Pss, Gs, m, n, r, 1)
+    assert host(info).tolist() == [0] * count
+    for i in (0, 7, 15, 16, count - 1):
+        one = qg.subspace_refresh(Pqs[i], Pss[i], Gs[i], m, n, r, 1)
+        assert np.array_equal(host(pq[i]), host(one[0])) and np.array_equal(host(ps[i]), host(one[1]))
+        assert float(host(cos)[i]) == float(host(one[2])[0])
+
+
 def test_refresh_at_llama7b_shapes_by_properties():
     """Full-size matrices of the 7B configuration (r = 1024): sampled entries of Y against fp64 dot products, Q
     orthonormal and spanning Y, the new P capturing more of G than the start."""
