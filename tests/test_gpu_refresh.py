@@ -52,7 +52,8 @@ def start(m, n, r, seed=0):
 
 
 # ---------------------------------------------------------------- Y = G Z^T
-@pytest.mark.parametrize("m,n,r", SHAPES + [(2048, 5461, 512)])
+# the last two: an output large enough for the 256 x 256 tiles, whole (direct global->LDS loads) and ragged
+@pytest.mark.parametrize("m,n,r", SHAPES + [(2048, 5461, 512), (16384, 512, 1024), (16400, 520, 1032)])
 def test_range_apply(m, n, r):
     Gb, Pq, Ps = start(m, n, r)
     Zb = Q.f64_to_bf16_bits(Q.project(Pq, Ps, Gb, m, n, r))

@@ -176,3 +176,26 @@ def test_zero_point_step_at_a_llama7b_shape_sampled_columns():
         assert rel_fro(host(st.R)[:, sl], o["R"]) <= 2e-5
         check_update(torch.from_numpy(gq[:, sl]), torch.from_numpy(gs[:, g:g + 1]), torch.from_numpy(gz[:, g:g + 1]),
                      o, first_step=True)
+
+
+def test_linear_zp_large_layer_by_sampled_outputs():
+    """4096 tokens through a 4096 x 4096 zero-point layer (the large-tile kernels): sampled outputs against fp64 dot
+    products of the same operands."""
+    tokens = m = n = 4096
+    g = np.random.default_rng(12)
+    q, s, z = Q.quant_int8_zp((g.standard_normal((m, n)) * 0.02 + g.standard_normal((m, 1)) * 0.02).astype(np.float32))
+    xb = Q.f64_to_bf16_bits(g.standard_normal((tokens, n)))
+    dyb = Q.f64_to_bf16_bits(g.standard_normal((tokens, m)) * 0.05)
+    x, dy, dq, ds, dz = bits_t(xb, (tokens, n)), bits_t(dyb, (tokens, m)), dev(q), dev(s), dev(z)
+    y = qg.int8_linear_zp_forward(x, dq, ds, dz)
+    dx, _ = qg.int8_linear_zp_backward(dy, None, dq, ds, dz, m, n, want_G=False)
+    Wd = Q.dequant_w_zp_bf16(q, s, z)
+    xh = Q.bf16_bits_to_f64(xb).reshape(tokens, n)
+    dyh = Q.bf16_bits_to_f64(dyb).reshape(tokens, m)
+    rs = np.random.default_rng(13)
+    for out, f, k, sc in ((y, lambda a, b: xh[a] @ Wd[b], n, 0.04), (dx, lambda a, b: dyh[a] @ Wd[:, b], m, 2e-3)):
+        oh = host_f64(out)
+        ii = np.concatenate([rs.integers(0, oh.shape[0], 200), [oh.shape[0] - 1]])
+        jj = np.concatenate([rs.integers(0, oh.shape[1], 200), [oh.shape[1] - 1]])
+        want = np.array([f(a, b) for a, b in zip(ii, jj)])
+        assert np.all(np.abs(oh[ii, jj] - want) <= 2.0 ** -8 * np.abs(want) + 4 * k * 2.0 ** -24 * sc)
