@@ -1012,6 +1012,9 @@ __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject(co
                                                 (int)(tile / tiles_m), alpha, lr, key, smem);
 }
 
+constexpr int kBpStrip = 16;   // row tiles per strip of the grouped back-projection's tile numbering (8: the same
+                               // time; 32: 2 % slower; whole columns of tiles, as before: 1 % slower)
+
 template <int BMm, int BK, int WGn, int WGm, int MODE, bool W_PREFETCH = true, int MIN_WG_PER_CU = 1, bool ZP = false>
 __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_many(const PlanHeader* __restrict__ plan, int first,
                                                                                    int count, uint32_t tiles,
@@ -1024,9 +1027,16 @@ __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject_ma
     const PlanMatrix& d = mats[plan_find(mats, count, tile, [](const PlanMatrix& x) { return x.bp_tile0; })];
     const uint32_t local = tile - d.bp_tile0;
     const uint32_t key = sr_key(seed + (uint64_t)d.index * 0x9E3779B97F4A7C15ull, step, 0u);
+    // Tiles are numbered in strips kBpStrip row tiles tall, column tile by column tile inside a strip: the ~100 tiles
+    // an XCD has in flight then share the P rows of one strip (1 MB of INT4 at r = 1024) and a few N panels, which
+    // fits its 4 MB L2 also when the matrix is tall (86 row tiles at m = 11008: numbered column by column the
+    // tiles in flight need all of P, 5.6 MB).
+    const uint32_t tiles_n = (uint32_t)((d.n + kGroup - 1) / kGroup);
+    const uint32_t strip = local / (kBpStrip * tiles_n), in_strip = local % (kBpStrip * tiles_n);
+    const uint32_t strip_rows = min((uint32_t)kBpStrip, d.bp_tiles_m - strip * kBpStrip);
+    const uint32_t tile_m = strip * kBpStrip + in_strip % strip_rows, tile_n = in_strip / strip_rows;
     backproject_tile<BMm, BK, WGn, WGm, MODE, false, W_PREFETCH, ZP>(d.Pq, d.Ps, d.N, d.Wq, d.Ws, d.Wz, nullptr, (int)d.m, (int)d.n, (int)d.ld, (int)d.r,
-                                                (int)(local % d.bp_tiles_m) * BMm, (int)(local / d.bp_tiles_m),
-                                                alpha, lr, key, smem);
+                                                (int)tile_m * BMm, (int)tile_n, alpha, lr, key, smem);
 }
 
 }  // namespace qg
