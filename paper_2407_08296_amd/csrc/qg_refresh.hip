@@ -17,6 +17,8 @@
 // the first round's pivots positive for cond(Y) well beyond 1e8 at no cost in the result.  A column that is
 // numerically dependent on its predecessors (a last-round pivot no larger than the shift) is reported through
 // `info`; every kernel runs to completion whatever the data.
+#include <type_traits>
+
 #include "qg_cossim.h"
 #include "qg_tile_gemm.h"
 
@@ -276,8 +278,31 @@ __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r
             }
         }
         __syncthreads();
+        // row i loses lij * L[c][j] in its columns c = c0, c0 + 4, ... <= i.  Unrolled to a fixed count that depends
+        // on j alone, with every LDS read issued before the first use (clamped addresses, predicated stores): as a
+        // loop with a data-dependent trip count each iteration waited out its own LDS round trip.
         const double lij = T[i * P + j];
-        for (int c = j + 1 + ((cg - (j + 1)) & 3); c <= i; c += 4) T[i * P + c] -= lij * T[c * P + j];
+        const int c0 = j + 1 + ((cg - (j + 1)) & 3);
+        auto update = [&](auto qn) {
+            constexpr int QN = decltype(qn)::value;
+            double a[QN], b[QN];
+#pragma unroll
+            for (int q = 0; q < QN; ++q) {
+                const int cc = min(c0 + 4 * q, kNB - 1);
+                a[q] = T[i * P + cc];
+                b[q] = T[cc * P + j];
+            }
+#pragma unroll
+            for (int q = 0; q < QN; ++q) {
+                const int c = c0 + 4 * q;
+                if (c <= i) T[i * P + c] = a[q] - lij * b[q];
+            }
+        };
+        const int need = (kNB - 1 - j + 3) >> 2;    // columns left of the four column groups, rounded up
+        if (need > 12) update(std::integral_constant<int, 16>());
+        else if (need > 8) update(std::integral_constant<int, 12>());
+        else if (need > 4) update(std::integral_constant<int, 8>());
+        else update(std::integral_constant<int, 4>());
     }
     __syncthreads();
     if (t < kNB) T[t * P + t] = dg[t];
@@ -301,7 +326,26 @@ __global__ __launch_bounds__(256) void k_chol_diag(double* __restrict__ S, int r
         __syncthreads();
         if (i > j) {
             const double lij = T[i * P + j];
-            for (int c = cg; c <= j; c += 4) T[c * P + i] -= lij * (c < j ? T[c * P + j] : xjj);
+            auto update = [&](auto qn) {            // rows c = cg, cg + 4, ... <= j of X^T, as in the factorization
+                constexpr int QN = decltype(qn)::value;
+                double a[QN], b[QN];
+#pragma unroll
+                for (int q = 0; q < QN; ++q) {
+                    const int cc = min(cg + 4 * q, kNB - 1);
+                    a[q] = T[cc * P + i];
+                    b[q] = T[cc * P + j];
+                }
+#pragma unroll
+                for (int q = 0; q < QN; ++q) {
+                    const int c = cg + 4 * q;
+                    if (c <= j) T[c * P + i] = a[q] - lij * (c < j ? b[q] : xjj);
+                }
+            };
+            const int need = (j >> 2) + 1;
+            if (need > 12) update(std::integral_constant<int, 16>());
+            else if (need > 8) update(std::integral_constant<int, 12>());
+            else if (need > 4) update(std::integral_constant<int, 8>());
+            else update(std::integral_constant<int, 4>());
         }
     }
     __syncthreads();
