@@ -123,3 +123,26 @@ def test_linear_zp_is_the_layer_on_the_dequantized_weight():
     assert np.allclose(dx, dy @ Wd, rtol=1e-12, atol=1e-12) and np.allclose(G, dy.T @ x, rtol=1e-12, atol=1e-12)
     # dropping the zero point (the symmetric reading of the same codes) gives a different layer
     assert np.linalg.norm(Q.int8_linear_forward(xb, q, s) - x @ Wd.T) > 0.1 * np.linalg.norm(x @ Wd.T)
+
+
+def test_column_blocks_step_alone_like_inside_the_matrix():
+    """update_sr_zp / step_zp on a slice of 256-column blocks (n_total, col0) give that slice of the full result:
+    the property the full-size GPU tests rely on when they recompute sampled column blocks."""
+    m, n, r = 64, 768, 16
+    W = I.weight_f32(m, n, 8) + np.float32(0.005)
+    q, s, z = Q.quant_int8_zp(W)
+    Pq, Ps = Q.quant_int4(I.projection_f32(m, r, 8))
+    Gb = np.asarray(I.gradient_bf16(m, n, 1, 8)).reshape(m, n)
+    hp = Q.HParams()
+    full = Q.step_zp(q, s, z, Gb, Pq, Ps, np.zeros((r, n)), np.zeros((r, n)), 2, hp, seed=3, r=r)
+    for g in (0, 2):
+        sl = slice(256 * g, 256 * (g + 1))
+        part = Q.step_zp(q[:, sl], s[:, g:g + 1], z[:, g:g + 1], Gb[:, sl], Pq, Ps, np.zeros((r, 256)), np.zeros((r, 256)),
+                         2, hp, seed=3, r=r, n_total=n, col0=256 * g)
+        assert np.array_equal(part["Wq"], full["Wq"][:, sl])
+        assert np.array_equal(part["Ws"], full["Ws"][:, g:g + 1]) and np.array_equal(part["Wz"], full["Wz"][:, g:g + 1])
+        assert np.array_equal(part["R"], full["R"][:, sl])
+    # without the slice parameters the stochastic-rounding stream is another one
+    alone = Q.step_zp(q[:, 256:512], s[:, 1:2], z[:, 1:2], Gb[:, 256:512], Pq, Ps, np.zeros((r, 256)), np.zeros((r, 256)),
+                      2, hp, seed=3, r=r)
+    assert not np.array_equal(alone["Wq"], full["Wq"][:, 256:512])
