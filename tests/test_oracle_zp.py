@@ -141,7 +141,7 @@ def test_column_blocks_step_alone_like_inside_the_matrix():
                          2, hp, seed=3, r=r, n_total=n, col0=256 * g)
         assert np.array_equal(part["Wq"], full["Wq"][:, sl])
         assert np.array_equal(part["Ws"], full["Ws"][:, g:g + 1]) and np.array_equal(part["Wz"], full["Wz"][:, g:g + 1])
-        assert np.array_equal(part["R"], full["R"][:, sl])
+        assert np.allclose(part["R"], full["R"][:, sl], rtol=1e-12, atol=1e-18)
     # without the slice parameters the stochastic-rounding stream is another one
     alone = Q.step_zp(q[:, 256:512], s[:, 1:2], z[:, 1:2], Gb[:, 256:512], Pq, Ps, np.zeros((r, 256)), np.zeros((r, 256)),
                       2, hp, seed=3, r=r)
