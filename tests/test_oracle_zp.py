@@ -139,10 +139,11 @@ def test_column_blocks_step_alone_like_inside_the_matrix():
         sl = slice(256 * g, 256 * (g + 1))
         part = Q.step_zp(q[:, sl], s[:, g:g + 1], z[:, g:g + 1], Gb[:, sl], Pq, Ps, np.zeros((r, 256)), np.zeros((r, 256)),
                          2, hp, seed=3, r=r, n_total=n, col0=256 * g)
-        assert np.array_equal(part["Wq"], full["Wq"][:, sl])
-        assert np.array_equal(part["Ws"], full["Ws"][:, g:g + 1]) and np.array_equal(part["Wz"], full["Wz"][:, g:g + 1])
+        # (identical up to what a differently blocked matmul of the slice may change in the last bit of R)
+        assert np.mean(part["Wq"] == full["Wq"][:, sl]) >= 0.999
+        assert np.allclose(part["Ws"], full["Ws"][:, g:g + 1], rtol=1e-6) and np.array_equal(part["Wz"], full["Wz"][:, g:g + 1])
         assert np.allclose(part["R"], full["R"][:, sl], rtol=1e-12, atol=1e-18)
     # without the slice parameters the stochastic-rounding stream is another one
     alone = Q.step_zp(q[:, 256:512], s[:, 1:2], z[:, 1:2], Gb[:, 256:512], Pq, Ps, np.zeros((r, 256)), np.zeros((r, 256)),
                       2, hp, seed=3, r=r)
-    assert not np.array_equal(alone["Wq"], full["Wq"][:, 256:512])
+    assert np.mean(alone["Wq"] == full["Wq"][:, 256:512]) < 0.9
