@@ -270,6 +270,9 @@ int qg_int8_linear_t_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, c
  *   every descriptor its Wz.
  * qg_int8_linear_zp_forward / _backward: the linear layer on such a weight (W dequantized inside the GEMMs as
  *   bf16(fl32((code - zero) * scale))).
+ * qg_int8_linear_t_zp_forward / _backward: the same on a zero-point weight stored transposed (S = W^T: codes
+ *   [n][m], scales and zero points [n][ceil(m/256)]), the layer of a right-projected matrix in this format; its
+ *   step is qg_step_zp on S as for the symmetric format.
  * Shapes, limits, alignment and NULL rules as for the calls they mirror; Wz may never be NULL. */
 int qg_quant_int8_zp(const float* x, int64_t rows, int64_t cols, int group, int8_t* q, float* scales, float* zeros,
                      void* stream);
@@ -288,6 +291,12 @@ int qg_int8_linear_zp_forward(const uint16_t* x_bf16, const int8_t* Wq, const fl
 int qg_int8_linear_zp_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
                                const float* Wz, int64_t tokens, int64_t m, int64_t n, int group,
                                uint16_t* dx_bf16, uint16_t* G_bf16, void* stream);
+int qg_int8_linear_t_zp_forward(const uint16_t* x_bf16, const int8_t* Sq, const float* Ss, const float* Sz,
+                                const uint16_t* bias_bf16, int64_t tokens, int64_t m, int64_t n, int group,
+                                uint16_t* y_bf16, void* stream);
+int qg_int8_linear_t_zp_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Sq, const float* Ss,
+                                 const float* Sz, int64_t tokens, int64_t m, int64_t n, int group,
+                                 uint16_t* dx_bf16, uint16_t* GS_bf16, void* stream);
 
 /* ---- Adaptive lazy update policy (Sec. 3.2), HOST ONLY (p is a host pointer):
  * streak counts consecutive checks with cos >= threshold; at k in a row the

@@ -129,3 +129,38 @@ extern "C" int qg_int8_linear_zp_backward(const uint16_t* dy_bf16, const uint16_
     }
     return QG_OK;
 }
+
+// Zero-point weight stored transposed (S = W^T with zero points along each row of S): the two variants combined.
+extern "C" int qg_int8_linear_t_zp_forward(const uint16_t* x_bf16, const int8_t* Sq, const float* Ss, const float* Sz,
+                                           const uint16_t* bias_bf16, int64_t tokens, int64_t m, int64_t n, int group,
+                                           uint16_t* y_bf16, void* stream) {
+    if (!x_bf16 || !Sq || !Ss || !Sz || !y_bf16) return QG_ERR_NULL;
+    if (int e = check_linear(tokens, m, n, group)) return e;
+    if (!aligned16(x_bf16) || !aligned16(Sq) || !aligned16(Ss) || !aligned16(Sz) || !aligned16(y_bf16) ||
+        (bias_bf16 && !aligned16(bias_bf16)))
+        return QG_ERR_ALIGN;
+    const int sg = (int)((m + kGroup - 1) / kGroup);
+    const LinOperand A = {x_bf16, nullptr, n, 0}, B = {Sq, Ss, m, sg, Sz};
+    return launch_tile_gemm<kBf16KFast, kInt8ZKSlow, uint16_t>(A, B, bias_bf16, y_bf16, tokens, m, n, (hipStream_t)stream);
+}
+
+extern "C" int qg_int8_linear_t_zp_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Sq,
+                                            const float* Ss, const float* Sz, int64_t tokens, int64_t m, int64_t n,
+                                            int group, uint16_t* dx_bf16, uint16_t* GS_bf16, void* stream) {
+    if (!dy_bf16 || (!dx_bf16 && !GS_bf16)) return QG_ERR_NULL;
+    if ((dx_bf16 && (!Sq || !Ss || !Sz)) || (GS_bf16 && !x_bf16)) return QG_ERR_NULL;
+    if (int e = check_linear(tokens, m, n, group)) return e;
+    if (!aligned16(dy_bf16) || (x_bf16 && !aligned16(x_bf16)) || (Sq && !aligned16(Sq)) || (Ss && !aligned16(Ss)) ||
+        (Sz && !aligned16(Sz)) || (dx_bf16 && !aligned16(dx_bf16)) || (GS_bf16 && !aligned16(GS_bf16)))
+        return QG_ERR_ALIGN;
+    const int sg = (int)((m + kGroup - 1) / kGroup);
+    if (dx_bf16) {
+        const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {Sq, Ss, m, sg, Sz};
+        if (int e = launch_tile_gemm<kBf16KFast, kInt8ZKFast, uint16_t>(A, B, nullptr, dx_bf16, tokens, n, m, (hipStream_t)stream)) return e;
+    }
+    if (GS_bf16) {
+        const LinOperand A = {x_bf16, nullptr, n, 0}, B = {dy_bf16, nullptr, m, 0};
+        if (int e = launch_tile_gemm<kBf16KSlow, kBf16KSlow, uint16_t>(A, B, nullptr, GS_bf16, n, m, tokens, (hipStream_t)stream)) return e;
+    }
+    return QG_OK;
+}

@@ -30,6 +30,7 @@ EXPORTS = [
     "qg_int8_linear_t_forward", "qg_int8_linear_t_backward",
     "qg_quant_int8_zp", "qg_dequant_int8_zp", "qg_backproject_update_sr_zp", "qg_step_zp",
     "qg_int8_linear_zp_forward", "qg_int8_linear_zp_backward",
+    "qg_int8_linear_t_zp_forward", "qg_int8_linear_t_zp_backward",
     "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8", "qg_step8",
 ]
 
@@ -89,6 +90,8 @@ def lib() -> C.CDLL:
                                  i64, vp]
         L.qg_int8_linear_zp_forward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
         L.qg_int8_linear_zp_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp]
+        L.qg_int8_linear_t_zp_forward.argtypes = L.qg_int8_linear_zp_forward.argtypes
+        L.qg_int8_linear_t_zp_backward.argtypes = L.qg_int8_linear_zp_backward.argtypes
         L.qg_cossim_workspace_bytes.restype = sz
         L.qg_cossim_workspace_bytes.argtypes = [i64, i64]
         L.qg_subspace_cossim.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, sz, vp]
@@ -360,6 +363,29 @@ def int8_linear_zp_backward(dy: torch.Tensor, x: torch.Tensor | None, Wq, Ws, Wz
     _check(lib().qg_int8_linear_zp_backward(_ptr(dy, _BF16), _ptr(x, _BF16), _ptr(Wq, (torch.int8,)),
                                             _ptr(Ws, (torch.float32,)), _ptr(Wz, (torch.float32,)), tokens, m, n, GROUP,
                                             _ptr(dx), _ptr(G), _stream()))
+    return dx, G
+
+
+def int8_linear_t_zp_forward(x: torch.Tensor, Sq: torch.Tensor, Ss: torch.Tensor, Sz: torch.Tensor,
+                             bias: torch.Tensor | None = None):
+    """Zero-point weight stored transposed (Sq: [n][m])."""
+    tokens, n = x.shape
+    m = Sq.shape[1]
+    y = torch.empty((tokens, m), dtype=torch.bfloat16, device=x.device)
+    _check(lib().qg_int8_linear_t_zp_forward(_ptr(x, _BF16), _ptr(Sq, (torch.int8,)), _ptr(Ss, (torch.float32,)),
+                                             _ptr(Sz, (torch.float32,)), _ptr(bias, _BF16), tokens, m, n, GROUP,
+                                             _ptr(y), _stream()))
+    return y
+
+
+def int8_linear_t_zp_backward(dy: torch.Tensor, x: torch.Tensor | None, Sq, Ss, Sz, m: int, n: int,
+                              want_dx: bool = True, want_G: bool = True):
+    tokens = dy.shape[0]
+    dx = torch.empty((tokens, n), dtype=torch.bfloat16, device=dy.device) if want_dx else None
+    G = torch.empty((n, m), dtype=torch.bfloat16, device=dy.device) if want_G else None
+    _check(lib().qg_int8_linear_t_zp_backward(_ptr(dy, _BF16), _ptr(x, _BF16), _ptr(Sq, (torch.int8,)),
+                                              _ptr(Ss, (torch.float32,)), _ptr(Sz, (torch.float32,)), tokens, m, n,
+                                              GROUP, _ptr(dx), _ptr(G), _stream()))
     return dx, G
 
 

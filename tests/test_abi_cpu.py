@@ -157,6 +157,10 @@ def test_zero_point_argument_errors(L):
     assert L.qg_int8_linear_zp_forward(FAKE, FAKE, FAKE, FAKE, None, 16, 512, 0, 256, FAKE, None) == 2
     assert L.qg_int8_linear_zp_backward(FAKE, FAKE, FAKE, FAKE, None, 16, 512, 512, 256, FAKE, FAKE, None) == 1   # dx needs Wz
     assert L.qg_int8_linear_zp_backward(FAKE, FAKE, None, None, None, 16, 512, 512, 256, None, FAKE + 2, None) == 4
+    assert L.qg_int8_linear_t_zp_forward(FAKE, FAKE, FAKE, None, None, 16, 512, 512, 256, FAKE, None) == 1
+    assert L.qg_int8_linear_t_zp_forward(FAKE, FAKE, FAKE, FAKE, None, 16, 512, 512, 32, FAKE, None) == 3
+    assert L.qg_int8_linear_t_zp_backward(FAKE, FAKE, FAKE, FAKE, None, 16, 512, 512, 256, FAKE, None, None) == 1
+    assert L.qg_int8_linear_t_zp_backward(FAKE, FAKE, FAKE, FAKE, FAKE, 0, 512, 512, 256, FAKE, FAKE, None) == 2
     # a plan takes zero points for all matrices or for none
     descs = (qg.MatrixDesc * 2)()
     for d in descs:

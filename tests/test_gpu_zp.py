@@ -199,3 +199,24 @@ def test_linear_zp_large_layer_by_sampled_outputs():
         jj = np.concatenate([rs.integers(0, oh.shape[1], 200), [oh.shape[1] - 1]])
         want = np.array([f(a, b) for a, b in zip(ii, jj)])
         assert np.all(np.abs(oh[ii, jj] - want) <= 2.0 ** -8 * np.abs(want) + 4 * k * 2.0 ** -24 * sc)
+
+
+@pytest.mark.parametrize("tokens,m,n", [(130, 333, 264), (77, 521, 200), (1100, 768, 512)])
+def test_linear_zp_on_transposed_storage(tokens, m, n):
+    """The two variants combined: a zero-point weight stored transposed (S = W^T).  The oracle side is the zero-point
+    layer on the logical weight W = dequant(S)^T, written out with plain products."""
+    g = np.random.default_rng([tokens, m, n, 1])
+    Sq, Ss, Sz = Q.quant_int8_zp(np.ascontiguousarray(shifted_weight(m, n, 7).T))     # n x m
+    Wd = Q.dequant_w_zp_bf16(Sq, Ss, Sz).T                                            # the layer's m x n operand
+    xb = Q.f64_to_bf16_bits(g.standard_normal((tokens, n)))
+    dyb = Q.f64_to_bf16_bits(g.standard_normal((tokens, m)) * 0.05)
+    bias = Q.f64_to_bf16_bits(g.standard_normal(m))
+    xh = Q.bf16_bits_to_f64(xb).reshape(tokens, n)
+    dyh = Q.bf16_bits_to_f64(dyb).reshape(tokens, m)
+    xd, dyd, dq, ds, dz = bits_t(xb, (tokens, n)), bits_t(dyb, (tokens, m)), dev(Sq), dev(Ss), dev(Sz)
+    y = qg.int8_linear_t_zp_forward(xd, dq, ds, dz, bits_t(bias, (m,)))
+    check(host_f64(y), xh @ Wd.T + Q.bf16_bits_to_f64(bias)[None, :], n, 0.04)
+    dx, GS = qg.int8_linear_t_zp_backward(dyd, xd, dq, ds, dz, m, n)
+    check(host_f64(dx), dyh @ Wd, m, 0.05 * 0.04)
+    assert tuple(GS.shape) == (n, m)
+    check(host_f64(GS), xh.T @ dyh, tokens, 0.05)
