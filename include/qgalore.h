@@ -151,7 +151,7 @@ int qg_step8(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t*
  * Adam applied in the GEMM epilogue while R is still in registers.  M, V in/out, N out; R (nullable) receives the
  * projected gradient only if the caller wants to inspect it - leaving it NULL saves writing and re-reading
  * 8 bytes per low-rank element.  Results are bit-identical to the two separate calls.  This is the form qg_step
- * and qg_step_many run (at LLaMA-7B shapes: 14.2 ms against 11.8 + 4.6 ms for the two separate launches). */
+ * and qg_step_many run (at LLaMA-7B shapes: 13.4 ms against 11.7 + 4.6 ms for the two separate launches). */
 int qg_project_adam(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
                     float* R /* nullable */, float* M, float* V, uint16_t* N_bf16,
                     int64_t m, int64_t n, int64_t r, int group, int64_t step, const qg_hparams* hp, void* stream);
