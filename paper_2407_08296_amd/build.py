@@ -1,16 +1,18 @@
-"""Builds libqgalore.so (HIP, gfx950 only) in-tree with hipcc."""
+"""Builds libqgalore.so (HIP, gfx950 only) in-tree with hipcc: one object per source, compiled in parallel, then linked."""
 from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqgalore.so")
 SOURCES = ["qg_api.hip", "qg_quant.hip", "qg_adam.hip", "qg_gemm.hip", "qg_cossim.hip", "qg_diag.hip", "qg_refresh.hip", "qg_linear.hip", "qg_adam8.hip"]
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                                   # fused multiply-adds only where written
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
@@ -18,13 +20,28 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, extra_flags: list[str] | None = None, lib: str = LIB) -> str:
+    """Compile every source (always: no up-to-date check) and link `lib`."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    os.makedirs(OBJ, exist_ok=True)
+    flags = FLAGS + list(extra_flags or [])
+    tag = os.path.splitext(os.path.basename(lib))[0]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(OBJ, f"{tag}.{os.path.splitext(src)[0]}.o")
+        cmd = [hipcc, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
