@@ -175,6 +175,17 @@ int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB,
                        int64_t m, int64_t r, int group, float* cos_out,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- qg_subspace_cossim for callers that cannot allocate device memory or carry a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same result, with the
+ * partial sums in a 4 MiB device array that is part of the library image (each GPU that loads the library holds its
+ * own copy until the process ends).  Limit: qg_cossim_workspace_bytes(m, r) <= 4 MiB, i.e. about
+ * ceil(m/64) * 3 * r <= 2^20 (m = 11008 with r = 1024 fits); larger shapes return QG_ERR_WORKSPACE.  The call
+ * allocates nothing and frees nothing; its first call on a device looks the array's address up (make that call
+ * outside graph capture).  All calls on one GPU share the array: calls that overlap on one GPU (different streams
+ * or threads) race; calls on one stream are ordered and safe.  Other errors as qg_subspace_cossim. */
+int qg_subspace_cossim_static(const uint8_t* PqA, const float* PsA, const uint8_t* PqB, const float* PsB,
+                              int64_t m, int64_t r, int group, float* cos_out, void* stream);
+
 /* ---- Subspace refresh (Sec. 3.2: every `interval` steps the projection is recomputed from the current gradient;
  * the paper takes the first r left singular vectors of G).  One pass of orthogonal iteration started from the stored
  * projection stands in for the SVD; it converges to the same singular vectors, in the same order, at the rate

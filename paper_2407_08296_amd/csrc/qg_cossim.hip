@@ -1,6 +1,8 @@
 // Subspace convergence check (Sec. 3.2, Fig. 2): mean over the r columns of the
 // cosine between corresponding columns of two INT4 projection matrices.
 // Deterministic: per-row-chunk partial sums, then per-column cosines and their mean, all in fixed orders.
+#include <atomic>
+
 #include "qg_common.h"
 #include "qg_cossim.h"
 
@@ -157,4 +159,55 @@ extern "C" int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const ui
         batch.PqA[i] = PqA; batch.PsA[i] = PsA; batch.PqB[i] = PqB; batch.PsB[i] = PsB;
     }
     return launch_cossim_batch(batch, 1, m, r, cos_out, (float*)workspace, (hipStream_t)stream);
+}
+
+// ---- The same check for callers that may not allocate: the partial sums live in a file-scope device array.
+// Every device that loads the library holds its own copy of the array at its own address; the address is looked up
+// once per device (hipGetSymbolAddress, with that device current) and only that pointer is ever handed to kernels.
+namespace qg {
+constexpr size_t kStaticScratchFloats = size_t(1) << 20;   // 4 MiB per device
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+static std::atomic<float*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (nullptr + QG_ERR_HIP on failure).
+static int static_scratch(float** out) {
+    int devid = -1;
+    hipError_t e = hipGetDevice(&devid);
+    if (e != hipSuccess || devid < 0 || devid >= kMaxDevices) {
+        set_hip_error(e != hipSuccess ? e : hipErrorInvalidDevice);
+        return QG_ERR_HIP;
+    }
+    float* p = g_scratch_ptr[devid].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void* sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || sym == nullptr) {
+            set_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol);
+            return QG_ERR_HIP;
+        }
+        p = static_cast<float*>(sym);
+        g_scratch_ptr[devid].store(p, std::memory_order_release);   // racing first calls store the same address
+    }
+    *out = p;
+    return QG_OK;
+}
+}  // namespace qg
+
+extern "C" int qg_subspace_cossim_static(const uint8_t* PqA, const float* PsA, const uint8_t* PqB, const float* PsB,
+                                         int64_t m, int64_t r, int group, float* cos_out, void* stream) {
+    if (!PqA || !PsA || !PqB || !PsB || !cos_out) return QG_ERR_NULL;
+    if (m <= 0 || r <= 0 || (r & 7) || r > m || m * r >= (int64_t(1) << 32)) return QG_ERR_SHAPE;
+    if (group != kGroup) return QG_ERR_GROUP;
+    if (!aligned16(PqA) || !aligned16(PsA) || !aligned16(PqB) || !aligned16(PsB)) return QG_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(cos_out) & 3u) != 0) return QG_ERR_ALIGN;
+    if (qg_cossim_workspace_bytes(m, r) > kStaticScratchFloats * sizeof(float)) return QG_ERR_WORKSPACE;
+    float* ws = nullptr;
+    if (int e = static_scratch(&ws)) return e;
+    CosBatch batch;
+    for (int i = 0; i < kCosBatchMax; ++i) {
+        batch.PqA[i] = PqA; batch.PsA[i] = PsA; batch.PqB[i] = PqB; batch.PsB[i] = PsB;
+    }
+    // every partial sum the later kernels read is written by the first one: nothing has to start at zero
+    return launch_cossim_batch(batch, 1, m, r, cos_out, ws, (hipStream_t)stream);
 }

@@ -32,6 +32,7 @@ EXPORTS = [
     "qg_int8_linear_zp_forward", "qg_int8_linear_zp_backward",
     "qg_int8_linear_t_zp_forward", "qg_int8_linear_t_zp_backward",
     "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8", "qg_step8",
+    "qg_subspace_cossim_static",
 ]
 
 
@@ -95,6 +96,7 @@ def lib() -> C.CDLL:
         L.qg_cossim_workspace_bytes.restype = sz
         L.qg_cossim_workspace_bytes.argtypes = [i64, i64]
         L.qg_subspace_cossim.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, sz, vp]
+        L.qg_subspace_cossim_static.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp]
         L.qg_policy_update.argtypes = [C.POINTER(Policy), f32]
         L.qg_workspace_bytes.restype = sz
         L.qg_workspace_bytes.argtypes = [i64, i64, i64]
@@ -232,6 +234,13 @@ def subspace_cossim(PqA, PsA, PqB, PsB, m: int, r: int) -> torch.Tensor:
     _check(lib().qg_subspace_cossim(_ptr(PqA, (torch.uint8,)), _ptr(PsA, (torch.float32,)), _ptr(PqB, (torch.uint8,)),
                                     _ptr(PsB, (torch.float32,)), m, r, GROUP, _ptr(out), _ptr(ws), nbytes, _stream()))
     return out
+
+
+def subspace_cossim_static(PqA, PsA, PqB, PsB, m: int, r: int, out: torch.Tensor) -> None:
+    """qg_subspace_cossim_static: no workspace; `out` is the caller's one-float device tensor."""
+    _check(lib().qg_subspace_cossim_static(_ptr(PqA, (torch.uint8,)), _ptr(PsA, (torch.float32,)),
+                                           _ptr(PqB, (torch.uint8,)), _ptr(PsB, (torch.float32,)), m, r, GROUP,
+                                           _ptr(out, (torch.float32,)), _stream()))
 
 
 def policy_update(p: Policy, cos: float) -> bool:
