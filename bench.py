@@ -10,7 +10,8 @@ Inputs are synthetic, generated on the device before the timed region, and stay 
 
 Prints ONE JSON line: metric, value (ms per step), roofline (the slower of the two launches against the bf16 MFMA
 peak, with measured HBM traffic), kernels (every launch with its rate), ceilings (what the machine sustained in the
-same run), cpu_baseline (the oracle on a sample of the workload).  Other modes: --refresh, --linear, --rsweep,
+same run), other_configs (configs 0-3 next to their bounds), rank_sweep and update_pass (config 3's sweep; the update
+pass where memory bounds it), cpu_baseline (the oracle on a sample of the workload).  Other modes: --refresh, --linear, --rsweep,
 --config N, --pad-rows, --zero-points.
 """
 from __future__ import annotations
@@ -39,19 +40,33 @@ WORKLOADS = {
 
 
 def measured_traffic(kernel: str, config: int):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
-    scaled by a plain copy of known size), or None if there is no summary for this workload."""
+    """(HBM bytes per launch of `kernel`, what the figure was profiled at) from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), or (None, None) if there is no summary for
+    this workload.  The summary names the source revision of the kernels it was taken from (`profiled_at`): a figure
+    from an older revision is stale and says so."""
     if config != 4:
-        return None
+        return None, None
     path = os.path.join(ROOT, "profiles", "grouped_step_llama7b_hbm_traffic.txt")
+    traffic, stamp = None, None
     try:
         for line in open(path):
             f = line.split()
             if len(f) == 3 and f[0] == "traffic_bytes" and f[1] == kernel:
-                return int(f[2])
+                traffic = int(f[2])
+            if len(f) >= 2 and f[0] == "profiled_at":
+                stamp = " ".join(f[1:])
     except OSError:
         pass
-    return None
+    return traffic, stamp
+
+
+def kernel_source_digest():
+    """sha256 (first 12 hex digits) over the GEMM kernel sources: what `profiled_at` in a profile summary refers to."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("qg_gemm_kernels.h", "qg_gemm.hip", "qg_common.h"):
+        h.update(open(os.path.join(ROOT, "paper_2407_08296_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:12]
 
 
 def algorithmic_work(shapes):
@@ -151,6 +166,109 @@ def cpu_baseline(config: int, shapes):
     scale = sum(m * n * r for m, n, r in shapes) / sum(m * n * r for m, n, r in sample)
     return {"value": total * scale * 1e3, "unit": "ms", "cores": int(threads), "kind": "oracle",
             "sample": note, "sample_seconds": total, "host_cpus": len(os.sched_getaffinity(0))}
+
+
+def timed_ms(f, reps):
+    import torch
+    f(); torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        f()
+    b.record(); torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def step_bounds(shapes):
+    """(MFMA-bound ms, HBM-bound ms) of one step over these matrices at the published peaks: both GEMMs' flops, and
+    the algorithmic bytes of the two fused launches (no R round trip)."""
+    flops, b_proj, b_adam, b_bp = algorithmic_work(shapes)
+    b_fused = b_proj + b_adam - sum(8 * r * n for m, n, r in shapes)
+    return 2 * flops / PEAK_BF16_TFLOPS / 1e9, (b_fused + b_bp) / PEAK_HBM_GBS / 1e6
+
+
+def other_configs(device):
+    """The step over configs 0-3 (the smaller workloads), each next to its roofline bounds.  Config 3 is run with the
+    row pitch its `down` matrices need for aligned rows (n = 5461) and, for comparison, with dense rows."""
+    import dataclasses
+
+    import torch
+
+    from paper_2407_08296_amd import inputs as I
+    from paper_2407_08296_amd import qgalore as qg
+
+    hp = qg.hparams()
+    rows = []
+    for config, pad in ((0, False), (1, False), (2, False), (3, True), (3, False)):
+        shapes = [(m, n, r) for (_, _, m, n, r) in I.config_matrices(config)]
+        mats = build_state(config, device, pad_rows=pad)
+        plan = qg.StepPlan([dataclasses.replace(s_, R=None) for s_ in mats])
+        tt = [0]
+
+        def one():
+            tt[0] += 1
+            qg.step_many(plan, hp, 0, tt[0])
+        ms = timed_ms(one, 20)
+        mfma_ms, hbm_ms = step_bounds(shapes)
+        bound = max(mfma_ms, hbm_ms)
+        rows.append({"config": config, "workload": WORKLOADS[config], "row_layout": "pitch 16" if pad else "dense",
+                     "ms_per_step": ms, "mfma_bound_ms": mfma_ms, "hbm_bound_ms": hbm_ms,
+                     "bound": "mfma" if mfma_ms >= hbm_ms else "hbm", "frac_of_bound": bound / ms,
+                     "note": "launch-bound: two launches of a few tiles" if config == 0 else None})
+        del plan, mats
+        torch.cuda.empty_cache()
+    return rows
+
+
+def rank_sweep(device):
+    """Config 3's sweep: 2048 x 5461 matrices (24 copies, stored with a row pitch of 5472: 16-byte aligned rows) through
+    the grouped launches for r in {128, 256, 512, 1024}, per matrix, next to the two bounds; and the update pass
+    where it is bound by memory rather than by the matrix cores (r = 128)."""
+    import torch
+
+    from paper_2407_08296_amd import inputs as I
+    from paper_2407_08296_amd import qgalore as qg
+
+    m, n, copies = 2048, 5461, 24
+    ld = (n + 15) // 16 * 16
+    hp = qg.hparams()
+    Wq, Ws = qg.quant_int8(torch.randn((m, n), device=device) * 0.02)
+    G = (torch.randn((m, n), device=device) * 1e-3).to(torch.bfloat16)
+    rows = []
+    for r in (128, 256, 512, 1024):
+        Pq, Ps = qg.quant_int4(torch.from_numpy(I.projection_f32(m, r)).to(device))
+        gm = [qg.MatrixState(m, n, r, Pq, Ps, pitched(G, ld), pitched(Wq.view(m, n), ld), Ws.clone(),
+                             torch.zeros((r, ld), device=device), torch.zeros((r, ld), device=device), None,
+                             torch.zeros((r, ld), dtype=torch.bfloat16, device=device), ld=ld) for _ in range(copies)]
+        plan = qg.StepPlan(gm)
+        pa = timed_ms(lambda: qg.project_adam_many(plan, hp, 2, False), 10) / copies
+        bp = timed_ms(lambda: qg.backproject_update_sr_many(plan, hp, 0, 2), 10) / copies
+        flops, b_proj, b_adam, b_bp = algorithmic_work([(m, n, r)])
+        b_fused = b_proj + b_adam - 8 * r * n
+        rows.append({"r": r, "project_adam_us": pa * 1e3, "backproject_update_us": bp * 1e3,
+                     "mfma_bound_us_per_gemm": flops / PEAK_BF16_TFLOPS / 1e6,
+                     "hbm_bound_project_adam_us": b_fused / PEAK_HBM_GBS / 1e3,
+                     "hbm_bound_backproject_update_us": b_bp / PEAK_HBM_GBS / 1e3,
+                     "project_adam_frac_mfma": flops / pa / 1e9 / PEAK_BF16_TFLOPS,
+                     "project_adam_frac_hbm": b_fused / pa / 1e6 / PEAK_HBM_GBS,
+                     "backproject_update_frac_mfma": flops / bp / 1e9 / PEAK_BF16_TFLOPS,
+                     "backproject_update_frac_hbm": b_bp / bp / 1e6 / PEAK_HBM_GBS})
+        del plan, gm
+    # the update pass (dequantize, subtract, block absmax, stochastic rounding, requantize) costs UPDATE_VALU_PER_ELEMENT
+    # vector instructions per weight element: next to the HBM bound it has a bound of its own from the vector ALUs
+    low = rows[0]
+    alu_us = m * n * UPDATE_VALU_PER_ELEMENT / PEAK_VALU_LANE_OPS * 1e6
+    update = {"where": "r = 128 (HBM-bound side of the crossover), 2048 x 5461, grouped over 24 matrices",
+              "us_per_matrix": low["backproject_update_us"], "frac_hbm": low["backproject_update_frac_hbm"],
+              "GB/s": low["backproject_update_frac_hbm"] * PEAK_HBM_GBS,
+              "alu_bound_us": alu_us, "frac_alu_bound": alu_us / low["backproject_update_us"],
+              "note": f"{UPDATE_VALU_PER_ELEMENT} vector instructions per element (8 of them the counter hash) against "
+                      "256 CUs x 64 lanes x 2.4 GHz: the update pass alone cannot run faster than this"}
+    return {"m": m, "n": n, "ld": ld, "copies": copies, "rows": rows}, update
+
+
+UPDATE_VALU_PER_ELEMENT = 17             # counted in the compiled epilogue: 3.5 (x = code*s - lr*alpha*U, absmax) + 13.5
+PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9    # vector lanes x clock: one 32-bit operation per lane per cycle
 
 
 def linear_bench(args, device):
@@ -349,6 +467,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the smaller workloads (configs 0-3), the rank sweep and the update-pass figure that the "
+                         "default run reports after the timed region")
     ap.add_argument("--rsweep", action="store_true",
                     help="time qg_project / qg_lowrank_adam / qg_backproject_update_sr on one 2048x5461 matrix for "
                          "r in {128, 256, 512, 1024} (the roofline crossover of the LLaMA-1B shape) and exit")
@@ -603,8 +724,11 @@ def main():
         roofline["sclk_mhz"] = kernels[dom_name]["sclk_mhz"]
         # the published peak assumes 2400 MHz
         roofline["frac_of_peak_at_measured_clock"] = roofline["frac"] * 2400.0 / roofline["sclk_mhz"]
-    roofline["traffic"] = measured_traffic(roofline["kernel"], args.config)
+    roofline["traffic"], stamp = measured_traffic(roofline["kernel"], args.config)
     roofline["traffic_unit"] = "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, see profiles/)"
+    roofline["traffic_profiled_at"] = stamp
+    roofline["kernel_sources_now"] = kernel_source_digest()
+    roofline["traffic_is_current"] = bool(stamp) and stamp.split()[0] == roofline["kernel_sources_now"]
     roofline["algorithmic_bytes"] = dom_bytes
     out = {
         "metric": "qgalore_step_ms_all_linear_weights", "value": ms_per_step, "unit": "ms", "n_gpus": 1,
@@ -617,9 +741,13 @@ def main():
     }
     if step8 is not None:
         out["step_with_8bit_adam_states"] = step8
+    del plan, plan_unfused, mats
+    torch.cuda.empty_cache()
+    if args.config == 4 and not args.pad_rows and not args.zero_points and not args.no_other_configs:
+        out["other_configs"] = other_configs(device)
+        out["rank_sweep"], out["update_pass"] = rank_sweep(device)
+        out["update_pass_hbm_frac"] = out["update_pass"]["frac_hbm"]
     if not args.no_cpu_baseline:
-        del plan, plan_unfused, mats
-        torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(args.config, shapes)
     print(json.dumps(out), flush=True)
 

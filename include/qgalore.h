@@ -111,8 +111,9 @@ int qg_dequant_int4(const uint8_t* q_packed, const float* scales, int64_t rows, 
 /* ---- Gradient projection (Sec. 3.5): R = dequant(P)^T G.
  * P is dequantized inside the GEMM: code*scale in fp32, rounded once to bf16;
  * bf16 MFMA with fp32 accumulation; R fp32 [r][n] is overwritten.
- * Requires 1 <= r <= m, r % 8 == 0, m*n < 2^32.  workspace may be NULL (unused
- * by the current kernels; qg_workspace_bytes reports 0 for this call). */
+ * Requires 1 <= r <= m, r % 8 == 0, m*n < 2^32.  `workspace` / `workspace_bytes`
+ * are reserved: no kernel of this call uses scratch memory, the arguments are
+ * not read and may be NULL / 0 (qg_workspace_bytes returns 0). */
 int qg_project(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
                int64_t m, int64_t n, int64_t r, int group,
                float* R, void* workspace, size_t workspace_bytes, void* stream);
@@ -151,7 +152,7 @@ int qg_step8(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t*
  * Adam applied in the GEMM epilogue while R is still in registers.  M, V in/out, N out; R (nullable) receives the
  * projected gradient only if the caller wants to inspect it - leaving it NULL saves writing and re-reading
  * 8 bytes per low-rank element.  Results are bit-identical to the two separate calls.  This is the form qg_step
- * and qg_step_many run (at LLaMA-7B shapes: 13.4 ms against 11.7 + 4.6 ms for the two separate launches). */
+ * and qg_step_many run. */
 int qg_project_adam(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
                     float* R /* nullable */, float* M, float* V, uint16_t* N_bf16,
                     int64_t m, int64_t n, int64_t r, int group, int64_t step, const qg_hparams* hp, void* stream);
@@ -320,7 +321,10 @@ int qg_policy_update(qg_policy* p, float cos);
  * SR update, as two kernels on `stream` (qg_project_adam, then
  * qg_backproject_update_sr): the same results as the three separate calls.
  * N is a caller-provided output (r x n bf16); R (r x n fp32) is written only
- * if it is not NULL.  No subspace refresh happens inside. */
+ * if it is not NULL.  No subspace refresh happens inside.
+ * qg_workspace_bytes: scratch bytes qg_project and qg_step need for a matrix of
+ * this shape: always 0 (both run out of registers and LDS); their `workspace`
+ * and `workspace_bytes` arguments are reserved, never read, and may be NULL / 0. */
 size_t qg_workspace_bytes(int64_t m, int64_t n, int64_t r);
 int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
             int8_t* Wq, float* Ws, float* M, float* V, float* R, uint16_t* N_bf16,

@@ -539,8 +539,8 @@ def int8_linear_t_backward(dy_bits, x_bits, Sq, Ss):
 
 
 # --------------------------------------------------------------------------
-# 8-bit Adam states (Sec. 3.5: "an 8-bit version of the Adam optimizer" is the
-# inner optimizer).  The paper takes the format from a third-party library
+# 8-bit Adam states (Sec. 3.5: the inner optimizer is Adam with its moments
+# held in 8 bits).  The paper takes the format from a third-party library
 # and does not define it; the format below is designed here after the
 # published idea of block-wise dynamic quantization (a data type whose
 # resolution is relative: a dynamic exponent plus a linear fraction, scaled by

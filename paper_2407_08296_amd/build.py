@@ -20,7 +20,8 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra_flags: list[str] | None = None, lib: str = LIB) -> str:
+def build(verbose: bool = False, extra_flags: list[str] | None = None, lib: str = LIB,
+          link_flags: list[str] | None = None) -> str:
     """Compile every source (always: no up-to-date check) and link `lib`."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
@@ -37,11 +38,31 @@ def build(verbose: bool = False, extra_flags: list[str] | None = None, lib: str 
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
         objs = list(pool.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *(link_flags or []), *objs, "-o", lib]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     return lib
+
+
+def build_sanitized(driver_src: str, verbose: bool = False) -> str:
+    """Host-side AddressSanitizer + UBSan build: the library with its HOST code instrumented (the sanitizer flags sit
+    behind -Xarch_host; device code is compiled as usual) as _build/libqgalore_san.so, and `driver_src` (a host
+    program that walks the ABI's validation paths) linked against it as _build/abi_sanitizer_driver.  Returns the
+    driver's path; run it with LD_LIBRARY_PATH pointing at _build/."""
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    lib = build(verbose=verbose, extra_flags=san, lib=os.path.join(OBJ, "libqgalore_san.so"),
+                link_flags=["-fsanitize=address", "-fsanitize=undefined"])
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    exe = os.path.join(OBJ, "abi_sanitizer_driver")
+    cmd = [hipcc, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fsanitize=undefined",
+           "-fno-sanitize-recover=undefined", "-I", os.path.join(ROOT, "include"), driver_src,
+           "-L", OBJ, "-lqgalore_san", "-Wl,-rpath," + OBJ, "-o", exe]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return exe
 
 
 if __name__ == "__main__":

@@ -26,10 +26,7 @@ constexpr int kPadK = 32;  // bf16 of padding per row of a K-major tile (64 B: r
 // leaves the operand panels there for the tiles that share them (+13 % on one large matrix alone, neutral inside
 // the full 7B step).
 constexpr int kAuxStream = 2;
-#ifndef QG_MFMA_PRIO
-#define QG_MFMA_PRIO 1
-#endif
-constexpr int kMfmaPrio = QG_MFMA_PRIO;   // wave priority during the MFMA phase of a K step (0 outside)
+constexpr int kMfmaPrio = 1;   // wave priority during the MFMA phase of a K step (0 outside)
 constexpr int kPadX = 8;   // bf16 of padding per row of a K-contiguous tile (16 B)
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;

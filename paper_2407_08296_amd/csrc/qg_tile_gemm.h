@@ -341,9 +341,9 @@ struct KFastDirect {
 // dequantized through registers.  256 x 256 tile, 64-deep steps, eight waves (64 x 128 each), whole tiles only:
 // M % 256 = N % 256 = K % 64 = 0, rows of A and B 16-byte aligned.  (With a bf16 B through direct loads as well the
 // refresh's G Z^T ran 0.5 % slower than through k_tile_gemm: a wave's fragment reads queue behind its own pending
-// direct loads, and with both operands direct nothing else is left to overlap them with.  With an INT8 B: forward
-// pass of a 7B layer 1.91 -> 1.84 ms, grad_input on transposed storage 1.72 -> 1.64 ms.  With an INT8 B whose
-// contraction index is slow, grad_input, the direct A loads made it 1.5 % slower: that case stays in k_tile_gemm.)
+// direct loads, and with both operands direct nothing else is left to overlap them with.  With an INT8 B the direct
+// A loads pay: about 4 % on the forward pass of a 7B layer and on grad_input on transposed storage.  With an INT8 B
+// whose contraction index is slow, grad_input, they made it 1.5 % slower: that case stays in k_tile_gemm.)
 template <int BL, typename OUT>
 __global__ __launch_bounds__(512, 1) void k_gemm_kfast_direct(LinOperand A, LinOperand B, const uint16_t* __restrict__ bias,
                                                               OUT* __restrict__ C, int M, int N, int K, int tiles_m,

@@ -15,7 +15,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqgalore.so")
+LIB_PATH = os.environ.get("QGALORE_LIB") or os.path.join(_HERE, "libqgalore.so")   # QGALORE_LIB: another build of the library
 GROUP = 256
 
 EXPORTS = [
