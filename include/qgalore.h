@@ -176,6 +176,13 @@ int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB,
                        int64_t m, int64_t r, int group, float* cos_out,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* qg_subspace_cossim_weighted: sum_k w_k cos_k / sum_k w_k over the same column cosines, with non-negative weights
+ * w (device, fp32 [r], 4-byte aligned; NULL = the plain mean above).  The subspace refresh below reports this form,
+ * with the gradient energy each new column captures as the weights.  Same workspace and errors. */
+int qg_subspace_cossim_weighted(const uint8_t* PqA, const float* PsA, const uint8_t* PqB, const float* PsB,
+                                const float* weights, int64_t m, int64_t r, int group, float* cos_out,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- qg_subspace_cossim for callers that cannot allocate device memory or carry a workspace (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same result, with the
  * partial sums in a 4 MiB device array that is part of the library image (each GPU that loads the library holds its
@@ -192,7 +199,11 @@ int qg_subspace_cossim_static(const uint8_t* PqA, const float* PsA, const uint8_
  * projection stands in for the SVD; it converges to the same singular vectors, in the same order, at the rate
  * (sigma_{r+1} / sigma_r)^2 per pass:
  *     R = dequant(P)^T G (qg_project);  Z = bf16(R);  Y = G Z^T;  Q = orthonormalize(Y);  P_new = quant_int4(Q)
- * and, after the last pass, *cos_out = qg_subspace_cossim(P, P_new).
+ * and, after the last pass, the convergence check of Sec. 3.2 between P and P_new:
+ *     *cos_out = qg_subspace_cossim_weighted(P, P_new, e),   e_k = sum_j (dequant(P_new)^T G)[k][j]^2,
+ * the column cosines weighted with the gradient energy each new column captures.  (The iteration starts from the old
+ * projection, so columns that capture next to no energy come back much as they went in whatever the gradient does;
+ * unweighted they would dominate the mean.  With comparable energies in all columns it is the plain mean.)
  *
  * qg_range_apply: Y (fp32 [m][r], overwritten) = G (bf16 [m][n]) * Z^T (Z bf16 [r][n]); bf16 MFMA, fp32 accumulation.
  *
@@ -211,8 +222,11 @@ int qg_subspace_cossim_static(const uint8_t* PqA, const float* PsA, const uint8_
  * qg_orthonormalize, first failure over all passes).  The fp64 stages run batched over the matrices, as many at a
  * time as the workspace holds: qg_refresh_workspace_bytes(count, m, n, r) bytes let all of them run in one batch,
  * qg_refresh_workspace_bytes(1, m, n, r) is the minimum; results do not depend on the batch size.  workspace is
- * 16-byte aligned; after the call it starts with R (fp32 [r][n]) of the last matrix's last pass.
+ * 16-byte aligned; after the call it starts with dequant(P_new)^T G (fp32 [r][n]) of the last matrix.
  * qg_subspace_refresh: the same for one matrix.
+ * qg_subspace_refresh_many_ld: the same with gradients stored at a row pitch of ld elements (ld >= n, a multiple of
+ * 16, or ld == n / 0 for dense rows; m*ld and r*ld below 2^32): rows then start 16-byte aligned whatever n is (the
+ * 2048 x 5461 matrices of the LLaMA-1B shapes).  Size the workspace with qg_refresh_workspace_bytes(count, m, ld, r).
  *
  * All require r % 8 == 0, r <= m, m*r < 2^31 and m*n < 2^32 (QG_ERR_SHAPE otherwise). */
 typedef struct {
@@ -231,6 +245,9 @@ size_t qg_refresh_workspace_bytes(int count, int64_t m, int64_t n, int64_t r);
 int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs, int64_t m, int64_t n, int64_t r, int group,
                              int passes, float* cos_out, int32_t* info,
                              void* workspace, size_t workspace_bytes, void* stream);
+int qg_subspace_refresh_many_ld(int count, const qg_refresh_desc* descs, int64_t m, int64_t n, int64_t ld, int64_t r,
+                                int group, int passes, float* cos_out, int32_t* info,
+                                void* workspace, size_t workspace_bytes, void* stream);
 int qg_subspace_refresh(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
                         int64_t m, int64_t n, int64_t r, int group, int passes,
                         uint8_t* Pq_new, float* Ps_new, float* cos_out, int32_t* info,
@@ -331,6 +348,16 @@ int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
             int64_t m, int64_t n, int64_t r, int group,
             const qg_hparams* hp, uint64_t seed, int64_t step,
             void* workspace, size_t workspace_bytes, void* stream);
+
+/* qg_step_ld: qg_step on arrays stored at a row pitch: G, Wq (m rows) and M, V, R, N (r rows) all have rows ld
+ * elements apart (ld >= n and a multiple of 16, or ld == n / 0 for dense rows; m*ld < 2^32), as in the `ld` field of
+ * qg_matrix_desc: a matrix whose n is not a multiple of 8 then runs in the kernels for 16-byte aligned rows.  Scales
+ * stay [m][ceil(n/256)]; the stochastic-rounding index stays i*n + j, so the n real columns get the dense layout's
+ * result.  Padding is never read for a result and not written, except that N is stored in pairs of columns. */
+int qg_step_ld(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16,
+               int8_t* Wq, float* Ws, float* M, float* V, float* R, uint16_t* N_bf16,
+               int64_t m, int64_t n, int64_t ld, int64_t r, int group,
+               const qg_hparams* hp, uint64_t seed, int64_t step, void* stream);
 
 /* ---- Grouped step over many matrices (the whole model's linear weights) in
  * two grouped launches per edge class (projection with Adam in its epilogue,

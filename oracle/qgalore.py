@@ -357,6 +357,30 @@ def subspace_cossim(PqA, PsA, PqB, PsB, m: int, r: int) -> float:
     return float(np.mean(dots / den))
 
 
+def column_energy(Pq, Ps, G_bits, m: int, n: int, r: int) -> np.ndarray:
+    """e_k = ||p_k^T G||^2: how much of the gradient's energy (squared Frobenius norm) column k of the projection, as
+    the step uses it, captures; the squared row norms of R = P^T G (Sec. 3.5)."""
+    R = project(Pq, Ps, G_bits, m, n, r)
+    return np.sum(R * R, axis=1)
+
+
+def subspace_cossim_weighted(PqA, PsA, PqB, PsB, w, m: int, r: int) -> float:
+    """sum_k w_k cos(a_k, b_k) / sum_k w_k: the column cosines of `subspace_cossim` under non-negative weights.
+
+    Reading for the subspace refresh that replaces the SVD (Sec. 3.2 compares the columns of two SVD bases): orthogonal
+    iteration started from the old projection keeps, among the directions that carry next to no gradient energy,
+    whatever the old projection held, so their cosines say nothing about the gradient; weighting each column with
+    the energy it captures makes the check follow the part of the subspace that matters to the method.  For a
+    projection whose columns all carry comparable energy it is the plain mean."""
+    A = dequant_int4(PqA, PsA, m, r)
+    B = dequant_int4(PqB, PsB, m, r)
+    dots = np.sum(A * B, axis=0)
+    den = np.maximum(np.sqrt(np.sum(A * A, axis=0)) * np.sqrt(np.sum(B * B, axis=0)), 1e-8)
+    w = np.asarray(w, dtype=np.float64)
+    tot = float(np.sum(w))
+    return float(np.sum(w * (dots / den)) / tot) if tot > 0 else 0.0
+
+
 @dataclass
 class Policy:
     """Adaptive lazy update of the SVD interval (Sec. 3.2): when the similarity
@@ -435,6 +459,15 @@ def subspace_refresh(Pq, Ps, G_bits, m: int, n: int, r: int, iters: int = 1):
         Q = orthonormalize(Y)
         Pq, Ps = quant_int4(Q.astype(np.float32))
     return Pq, Ps, Q
+
+
+def subspace_refresh_check(Pq, Ps, G_bits, m: int, n: int, r: int, iters: int = 1):
+    """`subspace_refresh` followed by the convergence check of Sec. 3.2 between the old and the new projection, the
+    column cosines weighted with the gradient energy each NEW column captures (`column_energy`).
+    Returns (Pq_new, Ps_new, cos)."""
+    Pq1, Ps1, _ = subspace_refresh(Pq, Ps, G_bits, m, n, r, iters)
+    e = column_energy(Pq1, Ps1, G_bits, m, n, r)
+    return Pq1, Ps1, subspace_cossim_weighted(Pq, Ps, Pq1, Ps1, e, m, r)
 
 
 # --------------------------------------------------------------------------

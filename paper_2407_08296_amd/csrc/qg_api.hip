@@ -22,15 +22,15 @@ int check_launch() {
 }
 
 // defined in qg_gemm.hip / qg_adam.hip
-int launch_project(const uint8_t*, const float*, const uint16_t*, float*, int64_t, int64_t, int64_t, hipStream_t);
+int launch_project(const uint8_t*, const float*, const uint16_t*, float*, int64_t, int64_t, int64_t, int64_t, hipStream_t);
 int launch_backproject(const uint8_t*, const float*, const uint16_t*, int8_t*, float*, float*, float*, int64_t, int64_t,
-                       int64_t, float, float, uint64_t, int64_t, hipStream_t);   // ..., Ws, Wz (or null), U dump (or null)
+                       int64_t, int64_t, float, float, uint64_t, int64_t, hipStream_t);   // ..., Ws, Wz (or null), U dump (or null); m, n, ld, r
 int launch_adam(const float*, float*, float*, uint16_t*, int64_t, int64_t, const qg_hparams*, hipStream_t);
 int launch_project_many(const PlanHeader*, const PlanHeader*, hipStream_t);
 int launch_backproject_many(const PlanHeader*, const PlanHeader*, float, float, uint64_t, int64_t, hipStream_t);
 int launch_adam_many(const PlanHeader*, const PlanHeader*, int64_t, const qg_hparams*, hipStream_t);
 int launch_project_adam(const uint8_t*, const float*, const uint16_t*, float*, float*, float*, uint16_t*, int64_t, int64_t,
-                        int64_t, int64_t, const qg_hparams*, hipStream_t);
+                        int64_t, int64_t, int64_t, const qg_hparams*, hipStream_t);   // m, n, ld, r, step
 int launch_project_adam_many(const PlanHeader*, const PlanHeader*, int, int64_t, const qg_hparams*, hipStream_t);
 int project_mode(int64_t m, int64_t n, int64_t ld, int64_t r);       // edge class the grouped projection needs for a matrix
 int backproject_mode(int64_t m, int64_t n, int64_t ld, int64_t r);   // ... and the grouped back-projection
@@ -71,7 +71,7 @@ extern "C" int qg_project(const uint8_t* Pq, const float* Ps, const uint16_t* G_
     if (!Pq || !Ps || !G_bf16 || !R) return QG_ERR_NULL;
     if (int e = check_mnr(m, n, r, group)) return e;
     if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(G_bf16) || !aligned16(R)) return QG_ERR_ALIGN;
-    return launch_project(Pq, Ps, G_bf16, R, m, n, r, (hipStream_t)stream);
+    return launch_project(Pq, Ps, G_bf16, R, m, n, n, r, (hipStream_t)stream);
 }
 
 extern "C" int qg_backproject_update_sr(const uint8_t* Pq, const float* Ps, const uint16_t* N_bf16, int8_t* Wq,
@@ -83,7 +83,7 @@ extern "C" int qg_backproject_update_sr(const uint8_t* Pq, const float* Ps, cons
     if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(N_bf16) || !aligned16(Wq) || !aligned16(Ws) ||
         (U_debug && !aligned16(U_debug)))
         return QG_ERR_ALIGN;
-    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, U_debug, m, n, r, alpha, lr, seed, step, (hipStream_t)stream);
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, U_debug, m, n, n, r, alpha, lr, seed, step, (hipStream_t)stream);
 }
 
 extern "C" int qg_backproject_update_sr_zp(const uint8_t* Pq, const float* Ps, const uint16_t* N_bf16, int8_t* Wq,
@@ -94,7 +94,7 @@ extern "C" int qg_backproject_update_sr_zp(const uint8_t* Pq, const float* Ps, c
     if (step < 1) return QG_ERR_SHAPE;
     if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(N_bf16) || !aligned16(Wq) || !aligned16(Ws) || !aligned16(Wz))
         return QG_ERR_ALIGN;
-    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, Wz, nullptr, m, n, r, alpha, lr, seed, step, (hipStream_t)stream);
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, Wz, nullptr, m, n, n, r, alpha, lr, seed, step, (hipStream_t)stream);
 }
 
 extern "C" int qg_step_zp(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t* Wq, float* Ws, float* Wz,
@@ -107,8 +107,8 @@ extern "C" int qg_step_zp(const uint8_t* Pq, const float* Ps, const uint16_t* G_
         !aligned16(M) || !aligned16(V) || (R && !aligned16(R)) || !aligned16(N_bf16))
         return QG_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
-    if (int e = launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, r, step, hp, s)) return e;
-    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, Wz, nullptr, m, n, r, hp->alpha, hp->lr, seed, step, s);
+    if (int e = launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, n, r, step, hp, s)) return e;
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, Wz, nullptr, m, n, n, r, hp->alpha, hp->lr, seed, step, s);
 }
 
 extern "C" int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t* Wq, float* Ws, float* M,
@@ -124,8 +124,24 @@ extern "C" int qg_step(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf1
         !aligned16(V) || (R && !aligned16(R)) || !aligned16(N_bf16))
         return QG_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
-    if (int e = launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, r, step, hp, s)) return e;
-    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, nullptr, m, n, r, hp->alpha, hp->lr, seed, step, s);
+    if (int e = launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, n, r, step, hp, s)) return e;
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, nullptr, m, n, n, r, hp->alpha, hp->lr, seed, step, s);
+}
+
+extern "C" int qg_step_ld(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int8_t* Wq, float* Ws, float* M,
+                          float* V, float* R, uint16_t* N_bf16, int64_t m, int64_t n, int64_t ld, int64_t r, int group,
+                          const qg_hparams* hp, uint64_t seed, int64_t step, void* stream) {
+    if (!Pq || !Ps || !G_bf16 || !Wq || !Ws || !M || !V || !N_bf16 || !hp) return QG_ERR_NULL;
+    if (int e = check_mnr(m, n, r, group)) return e;
+    if (step < 1) return QG_ERR_SHAPE;
+    if (ld == 0) ld = n;
+    if (ld != n && (ld < n || (ld & 15) || m * ld >= (int64_t(1) << 32))) return QG_ERR_SHAPE;
+    if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(G_bf16) || !aligned16(Wq) || !aligned16(Ws) || !aligned16(M) ||
+        !aligned16(V) || (R && !aligned16(R)) || !aligned16(N_bf16))
+        return QG_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (int e = launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, ld, r, step, hp, s)) return e;
+    return launch_backproject(Pq, Ps, N_bf16, Wq, Ws, nullptr, nullptr, m, n, ld, r, hp->alpha, hp->lr, seed, step, s);
 }
 
 extern "C" int qg_policy_update(qg_policy* p, float cos) {
@@ -260,7 +276,7 @@ extern "C" int qg_project_adam(const uint8_t* Pq, const float* Ps, const uint16_
     if (!aligned16(Pq) || !aligned16(Ps) || !aligned16(G_bf16) || (R && !aligned16(R)) || !aligned16(M) ||
         !aligned16(V) || !aligned16(N_bf16))
         return QG_ERR_ALIGN;
-    return launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, r, step, hp, (hipStream_t)stream);
+    return launch_project_adam(Pq, Ps, G_bf16, R, M, V, N_bf16, m, n, n, r, step, hp, (hipStream_t)stream);
 }
 
 extern "C" int qg_project_adam_many(int count, const void* plan_host, const void* plan_dev, size_t plan_bytes,

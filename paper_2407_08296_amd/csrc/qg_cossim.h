@@ -14,9 +14,10 @@ struct CosBatch {   // pair z: old projection (PqA, PsA)[z] against new projecti
     const float* PsB[kCosBatchMax];
 };
 
-// cos_out[z] for z < count <= kCosBatchMax; ws holds cossim_batch_workspace_bytes(m, r, count) bytes.
+// cos_out[z] for z < count <= kCosBatchMax; ws holds cossim_batch_workspace_bytes(m, r, count) bytes.  weights
+// (nullable): pair z weights its column cosines with weights[z * w_stride + k], k < r.
 int launch_cossim_batch(const CosBatch& batch, int count, int64_t m, int64_t r, float* cos_out, float* ws,
-                        hipStream_t stream);
+                        hipStream_t stream, const float* weights, int64_t w_stride);
 size_t cossim_batch_workspace_bytes(int64_t m, int64_t r, int count);
 
 }  // namespace qg

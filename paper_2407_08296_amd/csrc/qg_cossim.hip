@@ -60,12 +60,17 @@ __global__ __launch_bounds__(256) void k_cossim_partial(CosBatch batch, int m, i
 // cosines are added by a fixed tree -> group_sum[blockIdx.x].
 constexpr int kCosGroup = 64;
 
+// With `weights` (one float per column, batch entry z at weights + z * w_stride) the column cosines are weighted:
+// group_sum holds sum w_k cos_k and group_sum[groups + g] the weights' sum of group g.
 __global__ __launch_bounds__(256) void k_cossim_columns(const float* __restrict__ partial, int r, int chunks,
-                                                        float* __restrict__ group_sum, int64_t ws_stride) {
+                                                        float* __restrict__ group_sum, int64_t ws_stride,
+                                                        const float* __restrict__ weights, int64_t w_stride) {
     partial += ws_stride * blockIdx.y;
     group_sum += ws_stride * blockIdx.y;
+    if (weights != nullptr) weights += w_stride * blockIdx.y;
     __shared__ float sh[3][4][kCosGroup];
     __shared__ float cosv[kCosGroup];
+    __shared__ float wv[kCosGroup];
     const int t = threadIdx.x, cl = t & 63, part = t >> 6;
     const int k = blockIdx.x * kCosGroup + cl;
     float dot = 0.f, na = 0.f, nb = 0.f;
@@ -86,33 +91,46 @@ __global__ __launch_bounds__(256) void k_cossim_columns(const float* __restrict_
         float v[3];
 #pragma unroll
         for (int q = 0; q < 3; ++q) v[q] = ((sh[q][0][cl] + sh[q][1][cl]) + sh[q][2][cl]) + sh[q][3][cl];
-        cosv[cl] = k < r ? v[0] / fmaxf(sqrtf(v[1]) * sqrtf(v[2]), 1e-8f) : 0.f;
+        const float c = k < r ? v[0] / fmaxf(sqrtf(v[1]) * sqrtf(v[2]), 1e-8f) : 0.f;
+        const float w = (weights != nullptr && k < r) ? weights[k] : 1.f;
+        cosv[cl] = weights != nullptr ? w * c : c;
+        wv[cl] = k < r ? w : 0.f;
     }
     __syncthreads();
     for (int s = kCosGroup / 2; s > 0; s >>= 1) {
-        if (t < s) cosv[t] += cosv[t + s];
+        if (t < s) {
+            cosv[t] += cosv[t + s];
+            wv[t] += wv[t + s];
+        }
         __syncthreads();
     }
-    if (t == 0) group_sum[blockIdx.x] = cosv[0];
+    if (t == 0) {
+        group_sum[blockIdx.x] = cosv[0];
+        group_sum[gridDim.x + blockIdx.x] = wv[0];
+    }
 }
 
+// cos_out = sum of the groups' (weighted) cosine sums over the sum of the weights (r when unweighted).
 __global__ void k_cossim_mean(const float* __restrict__ group_sum, int groups, int r, float* __restrict__ cos_out,
-                              int64_t ws_stride) {
+                              int64_t ws_stride, int weighted) {
     group_sum += ws_stride * blockIdx.x;
-    float acc = 0.f;
-    for (int g = 0; g < groups; ++g) acc += group_sum[g];
-    cos_out[blockIdx.x] = acc / (float)r;
+    float acc = 0.f, wsum = 0.f;
+    for (int g = 0; g < groups; ++g) {
+        acc += group_sum[g];
+        wsum += group_sum[groups + g];
+    }
+    cos_out[blockIdx.x] = weighted ? (wsum > 0.f ? acc / wsum : 0.f) : acc / (float)r;
 }
 
 static size_t cossim_ws_floats(int64_t m, int64_t r) {
     const int64_t chunks = (m + kCosRows - 1) / kCosRows;
     const int64_t groups = (r + kCosGroup - 1) / kCosGroup;
-    return (size_t)((chunks * 3 * r + groups + 63) / 64 * 64);   // partial sums, then one sum per column group; padded
+    return (size_t)((chunks * 3 * r + 2 * groups + 63) / 64 * 64);   // partial sums, then two sums per column group; padded
 }
 
 // `count` <= kCosBatchMax pairs; workspace: count slices of cossim_ws_floats(m, r) floats.
 int launch_cossim_batch(const CosBatch& batch, int count, int64_t m, int64_t r, float* cos_out, float* ws,
-                        hipStream_t stream) {
+                        hipStream_t stream, const float* weights, int64_t w_stride) {
     const int W = (int)(r >> 3);
     const int wpr = W < 256 ? W : 256;
     const int lanes_rows = 256 / wpr;
@@ -125,9 +143,9 @@ int launch_cossim_batch(const CosBatch& batch, int count, int64_t m, int64_t r, 
     const int groups = (int)((r + kCosGroup - 1) / kCosGroup);
     float* group_sum = ws + (int64_t)chunks * 3 * r;
     hipLaunchKernelGGL(k_cossim_columns, dim3(groups, count), dim3(256), 0, stream, (const float*)ws, (int)r, chunks,
-                       group_sum, stride);
+                       group_sum, stride, weights, w_stride);
     hipLaunchKernelGGL(k_cossim_mean, dim3(count), dim3(1), 0, stream, (const float*)group_sum, groups, (int)r, cos_out,
-                       stride);
+                       stride, weights != nullptr ? 1 : 0);
     return check_launch();
 }
 
@@ -141,13 +159,24 @@ extern "C" size_t qg_cossim_workspace_bytes(int64_t m, int64_t r) {
     if (m <= 0 || r <= 0) return 0;
     const int64_t chunks = (m + kCosRows - 1) / kCosRows;
     const int64_t groups = (r + kCosGroup - 1) / kCosGroup;
-    return (size_t)((chunks * 3 * r + groups) * (int64_t)sizeof(float));   // partial sums, then one sum per column group
+    return (size_t)((chunks * 3 * r + 2 * groups) * (int64_t)sizeof(float));   // partial sums, then two sums per column group
 }
+
+extern "C" int qg_subspace_cossim_weighted(const uint8_t* PqA, const float* PsA, const uint8_t* PqB, const float* PsB,
+                                           const float* weights, int64_t m, int64_t r, int group, float* cos_out,
+                                           void* workspace, size_t workspace_bytes, void* stream);
 
 extern "C" int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const uint8_t* PqB, const float* PsB, int64_t m,
                                   int64_t r, int group, float* cos_out, void* workspace, size_t workspace_bytes,
                                   void* stream) {
+    return qg_subspace_cossim_weighted(PqA, PsA, PqB, PsB, nullptr, m, r, group, cos_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int qg_subspace_cossim_weighted(const uint8_t* PqA, const float* PsA, const uint8_t* PqB, const float* PsB,
+                                           const float* weights, int64_t m, int64_t r, int group, float* cos_out,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
     if (!PqA || !PsA || !PqB || !PsB || !cos_out) return QG_ERR_NULL;
+    if (weights && (reinterpret_cast<uintptr_t>(weights) & 3u) != 0) return QG_ERR_ALIGN;
     if (m <= 0 || r <= 0 || (r & 7) || r > m || m * r >= (int64_t(1) << 32)) return QG_ERR_SHAPE;
     if (group != kGroup) return QG_ERR_GROUP;
     if (!aligned16(PqA) || !aligned16(PsA) || !aligned16(PqB) || !aligned16(PsB)) return QG_ERR_ALIGN;
@@ -158,7 +187,7 @@ extern "C" int qg_subspace_cossim(const uint8_t* PqA, const float* PsA, const ui
     for (int i = 0; i < kCosBatchMax; ++i) {
         batch.PqA[i] = PqA; batch.PsA[i] = PsA; batch.PqB[i] = PqB; batch.PsB[i] = PsB;
     }
-    return launch_cossim_batch(batch, 1, m, r, cos_out, (float*)workspace, (hipStream_t)stream);
+    return launch_cossim_batch(batch, 1, m, r, cos_out, (float*)workspace, (hipStream_t)stream, weights, 0);
 }
 
 // ---- The same check for callers that may not allocate: the partial sums live in a file-scope device array.
@@ -209,5 +238,5 @@ extern "C" int qg_subspace_cossim_static(const uint8_t* PqA, const float* PsA, c
         batch.PqA[i] = PqA; batch.PsA[i] = PsA; batch.PqB[i] = PqB; batch.PsB[i] = PsB;
     }
     // every partial sum the later kernels read is written by the first one: nothing has to start at zero
-    return launch_cossim_batch(batch, 1, m, r, cos_out, ws, (hipStream_t)stream);
+    return launch_cossim_batch(batch, 1, m, r, cos_out, ws, (hipStream_t)stream, nullptr, 0);
 }

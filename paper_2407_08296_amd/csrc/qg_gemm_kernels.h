@@ -510,23 +510,23 @@ template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU 
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project(const uint8_t* __restrict__ Pq,
                                                            const float* __restrict__ Ps,
                                                            const uint16_t* __restrict__ G, float* __restrict__ R,
-                                                           int m, int n, int r, uint32_t tiles_r, uint32_t tiles) {
+                                                           int m, int n, int ld, int r, uint32_t tiles_r, uint32_t tiles) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    project_tile<BM, BN, BK, WGM, WGN, MODE>(Pq, Ps, G, R, m, n, n, r, (int)(tile % tiles_r) * BM,
+    project_tile<BM, BN, BK, WGM, WGN, MODE>(Pq, Ps, G, R, m, n, ld, r, (int)(tile % tiles_r) * BM,
                                                (int)(tile / tiles_r) * BN, smem);
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_adam(
     const uint8_t* __restrict__ Pq, const float* __restrict__ Ps, const uint16_t* __restrict__ G,
-    float* __restrict__ R, float* __restrict__ M, float* __restrict__ V, uint16_t* __restrict__ N, int m, int n, int r,
-    uint32_t tiles_r, uint32_t tiles, AdamCoef coef) {
+    float* __restrict__ R, float* __restrict__ M, float* __restrict__ V, uint16_t* __restrict__ N, int m, int n, int ld,
+    int r, uint32_t tiles_r, uint32_t tiles, AdamCoef coef) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    project_tile<BM, BN, BK, WGM, WGN, MODE, true>(Pq, Ps, G, R, m, n, n, r, (int)(tile % tiles_r) * BM,
+    project_tile<BM, BN, BK, WGM, WGN, MODE, true>(Pq, Ps, G, R, m, n, ld, r, (int)(tile % tiles_r) * BM,
                                                      (int)(tile / tiles_r) * BN, smem, M, V, N, &coef);
 }
 
@@ -556,7 +556,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_many(c
 
 // Up to kProjBatchMax matrices of one shape in one launch, their pointers passed by value (no plan in device memory:
 // what the subspace refresh needs, which owns no device buffer beyond its workspace and may run under graph capture).
-// R of matrix z goes to R + z * strideR.
+// R of matrix z goes to R + z * strideR, with the row pitch ld of the gradients.
 constexpr int kProjBatchMax = 16;
 struct ProjBatch {
     const uint8_t* Pq[kProjBatchMax];
@@ -566,14 +566,14 @@ struct ProjBatch {
 
 template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int MIN_WG_PER_CU = 1>
 __global__ __launch_bounds__(WGM* WGN * 64, MIN_WG_PER_CU) void k_project_batch(ProjBatch batch, float* __restrict__ R,
-                                                                                int64_t strideR, int m, int n, int r,
-                                                                                uint32_t tiles_r, uint32_t tiles_per,
-                                                                                uint32_t tiles) {
+                                                                                int64_t strideR, int m, int n, int ld,
+                                                                                int r, uint32_t tiles_r,
+                                                                                uint32_t tiles_per, uint32_t tiles) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[ProjShape<BM, BN, BK, WGM, WGN>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
     const uint32_t z = tile / tiles_per, local = tile % tiles_per;
-    project_tile<BM, BN, BK, WGM, WGN, MODE>(batch.Pq[z], batch.Ps[z], batch.G[z], R + (int64_t)z * strideR, m, n, n, r,
+    project_tile<BM, BN, BK, WGM, WGN, MODE>(batch.Pq[z], batch.Ps[z], batch.G[z], R + (int64_t)z * strideR, m, n, ld, r,
                                                (int)(local % tiles_r) * BM, (int)(local / tiles_r) * BN, smem);
 }
 
@@ -999,13 +999,13 @@ __global__ __launch_bounds__(WGn* WGm * 64, MIN_WG_PER_CU) void k_backproject(co
                                                                const uint16_t* __restrict__ N,
                                                                int8_t* __restrict__ Wq, float* __restrict__ Ws,
                                                                float* __restrict__ Wz,
-                                                               float* __restrict__ Udbg, int m, int n, int r,
+                                                               float* __restrict__ Udbg, int m, int n, int ld, int r,
                                                                float alpha, float lr, uint32_t key, uint32_t tiles_m,
                                                                uint32_t tiles) {
     __shared__ __attribute__((aligned(16))) uint16_t smem[BpShape<BMm, BK, WGn, WGm, W_PREFETCH, ZP>::SMEM];
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
     if (tile >= tiles) return;
-    backproject_tile<BMm, BK, WGn, WGm, MODE, DUMP_U, W_PREFETCH, ZP>(Pq, Ps, N, Wq, Ws, Wz, Udbg, m, n, n, r, (int)(tile % tiles_m) * BMm,
+    backproject_tile<BMm, BK, WGn, WGm, MODE, DUMP_U, W_PREFETCH, ZP>(Pq, Ps, N, Wq, Ws, Wz, Udbg, m, n, ld, r, (int)(tile % tiles_m) * BMm,
                                                 (int)(tile / tiles_m), alpha, lr, key, smem);
 }
 

@@ -24,8 +24,10 @@
 
 namespace qg {
 
-int launch_project_batch(const ProjBatch& batch, int count, float* R, int64_t strideR, int64_t m, int64_t n, int64_t r,
-                         hipStream_t stream);   // qg_gemm.hip
+int launch_project_batch(const ProjBatch& batch, int count, float* R, int64_t strideR, int64_t m, int64_t n, int64_t ld,
+                         int64_t r, hipStream_t stream);   // qg_gemm.hip
+int launch_project(const uint8_t* Pq, const float* Ps, const uint16_t* G, float* R, int64_t m, int64_t n, int64_t ld,
+                   int64_t r, hipStream_t stream);        // qg_gemm.hip
 
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef double f64x2 __attribute__((ext_vector_type(2)));
@@ -149,6 +151,24 @@ __global__ __launch_bounds__(256) void k_f32_to_bf16(const float* __restrict__ x
         o[1] = pack_bf16x2(v[2], v[3]);
         reinterpret_cast<u32x2*>(y)[i] = o;
     }
+}
+
+// Energy that each column of a projection captures from the gradient: e[z][k] = sum_j R_z[k][j]^2 with
+// R_z = P_z^T G_z (r rows of n elements, pitch ld, matrix z at R + z * strideR).  One workgroup per row; every thread
+// adds its elements in index order, the 256 partial sums are added by a fixed tree: deterministic.
+__global__ __launch_bounds__(256) void k_row_energy(const float* __restrict__ R, int64_t strideR, int n, int ld, int r,
+                                                    float* __restrict__ e) {
+    __shared__ float sh[256];
+    const float* row = R + (int64_t)blockIdx.y * strideR + (int64_t)blockIdx.x * ld;
+    float acc = 0.f;
+    for (int j = threadIdx.x; j < n; j += 256) acc = __builtin_fmaf(row[j], row[j], acc);
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) e[(int64_t)blockIdx.y * r + blockIdx.x] = sh[0];
 }
 
 __global__ void k_set_i32(int32_t* p, int32_t v, int count) {
@@ -554,11 +574,12 @@ static OrthLayout orth_layout(int64_t m, int64_t r, int64_t batch) {
 constexpr int kRefreshGroup = 16;
 static_assert(kRefreshGroup <= kProjBatchMax && kRefreshGroup <= kLinBatchMax && kRefreshGroup <= kCosBatchMax, "group size");
 struct RefreshLayout {
-    size_t R, Z, Y, orth, cos, total;
+    size_t R, Z, Y, orth, cos, wts, total;
     size_t y_bytes;   // per matrix
     size_t r_bytes, z_bytes;
     int group;        // matrices per GEMM launch
 };
+// n: elements per row of R and Z as stored, i.e. the row pitch of the gradients.
 static RefreshLayout refresh_layout(int64_t m, int64_t n, int64_t r, int64_t batch) {
     RefreshLayout L;
     L.group = (int)(batch < kRefreshGroup ? batch : kRefreshGroup);
@@ -571,7 +592,8 @@ static RefreshLayout refresh_layout(int64_t m, int64_t n, int64_t r, int64_t bat
     L.Y = L.Z + L.z_bytes * L.group;
     L.orth = L.Y + 2 * L.y_bytes * batch;        // Y and Q of every matrix
     L.cos = L.orth + orth_layout(m, r, batch).total;
-    L.total = L.cos + align256(cossim_batch_workspace_bytes(m, r, L.group));
+    L.wts = L.cos + align256(cossim_batch_workspace_bytes(m, r, L.group));
+    L.total = L.wts + align256((size_t)L.group * r * 4);   // the columns' captured energies, one group at a time
     return L;
 }
 
@@ -581,8 +603,10 @@ static int check_mr(int64_t m, int64_t r) {
 }
 
 // Y = G Z^T: G m x n and Z r x n, both bf16 with the contraction index n as their fast index; Y fp32 m x r.
-static int launch_range(const uint16_t* G, const uint16_t* Z, float* Y, int64_t m, int64_t n, int64_t r, hipStream_t st) {
-    const LinOperand A = {G, nullptr, n, 0}, B = {Z, nullptr, n, 0};
+// ldg, ldz: row pitches of G and Z in elements.
+static int launch_range(const uint16_t* G, const uint16_t* Z, float* Y, int64_t m, int64_t n, int64_t ldg, int64_t ldz,
+                        int64_t r, hipStream_t st) {
+    const LinOperand A = {G, nullptr, ldg, 0}, B = {Z, nullptr, ldz, 0};
     return launch_tile_gemm<kBf16KFast, kBf16KFast, float>(A, B, nullptr, Y, m, r, n, st);
 }
 
@@ -648,7 +672,7 @@ extern "C" int qg_range_apply(const uint16_t* G_bf16, const uint16_t* Z_bf16, in
     if (int e = check_mr(m, r)) return e;
     if (n <= 0 || m * n >= (int64_t(1) << 32) || r * n >= (int64_t(1) << 32)) return QG_ERR_SHAPE;
     if (!aligned16(G_bf16) || !aligned16(Z_bf16) || !aligned16(Y)) return QG_ERR_ALIGN;
-    return launch_range(G_bf16, Z_bf16, Y, m, n, r, (hipStream_t)stream);
+    return launch_range(G_bf16, Z_bf16, Y, m, n, n, n, r, (hipStream_t)stream);
 }
 
 extern "C" size_t qg_orthonormalize_workspace_bytes(int64_t m, int64_t r) {
@@ -666,18 +690,25 @@ extern "C" int qg_orthonormalize(const float* Y, int64_t m, int64_t r, float* Q,
     return launch_orth(Y, 0, Q, 0, m, r, 1, info, true, static_cast<char*>(workspace), (hipStream_t)stream);
 }
 
+static int check_ld(int64_t m, int64_t n, int64_t r, int64_t ld) {
+    if (n <= 0 || ld < n || (ld != n && (ld & 15))) return QG_ERR_SHAPE;
+    if (m * ld >= (int64_t(1) << 32) || r * ld >= (int64_t(1) << 32)) return QG_ERR_SHAPE;
+    return QG_OK;
+}
+
 extern "C" size_t qg_refresh_workspace_bytes(int count, int64_t m, int64_t n, int64_t r) {
-    if (count < 1 || check_mr(m, r) != QG_OK || n <= 0 || m * n >= (int64_t(1) << 32)) return 0;
+    if (count < 1 || check_mr(m, r) != QG_OK || check_ld(m, n, r, n) != QG_OK) return 0;
     return refresh_layout(m, n, r, count).total;
 }
 
-extern "C" int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs, int64_t m, int64_t n, int64_t r, int group,
-                                        int passes, float* cos_out, int32_t* info, void* workspace,
-                                        size_t workspace_bytes, void* stream) {
+extern "C" int qg_subspace_refresh_many_ld(int count, const qg_refresh_desc* descs, int64_t m, int64_t n, int64_t ld,
+                                           int64_t r, int group, int passes, float* cos_out, int32_t* info,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
     if (!descs || !cos_out || !info) return QG_ERR_NULL;
     if (count < 1 || passes < 1 || passes > 64) return QG_ERR_SHAPE;
     if (int e = check_mr(m, r)) return e;
-    if (n <= 0 || m * n >= (int64_t(1) << 32)) return QG_ERR_SHAPE;
+    if (ld == 0) ld = n;
+    if (int e = check_ld(m, n, r, ld)) return e;
     if (group != kGroup) return QG_ERR_GROUP;
     if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(cos_out) & 3) || (reinterpret_cast<uintptr_t>(info) & 3))
         return QG_ERR_ALIGN;
@@ -689,51 +720,52 @@ extern "C" int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs,
         if (d.Pq == d.Pq_new || d.Ps == d.Ps_new) return QG_ERR_SHAPE;   // the cosine check needs the old P intact
     }
     if (!workspace) return QG_ERR_WORKSPACE;
-    // as many matrices per batch as the workspace holds
+    // as many matrices per batch as the workspace holds; R and Z are stored with the gradients' row pitch
     int batch = count < 32768 ? count : 32768;   // the batch index is a grid dimension
-    while (batch > 1 && refresh_layout(m, n, r, batch).total > workspace_bytes) batch = (batch + 1) / 2;
-    const RefreshLayout L = refresh_layout(m, n, r, batch);
+    while (batch > 1 && refresh_layout(m, ld, r, batch).total > workspace_bytes) batch = (batch + 1) / 2;
+    const RefreshLayout L = refresh_layout(m, ld, r, batch);
     if (L.total > workspace_bytes) return QG_ERR_WORKSPACE;
     char* ws = static_cast<char*>(workspace);
     float* R = reinterpret_cast<float*>(ws + L.R);
     uint16_t* Z = reinterpret_cast<uint16_t*>(ws + L.Z);
     float* Y = reinterpret_cast<float*>(ws + L.Y);
     float* Q = reinterpret_cast<float*>(ws + L.Y + L.y_bytes * batch);
+    float* wts = reinterpret_cast<float*>(ws + L.wts);
     const int64_t sY = (int64_t)(L.y_bytes / 4);
     hipStream_t st = (hipStream_t)stream;
     const int64_t sR = (int64_t)(L.r_bytes / 4);
+    // R_b = dequant(P_b)^T G_b for the `ng` matrices from descriptor `d0` on, into the R slices
+    auto project_group = [&](const qg_refresh_desc* d0, int ng, bool new_p) -> int {
+        if (ng == 1) {   // one matrix: the single-matrix launch (smaller tiles, lower latency)
+            return launch_project(new_p ? d0->Pq_new : d0->Pq, new_p ? d0->Ps_new : d0->Ps, d0->G, R, m, n, ld, r, st);
+        }
+        ProjBatch pb;
+        for (int b = 0; b < kRefreshGroup; ++b) {   // unused slots: valid pointers, never dereferenced
+            const qg_refresh_desc& d = d0[b < ng ? b : 0];
+            pb.Pq[b] = new_p ? d.Pq_new : d.Pq;
+            pb.Ps[b] = new_p ? d.Ps_new : d.Ps;
+            pb.G[b] = d.G;
+        }
+        return launch_project_batch(pb, ng, R, sR, m, n, ld, r, st);
+    };
     for (int first = 0; first < count; first += batch) {
         const int nb = count - first < batch ? count - first : batch;
         for (int pass = 0; pass < passes; ++pass) {
             for (int g0 = 0; g0 < nb; g0 += L.group) {
                 const int ng = nb - g0 < L.group ? nb - g0 : L.group;
-                if (ng == 1) {   // one matrix: the single-matrix launches (smaller tiles, lower latency)
-                    const qg_refresh_desc& d = descs[first + g0];
-                    const uint8_t* pq = pass == 0 ? d.Pq : d.Pq_new;
-                    const float* ps = pass == 0 ? d.Ps : d.Ps_new;
-                    if (int e = qg_project(pq, ps, d.G, m, n, r, group, R, nullptr, 0, stream)) return e;
-                    if (int e = launch_to_bf16(R, Z, r * n, st)) return e;
-                    if (int e = launch_range(d.G, Z, Y + g0 * sY, m, n, r, st)) return e;
+                const qg_refresh_desc* d0 = descs + first + g0;
+                if (int e = project_group(d0, ng, pass > 0)) return e;
+                // the slices of R and of Z hold the same number of elements
+                if (int e = launch_to_bf16(R, Z, sR * (ng - 1) + r * ld, st)) return e;
+                if (ng == 1) {
+                    if (int e = launch_range(d0->G, Z, Y + g0 * sY, m, n, ld, ld, r, st)) return e;
                     continue;
                 }
-                ProjBatch pb;
                 LinBatch lb;
-                for (int b = 0; b < ng; ++b) {
-                    const qg_refresh_desc& d = descs[first + g0 + b];
-                    pb.Pq[b] = pass == 0 ? d.Pq : d.Pq_new;
-                    pb.Ps[b] = pass == 0 ? d.Ps : d.Ps_new;
-                    pb.G[b] = d.G;
-                    lb.a[b] = d.G;
-                }
-                for (int b = ng; b < kRefreshGroup; ++b) {   // unused slots: valid pointers, never dereferenced
-                    pb.Pq[b] = pb.Pq[0]; pb.Ps[b] = pb.Ps[0]; pb.G[b] = pb.G[0]; lb.a[b] = lb.a[0];
-                }
+                for (int b = 0; b < kRefreshGroup; ++b) lb.a[b] = d0[b < ng ? b : 0].G;
                 lb.strideB_bytes = (int64_t)L.z_bytes;
                 lb.strideC = sY;
-                if (int e = launch_project_batch(pb, ng, R, sR, m, n, r, st)) return e;
-                // the slices of R and of Z hold the same number of elements
-                if (int e = launch_to_bf16(R, Z, sR * (ng - 1) + r * n, st)) return e;
-                const LinOperand A = {pb.G[0], nullptr, n, 0}, B = {Z, nullptr, n, 0};
+                const LinOperand A = {d0->G, nullptr, ld, 0}, B = {Z, nullptr, ld, 0};
                 if (int e = launch_tile_gemm<kBf16KFast, kBf16KFast, float>(A, B, nullptr, Y + g0 * sY, m, r, n, st, &lb, ng))
                     return e;
             }
@@ -743,18 +775,33 @@ extern "C" int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs,
                 if (int e = qg_quant_int4(Q + b * sY, m, r, group, d.Pq_new, d.Ps_new, stream)) return e;
             }
         }
+        // the convergence check: column cosines of the old and the new projection, each weighted with the energy of
+        // the gradient that the new column captures (squared row norms of R_new = dequant(P_new)^T G)
         for (int g0 = 0; g0 < nb; g0 += L.group) {
             const int ng = nb - g0 < L.group ? nb - g0 : L.group;
+            const qg_refresh_desc* d0 = descs + first + g0;
+            if (int e = project_group(d0, ng, true)) return e;
+            hipLaunchKernelGGL(k_row_energy, dim3((unsigned)r, (unsigned)ng), dim3(256), 0, st, (const float*)R, sR, (int)n,
+                               (int)ld, (int)r, wts);
+            if (int e = check_launch()) return e;
             CosBatch cb;
             for (int b = 0; b < kCosBatchMax; ++b) {   // unused slots repeat the first pair
-                const qg_refresh_desc& d = descs[first + g0 + (b < ng ? b : 0)];
+                const qg_refresh_desc& d = d0[b < ng ? b : 0];
                 cb.PqA[b] = d.Pq; cb.PsA[b] = d.Ps; cb.PqB[b] = d.Pq_new; cb.PsB[b] = d.Ps_new;
             }
-            if (int e = launch_cossim_batch(cb, ng, m, r, cos_out + first + g0, reinterpret_cast<float*>(ws + L.cos), st))
+            if (int e = launch_cossim_batch(cb, ng, m, r, cos_out + first + g0, reinterpret_cast<float*>(ws + L.cos), st,
+                                            wts, r))
                 return e;
         }
     }
     return QG_OK;
+}
+
+extern "C" int qg_subspace_refresh_many(int count, const qg_refresh_desc* descs, int64_t m, int64_t n, int64_t r, int group,
+                                        int passes, float* cos_out, int32_t* info, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+    return qg_subspace_refresh_many_ld(count, descs, m, n, n, r, group, passes, cos_out, info, workspace, workspace_bytes,
+                                       stream);
 }
 
 extern "C" int qg_subspace_refresh(const uint8_t* Pq, const float* Ps, const uint16_t* G_bf16, int64_t m, int64_t n,

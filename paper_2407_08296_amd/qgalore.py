@@ -32,7 +32,7 @@ EXPORTS = [
     "qg_int8_linear_zp_forward", "qg_int8_linear_zp_backward",
     "qg_int8_linear_t_zp_forward", "qg_int8_linear_t_zp_backward",
     "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8", "qg_step8",
-    "qg_subspace_cossim_static",
+    "qg_subspace_cossim_static", "qg_subspace_cossim_weighted", "qg_step_ld", "qg_subspace_refresh_many_ld",
 ]
 
 
@@ -97,6 +97,9 @@ def lib() -> C.CDLL:
         L.qg_cossim_workspace_bytes.argtypes = [i64, i64]
         L.qg_subspace_cossim.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, sz, vp]
         L.qg_subspace_cossim_static.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp]
+        L.qg_subspace_cossim_weighted.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, vp, sz, vp]
+        L.qg_step_ld.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, C.POINTER(HParams), u64, i64,
+                                 vp]
         L.qg_policy_update.argtypes = [C.POINTER(Policy), f32]
         L.qg_workspace_bytes.restype = sz
         L.qg_workspace_bytes.argtypes = [i64, i64, i64]
@@ -131,6 +134,8 @@ def lib() -> C.CDLL:
         L.qg_int8_linear_t_forward.argtypes = L.qg_int8_linear_forward.argtypes
         L.qg_int8_linear_t_backward.argtypes = L.qg_int8_linear_backward.argtypes
         L.qg_subspace_refresh_many.argtypes = [i32, C.POINTER(RefreshDesc), i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
+        L.qg_subspace_refresh_many_ld.argtypes = [i32, C.POINTER(RefreshDesc), i64, i64, i64, i64, i32, i32, vp, vp, vp, sz,
+                                                  vp]
         _lib = L
     return _lib
 
@@ -227,12 +232,19 @@ def backproject_update_sr(Pq, Ps, N, Wq, Ws, m: int, n: int, r: int, alpha: floa
                                           alpha, lr, seed, step, _ptr(U_debug, (torch.float32,)), _stream()))
 
 
-def subspace_cossim(PqA, PsA, PqB, PsB, m: int, r: int) -> torch.Tensor:
+def subspace_cossim(PqA, PsA, PqB, PsB, m: int, r: int, weights: torch.Tensor | None = None) -> torch.Tensor:
+    """qg_subspace_cossim, or qg_subspace_cossim_weighted when `weights` (fp32 [r]) is given."""
     nbytes = lib().qg_cossim_workspace_bytes(m, r)
     ws = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=PqA.device)
     out = torch.empty((1,), dtype=torch.float32, device=PqA.device)
-    _check(lib().qg_subspace_cossim(_ptr(PqA, (torch.uint8,)), _ptr(PsA, (torch.float32,)), _ptr(PqB, (torch.uint8,)),
-                                    _ptr(PsB, (torch.float32,)), m, r, GROUP, _ptr(out), _ptr(ws), nbytes, _stream()))
+    if weights is None:
+        _check(lib().qg_subspace_cossim(_ptr(PqA, (torch.uint8,)), _ptr(PsA, (torch.float32,)), _ptr(PqB, (torch.uint8,)),
+                                        _ptr(PsB, (torch.float32,)), m, r, GROUP, _ptr(out), _ptr(ws), nbytes, _stream()))
+    else:
+        _check(lib().qg_subspace_cossim_weighted(_ptr(PqA, (torch.uint8,)), _ptr(PsA, (torch.float32,)),
+                                                 _ptr(PqB, (torch.uint8,)), _ptr(PsB, (torch.float32,)),
+                                                 _ptr(weights, (torch.float32,)), m, r, GROUP, _ptr(out), _ptr(ws),
+                                                 nbytes, _stream()))
     return out
 
 
@@ -255,6 +267,14 @@ def step(Pq, Ps, G, Wq, Ws, M, V, R, N, m: int, n: int, r: int, hp: HParams, see
                          _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)), _ptr(M, (torch.float32,)),
                          _ptr(V, (torch.float32,)), _ptr(R, (torch.float32,)), _ptr(N, _BF16), m, n, r, GROUP,
                          C.byref(hp), seed, step, None, 0, _stream()))
+
+
+def step_ld(Pq, Ps, G, Wq, Ws, M, V, R, N, m: int, n: int, ld: int, r: int, hp: HParams, seed: int, step: int) -> None:
+    """qg_step_ld: every n-wide array is stored with rows ld elements apart."""
+    _check(lib().qg_step_ld(_ptr(Pq, (torch.uint8,)), _ptr(Ps, (torch.float32,)), _ptr(G, _BF16),
+                            _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)), _ptr(M, (torch.float32,)),
+                            _ptr(V, (torch.float32,)), _ptr(R, (torch.float32,)), _ptr(N, _BF16), m, n, ld, r, GROUP,
+                            C.byref(hp), seed, step, _stream()))
 
 
 @dataclass
@@ -505,14 +525,15 @@ def subspace_refresh(Pq, Ps, G, m: int, n: int, r: int, passes: int = 1, workspa
 
 
 def subspace_refresh_many(Pqs, Pss, Gs, m: int, n: int, r: int, passes: int = 1,
-                          workspace: torch.Tensor | None = None, out=None):
+                          workspace: torch.Tensor | None = None, out=None, ld: int = 0):
     """Refresh of several matrices of one shape.  Pqs, Pss, Gs: lists of device tensors.  `out`: optional
-    (list of Pq_new, list of Ps_new) to write into.  Returns (Pq_news, Ps_news, cos[count], info[count], workspace)."""
+    (list of Pq_new, list of Ps_new) to write into.  ld: row pitch of the gradients (0: dense).
+    Returns (Pq_news, Ps_news, cos[count], info[count], workspace)."""
     count = len(Gs)
     if count == 0 or len(Pqs) != count or len(Pss) != count:
         raise QGError("libqgalore: one Pq and one Ps per gradient expected")
     if workspace is None:
-        nbytes = lib().qg_refresh_workspace_bytes(count, m, n, r)
+        nbytes = lib().qg_refresh_workspace_bytes(count, m, ld or n, r)
         if nbytes == 0:
             raise QGError("libqgalore: shape out of range")
         workspace = torch.empty((nbytes,), dtype=torch.uint8, device=Gs[0].device)
@@ -524,8 +545,8 @@ def subspace_refresh_many(Pqs, Pss, Gs, m: int, n: int, r: int, passes: int = 1,
                                _ptr(out[0][i], (torch.uint8,)), _ptr(out[1][i], (torch.float32,)))
     cos = torch.empty((count,), dtype=torch.float32, device=Gs[0].device)
     info = torch.empty((count,), dtype=torch.int32, device=Gs[0].device)
-    _check(lib().qg_subspace_refresh_many(count, descs, m, n, r, GROUP, passes, _ptr(cos), _ptr(info),
-                                          _ptr(workspace), workspace.numel(), _stream()))
+    _check(lib().qg_subspace_refresh_many_ld(count, descs, m, n, ld, r, GROUP, passes, _ptr(cos), _ptr(info),
+                                             _ptr(workspace), workspace.numel(), _stream()))
     return out[0], out[1], cos, info, workspace
 
 

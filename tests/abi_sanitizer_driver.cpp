@@ -63,10 +63,14 @@ int main() {
     EXPECT(qg_diag_mfma_loop(0, 0, FF, nullptr), QG_ERR_SHAPE);
     EXPECT(qg_diag_mfma_f64_loop(10, 0, FF, nullptr), QG_ERR_SHAPE);
 
-    EXPECT(qg_cossim_workspace_bytes(512, 128), (8 * 3 * 128 + 2) * 4);
+    EXPECT(qg_cossim_workspace_bytes(512, 128), (8 * 3 * 128 + 2 * 2) * 4);
     EXPECT(qg_cossim_workspace_bytes(-5, 128), 0);
     EXPECT(qg_subspace_cossim(F8, FF, F8, FF, 512, 128, 256, FF, nullptr, 0, nullptr), QG_ERR_WORKSPACE);
     EXPECT(qg_subspace_cossim(F8, FF, F8, FF, 512, 130, 256, FF, FF, 1 << 20, nullptr), QG_ERR_SHAPE);
+    EXPECT(qg_subspace_cossim_weighted(F8, FF, F8, FF, FF, 512, 128, 256, FF, nullptr, 0, nullptr), QG_ERR_WORKSPACE);
+    EXPECT(qg_subspace_cossim_weighted(F8, FF, F8, FF, reinterpret_cast<float*>(0x10002), 512, 128, 256, FF, FF, 1 << 20, nullptr), QG_ERR_ALIGN);
+    EXPECT(qg_step_ld(F8, FF, F16, FI8, FF, FF, FF, nullptr, F16, 2048, 5461, 5464, 512, 256, &hp, 0, 1, nullptr), QG_ERR_SHAPE);
+    EXPECT(qg_step_ld(F8, FF, F16, FI8, FF, FF, FF, nullptr, F16, 2048, 5461, 5472, 512, 256, nullptr, 0, 1, nullptr), QG_ERR_NULL);
     EXPECT(qg_subspace_cossim_static(F8, FF, F8, nullptr, 512, 128, 256, FF, nullptr), QG_ERR_NULL);
     EXPECT(qg_subspace_cossim_static(F8, FF, F8, FF, 65536, 2048, 256, FF, nullptr), QG_ERR_WORKSPACE);
     EXPECT(qg_subspace_cossim_static(F8, FF, F8, FF, 512, 128, 256, FF4 + 0, nullptr) == QG_ERR_HIP ||
@@ -104,6 +108,8 @@ int main() {
         rd[1] = {F8, FF, F16, F8 + 4096, nullptr};
         EXPECT(qg_subspace_refresh_many(2, rd.data(), 512, 512, 128, 256, 1, FF, FI32, FF, rb, nullptr), QG_ERR_NULL);
         EXPECT(qg_subspace_refresh_many(0, rd.data(), 512, 512, 128, 256, 1, FF, FI32, FF, rb, nullptr), QG_ERR_SHAPE);
+        EXPECT(qg_subspace_refresh_many_ld(1, rd.data(), 512, 500, 504, 128, 256, 1, FF, FI32, FF, rb, nullptr), QG_ERR_SHAPE);
+        EXPECT(qg_subspace_refresh_many_ld(1, rd.data(), 512, 500, 512, 128, 256, 1, FF, FI32, nullptr, 0, nullptr), QG_ERR_WORKSPACE);
         EXPECT(qg_subspace_refresh_many(1, rd.data(), 512, 512, 128, 256, 65, FF, FI32, FF, rb, nullptr), QG_ERR_SHAPE);
         EXPECT(qg_subspace_refresh(F8, FF, F16, 512, 512, 128, 256, 1, F8, FF + 4096, FF, FI32, FF, rb, nullptr), QG_ERR_SHAPE);
     }

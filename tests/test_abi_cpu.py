@@ -63,7 +63,7 @@ def test_step_piece_argument_errors(L):
     assert L.qg_subspace_cossim(FAKE, FAKE, FAKE, FAKE, 512, 128, 256, FAKE, None, 0, None) == 5
     assert L.qg_subspace_cossim(FAKE, FAKE, FAKE, FAKE, 512, 128, 256, FAKE, FAKE, 16, None) == 5
     assert L.qg_subspace_cossim(FAKE, FAKE, FAKE, FAKE, 512, 130, 256, FAKE, FAKE, 1 << 20, None) == 2
-    assert L.qg_cossim_workspace_bytes(512, 128) == (8 * 3 * 128 + 2) * 4
+    assert L.qg_cossim_workspace_bytes(512, 128) == (8 * 3 * 128 + 2 * 2) * 4
     assert L.qg_step(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 128, 256, None, 0, 1, None, 0, None) == 1
     assert L.qg_step(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 512, 128, 256, C.byref(hp), 0, 0, None, 0, None) == 2
     assert L.qg_sr_uniform(0, 1, 0, 0, FAKE, None) == 2

@@ -650,3 +650,27 @@ def test_llama1b_down_shape_with_row_pitch_sampled_columns():
         check_codes(gWq[:, sl], o["Wq"])
         check_scales_step(gWs[:, g:g + 1], o["Ws"], rel=5e-4)
     assert np.all(gWq[:, n:] == 85)
+
+
+@pytest.mark.parametrize("m,n,r,ld", [(333, 261, 144, 272), (512, 1365, 128, 1376), (768, 768, 256, 800), (300, 700, 40, 704)])
+def test_single_matrix_step_with_row_pitch(m, n, r, ld):
+    """qg_step_ld: the single-matrix step on arrays with rows ld elements apart.  The n real columns get the oracle's
+    result and, bit for bit, the grouped step's on the same pitched arrays; the padding (NaN in the gradient) is neither
+    used nor overwritten."""
+    mats, data = _pitched_state([(m, n, r, ld)])
+    ref, _ = _pitched_state([(m, n, r, ld)])
+    s, d, g = mats[0], data[0], ref[0]
+    seed, t = 33, 1
+    qg.step_ld(s.Pq, s.Ps, s.G, s.Wq, s.Ws, s.M, s.V, s.R, s.N, m, n, ld, r, qg.hparams(), seed, t)
+    qg.step_many(qg.StepPlan([g]), qg.hparams(), seed, t)
+    torch.cuda.synchronize()
+    o = Q.step(d["Wq"], d["Ws"], d["Gb"], d["Pq"], d["Ps"], np.zeros((r, n)), np.zeros((r, n)), t, HP, seed=seed, r=r)
+    assert rel_fro(host(s.R[:, :n]), o["R"]) <= 2e-5
+    assert rel_fro(bf16_t_to_f64(s.N.view(torch.bfloat16)[:, :n].contiguous()), o["Nb"]) <= 1e-3
+    assert rel_fro(host(s.M[:, :n]), o["M"]) <= 2e-5 and rel_fro(host(s.V[:, :n]), o["V"]) <= 4e-5
+    check_codes(host(s.Wq[:, :n]), o["Wq"].reshape(m, n))
+    check_scales_step(host(s.Ws), o["Ws"], rel=5e-4)
+    assert torch.all(s.Wq[:, n:] == 85) and torch.all(s.M[:, n:] == 777.0) and torch.all(s.V[:, n:] == 777.0)
+    assert torch.all(s.N[:, n + n % 2:] == 0x1234) and torch.all(torch.isnan(s.R[:, n:]))
+    assert torch.equal(s.Wq, g.Wq) and torch.equal(s.Ws, g.Ws) and torch.equal(s.M[:, :n], g.M[:, :n])
+    assert torch.equal(s.R[:, :n], g.R[:, :n]) and torch.equal(s.N[:, :n], g.N[:, :n])

@@ -181,13 +181,18 @@ def test_subspace_refresh_equals_its_parts_and_the_oracle(m, n, r, passes):
         c = _chain(Gb, pq, ps, m, n, r)
         pq, ps = host(c["Pq"]), host(c["Ps"])
     assert np.array_equal(host(Pq1), pq) and np.array_equal(host(Ps1), ps)
+    # the workspace starts with R_new = dequant(P_new)^T G, whose squared row norms weight the cosine check
     R_ws = host(ws[: r * n * 4].view(torch.float32)).reshape(r, n)
-    assert np.array_equal(R_ws, host(c["R"]))
-    want_cos = Q.subspace_cossim(Pq, Ps, pq, ps, m, r)        # the library's own new P: isolates the cosine kernel
-    assert abs(float(host(cos)[0]) - want_cos) <= 1e-5
+    assert np.array_equal(R_ws, host(qg.project(dev(pq), dev(ps), bits_t(Gb), m, n, r)))
+    e_own = Q.column_energy(pq, ps, Gb, m, n, r)
+    want_cos = Q.subspace_cossim_weighted(Pq, Ps, pq, ps, e_own, m, r)   # the library's own new P: isolates the check
+    assert abs(float(host(cos)[0]) - want_cos) <= 2e-5
+    # the public weighted check on the same pair and weights gives the same number
+    again_cos = qg.subspace_cossim(dev(Pq), dev(Ps), dev(pq), dev(ps), m, r, weights=dev(e_own.astype(np.float32)))
+    assert abs(float(host(again_cos)[0]) - want_cos) <= 2e-5
     # against the oracle's passes: what the method uses downstream
-    oPq, oPs, _ = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=passes)
-    assert abs(float(host(cos)[0]) - Q.subspace_cossim(Pq, Ps, oPq, oPs, m, r)) <= 2e-3 * passes
+    oPq, oPs, ocos = Q.subspace_refresh_check(Pq, Ps, Gb, m, n, r, iters=passes)
+    assert abs(float(host(cos)[0]) - ocos) <= 2e-3 * passes
     e_got = np.linalg.norm(Q.project(pq, ps, Gb, m, n, r)) ** 2
     e_want = np.linalg.norm(Q.project(oPq, oPs, Gb, m, n, r)) ** 2
     assert abs(e_got - e_want) <= 1e-3 * passes * e_want
@@ -324,3 +329,50 @@ def test_refresh_and_step_replay_from_a_graph():
         assert int(info[0]) == 0
         for got, want in zip(gstate + [gN], ref_S):
             assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+
+
+@pytest.mark.parametrize("m,n,r,ld,passes", [(333, 261, 144, 272, 1), (512, 1365, 128, 1376, 2), (300, 700, 40, 704, 1)])
+def test_refresh_with_a_row_pitch_equals_the_dense_refresh(m, n, r, ld, passes):
+    """qg_subspace_refresh_many_ld: gradients stored with rows ld elements apart (NaN in the padding).  The products
+    are the dense call's up to the order of a sum (the kernels differ with the alignment of the rows), so the new
+    projection agrees with the dense call's to a code, and the energy and the cosine check with the oracle's."""
+    ins = [start(m, n, r, seed=s) for s in (0, 1)]
+    Gp = []
+    for Gb, _, _ in ins:
+        g = np.full((m, ld), 0x7FC0, dtype=np.uint16)
+        g[:, :n] = np.asarray(Gb).reshape(m, n)
+        Gp.append(torch.from_numpy(g.view(np.int16)).to(DEV))
+    Pqs = [dev(Pq) for _, Pq, _ in ins]
+    Pss = [dev(Ps) for _, _, Ps in ins]
+    pq, ps, cos, info, _ = qg.subspace_refresh_many(Pqs, Pss, Gp, m, n, r, passes, ld=ld)
+    assert host(info).tolist() == [0, 0]
+    for i, (Gb, Pq, Ps) in enumerate(ins):
+        dq, ds, dcos, _, _ = qg.subspace_refresh(Pqs[i], Pss[i], bits_t(Gb), m, n, r, passes)
+        gc, dc = Q.unpack_int4(host(pq[i]), m * r).astype(np.int32), Q.unpack_int4(host(dq), m * r).astype(np.int32)
+        assert np.abs(gc - dc).max() <= 1 and np.mean(gc == dc) >= 0.99
+        assert abs(float(host(cos)[i]) - float(host(dcos)[0])) <= 2e-3
+        oPq, oPs, ocos = Q.subspace_refresh_check(Pq, Ps, Gb, m, n, r, iters=passes)
+        assert abs(float(host(cos)[i]) - ocos) <= 2e-3 * passes
+        e_got = np.linalg.norm(Q.project(host(pq[i]), host(ps[i]), Gb, m, n, r)) ** 2
+        e_want = np.linalg.norm(Q.project(oPq, oPs, Gb, m, n, r)) ** 2
+        assert abs(e_got - e_want) <= 1e-3 * passes * e_want
+
+
+def test_refresh_check_reads_an_unrelated_gradient_as_change():
+    """The convergence check the refresh reports, on the synthetic gradients (rank-16 signal over a noise floor): the
+    same gradient again reads as converged, an unrelated one as changed (below the paper's 0.4), and the library's
+    figure is the oracle's; the host policy takes the matching decisions."""
+    m, n, r = 512, 512, 128
+    G1, G2 = I.gradient_bf16(m, n, 1), I.gradient_bf16(m, n, 2)
+    Pq0, Ps0 = Q.quant_int4(I.projection_f32(m, r))
+    Pq1, Ps1, _ = Q.subspace_refresh_check(Pq0, Ps0, G1, m, n, r)
+    pol = qg.Policy(200, 0, 1, 200, 0.4, 0.0)
+    opol = Q.Policy(interval=200, k=1, threshold=0.4, next_refresh=200)
+    for Gb, converged in ((G1, True), (G2, False)):
+        _, _, ocos = Q.subspace_refresh_check(Pq1, Ps1, Gb, m, n, r)
+        _, _, gcos, info, _ = qg.subspace_refresh(dev(Pq1), dev(Ps1), bits_t(Gb), m, n, r, 1)
+        g = float(host(gcos)[0])
+        assert int(host(info)[0]) == 0 and abs(g - ocos) <= 2e-3
+        assert (g >= 0.4) == converged and (ocos >= 0.4) == converged
+        assert qg.policy_update(pol, g) == opol.update(float(np.float32(ocos))) == converged
+    assert (pol.interval, pol.next_refresh) == (opol.interval, opol.next_refresh) == (400, 200 + 400 + 400)

@@ -75,10 +75,9 @@ def test_forward_backward_refresh_step_loop():
 
         # subspace refresh when due (the first one at step 1, as GaLore does)
         if t == pol_o.next_refresh:
-            oPq, oPs, _ = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+            oPq, oPs, ocos = Q.subspace_refresh_check(Pq, Ps, Gb, m, n, r, iters=1)
             gPq, gPs, gcos, ginfo, _ = qg.subspace_refresh(dev(Pq), dev(Ps), Gd, m, n, r, 1)
             assert int(host(ginfo)[0]) == 0
-            ocos = Q.subspace_cossim(Pq, Ps, oPq, oPs, m, r)
             assert abs(float(host(gcos)[0]) - ocos) <= 2e-3
             e_g = np.linalg.norm(Q.project(host(gPq), host(gPs), Gb, m, n, r)) ** 2
             e_o = np.linalg.norm(Q.project(oPq, oPs, Gb, m, n, r)) ** 2

@@ -167,3 +167,79 @@ def test_refresh_on_the_synthetic_gradient_captures_the_planted_signal():
     c1 = Q.subspace_cossim(Pq, Ps, Pq1, Ps1, m, r)
     c2 = Q.subspace_cossim(Pq1, Ps1, Pq2, Ps2, m, r)
     assert c1 < 0.9 and c2 > c1 + 0.05, (c1, c2)
+
+
+# ---------------------------------------------------------------- the convergence check of the refresh
+def test_weighted_cosine_reduces_to_the_plain_mean_and_to_single_columns():
+    m, r = 96, 16
+    P = I.projection_f32(m, r, seed=1)
+    a = Q.quant_int4(P)
+    b = Q.quant_int4(I.perturbed_projection_f32(P, 0.3, seed=2))
+    plain = Q.subspace_cossim(a[0], a[1], b[0], b[1], m, r)
+    assert abs(Q.subspace_cossim_weighted(a[0], a[1], b[0], b[1], np.ones(r), m, r) - plain) < 1e-15
+    assert abs(Q.subspace_cossim_weighted(a[0], a[1], b[0], b[1], np.full(r, 7.5), m, r) - plain) < 1e-15
+    A, B = Q.dequant_int4(a[0], a[1], m, r), Q.dequant_int4(b[0], b[1], m, r)
+    for k in (0, 5, r - 1):                                   # all the weight on one column: that column's cosine
+        w = np.zeros(r); w[k] = 2.0
+        want = float(A[:, k] @ B[:, k] / (np.linalg.norm(A[:, k]) * np.linalg.norm(B[:, k])))
+        assert abs(Q.subspace_cossim_weighted(a[0], a[1], b[0], b[1], w, m, r) - want) < 1e-14
+    assert Q.subspace_cossim_weighted(a[0], a[1], b[0], b[1], np.zeros(r), m, r) == 0.0
+
+
+def test_column_energy_sums_to_the_projected_energy():
+    m, n, r = 128, 192, 24
+    Gb = I.gradient_bf16(m, n, 1)
+    Pq, Ps = _start(m, r)
+    e = Q.column_energy(Pq, Ps, Gb, m, n, r)
+    R = Q.project(Pq, Ps, Gb, m, n, r)
+    assert e.shape == (r,) and (e >= 0).all() and np.isclose(e.sum(), np.linalg.norm(R) ** 2, rtol=1e-12)
+    G = Q.bf16_bits_to_f64(Gb).reshape(m, n)
+    Pd = Q.dequant_p_bf16(Pq, Ps, m, r)
+    k = 7
+    assert np.isclose(e[k], sum((sum(Pd[i, k] * G[i, j] for i in range(m))) ** 2 for j in range(n)), rtol=1e-10)
+
+
+def test_refresh_check_follows_the_gradient_not_the_start():
+    """The statistic the refresh reports (Sec. 3.2) on the synthetic gradients (rank-16 signal over a flat noise
+    floor): an unrelated gradient reads as change (below the paper's 0.4 threshold), the same gradient again as
+    convergence, and a drifting gradient in between and monotonically; the policy decisions are those that the
+    SVD's vectors give under the same weighting.  The plain column mean fails the first of these: the 112 columns
+    without signal energy come back as they went in."""
+    m, n, r = 512, 512, 128
+    G1 = I.gradient_bf16(m, n, 1)
+    G2 = I.gradient_bf16(m, n, 2)
+    Pq0, Ps0 = _start(m, r)
+    Pq1, Ps1, _ = Q.subspace_refresh_check(Pq0, Ps0, G1, m, n, r)            # the stored projection after a refresh on G1
+    _, _, c_same = Q.subspace_refresh_check(Pq1, Ps1, G1, m, n, r)
+    Pq2, Ps2, c_other = Q.subspace_refresh_check(Pq1, Ps1, G2, m, n, r)
+    assert c_same > 0.9 and c_other < 0.4, (c_same, c_other)
+    assert Q.subspace_cossim(Pq1, Ps1, Pq2, Ps2, m, r) > 0.4                # the unweighted mean would call it converged
+    g1 = Q.bf16_bits_to_f64(G1).reshape(m, n); g2 = Q.bf16_bits_to_f64(G2).reshape(m, n)
+    U1, s1, _ = np.linalg.svd(g1, full_matrices=False)
+    prev = c_same
+    for eps in (0.1, 0.5, 2.0, 8.0):                                        # G1 drifting towards G2
+        Gd = Q.f64_to_bf16_bits(g1 + eps * g2)
+        _, _, c = Q.subspace_refresh_check(Pq1, Ps1, Gd, m, n, r)
+        assert c < prev + 1e-3, (eps, c, prev)
+        prev = c
+        # the same decision from the definition: SVD bases of the two gradients, |cosine| per column (an SVD fixes
+        # columns up to sign), weighted with the new singular values squared
+        Ud, sd, _ = np.linalg.svd(Q.bf16_bits_to_f64(Gd).reshape(m, n), full_matrices=False)
+        cs = np.abs(np.sum(U1[:, :r] * Ud[:, :r], axis=0))
+        c_svd = float(np.sum(sd[:r] ** 2 * cs) / np.sum(sd[:r] ** 2))
+        if abs(c_svd - 0.4) > 0.15 and abs(c - 0.4) > 0.15:
+            assert (c >= 0.4) == (c_svd >= 0.4), (eps, c, c_svd)
+    assert prev < 0.4
+
+
+def test_refresh_check_equals_the_plain_mean_on_a_separated_spectrum():
+    """A gradient of exact rank r with distinct singular values and a start that has converged: every column carries
+    energy and has settled, so the weighted and the plain cosine agree (both close to 1), as the SVD's do."""
+    m, n, r = 128, 128, 6
+    Gb, _ = _spectrum_matrix(m, n, np.r_[[8, 5, 3, 2, 1.2, 0.8], np.full(20, 0.02)], seed=11)
+    Pq, Ps = _start(m, r, seed=4)
+    for _ in range(12):
+        Pq, Ps, _ = Q.subspace_refresh(Pq, Ps, Gb, m, n, r, iters=1)
+    Pq2, Ps2, c = Q.subspace_refresh_check(Pq, Ps, Gb, m, n, r)
+    plain = Q.subspace_cossim(Pq, Ps, Pq2, Ps2, m, r)
+    assert c > 0.97 and abs(c - plain) < 0.02, (c, plain)
