@@ -268,6 +268,18 @@ int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, con
                             int64_t tokens, int64_t m, int64_t n, int group,
                             uint16_t* dx_bf16, uint16_t* G_bf16, void* stream);
 
+/* The same two calls on arrays stored at a row pitch: ld_n is the pitch of the arrays with n elements per row (x, dx,
+ * Wq, G), ld_m that of the arrays with m (y, dy); each is the row length itself (or 0), or at least it and a multiple
+ * of 16 elements, with rows * pitch below 2^31.  Rows then start 16-byte aligned whatever m and n are (n = 5461 in the
+ * LLaMA-1B shapes); G comes out in the layout qg_step_ld and the `ld` of qg_matrix_desc take.  Scales stay
+ * [m][ceil(n/256)].  Padding is never read for a result and never written. */
+int qg_int8_linear_forward_ld(const uint16_t* x_bf16, const int8_t* Wq, const float* Ws, const uint16_t* bias_bf16,
+                              int64_t tokens, int64_t m, int64_t n, int64_t ld_n, int64_t ld_m, int group,
+                              uint16_t* y_bf16, void* stream);
+int qg_int8_linear_backward_ld(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
+                               int64_t tokens, int64_t m, int64_t n, int64_t ld_n, int64_t ld_m, int group,
+                               uint16_t* dx_bf16, uint16_t* G_bf16, void* stream);
+
 /* ---- Right-side projection (GaLore's second form, which Sec. 3.5 inherits: R = G Q with Q the n x r matrix of right
  * singular vectors, moments m x r, update alpha N Q^T; used where a weight has more rows than columns).  A weight
  * that is projected from the right is kept TRANSPOSED, S = W^T: n x m INT8 codes, blocks of 256 along each row of S,

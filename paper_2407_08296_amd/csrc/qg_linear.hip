@@ -20,40 +20,70 @@ static int check_linear(int64_t tokens, int64_t m, int64_t n, int group) {
     return QG_OK;
 }
 
+// Row pitches of the pitched entry points: ld_n for the arrays with n elements per row (x, dx, Wq, G), ld_m for those
+// with m (y, dy).  Each is the row length itself, or at least it and a multiple of 16 elements.
+static int check_pitch(int64_t rows_limit, int64_t len, int64_t& ld) {
+    if (ld == 0) ld = len;
+    if (ld != len && (ld < len || (ld & 15))) return QG_ERR_SHAPE;
+    if (rows_limit >= (int64_t(1) << 31) / ld) return QG_ERR_SHAPE;
+    return QG_OK;
+}
+
 }  // namespace qg
 
 using namespace qg;
 
-extern "C" int qg_int8_linear_forward(const uint16_t* x_bf16, const int8_t* Wq, const float* Ws, const uint16_t* bias_bf16,
-                                      int64_t tokens, int64_t m, int64_t n, int group, uint16_t* y_bf16, void* stream) {
+extern "C" int qg_int8_linear_forward_ld(const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
+                                         const uint16_t* bias_bf16, int64_t tokens, int64_t m, int64_t n, int64_t ld_n,
+                                         int64_t ld_m, int group, uint16_t* y_bf16, void* stream) {
     if (!x_bf16 || !Wq || !Ws || !y_bf16) return QG_ERR_NULL;
     if (int e = check_linear(tokens, m, n, group)) return e;
+    if (int e = check_pitch(tokens > m ? tokens : m, n, ld_n)) return e;
+    if (int e = check_pitch(tokens, m, ld_m)) return e;
     if (!aligned16(x_bf16) || !aligned16(Wq) || !aligned16(Ws) || !aligned16(y_bf16) || (bias_bf16 && !aligned16(bias_bf16)))
         return QG_ERR_ALIGN;
     const int sg = (int)((n + kGroup - 1) / kGroup);
-    const LinOperand A = {x_bf16, nullptr, n, 0}, B = {Wq, Ws, n, sg};
-    return launch_tile_gemm<kBf16KFast, kInt8KFast, uint16_t>(A, B, bias_bf16, y_bf16, tokens, m, n, (hipStream_t)stream);
+    const LinOperand A = {x_bf16, nullptr, ld_n, 0}, B = {Wq, Ws, ld_n, sg};
+    return launch_tile_gemm<kBf16KFast, kInt8KFast, uint16_t>(A, B, bias_bf16, y_bf16, tokens, m, n, (hipStream_t)stream,
+                                                              nullptr, 1, ld_m);
 }
 
-extern "C" int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
-                                       int64_t tokens, int64_t m, int64_t n, int group, uint16_t* dx_bf16,
-                                       uint16_t* G_bf16, void* stream) {
+extern "C" int qg_int8_linear_forward(const uint16_t* x_bf16, const int8_t* Wq, const float* Ws, const uint16_t* bias_bf16,
+                                      int64_t tokens, int64_t m, int64_t n, int group, uint16_t* y_bf16, void* stream) {
+    return qg_int8_linear_forward_ld(x_bf16, Wq, Ws, bias_bf16, tokens, m, n, n, m, group, y_bf16, stream);
+}
+
+extern "C" int qg_int8_linear_backward_ld(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq,
+                                          const float* Ws, int64_t tokens, int64_t m, int64_t n, int64_t ld_n,
+                                          int64_t ld_m, int group, uint16_t* dx_bf16, uint16_t* G_bf16, void* stream) {
     if (!dy_bf16 || (!dx_bf16 && !G_bf16)) return QG_ERR_NULL;
     if ((dx_bf16 && (!Wq || !Ws)) || (G_bf16 && !x_bf16)) return QG_ERR_NULL;
     if (int e = check_linear(tokens, m, n, group)) return e;
+    if (int e = check_pitch(tokens > m ? tokens : m, n, ld_n)) return e;
+    if (int e = check_pitch(tokens, m, ld_m)) return e;
     if (!aligned16(dy_bf16) || (x_bf16 && !aligned16(x_bf16)) || (Wq && !aligned16(Wq)) || (Ws && !aligned16(Ws)) ||
         (dx_bf16 && !aligned16(dx_bf16)) || (G_bf16 && !aligned16(G_bf16)))
         return QG_ERR_ALIGN;
     const int sg = (int)((n + kGroup - 1) / kGroup);
     if (dx_bf16) {   // dx[t][i] = sum_o dy[t][o] W[o][i]
-        const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {Wq, Ws, n, sg};
-        if (int e = launch_tile_gemm<kBf16KFast, kInt8KSlow, uint16_t>(A, B, nullptr, dx_bf16, tokens, n, m, (hipStream_t)stream)) return e;
+        const LinOperand A = {dy_bf16, nullptr, ld_m, 0}, B = {Wq, Ws, ld_n, sg};
+        if (int e = launch_tile_gemm<kBf16KFast, kInt8KSlow, uint16_t>(A, B, nullptr, dx_bf16, tokens, n, m, (hipStream_t)stream,
+                                                                       nullptr, 1, ld_n))
+            return e;
     }
     if (G_bf16) {    // G[o][i] = sum_t dy[t][o] x[t][i]
-        const LinOperand A = {dy_bf16, nullptr, m, 0}, B = {x_bf16, nullptr, n, 0};
-        if (int e = launch_tile_gemm<kBf16KSlow, kBf16KSlow, uint16_t>(A, B, nullptr, G_bf16, m, n, tokens, (hipStream_t)stream)) return e;
+        const LinOperand A = {dy_bf16, nullptr, ld_m, 0}, B = {x_bf16, nullptr, ld_n, 0};
+        if (int e = launch_tile_gemm<kBf16KSlow, kBf16KSlow, uint16_t>(A, B, nullptr, G_bf16, m, n, tokens, (hipStream_t)stream,
+                                                                       nullptr, 1, ld_n))
+            return e;
     }
     return QG_OK;
+}
+
+extern "C" int qg_int8_linear_backward(const uint16_t* dy_bf16, const uint16_t* x_bf16, const int8_t* Wq, const float* Ws,
+                                       int64_t tokens, int64_t m, int64_t n, int group, uint16_t* dx_bf16,
+                                       uint16_t* G_bf16, void* stream) {
+    return qg_int8_linear_backward_ld(dy_bf16, x_bf16, Wq, Ws, tokens, m, n, n, m, group, dx_bf16, G_bf16, stream);
 }
 
 // The same layer on a weight stored transposed, S = W^T (n x m, blocks along m): the storage of a matrix whose

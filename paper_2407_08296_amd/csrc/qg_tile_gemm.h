@@ -62,6 +62,7 @@ struct LinBatch {
     const void* a[kLinBatchMax];
     int64_t strideB_bytes;
     int64_t strideC;
+    int64_t ldc = 0;   // row pitch of C in elements (0: N, dense rows)
 };
 
 // Staging of one operand tile: global -> registers (fetch) -> LDS (commit; INT8 is dequantized here).  EXACT: the
@@ -142,6 +143,7 @@ __global__ __launch_bounds__(WM * 128, WM == 2 ? 2 : 1) void k_tile_gemm(LinOper
     A.base = batch.a[blockIdx.y];
     B.base = static_cast<const char*>(B.base) + batch.strideB_bytes * blockIdx.y;
     C += batch.strideC * blockIdx.y;
+    const int64_t ldc = batch.ldc ? batch.ldc : N;
     __shared__ __attribute__((aligned(16))) uint16_t At[2][SA::ELEMS];
     __shared__ __attribute__((aligned(16))) uint16_t Bt[2][SB::ELEMS];
     const int lane = threadIdx.x & 63;
@@ -211,8 +213,8 @@ __global__ __launch_bounds__(WM * 128, WM == 2 ? 2 : 1) void k_tile_gemm(LinOper
                 const int row = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 const float x = acc[a][b][v];
                 if (EXACT || (row < M && col_ok)) {
-                    if constexpr (sizeof(OUT) == 4) C[(int64_t)row * N + col] = x + bj;
-                    else C[(int64_t)row * N + col] = to_bf16(x + bj);
+                    if constexpr (sizeof(OUT) == 4) C[(int64_t)row * ldc + col] = x + bj;
+                    else C[(int64_t)row * ldc + col] = to_bf16(x + bj);
                 }
             }
         }
@@ -227,6 +229,7 @@ __global__ __launch_bounds__(256, 3) void k_gemm_kslow_direct(const uint16_t* __
                                                               OUT* __restrict__ C, int M, int N, int K, int tiles_m,
                                                               int tiles_n) {
     constexpr int TN = 256, BK = 32;
+    const int64_t ldc = N;   // dense operands and output only
     using AD = KMajorSwizzled<kLinTM, BK, 256>;
     using BD = KMajorSwizzled<TN, BK, 256>;
     __shared__ __attribute__((aligned(16))) uint16_t As[2][AD::STAGE];
@@ -307,8 +310,8 @@ __global__ __launch_bounds__(256, 3) void k_gemm_kslow_direct(const uint16_t* __
             for (int v = 0; v < 16; ++v) {
                 const int row = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 const float x = acc[a][b][v];
-                if constexpr (sizeof(OUT) == 4) C[(int64_t)row * N + col] = x;
-                else C[(int64_t)row * N + col] = to_bf16(x);
+                if constexpr (sizeof(OUT) == 4) C[(int64_t)row * ldc + col] = x;
+                else C[(int64_t)row * ldc + col] = to_bf16(x);
             }
         }
 }
@@ -357,6 +360,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm_kfast_direct(LinOperand A, LinO
     A.base = batch.a[blockIdx.y];
     B.base = static_cast<const char*>(B.base) + batch.strideB_bytes * blockIdx.y;
     C += batch.strideC * blockIdx.y;
+    const int64_t ldc = batch.ldc ? batch.ldc : N;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
     const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x);
@@ -429,15 +433,15 @@ __global__ __launch_bounds__(512, 1) void k_gemm_kfast_direct(LinOperand A, LinO
             for (int v = 0; v < 16; ++v) {
                 const int row = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 const float x = acc[a][b][v] + bj;
-                if constexpr (sizeof(OUT) == 4) C[(int64_t)row * N + col] = x;
-                else C[(int64_t)row * N + col] = to_bf16(x);
+                if constexpr (sizeof(OUT) == 4) C[(int64_t)row * ldc + col] = x;
+                else C[(int64_t)row * ldc + col] = to_bf16(x);
             }
         }
 }
 
 template <int AL, int BL, typename OUT, int TN, int BK, int WM = 2>
 static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M,
-                                   int64_t N, int64_t K, hipStream_t st, const LinBatch* many, int count) {
+                                   int64_t N, int64_t K, hipStream_t st, const LinBatch* many, int count, int64_t ldc) {
     constexpr int TM = 64 * WM;
     const int64_t tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
     const dim3 grid((unsigned)((tiles_m * tiles_n + 7) / 8 * 8), (unsigned)count);   // x: a multiple of the 8 XCDs
@@ -449,6 +453,7 @@ static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, con
         batch.strideB_bytes = 0;
         batch.strideC = 0;
     }
+    batch.ldc = ldc;
     // no checks at all when every tile and every step is whole and rows start 16-byte aligned
     const bool exact = M % TM == 0 && N % TN == 0 && K % BK == 0 && A.ld % 8 == 0 && B.ld % 16 == 0;
     if (exact)
@@ -469,14 +474,15 @@ static void launch_tile_gemm_shape(const LinOperand& A, const LinOperand& B, con
 //    for 128 x 256 x 32 and 2.80 for 128 x 128 x 32 on the forward pass), 128 x 256 x 32 when that fills the chip,
 //    128 x 128 x 32 for small outputs.
 template <int AL, int BL, typename OUT>
+// ldc: row pitch of C in elements (0: N).
 static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint16_t* bias, OUT* C, int64_t M, int64_t N,
-                            int64_t K, hipStream_t st, const LinBatch* many = nullptr, int count = 1) {
+                            int64_t K, hipStream_t st, const LinBatch* many = nullptr, int count = 1, int64_t ldc = 0) {
     constexpr bool both_fast = (AL == kBf16KFast || AL == kInt8KFast || AL == kInt8ZKFast) &&
                                (BL == kBf16KFast || BL == kInt8KFast || BL == kInt8ZKFast);
     if constexpr (AL == kBf16KSlow && BL == kBf16KSlow) {
         const int64_t tiles_m = M / kLinTM, tiles_n = N / 256;
         if (many == nullptr && M % kLinTM == 0 && N % 256 == 0 && K % 32 == 0 && bias == nullptr &&
-            tiles_m * tiles_n >= 512 && K >= 32) {
+            tiles_m * tiles_n >= 512 && K >= 32 && A.ld == M && B.ld == N && (ldc == 0 || ldc == N)) {
             const unsigned grid = (unsigned)((tiles_m * tiles_n + 7) / 8 * 8);
             hipLaunchKernelGGL((k_gemm_kslow_direct<OUT>), dim3(grid), dim3(256), 0, st, static_cast<const uint16_t*>(A.base),
                                static_cast<const uint16_t*>(B.base), C, (int)M, (int)N, (int)K, (int)tiles_m, (int)tiles_n);
@@ -499,21 +505,22 @@ static int launch_tile_gemm(const LinOperand& A, const LinOperand& B, const uint
                         batch.strideB_bytes = 0;
                         batch.strideC = 0;
                     }
+                    batch.ldc = ldc;
                     hipLaunchKernelGGL((k_gemm_kfast_direct<BL, OUT>), grid, dim3(512), 0, st, A, B, bias, C, (int)M, (int)N,
                                        (int)K, (int)tiles_m, (int)tiles_n, batch);
                     return check_launch();
                 }
             }
-            launch_tile_gemm_shape<AL, BL, OUT, 256, 64, 4>(A, B, bias, C, M, N, K, st, many, count);
+            launch_tile_gemm_shape<AL, BL, OUT, 256, 64, 4>(A, B, bias, C, M, N, K, st, many, count, ldc);
             return check_launch();
         }
     }
     if constexpr (both_fast)
-        launch_tile_gemm_shape<AL, BL, OUT, 128, 64>(A, B, bias, C, M, N, K, st, many, count);
+        launch_tile_gemm_shape<AL, BL, OUT, 128, 64>(A, B, bias, C, M, N, K, st, many, count, ldc);
     else if (((M + kLinTM - 1) / kLinTM) * ((N + 255) / 256) * count >= 512)
-        launch_tile_gemm_shape<AL, BL, OUT, 256, 32>(A, B, bias, C, M, N, K, st, many, count);
+        launch_tile_gemm_shape<AL, BL, OUT, 256, 32>(A, B, bias, C, M, N, K, st, many, count, ldc);
     else
-        launch_tile_gemm_shape<AL, BL, OUT, 128, 32>(A, B, bias, C, M, N, K, st, many, count);
+        launch_tile_gemm_shape<AL, BL, OUT, 128, 32>(A, B, bias, C, M, N, K, st, many, count, ldc);
     return check_launch();
 }
 

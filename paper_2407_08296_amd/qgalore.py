@@ -33,6 +33,7 @@ EXPORTS = [
     "qg_int8_linear_t_zp_forward", "qg_int8_linear_t_zp_backward",
     "qg_state8_quant", "qg_state8_dequant", "qg_lowrank_adam8", "qg_step8",
     "qg_subspace_cossim_static", "qg_subspace_cossim_weighted", "qg_step_ld", "qg_subspace_refresh_many_ld",
+    "qg_int8_linear_forward_ld", "qg_int8_linear_backward_ld",
 ]
 
 
@@ -131,6 +132,8 @@ def lib() -> C.CDLL:
         L.qg_step8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, C.POINTER(HParams), u64, i64, vp]
         L.qg_int8_linear_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
         L.qg_int8_linear_backward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp]
+        L.qg_int8_linear_forward_ld.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, vp, vp]
+        L.qg_int8_linear_backward_ld.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, vp, vp, vp]
         L.qg_int8_linear_t_forward.argtypes = L.qg_int8_linear_forward.argtypes
         L.qg_int8_linear_t_backward.argtypes = L.qg_int8_linear_backward.argtypes
         L.qg_subspace_refresh_many.argtypes = [i32, C.POINTER(RefreshDesc), i64, i64, i64, i32, i32, vp, vp, vp, sz, vp]
@@ -465,6 +468,19 @@ def int8_linear_backward(dy: torch.Tensor, x: torch.Tensor | None, Wq: torch.Ten
     _check(lib().qg_int8_linear_backward(_ptr(dy, _BF16), _ptr(x, _BF16), _ptr(Wq, (torch.int8,)),
                                          _ptr(Ws, (torch.float32,)), tokens, m, n, GROUP, _ptr(dx), _ptr(G), _stream()))
     return dx, G
+
+
+def int8_linear_forward_ld(x, Wq, Ws, bias, tokens: int, m: int, n: int, ld_n: int, ld_m: int, y: torch.Tensor) -> None:
+    """qg_int8_linear_forward_ld: x [tokens][ld_n], Wq [m][ld_n], y [tokens][ld_m] (the caller's, padding untouched)."""
+    _check(lib().qg_int8_linear_forward_ld(_ptr(x, _BF16), _ptr(Wq, (torch.int8,)), _ptr(Ws, (torch.float32,)),
+                                           _ptr(bias, _BF16), tokens, m, n, ld_n, ld_m, GROUP, _ptr(y, _BF16), _stream()))
+
+
+def int8_linear_backward_ld(dy, x, Wq, Ws, tokens: int, m: int, n: int, ld_n: int, ld_m: int, dx, G) -> None:
+    """qg_int8_linear_backward_ld: dy [tokens][ld_m], x and dx [tokens][ld_n], Wq and G [m][ld_n]; dx or G may be None."""
+    _check(lib().qg_int8_linear_backward_ld(_ptr(dy, _BF16), _ptr(x, _BF16), _ptr(Wq, (torch.int8,)),
+                                            _ptr(Ws, (torch.float32,)), tokens, m, n, ld_n, ld_m, GROUP,
+                                            _ptr(dx, _BF16), _ptr(G, _BF16), _stream()))
 
 
 def int8_linear_t_forward(x: torch.Tensor, Sq: torch.Tensor, Ss: torch.Tensor, bias: torch.Tensor | None = None):

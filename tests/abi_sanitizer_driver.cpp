@@ -84,6 +84,9 @@ int main() {
     EXPECT(qg_int8_linear_forward(nullptr, FI8, FF, nullptr, 16, 512, 512, 256, F16, nullptr), QG_ERR_NULL);
     EXPECT(qg_int8_linear_forward(F16, FI8, FF, nullptr, (int64_t)1 << 20, (int64_t)1 << 12, 512, 256, F16, nullptr), QG_ERR_SHAPE);
     EXPECT(qg_int8_linear_backward(F16, F16, FI8, FF, 16, 512, 512, 256, nullptr, nullptr, nullptr), QG_ERR_NULL);
+    EXPECT(qg_int8_linear_forward_ld(F16, FI8, FF, nullptr, 16, 512, 500, 504, 512, 256, F16, nullptr), QG_ERR_SHAPE);
+    EXPECT(qg_int8_linear_forward_ld(F16, FI8, FF, nullptr, 16, 512, 500, 512, 512, 256, nullptr, nullptr), QG_ERR_NULL);
+    EXPECT(qg_int8_linear_backward_ld(F16, F16, FI8, FF, 16, 500, 512, 512, 496, 256, F16, F16, nullptr), QG_ERR_SHAPE);
     EXPECT(qg_int8_linear_t_forward(F16, nullptr, FF, nullptr, 16, 512, 512, 256, F16, nullptr), QG_ERR_NULL);
     EXPECT(qg_int8_linear_t_backward(F16, F16, FI8, FF, 16, 512, 512, 256, nullptr, nullptr, nullptr), QG_ERR_NULL);
     EXPECT(qg_int8_linear_zp_forward(F16, FI8, FF, nullptr, nullptr, 16, 512, 512, 256, F16, nullptr), QG_ERR_NULL);

@@ -136,3 +136,39 @@ def test_random_shapes():
         check(host_f64(y), Q.int8_linear_forward(xb, Wq, Ws), n, 0.02)
         check(host_f64(dx), want_dx, m, 0.05 * 0.02)
         check(host_f64(G), want_G, tokens, 0.05)
+
+
+def _pitched_bits(bits, rows, cols, ld, fill=0x7FC0):
+    """bf16 bit patterns [rows][cols] -> device int16 [rows][ld], the padding filled with `fill` (a NaN by default)."""
+    a = np.full((rows, ld), fill, dtype=np.uint16)
+    a[:, :cols] = np.asarray(bits).reshape(rows, cols)
+    return dev(a.view(np.int16))
+
+
+@pytest.mark.parametrize("tokens,m,n", [(130, 333, 261), (77, 200, 521), (64, 519, 256), (96, 256, 1365)])
+def test_layer_with_row_pitches_equals_the_dense_layer(tokens, m, n):
+    """qg_int8_linear_forward_ld / _backward_ld: activations, weight and gradients stored with rows a multiple of 16
+    elements apart (NaN in the activations' padding, junk codes in the weight's).  The real columns get the oracle's
+    values within the layer's bars and the dense call's values, and the outputs' padding keeps its fill."""
+    Wq, Ws, xb, dyb = case(tokens, m, n, seed=3)
+    ld_n, ld_m = (n + 15) // 16 * 16 + 16, (m + 15) // 16 * 16
+    xp, dyp = _pitched_bits(xb, tokens, n, ld_n), _pitched_bits(dyb, tokens, m, ld_m)
+    Wp = np.full((m, ld_n), 85, dtype=np.int8); Wp[:, :n] = Wq
+    Wp = dev(Wp)
+    y = torch.full((tokens, ld_m), 0x1234, dtype=torch.int16, device=DEV)
+    dx = torch.full((tokens, ld_n), 0x1234, dtype=torch.int16, device=DEV)
+    G = torch.full((m, ld_n), 0x1234, dtype=torch.int16, device=DEV)
+    qg.int8_linear_forward_ld(xp, Wp, dev(Ws), None, tokens, m, n, ld_n, ld_m, y)
+    qg.int8_linear_backward_ld(dyp, xp, Wp, dev(Ws), tokens, m, n, ld_n, ld_m, dx, G)
+    torch.cuda.synchronize()
+    oy = Q.int8_linear_forward(xb, Wq, Ws)
+    odx, oG = Q.int8_linear_backward(dyb, xb, Wq, Ws)
+    check(host_f64(y[:, :m].contiguous().view(torch.bfloat16)), oy, n, 0.02)
+    check(host_f64(dx[:, :n].contiguous().view(torch.bfloat16)), odx, m, 0.05 * 0.02)
+    check(host_f64(G[:, :n].contiguous().view(torch.bfloat16)), oG, tokens, 0.05)
+    assert torch.all(y[:, m:] == 0x1234) and torch.all(dx[:, n:] == 0x1234) and torch.all(G[:, n:] == 0x1234)
+    # the dense calls on the same data: the same sums in the same order
+    yd = qg.int8_linear_forward(bits_t(xb, (tokens, n)), dev(Wq), dev(Ws))
+    dxd, Gd = qg.int8_linear_backward(bits_t(dyb, (tokens, m)), bits_t(xb, (tokens, n)), dev(Wq), dev(Ws), m, n)
+    assert torch.equal(y[:, :m], yd.view(torch.int16)) and torch.equal(dx[:, :n], dxd.view(torch.int16))
+    assert torch.equal(G[:, :n], Gd.view(torch.int16))
