@@ -132,7 +132,8 @@ int qg_lowrank_adam(const float* R, float* M, float* V, uint16_t* N_bf16,
  * a sorted table with relative resolution.  Unsigned table (second moment): entry 0 is 0, entry p >= 1 has level
  * L = floor(log2 p), k = p - 2^L and value 10^-(7-L) * (0.1 + 0.9 (k+1) / 2^L) (2^L values spaced linearly over each
  * decade from 1e-7 to 1).  Signed table (first moment): levels 0..6 (1e-6 to 1), indices 0..126 the negatives from
- * -1 up, 127 zero, 128..254 the positives, 255 unused.
+ * -1 up, 127 zero, 128..254 the positives, 255 unused.  A positive second moment takes code 1 at least (it never
+ * rounds to zero while the first moment, whose table reaches ten times further down, survives).
  * qg_state8_quant / qg_state8_dequant: fp32 [count] <-> (codes, scales); is_signed selects the table.
  * qg_lowrank_adam8: as qg_lowrank_adam, with M and V held in this format (Mq/Ms signed, Vq/Vs unsigned, updated in
  * place): dequantize (table[code] * scale), the same update and direction N, quantize again.

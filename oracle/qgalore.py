@@ -579,6 +579,7 @@ def int8_linear_t_backward(dy_bits, x_bits, Sq, Ss):
 # resolution is relative: a dynamic exponent plus a linear fraction, scaled by
 # the block's absolute maximum).  Parity unpinned against the paper.
 #
+#   (rule added for the second moment: a positive value takes code 1 at least, see state8_quant)
 #   block      256 consecutive elements of the flattened r x n state
 #   scale      fp32 absmax of the block (0 for an all-zero block)
 #   code       index into a sorted table of 8-bit values in [-1, 1] (first
@@ -627,7 +628,12 @@ def state8_quant(x, signed: bool):
             continue
         inv = np.float32(1.0) / a                       # correctly rounded fp32 quotient
         xn = (blk * inv).astype(np.float32)
-        codes[b * GROUP:(b + 1) * GROUP] = np.searchsorted(mids, xn, side="left").astype(np.uint8)
+        c = np.searchsorted(mids, xn, side="left").astype(np.uint8)
+        if not signed:
+            # a positive second moment never rounds to zero: with V flushed to 0 while M survives (the signed table
+            # reaches ten times further down), Adam's quotient would be formed from the newest gradient alone
+            c = np.where((xn > 0) & (c == 0), np.uint8(1), c)
+        codes[b * GROUP:(b + 1) * GROUP] = c
     return codes, scales
 
 

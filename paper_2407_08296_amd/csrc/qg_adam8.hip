@@ -6,7 +6,8 @@
 //           relative resolution: entry p >= 1 of the unsigned table (second moment) has level L = floor(log2 p),
 //           k = p - 2^L and value 10^-(7-L) * (0.1 + 0.9 (k+1) / 2^L), entry 0 is 0: 2^L values spaced linearly over
 //           each decade from 1e-7 to 1.  The signed table (first moment) has levels 0..6 (1e-6 to 1): indices 0..126
-//           the negatives from -1 up, 127 zero, 128..254 the positives; index 255 is not used.
+//           the negatives from -1 up, 127 zero, 128..254 the positives; index 255 is not used.  One exception to
+//           "nearest": a positive second moment takes code 1 at least.
 // One step: states are dequantized (table[code] * scale), updated exactly like the fp32 states, and quantized again;
 // 10 bytes of HBM traffic per element instead of 22.  A wave owns a block: a lane holds four consecutive elements,
 // the block maximum is a wave reduction; the nearest entry comes from a bucket table indexed by the value's top
@@ -103,6 +104,9 @@ __device__ inline uint32_t s8_encode4(const S8Tables& T, const float (&x)[4], fl
         } else {
             const int c = T.ulut[s8_bucket<kS8UKey0, kS8ULut>(fmaxf(xn, 0.f))];   // nothing lies below a negative value
             code = (uint32_t)(c + (T.umid[c] < xn));
+            // a positive second moment never rounds to zero (the first moment's table reaches ten times further down:
+            // with V flushed and M kept, Adam's quotient would come from the newest gradient alone)
+            code = xn > 0.f ? max(code, 1u) : code;
         }
         pk |= code << (8 * j);
     }

@@ -108,3 +108,32 @@ def test_step8_is_project_adam8_backproject(m, n, r):
         Wq, Ws = Q.update_sr(Wq, Ws, oU, HP.lr, seed, t)
         d = host(a[3]).astype(np.int32) - Wq.astype(np.int32)
         assert np.abs(d).max() <= 1 and np.mean(d == 0) >= (0.995 if t == 1 else 0.9999)
+
+
+def test_small_gradient_elements_keep_a_bounded_direction_on_the_gpu():
+    """Sixty free-running steps on the device with elements whose gradient stays between the floors of the two state
+    tables (1e-4 ... 5e-6 of their block's largest): the second moment is held at the smallest positive entry instead of
+    rounding to zero, and the direction stays of order one - as in the oracle, whose run it follows code for code."""
+    hp = qg.hparams()
+    R = np.full((4, 256), 1e-2, dtype=np.float32)
+    small = [(0, 3), (1, 100), (2, 200), (3, 17)]
+    for (i, j), f in zip(small, (1e-4, -3e-5, 5e-6, 2e-5)):
+        R[i, j] = np.float32(1e-2 * f)
+    count = R.size
+    Mq, Ms = Q.state8_quant(np.zeros(count), True)
+    Vq, Vs = Q.state8_quant(np.zeros(count), False)
+    dMq, dMs, dVq, dVs = dev(Mq), dev(Ms), dev(Vq), dev(Vs)
+    dR = dev(R)
+    N = torch.empty((4, 256), dtype=torch.bfloat16, device=DEV)
+    worst = 0.0
+    for t in range(1, 61):
+        qg.lowrank_adam8(dR, dMq, dMs, dVq, dVs, N, t, hp)
+        Mq, Ms, Vq, Vs, oN, _, _ = Q.lowrank_adam8(R, Mq, Ms, Vq, Vs, t, HP)
+        gN = Q.bf16_bits_to_f64(host(N.view(torch.int16)).view(np.uint16)).reshape(4, 256)
+        worst = max(worst, max(abs(gN[i, j]) for i, j in small))
+        gv = host(dVq).reshape(4, 256)
+        assert all(gv[i, j] >= 1 for i, j in small)
+    assert worst <= 1.5, worst
+    # free-running for 60 steps the device states still sit on the oracle's (at most one entry apart)
+    for got, want in ((host(dMq), Mq), (host(dVq), Vq)):
+        assert np.abs(got.astype(np.int32) - want.astype(np.int32)).max() <= 1

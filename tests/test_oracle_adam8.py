@@ -34,7 +34,11 @@ def test_quantization_is_nearest_entry_with_ties_down():
         a = np.float32(np.abs(x.astype(np.float32)).max())
         assert scales.shape == (1,) and scales[0] == a
         xn = (x.astype(np.float32) * (np.float32(1) / a)).astype(np.float64)
+        first_mid = 0.5 * (tab[0] + tab[1])
         for i in range(256):                                        # brute force over the whole table
+            if not signed and 0 < xn[i] <= first_mid:
+                assert codes[i] == 1                                # a positive second moment never rounds to zero
+                continue
             d = np.abs(tab - xn[i])
             assert d[codes[i]] <= d.min() * (1 + 1e-6) + 1e-12
         # a value exactly on a midpoint goes to the lower entry
@@ -109,3 +113,29 @@ def test_midpoints_are_wider_apart_than_float_buckets_of_15_bits():
         below = np.searchsorted(pm, edges, side="left")
         assert np.diff(below).max() == 1
         assert (k0, k1) == ((13574, 16256) if signed else (13142, 16256))
+
+
+def test_a_persistently_small_gradient_keeps_a_bounded_direction():
+    """An element whose gradient stays far below its block's largest (between the floors of the two tables: its
+    first moment survives quantization, its second moment would round to zero) over 60 steps: Adam's direction for
+    it must stay of order one.  With V flushed to zero every step the quotient would come from the newest gradient
+    alone, m / sqrt((1 - beta2) g^2) ~ 30 at large t; storing a positive V at the smallest positive entry instead
+    bounds it (and errs towards the smaller step)."""
+    hp = Q.HParams()
+    R = np.full(256, 1e-2)
+    small = [3, 100, 200]
+    R[small] = [1e-2 * 1e-4, -1e-2 * 3e-5, 1e-2 * 5e-6]           # 1e-4, 3e-5, 5e-6 of the block maximum
+    Mq, Ms = Q.state8_quant(np.zeros(256), True)
+    Vq, Vs = Q.state8_quant(np.zeros(256), False)
+    worst = 0.0
+    for t in range(1, 61):
+        Mq, Ms, Vq, Vs, N, M1, V1 = Q.lowrank_adam8(R, Mq, Ms, Vq, Vs, t, hp)
+        worst = max(worst, float(np.abs(N[small]).max()))
+        assert np.all(Vq[small] >= 1)                               # never flushed
+        assert np.allclose(N[[0, 1, 2]], 1.0, atol=0.1)             # the ordinary elements: direction 1
+    assert worst <= 1.5, worst
+    assert np.all(Mq[small] != 127)                                 # their first moments did survive
+    # the format rule itself: any positive value takes code >= 1, zero keeps code 0, nearest-entry otherwise
+    x = np.zeros(256); x[0] = 1.0; x[1] = 1e-9; x[2] = 4e-8; x[3] = 6e-8; x[4] = 1.4e-7
+    c, _ = Q.state8_quant(x, False)
+    assert list(c[:6]) == [255, 1, 1, 1, 1, 0]
