@@ -853,6 +853,16 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
     }
 
     if (!W_PREFETCH) load_wtile();    // the staging buffers are free now (the main loop ends with a barrier)
+    // The rows' old scales (and zero points) are fetched together with the weight tile: one wait covers both, where
+    // loading them inside the epilogue exposed a second memory latency per tile.
+    float s_old_row[JB], z_old_row[ZP ? JB : 1];
+#pragma unroll
+    for (int b = 0; b < JB; ++b) {
+        const int mrow = m0 + wm * SM + b * 32 + (lane & 31);
+        const bool row_ok = !RAGGED || mrow < m;
+        s_old_row[b] = row_ok ? Ws[(int64_t)mrow * ng + tile_n] : 0.f;
+        if constexpr (ZP) z_old_row[b] = row_ok ? Wz[(int64_t)mrow * ng + tile_n] : 0.f;
+    }
     // The weight tile's direct loads are counted by vmcnt like any other load.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -868,9 +878,9 @@ __device__ __forceinline__ void backproject_tile(const uint8_t* __restrict__ Pq,
         const int rl = wm * SM + b * 32 + lrow;       // row inside the tile
         const int mrow = m0 + rl;
         const bool row_ok = !RAGGED || mrow < m;
-        const float s_old = row_ok ? Ws[(int64_t)mrow * ng + tile_n] : 0.f;
+        const float s_old = s_old_row[b];
         float z_old = 0.f;
-        if constexpr (ZP) z_old = row_ok ? Wz[(int64_t)mrow * ng + tile_n] : 0.f;
+        if constexpr (ZP) z_old = z_old_row[b];
         float mx = 0.f, mn = 0.f;   // the zero-point range contains zero
         const int wt_lane = wtile_offset(rl, wn * SN + 4 * lhalf);
 #pragma unroll
