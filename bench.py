@@ -419,7 +419,7 @@ def refresh_bench(args, shapes, mats):
         t = timed(lambda: qg.diag_mfma_f64_loop(it, 256 * per_cu, sink), 3)
         ceilings[f"mfma_f64_loop_{per_cu}_workgroups_per_cu"] = fl / t / 1e9
     del sink
-    bf16_flop = sum(4.0 * m * n * r for m, n, r in shapes)                 # R = P^T G and Y = G Z^T
+    bf16_flop = sum(6.0 * m * n * r for m, n, r in shapes)     # P^T G, Y = G Z^T, and P_new^T G for the check's weights
     fp64_flop = sum(2 * (m * r * r + r ** 3 / 3 + r ** 3 / 3 + m * r * r) for m, n, r in shapes)   # two rounds
     out = {"metric": "Q-GaLore subspace refresh ms over all linear weights", "value": ms, "unit": "ms",
            "n_gpus": 1, "rounds": rounds, "higher_is_better": False, "dtype": "bf16 GEMMs + fp64 orthonormalisation",
