@@ -277,3 +277,24 @@ def test_product_package_does_not_touch_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle|oracle[./]|#include.*oracle", text, re.M), \
                     os.path.join(dirpath, f)
+
+
+def test_sizes_past_the_index_limit_are_refused(L):
+    """m * n = 2^32: every call that indexes elements with 32 bits returns the shape error; just below it passes the
+    shape check (and fails the next one, here a misaligned pointer)."""
+    hp = qg.hparams()
+    assert L.qg_step(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 65536, 65536, 128, 256, C.byref(hp), 0, 1,
+                     None, 0, None) == 2
+    assert L.qg_backproject_update_sr(FAKE, FAKE, FAKE, FAKE, FAKE, 65536, 65536, 128, 256, 0.25, 1e-3, 0, 1, None, None) == 2
+    assert L.qg_project(FAKE, FAKE, FAKE, 65536, 65536, 128, 256, FAKE, None, 0, None) == 2
+    assert L.qg_backproject_update_sr(FAKE, FAKE, FAKE, FAKE + 4, FAKE, 32768, 130816, 128, 256, 0.25, 1e-3, 0, 1, None,
+                                      None) == 4
+    descs = (qg.MatrixDesc * 1)()
+    d = descs[0]
+    d.m, d.n, d.r = 65536, 65536, 128
+    for f in ("Pq", "Ps", "G", "Wq", "Ws", "M", "V", "R", "N"):
+        setattr(d, f, FAKE)
+    nbytes = L.qg_plan_bytes(1, descs)
+    buf = C.create_string_buffer(nbytes)
+    assert L.qg_plan_build(1, descs, buf, nbytes) == 2
+
