@@ -8,7 +8,8 @@
  *    in as `workspace` (size from the matching *_workspace_bytes query).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls enqueue work and return WITHOUT synchronising.
- *  - All matrices are dense row-major with leading dimension = row length.
+ *  - All matrices are dense row-major with leading dimension = row length
+ *    (the *_ld entry points and the grouped descriptors take a row pitch).
  *    Base pointers must be 16-byte aligned (QG_ERR_ALIGN otherwise).
  *  - Notation (the paper's): W is the m x n weight, G the m x n gradient,
  *    P the m x r projection matrix, R = P^T G (r x n), M and V the Adam moments
@@ -24,6 +25,10 @@
  *    codes per byte, flat element 2b in the low nibble of byte b, stored
  *    nibble = code + 8.
  *  - bf16 tensors are passed as uint16_t bit patterns.
+ *  - Sizes are positive: an empty tensor (m, n, r or an element count of 0) is
+ *    an argument error (QG_ERR_SHAPE), not a no-op; m * n must stay below 2^32
+ *    (the stochastic-rounding stream and the kernels index elements with 32
+ *    bits), r is a multiple of 8 and at most m.
  *  - Return value: QG_OK or a QG_ERR_* code.  Arguments are validated before
  *    any HIP call, so argument errors are reported even with no GPU present.
  *    After QG_ERR_HIP, qg_last_hip_error() returns the hipError_t value.
